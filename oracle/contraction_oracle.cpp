@@ -1,0 +1,340 @@
+// CPU ORACLE for the binary tensor contraction  D := alpha * op(A) * op(B) + beta * op(C).
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the GPU
+// library is checked against.  It shares no code with the library, is never linked
+// into it, and only tests, the smoke check and the bench's cpu_baseline leg call it.
+//
+// What it computes (paper, Sec. "Mathematical Definitions"):
+//   * Eq. (binary_contraction):  D := alpha A B + beta C.
+//   * Case 1 / Eq. (case1): labels shared by A and B only (P) are summed; labels
+//     shared by A and D (F_A) or by B and D (F_B) are free.
+//   * Case 2 / Eq. (case2): labels present in A, B and D (H) are element-wise.
+//   * Case 3 + Note 6: a label repeated inside one tensor addresses a diagonal; the
+//     strides of all its occurrences are added.
+//   * Cases 4 and 5 (labels in only one of A, B, or only in D) are not required by
+//     the standard (Note 7) and are rejected by oracle_validate().
+// How it computes it (paper, Sec. "Algorithm Structure", Figs. "implementation" and
+// "helper-functions"): an odometer over the distinct labels of D, first label fastest,
+// an inner odometer over the contracted labels, one offset = sum(index*stride) per
+// tensor per term.  Strides are in ELEMENTS, measured from the element whose indices
+// are all zero (glossary, "Strided layout"); absent labels get stride 0.
+//
+// Readings where the paper is silent:
+//   * op() is identity or complex conjugation applied to the element as it is read;
+//     on real types it is the identity.
+//   * beta == 0 means C is never read (so C may hold NaN or be a null pointer);
+//     alpha == 0 means A and B are never read.  (The paper-literal mode below is the
+//     exception: it follows the figure, which always reads C.)
+//   * C has exactly D's extents, labels and strides (Note 5) and is addressed with
+//     D's offset, as in the figure.
+//
+// Three evaluation modes of the same loop nest:
+//   MODE_TRUTH   accumulator is long double (x87 80-bit), one rounding to the storage
+//                type at the end; also returns S = sum |op(a)||op(b)| per D element,
+//                the normaliser of the error measure.
+//   MODE_TIMED   accumulator in the storage type's own precision: what a plain CPU
+//                code does; this is the instantiation the bench times.
+//   MODE_LITERAL the figure's order of operations: D <- beta*C, then
+//                D <- D + alpha*a*b for every term, read-modify-write on D in storage
+//                precision.
+//
+// Build:  g++ -O2 -fopenmp -shared -fPIC contraction_oracle.cpp -o liboracle.so
+
+#include <complex>
+#include <cstdint>
+#include <cstdlib>
+#include <cmath>
+#include <vector>
+#include <algorithm>
+
+namespace {
+
+enum { DT_F32 = 0, DT_F64 = 1, DT_C128 = 3 };
+enum { MODE_TRUTH = 0, MODE_TIMED = 1, MODE_LITERAL = 2 };
+enum { OP_IDENTITY = 0, OP_CONJ = 1 };
+
+// validation outcomes (classes, not the library's numeric codes)
+enum {
+    V_OK = 0,
+    V_EXTENT_MISMATCH = 1,   // same label, different extent (Preliminaries: Id(i)=Id(j) only if d_i=d_j)
+    V_CD_MISMATCH = 2,       // C is not laid out exactly as D (Note 5)
+    V_D_ALIASING = 3,        // two index tuples of D address the same element
+    V_ISOLATED = 4,          // Case 4 or Case 5 label
+    V_BAD_ARG = 5            // non-positive extent, bad rank
+};
+
+struct Tensor {
+    int n;
+    const int64_t* extent;
+    const int64_t* stride;
+    const int64_t* label;
+};
+
+// One entry per distinct label of the whole operation (paper: "pre-processing").
+struct Loop {
+    int64_t label;
+    int64_t extent;
+    int64_t sA, sB, sD;   // summed strides (Note 6); 0 where the label is absent
+    bool inA, inB, inD;
+};
+
+bool has_label(const Tensor& t, int64_t lab) {
+    for (int i = 0; i < t.n; ++i) if (t.label[i] == lab) return true;
+    return false;
+}
+
+int64_t summed_stride(const Tensor& t, int64_t lab) {
+    int64_t s = 0;
+    for (int i = 0; i < t.n; ++i) if (t.label[i] == lab) s += t.stride[i];
+    return s;
+}
+
+// Distinct labels of `t`, in order of first appearance.
+std::vector<int64_t> distinct_labels(const Tensor& t) {
+    std::vector<int64_t> out;
+    for (int i = 0; i < t.n; ++i)
+        if (std::find(out.begin(), out.end(), t.label[i]) == out.end()) out.push_back(t.label[i]);
+    return out;
+}
+
+int validate(const Tensor& A, const Tensor& B, const Tensor& C, const Tensor& D) {
+    const Tensor* all[4] = {&A, &B, &C, &D};
+    for (const Tensor* t : all) {
+        if (t->n < 0) return V_BAD_ARG;
+        for (int i = 0; i < t->n; ++i) if (t->extent[i] <= 0) return V_BAD_ARG;
+    }
+    // equal labels carry equal extents, within and across tensors
+    for (const Tensor* t : all)
+        for (int i = 0; i < t->n; ++i)
+            for (const Tensor* u : all)
+                for (int j = 0; j < u->n; ++j)
+                    if (t->label[i] == u->label[j] && t->extent[i] != u->extent[j])
+                        return V_EXTENT_MISMATCH;
+    // C must be D: same rank, and position by position the same label, extent, stride
+    if (C.n != D.n) return V_CD_MISMATCH;
+    for (int i = 0; i < D.n; ++i)
+        if (C.label[i] != D.label[i] || C.extent[i] != D.extent[i] || C.stride[i] != D.stride[i])
+            return V_CD_MISMATCH;
+    // Eq. (FreeD): every label of D is in A or B.  Note 7: no label lives in A only or B only.
+    for (int i = 0; i < D.n; ++i)
+        if (!has_label(A, D.label[i]) && !has_label(B, D.label[i])) return V_ISOLATED;
+    for (int i = 0; i < A.n; ++i)
+        if (!has_label(B, A.label[i]) && !has_label(D, A.label[i])) return V_ISOLATED;
+    for (int i = 0; i < B.n; ++i)
+        if (!has_label(A, B.label[i]) && !has_label(D, B.label[i])) return V_ISOLATED;
+    // Aliasing inside D.  Work on distinct labels with summed strides, drop extent 1,
+    // sort by |stride| and require each stride to clear the span of the smaller ones.
+    // Sufficient for "no two tuples collide"; conservative for exotic layouts.
+    std::vector<std::pair<int64_t, int64_t>> se;   // (|stride|, extent)
+    for (int64_t lab : distinct_labels(D)) {
+        int64_t e = 0;
+        for (int i = 0; i < D.n; ++i) if (D.label[i] == lab) e = D.extent[i];
+        if (e == 1) continue;
+        int64_t s = summed_stride(D, lab);
+        se.push_back({s < 0 ? -s : s, e});
+    }
+    std::sort(se.begin(), se.end());
+    int64_t span = 0;               // largest |offset| reachable with the modes so far
+    for (auto& p : se) {
+        if (p.first <= span) return V_D_ALIASING;   // also catches stride 0
+        span += p.first * (p.second - 1);
+    }
+    return V_OK;
+}
+
+// ---- element access helpers -------------------------------------------------------
+template <class T> struct Real { using type = T; };
+template <class R> struct Real<std::complex<R>> { using type = R; };
+
+template <class T> inline T apply_op(T x, int) { return x; }
+template <class R> inline std::complex<R> apply_op(std::complex<R> x, int op) {
+    return op == OP_CONJ ? std::conj(x) : x;
+}
+
+template <class Acc, class T> struct Widen { static Acc of(T x) { return (Acc)x; } };
+template <class RA, class R> struct Widen<std::complex<RA>, std::complex<R>> {
+    static std::complex<RA> of(std::complex<R> x) { return {(RA)x.real(), (RA)x.imag()}; }
+};
+
+template <class T, class Acc> struct Narrow { static T of(Acc x) { return (T)x; } };
+template <class R, class RA> struct Narrow<std::complex<R>, std::complex<RA>> {
+    static std::complex<R> of(std::complex<RA> x) { return {(R)x.real(), (R)x.imag()}; }
+};
+
+inline long double modulus(long double x) { return fabsl(x); }
+inline long double modulus(std::complex<long double> x) { return hypotl(x.real(), x.imag()); }
+inline double modulus(double x) { return std::fabs(x); }
+inline float modulus(float x) { return std::fabs(x); }
+inline double modulus(std::complex<double> x) { return std::hypot(x.real(), x.imag()); }
+
+// Complex multiply written out (no library special-casing of inf/nan).
+template <class R> inline R mul(R a, R b) { return a * b; }
+template <class R> inline std::complex<R> mul(std::complex<R> a, std::complex<R> b) {
+    return {a.real() * b.real() - a.imag() * b.imag(), a.real() * b.imag() + a.imag() * b.real()};
+}
+
+template <class X> inline bool is_zero(X x) { return x == X(0); }
+
+// Odometer step, first index fastest (Fig. "helper-functions", increment).
+inline void increment(std::vector<int64_t>& idx, const std::vector<int64_t>& shape) {
+    for (size_t k = 0; k < shape.size(); ++k) {
+        idx[k] = (idx[k] + 1) % shape[k];
+        if (idx[k] > 0) return;
+    }
+}
+// Fig. "helper-functions", offset (with the return the figure leaves out).
+inline int64_t offset(const std::vector<int64_t>& idx, const std::vector<int64_t>& strides) {
+    int64_t off = 0;
+    for (size_t k = 0; k < strides.size(); ++k) off += idx[k] * strides[k];
+    return off;
+}
+
+template <class T, class Acc>
+void contract(int mode, const std::vector<Loop>& free_loops, const std::vector<Loop>& sum_loops,
+              int opA, int opB, int opC, Acc alpha, Acc beta,
+              const T* A, const T* B, const T* C, T* D, double* S) {
+    std::vector<int64_t> dshape, dsA, dsB, dsD, pshape, psA, psB;
+    int64_t size_D = 1, size_P = 1;
+    for (const Loop& l : free_loops) {
+        dshape.push_back(l.extent); dsA.push_back(l.sA); dsB.push_back(l.sB); dsD.push_back(l.sD);
+        size_D *= l.extent;
+    }
+    for (const Loop& l : sum_loops) {
+        pshape.push_back(l.extent); psA.push_back(l.sA); psB.push_back(l.sB);
+        size_P *= l.extent;
+    }
+    const bool read_ab = !is_zero(alpha);
+    const bool read_c = !is_zero(beta);
+
+    // The paper runs three nested odometers over H, F_A, F_B and notes that its own
+    // implementation folds them into one loop over the labels of D; so does this.
+    // Each iteration rebuilds its multi-index from the linear counter, so the result
+    // does not depend on how OpenMP cuts the range.
+#pragma omp parallel for schedule(static)
+    for (int64_t lin = 0; lin < size_D; ++lin) {
+        std::vector<int64_t> I(dshape.size());
+        int64_t rem = lin;
+        for (size_t k = 0; k < dshape.size(); ++k) { I[k] = rem % dshape[k]; rem /= dshape[k]; }
+        const int64_t off_D = offset(I, dsD);
+        const int64_t baseA = offset(I, dsA);
+        const int64_t baseB = offset(I, dsB);
+        std::vector<int64_t> K(pshape.size(), 0);
+
+        if (mode == MODE_LITERAL) {
+            // storage-precision read-modify-write, exactly the figure's statements
+            const T al = Narrow<T, Acc>::of(alpha), be = Narrow<T, Acc>::of(beta);
+            D[off_D] = mul(be, apply_op(C[off_D], opC));
+            for (int64_t k = 0; k < size_P; ++k) {
+                const int64_t off_A = baseA + offset(K, psA);
+                const int64_t off_B = baseB + offset(K, psB);
+                D[off_D] = D[off_D] + mul(al, mul(apply_op(A[off_A], opA), apply_op(B[off_B], opB)));
+                increment(K, pshape);
+            }
+            continue;
+        }
+
+        Acc acc = Acc(0);
+        long double s = 0.0L;
+        if (read_ab) {
+            for (int64_t k = 0; k < size_P; ++k) {
+                const int64_t off_A = baseA + offset(K, psA);
+                const int64_t off_B = baseB + offset(K, psB);
+                const Acc a = Widen<Acc, T>::of(apply_op(A[off_A], opA));
+                const Acc b = Widen<Acc, T>::of(apply_op(B[off_B], opB));
+                acc = acc + mul(a, b);
+                if (S) s += (long double)modulus(a) * (long double)modulus(b);
+                increment(K, pshape);
+            }
+        }
+        Acc d = mul(alpha, acc);
+        if (read_c) d = d + mul(beta, Widen<Acc, T>::of(apply_op(C[off_D], opC)));
+        D[off_D] = Narrow<T, Acc>::of(d);
+        if (S) S[off_D] = (double)s;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+// Validation by the rules of the paper, independent of the library's.  Returns a V_* class.
+int oracle_validate(int nA, const int64_t* extA, const int64_t* strA, const int64_t* labA,
+                    int nB, const int64_t* extB, const int64_t* strB, const int64_t* labB,
+                    int nC, const int64_t* extC, const int64_t* strC, const int64_t* labC,
+                    int nD, const int64_t* extD, const int64_t* strD, const int64_t* labD) {
+    Tensor A{nA, extA, strA, labA}, B{nB, extB, strB, labB}, C{nC, extC, strC, labC}, D{nD, extD, strD, labD};
+    return validate(A, B, C, D);
+}
+
+// The contraction.  alpha/beta: {re, im} as long double is awkward over ctypes, so they
+// come as double pairs (every test scalar is a double or float value anyway).
+// A, B, C, D point at the element with all indices zero.  S (may be null) has D's
+// layout but element type double.  Returns a V_* class; nothing is written unless V_OK.
+int oracle_contract(int dtype, int mode,
+                    int nA, const int64_t* extA, const int64_t* strA, const int64_t* labA, int opA,
+                    int nB, const int64_t* extB, const int64_t* strB, const int64_t* labB, int opB,
+                    int nC, const int64_t* extC, const int64_t* strC, const int64_t* labC, int opC,
+                    int nD, const int64_t* extD, const int64_t* strD, const int64_t* labD,
+                    const double* alpha, const double* beta,
+                    const void* A, const void* B, const void* C, void* D, double* S) {
+    Tensor tA{nA, extA, strA, labA}, tB{nB, extB, strB, labB}, tC{nC, extC, strC, labC}, tD{nD, extD, strD, labD};
+    const int v = validate(tA, tB, tC, tD);
+    if (v != V_OK) return v;
+
+    // classification by set membership (Secs. Case 1, Case 2): D's labels drive the
+    // outer odometer (H, F_A, F_B together, in D's order); A∩B minus D is P.
+    std::vector<Loop> free_loops, sum_loops;
+    for (int64_t lab : distinct_labels(tD)) {
+        Loop l{};
+        l.label = lab;
+        for (int i = 0; i < nD; ++i) if (labD[i] == lab) l.extent = extD[i];
+        l.sA = summed_stride(tA, lab); l.sB = summed_stride(tB, lab); l.sD = summed_stride(tD, lab);
+        free_loops.push_back(l);
+    }
+    for (int64_t lab : distinct_labels(tA)) {
+        if (has_label(tD, lab)) continue;
+        Loop l{};
+        l.label = lab;
+        for (int i = 0; i < nA; ++i) if (labA[i] == lab) l.extent = extA[i];
+        l.sA = summed_stride(tA, lab); l.sB = summed_stride(tB, lab); l.sD = 0;
+        sum_loops.push_back(l);
+    }
+
+    using cld = std::complex<long double>;
+    using cd = std::complex<double>;
+    if (dtype == DT_F64) {
+        if (mode == MODE_TRUTH)
+            contract<double, long double>(mode, free_loops, sum_loops, opA, opB, opC, alpha[0], beta[0],
+                                          (const double*)A, (const double*)B, (const double*)C, (double*)D, S);
+        else
+            contract<double, double>(mode, free_loops, sum_loops, opA, opB, opC, alpha[0], beta[0],
+                                     (const double*)A, (const double*)B, (const double*)C, (double*)D, S);
+    } else if (dtype == DT_F32) {
+        if (mode == MODE_TRUTH)
+            contract<float, long double>(mode, free_loops, sum_loops, opA, opB, opC, alpha[0], beta[0],
+                                         (const float*)A, (const float*)B, (const float*)C, (float*)D, S);
+        else
+            contract<float, float>(mode, free_loops, sum_loops, opA, opB, opC, (float)alpha[0], (float)beta[0],
+                                   (const float*)A, (const float*)B, (const float*)C, (float*)D, S);
+    } else if (dtype == DT_C128) {
+        if (mode == MODE_TRUTH)
+            contract<cd, cld>(mode, free_loops, sum_loops, opA, opB, opC, cld(alpha[0], alpha[1]), cld(beta[0], beta[1]),
+                              (const cd*)A, (const cd*)B, (const cd*)C, (cd*)D, S);
+        else
+            contract<cd, cd>(mode, free_loops, sum_loops, opA, opB, opC, cd(alpha[0], alpha[1]), cd(beta[0], beta[1]),
+                             (const cd*)A, (const cd*)B, (const cd*)C, (cd*)D, S);
+    } else {
+        return V_BAD_ARG;
+    }
+    return V_OK;
+}
+
+int oracle_max_threads(void);
+}
+
+#ifdef _OPENMP
+#include <omp.h>
+extern "C" int oracle_max_threads(void) { return omp_get_max_threads(); }
+#else
+extern "C" int oracle_max_threads(void) { return 1; }
+#endif

@@ -1,0 +1,96 @@
+"""Glue shared by the tests: run the oracle on a workloads.Problem, the error measure,
+and a random problem generator.  Holds no contraction arithmetic of its own."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+import workloads as W
+
+
+def desc(spec: W.TensorSpec, ids):
+    return (list(spec.extents), list(spec.strides), [ids[l] for l in spec.labels])
+
+
+def run_oracle(p: W.Problem, bufA, bufB, bufC, mode=oracle.MODE_TRUTH, want_S=False, alpha=None, beta=None):
+    """Returns (bufD, S).  bufC is not modified."""
+    ids = W.label_ids(p)
+    bufD = bufC.copy()
+    al = p.alpha if alpha is None else alpha
+    be = p.beta if beta is None else beta
+    st, S = oracle.contract(desc(p.A, ids), desc(p.B, ids), desc(p.D, ids), desc(p.D, ids),
+                            (p.opA, p.opB, p.opC), al, be, bufA, bufB, bufC, bufD,
+                            base=(p.A.base, p.B.base, p.D.base, p.D.base), mode=mode, want_S=want_S)
+    assert st == oracle.V_OK, oracle.V_NAMES[st]
+    return bufD, S
+
+
+UNIT_ROUNDOFF = {"f32": 2.0 ** -24, "f64": 2.0 ** -53, "c128": 2.0 ** -53}
+# Gate of the error measure |d - d_truth| / (|alpha| S + |beta| |c|), S = sum |a||b|.
+TOLERANCE = {"f32": 1e-5, "f64": 1e-12, "c128": 1e-12}
+
+
+def normalised_error(p: W.Problem, got, truth, S, bufC, alpha=None, beta=None):
+    """max over the addressed elements of D of |got - truth| / (|alpha| S + |beta||c|)."""
+    al = abs(p.alpha if alpha is None else alpha)
+    be = abs(p.beta if beta is None else beta)
+    g = W.strided_view(got, p.D).astype(np.complex128 if p.dtype == "c128" else np.float64)
+    t = W.strided_view(truth, p.D).astype(g.dtype)
+    s = W.strided_view(S, p.D)
+    c = np.abs(W.strided_view(bufC, p.D).astype(g.dtype)) if be != 0 else 0.0
+    den = al * s + be * c
+    num = np.abs(g - t)
+    tiny = np.finfo(np.float64).tiny
+    ok_zero = (den == 0) & (num == 0)
+    ratio = np.where(ok_zero, 0.0, num / np.maximum(den, tiny))
+    return float(ratio.max()) if ratio.size else 0.0
+
+
+def gaps_untouched(p: W.Problem, before, after) -> bool:
+    """True iff every buffer element that (extents, strides) does not address is bit-identical."""
+    mask = np.zeros(before.shape[0], dtype=bool)
+    W.strided_view(mask, p.D)[...] = True
+    return bool(np.array_equal(before[~mask].view(np.uint8), after[~mask].view(np.uint8)))
+
+
+def random_problem(rng: np.random.Generator, dtype="f64", max_group=2, max_extent=4, allow_neg=False,
+                   pad=True, min_k=0, name="rand") -> W.Problem:
+    """A random valid Case-1/2 problem: random numbers of H, M, N, K labels, random extents,
+    random label order per tensor, random memory order, optional padding / negative strides."""
+    while True:
+        nh, nm, nn = (int(rng.integers(0, max_group + 1)) for _ in range(3))
+        nk = int(rng.integers(min_k, max_group + 1))
+        if nh + nm + nn + nk > 0:
+            break
+    H = ["h%d" % i for i in range(nh)]
+    M = ["m%d" % i for i in range(nm)]
+    N = ["n%d" % i for i in range(nn)]
+    K = ["k%d" % i for i in range(nk)]
+    ext = {l: int(rng.integers(1, max_extent + 1)) for l in H + M + N + K}
+
+    def layout(labels):
+        labels = list(labels)
+        rng.shuffle(labels)
+        order = list(labels)
+        rng.shuffle(order)
+        strides, run = {}, 1
+        for l in order:
+            if pad and rng.random() < 0.3:
+                run *= int(rng.integers(2, 4))
+            strides[l] = run
+            run *= ext[l]
+        if allow_neg:
+            for l in order:
+                if rng.random() < 0.4:
+                    strides[l] = -strides[l]
+        return W.tensor(labels, ext, strides=strides)
+
+    A, B, D = layout(H + M + K), layout(H + N + K), layout(H + M + N)
+    cplx = dtype == "c128"
+    alpha = complex(rng.integers(-2, 3), rng.integers(-2, 3) if cplx else 0) or 1.0
+    beta = complex(rng.integers(-2, 3), rng.integers(-2, 3) if cplx else 0)
+    if not cplx:
+        alpha, beta = alpha.real, beta.real
+    return W.Problem(name, dtype, A, B, D, alpha=alpha, beta=beta,
+                     opA=int(rng.integers(0, 2)), opB=int(rng.integers(0, 2)), opC=int(rng.integers(0, 2)),
+                     seed=int(rng.integers(1, 1 << 30)))

@@ -1,0 +1,83 @@
+"""The pins have teeth: plant one plausible mistake at a time in a COPY of the oracle's
+source (on the CPU, in a temporary file), load it in place of the real oracle, and check
+that at least one pin fails.  Nothing here touches the GPU or the committed oracle."""
+import ctypes
+import os
+import subprocess
+import tempfile
+
+import pytest
+
+import oracle
+import test_oracle_pins as pins
+
+SRC = open(os.path.join(os.path.dirname(oracle.__file__), "contraction_oracle.cpp")).read()
+
+# (name, text to find, replacement); every `find` must occur in the source
+MUTANTS = [
+    ("conj_dropped", "return op == OP_CONJ ? std::conj(x) : x;", "return x;"),
+    ("complex_mul_sign", "a.real() * b.real() - a.imag() * b.imag()", "a.real() * b.real() + a.imag() * b.imag()"),
+    ("odometer_never_carries", "if (idx[k] > 0) return;", "return;"),
+    ("beta_term_dropped", "if (read_c) d = d + mul(beta,", "if (false) d = d + mul(beta,"),
+    ("repeated_label_last_stride_only", "if (t.label[i] == lab) s += t.stride[i];", "if (t.label[i] == lab) s = t.stride[i];"),
+    ("B_addressed_with_A_strides", "const int64_t off_B = baseB + offset(K, psB);", "const int64_t off_B = baseB + offset(K, psA);"),
+    ("opC_ignored", "Widen<Acc, T>::of(apply_op(C[off_D], opC))", "Widen<Acc, T>::of(C[off_D])"),
+    ("C_read_at_linear_index", "mul(beta, Widen<Acc, T>::of(apply_op(C[off_D], opC)))", "mul(beta, Widen<Acc, T>::of(apply_op(C[lin], opC)))"),
+    ("alpha_also_scales_C", "D[off_D] = Narrow<T, Acc>::of(d);", "D[off_D] = Narrow<T, Acc>::of(read_c ? mul(alpha, d) : d);"),
+    ("hadamard_label_summed", "if (has_label(tD, lab)) continue;", "if (has_label(tD, lab) && !has_label(tB, lab)) continue;"),
+    ("aliasing_check_off", "if (p.first <= span) return V_D_ALIASING;", "if (false) return V_D_ALIASING;"),
+    ("isolated_in_B_accepted", "if (!has_label(A, B.label[i]) && !has_label(D, B.label[i])) return V_ISOLATED;", ";"),
+    ("free_stride_of_A_dropped", "const int64_t baseA = offset(I, dsA);", "const int64_t baseA = 0;"),
+    ("last_term_skipped", "for (int64_t k = 0; k < size_P; ++k) {", "for (int64_t k = 1; k < size_P; ++k) {"),
+]
+
+
+def _pins_to_run():
+    calls = []
+    for dt in ("f64", "c128"):
+        for seed in range(12):
+            calls.append((pins.test_brute_force_integer_inputs_exact, (dt, seed)))
+    for dt in ("f64", "c128"):
+        for seed in range(4):
+            calls.append((pins.test_einsum_random_problems, (dt, seed)))
+    for row in pins._paper_examples():
+        calls.append((pins.test_paper_label_examples, (row,)))
+    calls += [(pins.test_repeated_label_equals_summed_stride, ()), (pins.test_validation_classes, ()),
+              (pins.test_conjugation_symmetry_and_op_equals_preconjugated_copy, ()),
+              (pins.test_delta_operand_reproduces_permutation, ("c128",)),
+              (pins.test_linearity_in_alpha_and_beta, ("c128",)),
+              (pins.test_degenerate_shapes, ()),
+              (pins.test_config4_hslowest_is_batched_AhB, ())]
+    for p in pins.W.configs_reduced():
+        calls.append((pins.test_all_ones_gives_product_of_contracted_extents, (p,)))
+    return calls
+
+
+@pytest.mark.parametrize("mutant", MUTANTS, ids=lambda m: m[0])
+def test_a_pin_catches_the_planted_mistake(mutant, monkeypatch):
+    name, find, repl = mutant
+    assert find in SRC, "mutant pattern no longer matches the oracle source"
+    with tempfile.TemporaryDirectory() as tmp:
+        src, lib = os.path.join(tmp, "m.cpp"), os.path.join(tmp, "m.so")
+        with open(src, "w") as f:
+            f.write(SRC.replace(find, repl))
+        subprocess.check_call(["g++", "-O1", "-fopenmp", "-shared", "-fPIC", "-std=c++17", src, "-o", lib])
+        bad = ctypes.CDLL(lib)
+        bad.oracle_validate.restype = ctypes.c_int
+        bad.oracle_contract.restype = ctypes.c_int
+        bad.oracle_max_threads.restype = ctypes.c_int
+        oracle._load()
+        monkeypatch.setattr(oracle, "_lib", bad)
+        caught = 0
+        for fn, args in _pins_to_run():
+            try:
+                fn(*args)
+            except AssertionError:
+                caught += 1
+                break
+        assert caught, "no pin noticed mutant %s" % name
+
+
+def test_unmutated_oracle_passes_the_same_pins():
+    for fn, args in _pins_to_run():
+        fn(*args)
