@@ -1,0 +1,185 @@
+/* tcx.h -- C interface of libtcx: general binary tensor contraction on one AMD MI355X.
+ *
+ *     D := alpha * opA(A) * opB(B) + beta * opC(C)          (paper, Eq. binary_contraction)
+ *
+ * A, B, C, D are dense tensors in a general strided layout (glossary, "Strided layout":
+ * address = base + sum_k i_k * s_k).  Every mode carries an integer label.  A label that
+ * occurs in A and B only is contracted (summed, set P); in A and D only, or in B and D
+ * only, it is free (F_A, F_B); in A, B and D it is a Hadamard / batch label (H)
+ * (Secs. "Case 1", "Case 2", Eqs. case1, case2).  A label repeated inside one tensor
+ * addresses a diagonal (Sec. "Case 3", Note 6).  Labels that occur in only one of A, B
+ * or only in D (Cases 4 and 5) are not required by the standard (Note 7) and are
+ * rejected with TCX_ERR_ISOLATED_INDEX.
+ *
+ * Object model (Sec. "Interface Components"): a library handle, an executor (a HIP
+ * stream), tensor descriptors ("tensor info": rank, extents, strides, dtype -- no data
+ * pointer), a product plan built from four descriptors, their labels, the element-wise
+ * ops and a precision, an execute call that takes only data pointers and scalars, an
+ * optional status object, and integer error codes with a text explanation
+ * (Sec. "Error Handling").  All handles are opaque integers; 0 is "no object".
+ *
+ * Conventions
+ *  - Every function returns a tcx_error_t; 0 is success.  Outputs come back through
+ *    pointers; where noted an output pointer may be NULL to skip it.
+ *  - Ownership: the library owns an object from create to destroy.  destroy takes the
+ *    handle by pointer and sets it to 0.  The library never owns tensor data.  A product
+ *    copies what it needs from its tensor infos, which may be destroyed right after.
+ *  - Strides are in ELEMENTS (not bytes), signed.  A data pointer addresses the element
+ *    whose indices are all zero.  Zero strides are legal in A and B (broadcast), not in D.
+ *  - Data pointers passed to tcx_execute_product are DEVICE pointers on the handle's GPU.
+ *    alpha and beta are HOST pointers to one element of D's dtype (two doubles for
+ *    TCX_C128) and are read before the call returns.
+ *  - beta == 0: C is never read and may be NULL; D is overwritten.  alpha == 0: A and B
+ *    are never read.  C may be the same pointer as D (in place); any other overlap of
+ *    D with A, B or C is undefined.  Buffer elements of D that (extents, strides) do not
+ *    address are left bit-unchanged.
+ *  - tcx_execute_product enqueues work on the executor's stream and returns; argument
+ *    errors are reported synchronously, before anything is enqueued.
+ *  - Objects are immutable after creation; concurrent execution of one product on
+ *    different executors is allowed.
+ */
+#ifndef TCX_H
+#define TCX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t tcx_error_t;
+typedef intptr_t tcx_handle_t;
+typedef intptr_t tcx_executor_t;
+typedef intptr_t tcx_tensor_info_t;
+typedef intptr_t tcx_product_t;
+typedef intptr_t tcx_status_t;
+
+typedef enum { TCX_F32 = 0, TCX_F64 = 1, TCX_C128 = 3 } tcx_dtype_t;     /* 2 is reserved for complex64 */
+typedef enum { TCX_OP_IDENTITY = 0, TCX_OP_CONJ = 1 } tcx_op_t;          /* conj of a real type is the identity */
+typedef enum { TCX_PREC_DEFAULT = 0 } tcx_prec_t;                        /* accumulate in the dtype's own real type */
+
+enum {
+    TCX_SUCCESS = 0,
+    TCX_ERR_NULL_ARG = 1,            /* a required pointer argument is NULL */
+    TCX_ERR_INVALID_HANDLE = 2,      /* handle is 0, destroyed, or of another object type */
+    TCX_ERR_BAD_DTYPE = 3,
+    TCX_ERR_BAD_NMODE = 4,           /* number of modes < 0 or > TCX_MAX_MODES */
+    TCX_ERR_BAD_EXTENT = 5,          /* an extent is <= 0 (Sec. Preliminaries: extents are positive) */
+    TCX_ERR_EXTENT_MISMATCH = 6,     /* one label, two extents (Sec. Preliminaries; appendix test 26) */
+    TCX_ERR_CD_MISMATCH = 7,         /* C is not described exactly like D (Note 5; appendix test 27) */
+    TCX_ERR_D_ALIASING = 8,          /* two index tuples of D share an address (appendix test 28) */
+    TCX_ERR_ISOLATED_INDEX = 9,      /* Case 4 / Case 5 label (Eq. FreeD, Note 7) */
+    TCX_ERR_DTYPE_MIX = 10,          /* the four tensors do not share one dtype */
+    TCX_ERR_UNSUPPORTED_OP = 11,     /* op value unknown, or opD != identity */
+    TCX_ERR_UNSUPPORTED_PRECISION = 12,
+    TCX_ERR_ALLOC = 13,              /* host or device allocation failed */
+    TCX_ERR_LAUNCH = 14,             /* the HIP runtime refused a launch or copy; see the status object */
+    TCX_ERR_NO_DEVICE = 15,          /* the handle was created without a usable gfx950 GPU (plans only) */
+    TCX_ERR_TOO_LARGE = 16,          /* an offset or an index range exceeds what the kernels address */
+    TCX_ERR_BAD_KEY = 17,            /* unknown key in tcx_status_get / tcx_product_get */
+    TCX_ERR_BUFFER_TOO_SMALL = 18    /* *nbytes is smaller than the value; *nbytes is set to the need */
+};
+
+#define TCX_MAX_MODES 32
+
+/* ---- library handle (Sec. "The Library Handle") -------------------------------------
+ * Binds to the current HIP device.  If no gfx950 device is usable the handle is still
+ * created in plan-only state: descriptors and products can be built and inspected,
+ * tcx_execute_product returns TCX_ERR_NO_DEVICE.  `out` must not be NULL. */
+tcx_error_t tcx_create_handle(tcx_handle_t* out);
+tcx_error_t tcx_destroy_handle(tcx_handle_t* handle);
+/* 1 if the handle can execute (a gfx950 device is bound), else 0. out must not be NULL. */
+tcx_error_t tcx_handle_has_device(tcx_handle_t handle, int32_t* out);
+
+/* ---- executor (Sec. "Executors") ----------------------------------------------------
+ * Wraps a hipStream_t owned by the caller (passed as void*; NULL is the default stream).
+ * The stream must stay alive while the executor is in use. */
+tcx_error_t tcx_create_executor(tcx_handle_t handle, void* hip_stream, tcx_executor_t* out);
+tcx_error_t tcx_destroy_executor(tcx_executor_t* executor);
+
+/* ---- tensor descriptor (Sec. "Tensor Descriptors") ----------------------------------
+ * extents[nmode], strides[nmode]: host arrays, copied.  nmode may be 0 (a scalar; the
+ * array pointers may then be NULL). */
+tcx_error_t tcx_create_tensor_info(tcx_handle_t handle, tcx_dtype_t dtype, int32_t nmode,
+                                   const int64_t* extents, const int64_t* strides, tcx_tensor_info_t* out);
+tcx_error_t tcx_destroy_tensor_info(tcx_tensor_info_t* info);
+/* Any output pointer may be NULL; extents/strides must hold nmode entries. */
+tcx_error_t tcx_tensor_info_get(tcx_tensor_info_t info, tcx_dtype_t* dtype, int32_t* nmode,
+                                int64_t* extents, int64_t* strides);
+
+/* ---- product plan (Sec. "Tensor Operation Descriptors") -----------------------------
+ * labelsX[nmode of X]: host arrays of integer labels, copied.  Validation and the index
+ * analysis (classification into H / F_A / F_B / P, merging of repeated labels, fusion of
+ * contiguous modes, choice of kernel path and tile plan) happen here, once, so that their
+ * cost is amortised over executions.  On a handle with a device this also uploads the
+ * plan's offset tables (synchronous, default stream).  C must match D mode by mode in
+ * label, extent and stride; opD must be TCX_OP_IDENTITY. */
+tcx_error_t tcx_create_product(tcx_handle_t handle,
+                               tcx_op_t opA, tcx_tensor_info_t A, const int64_t* labelsA,
+                               tcx_op_t opB, tcx_tensor_info_t B, const int64_t* labelsB,
+                               tcx_op_t opC, tcx_tensor_info_t C, const int64_t* labelsC,
+                               tcx_op_t opD, tcx_tensor_info_t D, const int64_t* labelsD,
+                               tcx_prec_t precision, tcx_product_t* out);
+tcx_error_t tcx_destroy_product(tcx_product_t* product);
+
+/* Keys of tcx_product_get / tcx_status_get.  Values are int64_t unless noted. */
+enum {
+    TCX_KEY_PATH = 1,          /* tcx_path_t chosen by the analyser */
+    TCX_KEY_SIZE_H = 2,        /* product of the extents of the Hadamard labels */
+    TCX_KEY_SIZE_M = 3,        /* ... of the free labels of A */
+    TCX_KEY_SIZE_N = 4,        /* ... of the free labels of B */
+    TCX_KEY_SIZE_K = 5,        /* ... of the contracted labels */
+    TCX_KEY_NMODES_H = 6,      /* number of modes per group after merging and fusion */
+    TCX_KEY_NMODES_M = 7,
+    TCX_KEY_NMODES_N = 8,
+    TCX_KEY_NMODES_K = 9,
+    TCX_KEY_TILE_M = 10,       /* macro-tile extents of the chosen kernel (0 if not tiled) */
+    TCX_KEY_TILE_N = 11,
+    TCX_KEY_TILE_K = 12,
+    TCX_KEY_GRID = 13,         /* number of workgroups launched */
+    TCX_KEY_BLOCK = 14,        /* threads per workgroup */
+    TCX_KEY_A_K_FASTEST = 15,  /* 1 if A's smallest stride belongs to a contracted mode */
+    TCX_KEY_B_K_FASTEST = 16,
+    TCX_KEY_D_N_FASTEST = 17,  /* 1 if D's smallest stride belongs to a free mode of B */
+    TCX_KEY_VARIANT = 18,      /* index of the kernel instantiation inside the path */
+    TCX_KEY_HIP_ERROR = 19,    /* status only: last hipError_t seen by the execute call */
+    TCX_KEY_MODES_M = 20,      /* int64_t[4 * nmodes]: (extent, strideA, strideB, strideD) per fused mode, fastest first */
+    TCX_KEY_MODES_N = 21,
+    TCX_KEY_MODES_K = 22,
+    TCX_KEY_MODES_H = 23,
+    TCX_KEY_FORCE_PATH = 24    /* tcx_product_set only: force a tcx_path_t (testing, tuning) */
+};
+typedef enum {
+    TCX_PATH_GENERIC = 0,      /* one thread per element of D, loops over the contracted index space */
+    TCX_PATH_GETT_MFMA = 1,    /* strided gather -> LDS tiles -> MFMA, fused alpha/beta scatter */
+    TCX_PATH_BANDWIDTH = 2     /* streaming path for low arithmetic intensity */
+} tcx_path_t;
+
+/* Read a property of the plan.  *nbytes: in = capacity of value, out = bytes written. */
+tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, size_t* nbytes);
+/* Override a plan decision (TCX_KEY_FORCE_PATH, TCX_KEY_VARIANT).  Returns
+ * TCX_ERR_UNSUPPORTED_OP if the plan cannot run that way. */
+tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* value, size_t nbytes);
+
+/* ---- execution (Sec. "Execution") ----------------------------------------------------
+ * status may be NULL (no status object is created).  If it is not NULL, *status receives
+ * a new status object (also on TCX_ERR_LAUNCH) that the caller destroys. */
+tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, tcx_status_t* status,
+                                const void* alpha, const void* A, const void* B,
+                                const void* beta, const void* C, void* D);
+
+/* ---- status object (Sec. "Status Objects") ------------------------------------------ */
+tcx_error_t tcx_status_get(tcx_status_t status, int32_t key, void* value, size_t* nbytes);
+tcx_error_t tcx_destroy_status(tcx_status_t* status);
+
+/* ---- error handling (Sec. "Error Handling") ------------------------------------------ */
+int tcx_check_success(tcx_error_t error);                                  /* 1 iff error == TCX_SUCCESS */
+/* strerror analogue: writes at most maxlen bytes (NUL-terminated if maxlen > 0) and
+ * returns the length the full message needs, excluding the NUL.  msg may be NULL. */
+size_t tcx_explain_error(tcx_error_t error, size_t maxlen, char* msg);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TCX_H */

@@ -110,11 +110,21 @@ int validate(const Tensor& A, const Tensor& B, const Tensor& C, const Tensor& D)
                 for (int j = 0; j < u->n; ++j)
                     if (t->label[i] == u->label[j] && t->extent[i] != u->extent[j])
                         return V_EXTENT_MISMATCH;
-    // C must be D: same rank, and position by position the same label, extent, stride
-    if (C.n != D.n) return V_CD_MISMATCH;
-    for (int i = 0; i < D.n; ++i)
-        if (C.label[i] != D.label[i] || C.extent[i] != D.extent[i] || C.stride[i] != D.stride[i])
-            return V_CD_MISMATCH;
+    // C must be D (Note 5: identical memory layout).  Compared label by label on the
+    // distinct labels (extent and summed stride), so writing C's modes in another order
+    // with the strides moved along is the same layout and is accepted.
+    {
+        std::vector<int64_t> lc = distinct_labels(C), ld = distinct_labels(D);
+        if (lc.size() != ld.size()) return V_CD_MISMATCH;
+        for (int64_t lab : ld) {
+            if (!has_label(C, lab)) return V_CD_MISMATCH;
+            int64_t ec = 0, ed = 0;
+            for (int i = 0; i < C.n; ++i) if (C.label[i] == lab) ec = C.extent[i];
+            for (int i = 0; i < D.n; ++i) if (D.label[i] == lab) ed = D.extent[i];
+            if (ec != ed) return V_CD_MISMATCH;
+            if (ed > 1 && summed_stride(C, lab) != summed_stride(D, lab)) return V_CD_MISMATCH;
+        }
+    }
     // Eq. (FreeD): every label of D is in A or B.  Note 7: no label lives in A only or B only.
     for (int i = 0; i < D.n; ++i)
         if (!has_label(A, D.label[i]) && !has_label(B, D.label[i])) return V_ISOLATED;

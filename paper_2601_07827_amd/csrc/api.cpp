@@ -1,0 +1,463 @@
+// C-ABI layer of libtcx: opaque objects, argument checking, plan construction (analyser +
+// offset tables + kernel choice) and the execute call.  See include/tcx.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <unordered_map>
+
+#include "tcx_internal.hpp"
+
+namespace tcx {
+namespace {
+
+enum : uint32_t { MAGIC_HANDLE = 0x74637801, MAGIC_EXEC, MAGIC_INFO, MAGIC_PRODUCT, MAGIC_STATUS };
+
+struct Handle {
+    int device = -1;
+    bool has_device = false;
+    int num_cu = 0;
+};
+struct Executor {
+    Handle handle;
+    hipStream_t stream = nullptr;
+};
+struct Info {
+    TensorDesc desc;
+};
+struct Product {
+    Handle handle;
+    Analysis an;
+    int variant = 0;                 // index into the tiled kernel instantiations
+    // offset tables, host copies and one device allocation holding all six
+    std::vector<int64_t> tables[6];  // oAM oAK oBN oBK oDM oDN
+    int64_t* dev_tables = nullptr;
+    size_t dev_offset[6] = {0, 0, 0, 0, 0, 0};
+    GenericArgs generic{};
+};
+struct Status {
+    int64_t path = 0, variant = 0, grid = 0, block = 0, tile_m = 0, tile_n = 0, tile_k = 0, hip_error = 0;
+};
+
+std::mutex g_mu;
+std::unordered_map<intptr_t, uint32_t> g_live;   // handle value -> object type
+
+template <class T> intptr_t publish(T* obj, uint32_t magic) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_live[(intptr_t)obj] = magic;
+    return (intptr_t)obj;
+}
+template <class T> T* lookup(intptr_t h, uint32_t magic) {
+    if (h == 0) return nullptr;
+    std::lock_guard<std::mutex> lk(g_mu);
+    auto it = g_live.find(h);
+    return (it != g_live.end() && it->second == magic) ? (T*)h : nullptr;
+}
+template <class T> tcx_error_t retire(intptr_t* h, uint32_t magic) {
+    if (!h) return TCX_ERR_NULL_ARG;
+    T* obj = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        auto it = g_live.find(*h);
+        if (*h == 0 || it == g_live.end() || it->second != magic) return TCX_ERR_INVALID_HANDLE;
+        obj = (T*)*h;
+        g_live.erase(it);
+    }
+    delete obj;
+    *h = 0;
+    return TCX_SUCCESS;
+}
+
+int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// Largest tile whose grid still covers the chip; the smallest shape if none does.
+int choose_variant(const Analysis& an, int num_cu) {
+    const int n = gett_num_variants(an.dtype);
+    const int want = num_cu > 0 ? num_cu : 256;
+    for (int v = 0; v < n; ++v) {
+        const GettVariant s = gett_variant(an.dtype, v);
+        const int64_t tiles = ((an.sizeM + s.mt_m - 1) / s.mt_m) * ((an.sizeN + s.mt_n - 1) / s.mt_n) * an.sizeH;
+        if (tiles >= want) return v;
+    }
+    return n - 1;
+}
+
+void fill_generic(const Analysis& an, GenericArgs* g) {
+    // every mode that indexes D, D-fastest first, so neighbouring threads write neighbouring elements
+    std::vector<Mode> d;
+    d.insert(d.end(), an.H.begin(), an.H.end());
+    d.insert(d.end(), an.M.begin(), an.M.end());
+    d.insert(d.end(), an.N.begin(), an.N.end());
+    std::stable_sort(d.begin(), d.end(), [](const Mode& a, const Mode& b) {
+        return (a.sD < 0 ? -a.sD : a.sD) < (b.sD < 0 ? -b.sD : b.sD);
+    });
+    g->nD = (int)d.size();
+    g->nK = (int)an.K.size();
+    g->sizeD = an.sizeH * an.sizeM * an.sizeN;
+    g->sizeK = an.sizeK;
+    for (int i = 0; i < g->nD; ++i) {
+        g->dExt[i] = d[i].extent; g->dSA[i] = d[i].sA; g->dSB[i] = d[i].sB; g->dSD[i] = d[i].sD;
+    }
+    for (int i = 0; i < g->nK; ++i) {
+        g->kExt[i] = an.K[i].extent; g->kSA[i] = an.K[i].sA; g->kSB[i] = an.K[i].sB;
+    }
+    g->opA = an.opA; g->opB = an.opB; g->opC = an.opC;
+}
+
+tcx_error_t build_tables(Product* p) {
+    const Analysis& an = p->an;
+    const int64_t padM = round_up(an.sizeM, 256), padN = round_up(an.sizeN, 256), padK = round_up(an.sizeK, 64);
+    try {
+        p->tables[0] = offset_table(an.M, 0, padM);
+        p->tables[1] = offset_table(an.K, 0, padK);
+        p->tables[2] = offset_table(an.N, 1, padN);
+        p->tables[3] = offset_table(an.K, 1, padK);
+        p->tables[4] = offset_table(an.M, 2, padM);
+        p->tables[5] = offset_table(an.N, 2, padN);
+    } catch (const std::bad_alloc&) {
+        return TCX_ERR_ALLOC;
+    }
+    if (!p->handle.has_device) return TCX_SUCCESS;
+    size_t total = 0;
+    for (int i = 0; i < 6; ++i) { p->dev_offset[i] = total; total += p->tables[i].size(); }
+    if (hipMalloc((void**)&p->dev_tables, total * sizeof(int64_t)) != hipSuccess) {
+        p->dev_tables = nullptr;
+        (void)hipGetLastError();
+        return TCX_ERR_ALLOC;
+    }
+    for (int i = 0; i < 6; ++i)
+        if (hipMemcpy(p->dev_tables + p->dev_offset[i], p->tables[i].data(), p->tables[i].size() * sizeof(int64_t),
+                      hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipGetLastError();
+            (void)hipFree(p->dev_tables);
+            p->dev_tables = nullptr;
+            return TCX_ERR_LAUNCH;
+        }
+    return TCX_SUCCESS;
+}
+
+tcx_error_t put(const void* src, size_t need, void* value, size_t* nbytes) {
+    if (!nbytes) return TCX_ERR_NULL_ARG;
+    if (!value || *nbytes < need) { *nbytes = need; return value ? TCX_ERR_BUFFER_TOO_SMALL : TCX_ERR_NULL_ARG; }
+    std::memcpy(value, src, need);
+    *nbytes = need;
+    return TCX_SUCCESS;
+}
+tcx_error_t put_i64(int64_t v, void* value, size_t* nbytes) { return put(&v, sizeof v, value, nbytes); }
+tcx_error_t put_modes(const std::vector<Mode>& m, void* value, size_t* nbytes) {
+    std::vector<int64_t> flat;
+    for (const Mode& x : m) { flat.push_back(x.extent); flat.push_back(x.sA); flat.push_back(x.sB); flat.push_back(x.sD); }
+    if (flat.empty()) { if (!nbytes) return TCX_ERR_NULL_ARG; *nbytes = 0; return TCX_SUCCESS; }
+    return put(flat.data(), flat.size() * sizeof(int64_t), value, nbytes);
+}
+
+const char* const kMessages[] = {
+    "success",
+    "a required pointer argument is NULL",
+    "invalid, destroyed or mistyped object handle",
+    "unsupported data type",
+    "number of modes is negative or exceeds TCX_MAX_MODES",
+    "an extent is not positive",
+    "modes that share a label have different extents",
+    "tensor C does not have tensor D's labels, extents and strides",
+    "two index tuples of tensor D address the same element",
+    "a label occurs in only one of A, B, D (isolated index: reduction or broadcast is not supported)",
+    "the four tensors do not share one data type",
+    "unsupported element-wise operation (opD must be the identity)",
+    "unsupported computational precision",
+    "memory allocation failed",
+    "the HIP runtime reported an error; query TCX_KEY_HIP_ERROR on the status object",
+    "the handle has no usable gfx950 device; plans can be built but not executed",
+    "an index range or offset exceeds what the kernels can address",
+    "unknown key",
+    "value buffer too small",
+};
+
+}  // namespace
+}  // namespace tcx
+
+using namespace tcx;
+
+extern "C" {
+
+tcx_error_t tcx_create_handle(tcx_handle_t* out) {
+    if (!out) return TCX_ERR_NULL_ARG;
+    Handle* h = new (std::nothrow) Handle;
+    if (!h) return TCX_ERR_ALLOC;
+    int count = 0;
+    if (hipGetDeviceCount(&count) == hipSuccess && count > 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+            std::strncmp(prop.gcnArchName, "gfx950", 6) == 0) {
+            h->device = dev;
+            h->has_device = true;
+            h->num_cu = prop.multiProcessorCount;
+        }
+    }
+    (void)hipGetLastError();
+    *out = publish(h, MAGIC_HANDLE);
+    return TCX_SUCCESS;
+}
+
+tcx_error_t tcx_destroy_handle(tcx_handle_t* handle) { return retire<Handle>(handle, MAGIC_HANDLE); }
+
+tcx_error_t tcx_handle_has_device(tcx_handle_t handle, int32_t* out) {
+    if (!out) return TCX_ERR_NULL_ARG;
+    Handle* h = lookup<Handle>(handle, MAGIC_HANDLE);
+    if (!h) return TCX_ERR_INVALID_HANDLE;
+    *out = h->has_device ? 1 : 0;
+    return TCX_SUCCESS;
+}
+
+tcx_error_t tcx_create_executor(tcx_handle_t handle, void* hip_stream, tcx_executor_t* out) {
+    if (!out) return TCX_ERR_NULL_ARG;
+    Handle* h = lookup<Handle>(handle, MAGIC_HANDLE);
+    if (!h) return TCX_ERR_INVALID_HANDLE;
+    Executor* e = new (std::nothrow) Executor;
+    if (!e) return TCX_ERR_ALLOC;
+    e->handle = *h;
+    e->stream = (hipStream_t)hip_stream;
+    *out = publish(e, MAGIC_EXEC);
+    return TCX_SUCCESS;
+}
+
+tcx_error_t tcx_destroy_executor(tcx_executor_t* executor) { return retire<Executor>(executor, MAGIC_EXEC); }
+
+tcx_error_t tcx_create_tensor_info(tcx_handle_t handle, tcx_dtype_t dtype, int32_t nmode, const int64_t* extents,
+                                   const int64_t* strides, tcx_tensor_info_t* out) {
+    if (!out) return TCX_ERR_NULL_ARG;
+    if (!lookup<Handle>(handle, MAGIC_HANDLE)) return TCX_ERR_INVALID_HANDLE;
+    if (dtype != TCX_F32 && dtype != TCX_F64 && dtype != TCX_C128) return TCX_ERR_BAD_DTYPE;
+    if (nmode < 0 || nmode > TCX_MAX_MODES) return TCX_ERR_BAD_NMODE;
+    if (nmode > 0 && (!extents || !strides)) return TCX_ERR_NULL_ARG;
+    for (int i = 0; i < nmode; ++i)
+        if (extents[i] <= 0) return TCX_ERR_BAD_EXTENT;
+    Info* t = new (std::nothrow) Info;
+    if (!t) return TCX_ERR_ALLOC;
+    t->desc.dtype = dtype;
+    t->desc.extent.assign(extents, extents + nmode);
+    t->desc.stride.assign(strides, strides + nmode);
+    *out = publish(t, MAGIC_INFO);
+    return TCX_SUCCESS;
+}
+
+tcx_error_t tcx_destroy_tensor_info(tcx_tensor_info_t* info) { return retire<Info>(info, MAGIC_INFO); }
+
+tcx_error_t tcx_tensor_info_get(tcx_tensor_info_t info, tcx_dtype_t* dtype, int32_t* nmode, int64_t* extents,
+                                int64_t* strides) {
+    Info* t = lookup<Info>(info, MAGIC_INFO);
+    if (!t) return TCX_ERR_INVALID_HANDLE;
+    if (dtype) *dtype = (tcx_dtype_t)t->desc.dtype;
+    if (nmode) *nmode = (int32_t)t->desc.extent.size();
+    for (size_t i = 0; i < t->desc.extent.size(); ++i) {
+        if (extents) extents[i] = t->desc.extent[i];
+        if (strides) strides[i] = t->desc.stride[i];
+    }
+    return TCX_SUCCESS;
+}
+
+tcx_error_t tcx_create_product(tcx_handle_t handle, tcx_op_t opA, tcx_tensor_info_t A, const int64_t* labelsA,
+                               tcx_op_t opB, tcx_tensor_info_t B, const int64_t* labelsB, tcx_op_t opC,
+                               tcx_tensor_info_t C, const int64_t* labelsC, tcx_op_t opD, tcx_tensor_info_t D,
+                               const int64_t* labelsD, tcx_prec_t precision, tcx_product_t* out) {
+    if (!out) return TCX_ERR_NULL_ARG;
+    Handle* h = lookup<Handle>(handle, MAGIC_HANDLE);
+    Info* a = lookup<Info>(A, MAGIC_INFO);
+    Info* b = lookup<Info>(B, MAGIC_INFO);
+    Info* c = lookup<Info>(C, MAGIC_INFO);
+    Info* d = lookup<Info>(D, MAGIC_INFO);
+    if (!h || !a || !b || !c || !d) return TCX_ERR_INVALID_HANDLE;
+    if ((!labelsA && !a->desc.extent.empty()) || (!labelsB && !b->desc.extent.empty()) ||
+        (!labelsC && !c->desc.extent.empty()) || (!labelsD && !d->desc.extent.empty()))
+        return TCX_ERR_NULL_ARG;
+    Product* p = new (std::nothrow) Product;
+    if (!p) return TCX_ERR_ALLOC;
+    p->handle = *h;
+    tcx_error_t err = analyse(a->desc, labelsA, b->desc, labelsB, c->desc, labelsC, d->desc, labelsD, (int)opA,
+                              (int)opB, (int)opC, (int)opD, (int)precision, &p->an);
+    if (err == TCX_SUCCESS) {
+        fill_generic(p->an, &p->generic);
+        if (p->an.path == TCX_PATH_GETT_MFMA) {
+            p->variant = choose_variant(p->an, h->num_cu);
+            err = build_tables(p);
+        }
+        p->an.variant = p->variant;
+    }
+    if (err != TCX_SUCCESS) { delete p; return err; }
+    *out = publish(p, MAGIC_PRODUCT);
+    return TCX_SUCCESS;
+}
+
+tcx_error_t tcx_destroy_product(tcx_product_t* product) {
+    if (!product) return TCX_ERR_NULL_ARG;
+    Product* p = lookup<Product>(*product, MAGIC_PRODUCT);
+    if (!p) return TCX_ERR_INVALID_HANDLE;
+    if (p->dev_tables) { (void)hipFree(p->dev_tables); p->dev_tables = nullptr; }
+    return retire<Product>(product, MAGIC_PRODUCT);
+}
+
+tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, size_t* nbytes) {
+    Product* p = lookup<Product>(product, MAGIC_PRODUCT);
+    if (!p) return TCX_ERR_INVALID_HANDLE;
+    const Analysis& an = p->an;
+    const bool tiled = an.path == TCX_PATH_GETT_MFMA;
+    const GettVariant s = tiled ? gett_variant(an.dtype, p->variant) : GettVariant{0, 0, 0, 256};
+    switch (key) {
+        case TCX_KEY_PATH: return put_i64(an.path, value, nbytes);
+        case TCX_KEY_SIZE_H: return put_i64(an.sizeH, value, nbytes);
+        case TCX_KEY_SIZE_M: return put_i64(an.sizeM, value, nbytes);
+        case TCX_KEY_SIZE_N: return put_i64(an.sizeN, value, nbytes);
+        case TCX_KEY_SIZE_K: return put_i64(an.sizeK, value, nbytes);
+        case TCX_KEY_NMODES_H: return put_i64((int64_t)an.H.size(), value, nbytes);
+        case TCX_KEY_NMODES_M: return put_i64((int64_t)an.M.size(), value, nbytes);
+        case TCX_KEY_NMODES_N: return put_i64((int64_t)an.N.size(), value, nbytes);
+        case TCX_KEY_NMODES_K: return put_i64((int64_t)an.K.size(), value, nbytes);
+        case TCX_KEY_TILE_M: return put_i64(s.mt_m, value, nbytes);
+        case TCX_KEY_TILE_N: return put_i64(s.mt_n, value, nbytes);
+        case TCX_KEY_TILE_K: return put_i64(s.kt, value, nbytes);
+        case TCX_KEY_GRID:
+            return put_i64(tiled ? ((an.sizeM + s.mt_m - 1) / s.mt_m) * ((an.sizeN + s.mt_n - 1) / s.mt_n) * an.sizeH
+                                 : (an.sizeH * an.sizeM * an.sizeN + 255) / 256,
+                           value, nbytes);
+        case TCX_KEY_BLOCK: return put_i64(s.threads, value, nbytes);
+        case TCX_KEY_A_K_FASTEST: return put_i64(an.a_k_fastest, value, nbytes);
+        case TCX_KEY_B_K_FASTEST: return put_i64(an.b_k_fastest, value, nbytes);
+        case TCX_KEY_D_N_FASTEST: return put_i64(an.d_n_fastest, value, nbytes);
+        case TCX_KEY_VARIANT: return put_i64(tiled ? p->variant : 0, value, nbytes);
+        case TCX_KEY_MODES_M: return put_modes(an.M, value, nbytes);
+        case TCX_KEY_MODES_N: return put_modes(an.N, value, nbytes);
+        case TCX_KEY_MODES_K: return put_modes(an.K, value, nbytes);
+        case TCX_KEY_MODES_H: return put_modes(an.H, value, nbytes);
+        default: return TCX_ERR_BAD_KEY;
+    }
+}
+
+tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* value, size_t nbytes) {
+    Product* p = lookup<Product>(product, MAGIC_PRODUCT);
+    if (!p) return TCX_ERR_INVALID_HANDLE;
+    if (!value) return TCX_ERR_NULL_ARG;
+    if (nbytes != sizeof(int64_t)) return TCX_ERR_BUFFER_TOO_SMALL;
+    int64_t v;
+    std::memcpy(&v, value, sizeof v);
+    if (key == TCX_KEY_FORCE_PATH) {
+        if (v == TCX_PATH_GENERIC) { p->an.path = TCX_PATH_GENERIC; return TCX_SUCCESS; }
+        if (v == TCX_PATH_GETT_MFMA) {
+            if (gett_num_variants(p->an.dtype) == 0 || (int)p->an.H.size() > kMaxHModes) return TCX_ERR_UNSUPPORTED_OP;
+            if (p->tables[0].empty()) {
+                p->variant = choose_variant(p->an, p->handle.num_cu);
+                const tcx_error_t err = build_tables(p);
+                if (err != TCX_SUCCESS) return err;
+            }
+            p->an.path = TCX_PATH_GETT_MFMA;
+            return TCX_SUCCESS;
+        }
+        return TCX_ERR_UNSUPPORTED_OP;
+    }
+    if (key == TCX_KEY_VARIANT) {
+        if (p->an.path != TCX_PATH_GETT_MFMA || v < 0 || v >= gett_num_variants(p->an.dtype)) return TCX_ERR_UNSUPPORTED_OP;
+        p->variant = (int)v;
+        p->an.variant = (int)v;
+        return TCX_SUCCESS;
+    }
+    return TCX_ERR_BAD_KEY;
+}
+
+tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, tcx_status_t* status, const void* alpha,
+                                const void* A, const void* B, const void* beta, const void* C, void* D) {
+    Product* p = lookup<Product>(product, MAGIC_PRODUCT);
+    Executor* e = lookup<Executor>(executor, MAGIC_EXEC);
+    if (!p || !e) return TCX_ERR_INVALID_HANDLE;
+    if (!alpha || !beta || !D) return TCX_ERR_NULL_ARG;
+    Scalars s{0, 0, 0, 0};
+    switch (p->an.dtype) {
+        case TCX_F32: s.alpha_re = *(const float*)alpha; s.beta_re = *(const float*)beta; break;
+        case TCX_F64: s.alpha_re = *(const double*)alpha; s.beta_re = *(const double*)beta; break;
+        default:
+            s.alpha_re = ((const double*)alpha)[0]; s.alpha_im = ((const double*)alpha)[1];
+            s.beta_re = ((const double*)beta)[0]; s.beta_im = ((const double*)beta)[1];
+    }
+    const bool read_ab = s.alpha_re != 0 || s.alpha_im != 0;
+    const bool read_c = s.beta_re != 0 || s.beta_im != 0;
+    if ((read_ab && (!A || !B)) || (read_c && !C)) return TCX_ERR_NULL_ARG;
+    if (!p->handle.has_device || !e->handle.has_device) return TCX_ERR_NO_DEVICE;
+
+    Status st;
+    int hip_err = 0;
+    int64_t grid = 0;
+    int block = 0;
+    const bool tiled = p->an.path == TCX_PATH_GETT_MFMA && read_ab && p->dev_tables;
+    if (tiled) {
+        const GettVariant v = gett_variant(p->an.dtype, p->variant);
+        GettArgs g{};
+        g.A = A; g.B = B; g.C = C; g.D = D;
+        g.oAM = p->dev_tables + p->dev_offset[0]; g.oAK = p->dev_tables + p->dev_offset[1];
+        g.oBN = p->dev_tables + p->dev_offset[2]; g.oBK = p->dev_tables + p->dev_offset[3];
+        g.oDM = p->dev_tables + p->dev_offset[4]; g.oDN = p->dev_tables + p->dev_offset[5];
+        g.sizeM = p->an.sizeM; g.sizeN = p->an.sizeN; g.sizeK = p->an.sizeK; g.sizeH = p->an.sizeH;
+        g.tilesM = (int32_t)((g.sizeM + v.mt_m - 1) / v.mt_m);
+        g.tilesN = (int32_t)((g.sizeN + v.mt_n - 1) / v.mt_n);
+        g.tilesK = (int32_t)((g.sizeK + v.kt - 1) / v.kt);
+        g.nH = (int32_t)p->an.H.size();
+        for (int i = 0; i < g.nH; ++i) {
+            g.hExt[i] = p->an.H[i].extent; g.hSA[i] = p->an.H[i].sA; g.hSB[i] = p->an.H[i].sB; g.hSD[i] = p->an.H[i].sD;
+        }
+        g.s = s;
+        g.opA = p->an.opA; g.opB = p->an.opB; g.opC = p->an.opC;
+        g.read_c = read_c;
+        hip_err = launch_gett(p->an.dtype, p->variant, p->an.a_k_fastest, p->an.b_k_fastest, p->an.d_n_fastest, g,
+                              (void*)e->stream, &grid, &block);
+        st.path = TCX_PATH_GETT_MFMA; st.variant = p->variant;
+        st.tile_m = v.mt_m; st.tile_n = v.mt_n; st.tile_k = v.kt;
+    } else {
+        GenericArgs g = p->generic;
+        g.A = A; g.B = B; g.C = C; g.D = D;
+        g.s = s;
+        g.read_c = read_c; g.read_ab = read_ab;
+        hip_err = launch_generic(p->an.dtype, g, (void*)e->stream, &grid, &block);
+        st.path = TCX_PATH_GENERIC;
+    }
+    st.grid = grid; st.block = block; st.hip_error = hip_err;
+    if (status) {
+        Status* so = new (std::nothrow) Status(st);
+        *status = so ? publish(so, MAGIC_STATUS) : 0;
+    }
+    return hip_err == 0 ? TCX_SUCCESS : TCX_ERR_LAUNCH;
+}
+
+tcx_error_t tcx_status_get(tcx_status_t status, int32_t key, void* value, size_t* nbytes) {
+    Status* s = lookup<Status>(status, MAGIC_STATUS);
+    if (!s) return TCX_ERR_INVALID_HANDLE;
+    switch (key) {
+        case TCX_KEY_PATH: return put_i64(s->path, value, nbytes);
+        case TCX_KEY_VARIANT: return put_i64(s->variant, value, nbytes);
+        case TCX_KEY_GRID: return put_i64(s->grid, value, nbytes);
+        case TCX_KEY_BLOCK: return put_i64(s->block, value, nbytes);
+        case TCX_KEY_TILE_M: return put_i64(s->tile_m, value, nbytes);
+        case TCX_KEY_TILE_N: return put_i64(s->tile_n, value, nbytes);
+        case TCX_KEY_TILE_K: return put_i64(s->tile_k, value, nbytes);
+        case TCX_KEY_HIP_ERROR: return put_i64(s->hip_error, value, nbytes);
+        default: return TCX_ERR_BAD_KEY;
+    }
+}
+
+tcx_error_t tcx_destroy_status(tcx_status_t* status) { return retire<Status>(status, MAGIC_STATUS); }
+
+int tcx_check_success(tcx_error_t error) { return error == TCX_SUCCESS ? 1 : 0; }
+
+size_t tcx_explain_error(tcx_error_t error, size_t maxlen, char* msg) {
+    const int n = (int)(sizeof(kMessages) / sizeof(kMessages[0]));
+    const char* text = (error >= 0 && error < n) ? kMessages[error] : "unknown error code";
+    const size_t need = std::strlen(text);
+    if (msg && maxlen > 0) {
+        const size_t ncopy = need < maxlen - 1 ? need : maxlen - 1;
+        std::memcpy(msg, text, ncopy);
+        msg[ncopy] = '\0';
+    }
+    return need;
+}
+
+}  // extern "C"

@@ -1,0 +1,288 @@
+// Tiled, stride-aware contraction kernels for gfx950 (real fp64 and fp32).
+//
+// The contraction is treated as |H| independent products of an |M| x |K| by |K| x |N|
+// operand pair (paper, Eqs. case1, case2: M = F_A, N = F_B, K = P), but no operand is ever
+// transposed or packed in memory: a workgroup gathers its MT_M x KT slab of A and KT x MT_N
+// slab of B straight from the strided tensors into LDS.  Element addresses are additively
+// separable -- offset(m, k) = oM[m] + oK[k], because the paper's `offset` helper
+// (Fig. "helper-functions") is linear in the indices -- so two small tables per operand,
+// built at plan time, replace the per-term index arithmetic of the reference loop nest.
+// Lanes run along whichever of the operand's two index groups holds its smallest stride, so
+// global loads are coalesced for either orientation, and LDS keeps that orientation
+// ([k][m] or [m][k]); only the MFMA fragment read differs.  Accumulation is register
+// blocked over 16x16x4 MFMA tiles; the alpha/beta epilogue scatters to strided D with lanes
+// along D's fastest group (the MFMA operand roles are swapped to make that so).
+#include <hip/hip_runtime.h>
+
+#include "tcx_internal.hpp"
+
+namespace tcx {
+namespace {
+
+typedef double double4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+// 16x16x4 MFMA: the row operand is held as (row = lane % 16, k = lane / 16), the column
+// operand as (col = lane % 16, k = lane / 16); the result register v of a lane holds column
+// lane % 16 and the row given by row_of().
+template <class T> struct Mfma;
+template <> struct Mfma<double> {
+    using vec = double4_t;
+    static __device__ __forceinline__ vec mac(double rowop, double colop, vec c) {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(rowop, colop, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int row_of(int lane, int v) { return 4 * v + (lane >> 4); }
+};
+template <> struct Mfma<float> {
+    using vec = float4_t;
+    static __device__ __forceinline__ vec mac(float rowop, float colop, vec c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(rowop, colop, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int row_of(int lane, int v) { return 4 * (lane >> 4) + v; }
+};
+
+constexpr int kPadMN = 16;   // [k][mn] rows: the four k-rows of a fragment land on distinct banks
+constexpr int kPadK = 1;     // [mn][k] rows: odd row pitch spreads the 16 rows of a fragment
+
+// One operand's slab: MT rows (m or n) by KT contracted indices.
+template <class T, int MT, int KT, int NT, bool KF>
+struct Slab {
+    static constexpr int PER = MT * KT / NT;                       // elements per thread per slab
+    static constexpr int LD = KF ? KT + kPadK : MT + kPadMN;
+    static constexpr int ELEMS = KF ? MT * LD : KT * LD;
+    static_assert(MT * KT % NT == 0, "slab must divide evenly over the workgroup");
+
+    static __device__ __forceinline__ int row(int e) { return KF ? e / KT : e % MT; }
+    static __device__ __forceinline__ int kin(int e) { return KF ? e % KT : e / MT; }
+    static __device__ __forceinline__ int lds_index(int e) { return KF ? row(e) * LD + kin(e) : kin(e) * LD + row(e); }
+    // fragment element for (row r of the slab, k index kk of the slab)
+    static __device__ __forceinline__ int frag_index(int r, int kk) { return KF ? r * LD + kk : kk * LD + r; }
+};
+
+template <class T, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF>
+__global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
+    constexpr int NT = WGM * WGN * 64;
+    constexpr int WT_M = MT_M / WGM, WT_N = MT_N / WGN;
+    constexpr int FM = WT_M / 16, FN = WT_N / 16;
+    using SA = Slab<T, MT_M, KT, NT, AKF>;
+    using SB = Slab<T, MT_N, KT, NT, BKF>;
+    using MF = Mfma<T>;
+    using vec = typename MF::vec;
+    static_assert(KT % 4 == 0 && WT_M % 16 == 0 && WT_N % 16 == 0, "tile shape");
+
+    __shared__ T lds[2 * (SA::ELEMS + SB::ELEMS)];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave % WGM, wn = wave / WGM;
+
+    // ---- which tile: consecutive workgroup ids go round-robin over the 8 XCDs, so give
+    // each XCD one contiguous stretch of the tile order (its own L2 then sees neighbouring
+    // tiles), and walk tiles in bands of 8 tile-rows.
+    int64_t lid = blockIdx.x;
+    {
+        const int64_t nb = gridDim.x, per = nb / 8;
+        if (lid < per * 8) lid = (lid % 8) * per + lid / 8;
+    }
+    const int64_t tiles_per_h = (int64_t)g.tilesM * g.tilesN;
+    const int64_t h = lid / tiles_per_h;
+    const int t = (int)(lid - h * tiles_per_h);
+    constexpr int BAND = 8;
+    const int band = t / (BAND * g.tilesN);
+    const int first_m = band * BAND;
+    const int band_rows = min(BAND, g.tilesM - first_m);
+    const int in_band = t - band * BAND * g.tilesN;
+    const int tm = first_m + in_band % band_rows;
+    const int tn = in_band / band_rows;
+    const int64_t m0 = (int64_t)tm * MT_M, n0 = (int64_t)tn * MT_N;
+
+    // ---- hyper index -> base offsets (Eq. case2: an independent product per value of H)
+    int64_t hA = 0, hB = 0, hD = 0;
+    {
+        int64_t rem = h;
+        for (int i = 0; i < g.nH; ++i) {
+            const int64_t q = rem / g.hExt[i], idx = rem - q * g.hExt[i];
+            rem = q;
+            hA += idx * g.hSA[i];
+            hB += idx * g.hSB[i];
+            hD += idx * g.hSD[i];
+        }
+    }
+    const T* __restrict__ A = (const T*)g.A + hA;
+    const T* __restrict__ B = (const T*)g.B + hB;
+
+    // ---- loop-invariant part of the gather: this thread's row offsets and masks
+    int64_t offA[SA::PER], offB[SB::PER];
+    bool okA[SA::PER], okB[SB::PER];
+#pragma unroll
+    for (int i = 0; i < SA::PER; ++i) {
+        const int r = SA::row(tid + i * NT);
+        offA[i] = g.oAM[m0 + r];
+        okA[i] = m0 + r < g.sizeM;
+    }
+#pragma unroll
+    for (int i = 0; i < SB::PER; ++i) {
+        const int r = SB::row(tid + i * NT);
+        offB[i] = g.oBN[n0 + r];
+        okB[i] = n0 + r < g.sizeN;
+    }
+
+    T ra[SA::PER], rb[SB::PER];
+    auto gather = [&](int kt) {
+        const int64_t k0 = (int64_t)kt * KT;
+        const int64_t kleft = g.sizeK - k0;
+#pragma unroll
+        for (int i = 0; i < SA::PER; ++i) {
+            const int kk = SA::kin(tid + i * NT);
+            const T v = A[offA[i] + g.oAK[k0 + kk]];
+            ra[i] = (okA[i] && kk < kleft) ? v : T(0);
+        }
+#pragma unroll
+        for (int i = 0; i < SB::PER; ++i) {
+            const int kk = SB::kin(tid + i * NT);
+            const T v = B[offB[i] + g.oBK[k0 + kk]];
+            rb[i] = (okB[i] && kk < kleft) ? v : T(0);
+        }
+    };
+    auto stage = [&](int buf) {
+        T* sa = lds + buf * (SA::ELEMS + SB::ELEMS);
+        T* sb = sa + SA::ELEMS;
+#pragma unroll
+        for (int i = 0; i < SA::PER; ++i) sa[SA::lds_index(tid + i * NT)] = ra[i];
+#pragma unroll
+        for (int i = 0; i < SB::PER; ++i) sb[SB::lds_index(tid + i * NT)] = rb[i];
+    };
+
+    vec acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j] = vec{0, 0, 0, 0};
+
+    const int fr = lane & 15, fq = lane >> 4;
+    auto compute = [&](int buf) {
+        const T* sa = lds + buf * (SA::ELEMS + SB::ELEMS);
+        const T* sb = sa + SA::ELEMS;
+#pragma unroll
+        for (int ks = 0; ks < KT; ks += 4) {
+            T fa[FM], fb[FN];
+#pragma unroll
+            for (int i = 0; i < FM; ++i) fa[i] = sa[SA::frag_index(wm * WT_M + i * 16 + fr, ks + fq)];
+#pragma unroll
+            for (int j = 0; j < FN; ++j) fb[j] = sb[SB::frag_index(wn * WT_N + j * 16 + fr, ks + fq)];
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = DNF ? MF::mac(fa[i], fb[j], acc[i][j])     // rows = m, lanes along n
+                                    : MF::mac(fb[j], fa[i], acc[i][j]);    // rows = n, lanes along m
+        }
+    };
+
+    // ---- main loop: gather slab kt+1 into registers while the MFMAs run on slab kt
+    const int nk = g.tilesK;
+    gather(0);
+    stage(0);
+    __syncthreads();
+    int buf = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+        const bool more = kt + 1 < nk;
+        if (more) gather(kt + 1);
+        compute(buf);
+        if (more) stage(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    // ---- epilogue: D = alpha * acc + beta * C, scattered through D's offset tables
+    const T alpha = (T)g.s.alpha_re, beta = (T)g.s.beta_re;
+    const T* __restrict__ C = (const T*)g.C + hD;
+    T* __restrict__ D = (T*)g.D + hD;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int rr = MF::row_of(lane, v);
+                const int ml = wm * WT_M + i * 16 + (DNF ? rr : fr);
+                const int nl = wn * WT_N + j * 16 + (DNF ? fr : rr);
+                if (m0 + ml < g.sizeM && n0 + nl < g.sizeN) {
+                    const int64_t off = g.oDM[m0 + ml] + g.oDN[n0 + nl];
+                    T d = alpha * acc[i][j][v];
+                    if (g.read_c) d += beta * C[off];
+                    D[off] = d;
+                }
+            }
+}
+
+// ---- instantiation table ------------------------------------------------------------------
+struct Shape {
+    int mt_m, mt_n, kt, wgm, wgn;
+};
+constexpr Shape kShapes[] = {
+    {256, 128, 16, 4, 2},
+    {128, 128, 16, 2, 2},
+    {64, 64, 16, 2, 2},
+    {32, 32, 16, 2, 2},
+};
+constexpr int kNumShapes = sizeof(kShapes) / sizeof(kShapes[0]);
+
+template <class T, int S, bool AKF, bool BKF, bool DNF>
+hipError_t launch_one(const GettArgs& a, int64_t blocks, hipStream_t st) {
+    constexpr Shape s = kShapes[S];
+    gett_kernel<T, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF>
+        <<<dim3((unsigned)blocks), dim3(s.wgm * s.wgn * 64), 0, st>>>(a);
+    return hipGetLastError();
+}
+
+template <class T, int S>
+hipError_t launch_flags(bool akf, bool bkf, bool dnf, const GettArgs& a, int64_t blocks, hipStream_t st) {
+    const int f = (akf ? 4 : 0) | (bkf ? 2 : 0) | (dnf ? 1 : 0);
+    switch (f) {
+        case 0: return launch_one<T, S, false, false, false>(a, blocks, st);
+        case 1: return launch_one<T, S, false, false, true>(a, blocks, st);
+        case 2: return launch_one<T, S, false, true, false>(a, blocks, st);
+        case 3: return launch_one<T, S, false, true, true>(a, blocks, st);
+        case 4: return launch_one<T, S, true, false, false>(a, blocks, st);
+        case 5: return launch_one<T, S, true, false, true>(a, blocks, st);
+        case 6: return launch_one<T, S, true, true, false>(a, blocks, st);
+        default: return launch_one<T, S, true, true, true>(a, blocks, st);
+    }
+}
+
+template <class T>
+hipError_t launch_shape(int variant, bool akf, bool bkf, bool dnf, const GettArgs& a, int64_t blocks, hipStream_t st) {
+    switch (variant) {
+        case 0: return launch_flags<T, 0>(akf, bkf, dnf, a, blocks, st);
+        case 1: return launch_flags<T, 1>(akf, bkf, dnf, a, blocks, st);
+        case 2: return launch_flags<T, 2>(akf, bkf, dnf, a, blocks, st);
+        case 3: return launch_flags<T, 3>(akf, bkf, dnf, a, blocks, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+int gett_num_variants(int dtype) { return (dtype == TCX_F64 || dtype == TCX_F32) ? kNumShapes : 0; }
+
+GettVariant gett_variant(int, int variant) {
+    const Shape s = kShapes[variant];
+    return {s.mt_m, s.mt_n, s.kt, s.wgm * s.wgn * 64};
+}
+
+int launch_gett(int dtype, int variant, bool a_kf, bool b_kf, bool d_nf, const GettArgs& args, void* stream,
+                int64_t* grid, int* block) {
+    if (variant < 0 || variant >= kNumShapes) return (int)hipErrorInvalidValue;
+    const int64_t blocks = (int64_t)args.tilesM * args.tilesN * args.sizeH;
+    *grid = blocks;
+    *block = kShapes[variant].wgm * kShapes[variant].wgn * 64;
+    if (blocks <= 0 || blocks > 0x7fffffff) return (int)hipErrorInvalidConfiguration;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == TCX_F64) return (int)launch_shape<double>(variant, a_kf, b_kf, d_nf, args, blocks, st);
+    if (dtype == TCX_F32) return (int)launch_shape<float>(variant, a_kf, b_kf, d_nf, args, blocks, st);
+    return (int)hipErrorInvalidValue;
+}
+
+}  // namespace tcx

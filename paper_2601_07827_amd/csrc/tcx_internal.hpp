@@ -1,0 +1,103 @@
+// Internal declarations of libtcx: the result of the index analysis, the kernel argument
+// blocks, and the launch entry points each kernel file exports to the API layer.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "tcx.h"
+
+namespace tcx {
+
+// One fused mode of a label group.  A stride is 0 where the tensor does not carry the mode
+// (paper, Sec. "Algorithm Structure": strides of absent indices are set to zero).
+struct Mode {
+    int64_t extent;
+    int64_t sA, sB, sD;
+};
+
+struct TensorDesc {
+    int32_t dtype = 0;
+    std::vector<int64_t> extent, stride;
+};
+
+// Result of validation + classification + merging + fusion + sorting.
+struct Analysis {
+    int32_t dtype = 0;
+    int32_t opA = 0, opB = 0, opC = 0;
+    std::vector<Mode> H, M, N, K;           // fastest mode first
+    int64_t sizeH = 1, sizeM = 1, sizeN = 1, sizeK = 1;
+    bool a_k_fastest = false;               // A's smallest |stride| over M and K modes is a K mode
+    bool b_k_fastest = false;
+    bool d_n_fastest = false;               // D's smallest |stride| over M and N modes is an N mode
+    int32_t path = TCX_PATH_GENERIC;
+    int32_t variant = 0;
+};
+
+// Host part of the planner (analyser.cpp).  Pure host code: no HIP calls.
+tcx_error_t analyse(const TensorDesc& A, const int64_t* labA, const TensorDesc& B, const int64_t* labB,
+                    const TensorDesc& C, const int64_t* labC, const TensorDesc& D, const int64_t* labD,
+                    int opA, int opB, int opC, int opD, int precision, Analysis* out);
+
+// offsets[g] = sum_i idx_i * stride_i for the linear index g over `modes` (first mode fastest);
+// which: 0 = A, 1 = B, 2 = D.  The table is padded with zeros up to `padded` entries.
+std::vector<int64_t> offset_table(const std::vector<Mode>& modes, int which, int64_t padded);
+
+// ---- kernel argument blocks (plain data, passed by value) ------------------------------
+constexpr int kMaxHModes = 8;      // hyper modes decoded inside the tiled kernels
+constexpr int kMaxGenericModes = 32;
+
+struct Scalars {
+    double alpha_re, alpha_im, beta_re, beta_im;
+};
+
+// Tiled (GETT) kernels.  Offsets are in elements.  Tables are padded to a whole number of
+// tiles with entries that address a valid element, so unmasked loads stay in bounds.
+struct GettArgs {
+    const void* A;
+    const void* B;
+    const void* C;
+    void* D;
+    const int64_t* oAM;  // [tilesM * MT_M]
+    const int64_t* oAK;  // [tilesK * KT]
+    const int64_t* oBN;  // [tilesN * MT_N]
+    const int64_t* oBK;  // [tilesK * KT]
+    const int64_t* oDM;  // [tilesM * MT_M]
+    const int64_t* oDN;  // [tilesN * MT_N]
+    int64_t sizeM, sizeN, sizeK, sizeH;
+    int32_t tilesM, tilesN, tilesK;
+    int32_t nH;
+    int64_t hExt[kMaxHModes], hSA[kMaxHModes], hSB[kMaxHModes], hSD[kMaxHModes];
+    Scalars s;
+    int32_t opA, opB, opC;
+    int32_t read_c;      // beta != 0
+};
+
+struct GettVariant {
+    int mt_m, mt_n, kt, threads;
+};
+
+// Generic fallback: every mode of D (H, M, N together, D-fastest first) and every K mode.
+struct GenericArgs {
+    const void* A;
+    const void* B;
+    const void* C;
+    void* D;
+    int32_t nD, nK;
+    int64_t dExt[kMaxGenericModes], dSA[kMaxGenericModes], dSB[kMaxGenericModes], dSD[kMaxGenericModes];
+    int64_t kExt[kMaxGenericModes], kSA[kMaxGenericModes], kSB[kMaxGenericModes];
+    int64_t sizeD, sizeK;
+    Scalars s;
+    int32_t opA, opB, opC;
+    int32_t read_c, read_ab;
+};
+
+// Launchers (defined in the .hip files).  `stream` is a hipStream_t.  Return a hipError_t.
+int launch_generic(int dtype, const GenericArgs& args, void* stream, int64_t* grid, int* block);
+
+int gett_num_variants(int dtype);
+GettVariant gett_variant(int dtype, int variant);
+int launch_gett(int dtype, int variant, bool a_kf, bool b_kf, bool d_nf, const GettArgs& args, void* stream,
+                int64_t* grid, int* block);
+
+}  // namespace tcx

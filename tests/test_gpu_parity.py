@@ -1,0 +1,106 @@
+"""Parity of the HIP paths with the CPU oracle, element by element, through the C-ABI.
+
+Tolerance (stated by the benchmark spec): max over D of |d_gpu - d_truth| / (|alpha| sum|a||b| + |beta||c|)
+<= 1e-12 (fp64, complex128), 1e-5 (fp32).  Integer-valued and permutation-only cases must
+match bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from helpers import TOLERANCE, gaps_untouched, normalised_error, random_problem, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+GENERIC, GETT = 0, 1
+
+
+def _paths_for(p):
+    from gpu_helpers import DT  # noqa: F401
+    paths = [(GENERIC, None)]
+    if p.dtype in ("f64", "f32"):
+        paths += [(GETT, v) for v in range(4)]
+    return paths
+
+
+def _check(p, a, b, c, path, variant, exact=False, truth=None, S=None):
+    from gpu_helpers import run_gpu, say
+    say("%s path=%s variant=%s exact=%s" % (p.name, path, variant, exact))
+    if truth is None:
+        truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+    got = run_gpu(p, a, b, c, force_path=path, variant=variant)
+    assert gaps_untouched(p, c, got), "elements outside (extents, strides) of D were modified"
+    if exact:
+        assert np.array_equal(W.strided_view(got, p.D), W.strided_view(truth, p.D))
+    else:
+        err = normalised_error(p, got, truth, S, c)
+        assert err <= TOLERANCE[p.dtype], "normalised error %.3e" % err
+
+
+@pytest.mark.parametrize("p", W.configs_reduced(), ids=lambda p: p.name)
+def test_reduced_configs_all_paths(p):
+    a, b, c = W.make_operands(p)
+    truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+    for path, variant in _paths_for(p):
+        _check(p, a, b, c, path, variant, truth=truth, S=S)
+    # the plan's own choice
+    _check(p, a, b, c, None, None, truth=truth, S=S)
+
+
+@pytest.mark.parametrize("p", W.configs_reduced(), ids=lambda p: p.name)
+def test_reduced_configs_integer_inputs_bit_exact(p):
+    a, b, c = W.make_operands(p, "ints")
+    p2 = W.Problem(p.name + "_ints", p.dtype, p.A, p.B, p.D, alpha=2.0, beta=(-1.0 if p.beta != 0 else 0.0),
+                   opA=p.opA, opB=p.opB, opC=p.opC, seed=p.seed)
+    truth, S = run_oracle(p2, a, b, c, oracle.MODE_TRUTH, want_S=True)
+    for path, variant in _paths_for(p2) + [(None, None)]:
+        _check(p2, a, b, c, path, variant, exact=True, truth=truth, S=S)
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128"])
+def test_random_problems(dtype):
+    rng = np.random.default_rng(31337)
+    for i in range(40):
+        p = random_problem(rng, dtype, max_group=3, max_extent=6, allow_neg=(i % 3 == 0), name="rand%d_%s" % (i, dtype))
+        a, b, c = W.make_operands(p)
+        truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+        paths = [(GENERIC, None)]
+        if dtype != "c128":
+            paths.append((GETT, 2 + i % 2))
+        for path, variant in paths:
+            _check(p, a, b, c, path, variant, truth=truth, S=S)
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128"])
+def test_one_hot_operand_is_a_bit_exact_permutation(dtype):
+    ext = dict(m0=7, m1=9, k0=11, k1=5, n0=11, n1=5)
+    A = W.tensor(["m0", "k1", "m1", "k0"], ext, memory_order=["k0", "m1", "m0", "k1"])
+    B = W.tensor(["n1", "k0", "k1", "n0"], ext)
+    D = W.tensor(["n0", "m1", "n1", "m0"], ext, memory_order=["m0", "n1", "n0", "m1"])
+    p = W.Problem("delta_" + dtype, dtype, A, B, D, alpha=1.0, beta=0.0)
+    a = W.fill(p.A, 11, 0, p.np_dtype)
+    b = np.zeros(B.size, dtype=p.np_dtype)
+    vb = W.strided_view(b, B)
+    for k0 in range(11):
+        for k1 in range(5):
+            vb[k1, k0, k1, k0] = 1.0
+    c = np.full(D.size, np.nan, dtype=p.np_dtype)
+    for path, variant in _paths_for(p):
+        _check(p, a, b, c, path, variant, exact=True)
+
+
+FULL = [W.config1(), W.config3(), W.config3(d_layout="R2"), W.config4(), W.config4(h_slowest=True), W.config5()]
+
+
+@pytest.mark.parametrize("p", FULL, ids=lambda p: p.name)
+def test_full_size_configs(p):
+    """Configurations 1, 3, 4, 5 at their full sizes, plan's own path, whole output compared."""
+    a, b, c = W.make_operands(p)
+    _check(p, a, b, c, None, None)
+
+
+@pytest.mark.parametrize("p", [W.config1(), W.config3(), W.config5()], ids=lambda p: p.name)
+def test_full_size_integer_inputs_bit_exact(p):
+    a, b, c = W.make_operands(p, "ints")
+    p2 = W.Problem(p.name + "_ints", p.dtype, p.A, p.B, p.D, alpha=2.0, beta=(0.5 if p.beta != 0 else 0.0), seed=p.seed)
+    _check(p2, a, b, c, None, None, exact=True)

@@ -455,7 +455,8 @@ def test_validation_classes():
     assert oracle.validate(A, B, D, D) == oracle.V_OK
     bad = ([3, 6], [1, 3], [1, 3])                                    # k has extent 6 in A
     assert oracle.validate(bad, B, D, D) == oracle.V_EXTENT_MISMATCH
-    assert oracle.validate(A, B, t("nm"), D) == oracle.V_CD_MISMATCH    # C permuted
+    assert oracle.validate(A, B, t("nm"), D) == oracle.V_CD_MISMATCH    # C transposed in memory
+    assert oracle.validate(A, B, t("nm", strides=dict(m=1, n=3)), D) == oracle.V_OK   # same layout, modes listed in another order
     assert oracle.validate(A, B, t("mn", strides=dict(m=1, n=4)), D) == oracle.V_CD_MISMATCH
     assert oracle.validate(A, B, t("mn", strides=dict(m=1, n=2)), t("mn", strides=dict(m=1, n=2))) == oracle.V_D_ALIASING
     assert oracle.validate(A, B, t("mn", strides=dict(m=0, n=1)), t("mn", strides=dict(m=0, n=1))) == oracle.V_D_ALIASING

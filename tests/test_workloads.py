@@ -1,0 +1,47 @@
+"""The input generators: determinism, ranges, and the torch twin of the numpy generator."""
+import numpy as np
+import torch
+
+import workloads as W
+
+
+def test_uniform_is_deterministic_in_range_and_exact():
+    idx = np.arange(100000, dtype=np.uint64)
+    u = W.uniform_pm1(7, 1, idx, np.float64)
+    assert np.array_equal(u, W.uniform_pm1(7, 1, idx, np.float64))
+    assert u.min() >= -1.0 and u.max() < 1.0 and abs(u.mean()) < 0.01
+    assert not np.array_equal(u, W.uniform_pm1(8, 1, idx, np.float64))
+    assert not np.array_equal(u, W.uniform_pm1(7, 2, idx, np.float64))
+    f = W.uniform_pm1(7, 1, idx, np.float32)
+    assert f.dtype == np.float32 and f.min() >= -1.0 and f.max() < 1.0
+
+
+def test_torch_generator_matches_numpy_bit_for_bit():
+    for start, count in ((0, 5000), (123456789012, 4097)):
+        idx = np.arange(start, start + count, dtype=np.uint64)
+        for tdt, ndt in ((torch.float64, np.float64), (torch.float32, np.float32)):
+            t = W.torch_uniform_pm1(W.BASE_SEED + 2, W.TAG_A, start, count, tdt, "cpu").numpy()
+            assert np.array_equal(t, W.uniform_pm1(W.BASE_SEED + 2, W.TAG_A, idx, ndt))
+
+
+def test_values_follow_logical_index_not_memory_order():
+    e = dict(a=3, b=4, c=5)
+    t1 = W.tensor("abc", e)
+    t2 = W.tensor("abc", e, memory_order="cab")
+    v1 = W.strided_view(W.fill(t1, 5, 0, np.float64), t1)
+    v2 = W.strided_view(W.fill(t2, 5, 0, np.float64), t2)
+    assert np.array_equal(v1, v2)
+
+
+def test_config_shapes_match_the_stated_sizes():
+    sizes = [p.sizes() for p in W.configs_full()]
+    assert sizes[0] == (1, 576, 576, 576)
+    assert sizes[1] == (1, 36864, 4096, 36864)
+    assert sizes[2] == (1, 1961, 61, 1189)
+    assert sizes[3] == (512, 96, 96, 96)
+    assert sizes[4] == (1, 1024, 1024, 1024)
+    assert W.config2().real_flops() == 2 * 36864 * 4096 * 36864
+    assert W.config2().algorithmic_bytes() == 14495514624
+    assert W.config4().real_flops() == 3623878656
+    assert W.config3().D.size == 2 * 37 * 53 * 61 and W.config3().D.strides == (122, 4514, 2)
+    assert W.config3().A.strides == (2173, 80401, 1, 41)

@@ -324,3 +324,36 @@ def configs_reduced() -> List[Problem]:
     return [config1(12), config2(v=20, o=7), config3(0.45), config3(0.45, "R2"), config4(h=6, n=20),
             config4(h=5, n=18, h_slowest=True), config5(extent=3, nshared=3, nfree=3),
             config5(extent=4, nshared=3, nfree=3)]
+
+
+# --------------------------------------------------------------------------------------
+# the same generator on a torch device (for tensors too large to build on the host)
+# --------------------------------------------------------------------------------------
+def _as_i64(u: int) -> int:
+    u &= 0xFFFFFFFFFFFFFFFF
+    return u - (1 << 64) if u >= (1 << 63) else u
+
+
+def torch_uniform_pm1(seed: int, tag: int, start: int, count: int, dtype, device, out=None):
+    """uniform_pm1(seed, tag, arange(start, start+count)) as a torch tensor on `device`,
+    bit-identical to the numpy version (wrapping 64-bit integer arithmetic, exact conversion)."""
+    import torch
+    assert dtype in (torch.float64, torch.float32)
+    key = _as_i64(((int(seed) * 8 + int(tag) + 1) & 0xFFFFFFFFFFFFFFFF) * 0x9E3779B97F4A7C15)
+    if out is None:
+        out = torch.empty(count, dtype=dtype, device=device)
+    chunk = 1 << 26
+    for lo in range(0, count, chunk):
+        n = min(chunk, count - lo)
+        z = torch.arange(start + lo, start + lo + n, dtype=torch.int64, device=device) + key
+
+        def lsr(x, s):
+            return (x >> s) & ((1 << (64 - s)) - 1)
+        z = (z ^ lsr(z, 30)) * _as_i64(0xBF58476D1CE4E5B9)
+        z = (z ^ lsr(z, 27)) * _as_i64(0x94D049BB133111EB)
+        z = z ^ lsr(z, 31)
+        if dtype == torch.float64:
+            out[lo:lo + n] = lsr(z, 11).to(torch.float64) * 2.0 ** -52 - 1.0
+        else:
+            out[lo:lo + n] = lsr(z, 40).to(torch.float32) * 2.0 ** -23 - 1.0
+    return out
