@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the contraction hot path on ONE MI355X.
+
+A "step" is one execution of the planned contraction over resident device buffers
+(default workload: configuration 2, the fp64 particle-particle ladder
+D[a,b,i,j] += sum_{c,d} V[a,b,c,d] T[c,d,i,j], v = 192, o = 64: 1.1133e13 flop).
+Prints ONE JSON line: whole-job GFLOP/s, the dominant kernel's roofline figure measured
+with HIP events inside the timed region, and the CPU oracle timed on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg3|cfg4|cfg5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads as W  # noqa: E402
+
+PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3, "c128": 78.6}     # MI355X dense matrix peaks
+PEAK_HBM_GBS = 8000.0
+DT = {"f32": 0, "f64": 1, "c128": 3}
+
+
+def make_problem(name: str) -> W.Problem:
+    return {"cfg1": W.config1, "cfg2": W.config2, "cfg3": W.config3, "cfg4": W.config4, "cfg5": W.config5}[name]()
+
+
+def device_operands(p: W.Problem, torch):
+    """Inputs resident in HBM.  Config 2 is generated on the device (10.9 GB for V) with the
+    torch twin of the counter-based generator; the small configurations come from the host."""
+    dev = "cuda:0"
+    if p.name.startswith("cfg2"):
+        a = W.torch_uniform_pm1(p.seed, W.TAG_A, 0, p.A.size, torch.float64, dev)
+        b = W.torch_uniform_pm1(p.seed, W.TAG_B, 0, p.B.size, torch.float64, dev)
+        d = W.torch_uniform_pm1(p.seed, W.TAG_C, 0, p.D.size, torch.float64, dev)
+        return a, b, d, None
+    ha, hb, hc = W.make_operands(p)
+    return torch.from_numpy(ha).to(dev), torch.from_numpy(hb).to(dev), torch.from_numpy(hc).to(dev), (ha, hb, hc)
+
+
+def cpu_baseline(p: W.Problem):
+    """The oracle's storage-precision loop nest on the host cores, on a bounded sample."""
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import oracle
+    from helpers import run_oracle
+    if p.name.startswith("cfg2"):
+        sm, sn = 4096, 192
+        sub, a, b, c = W.config2_sample(p, np.arange(sm), np.arange(sn))
+        sample = "rows m<%d of V, columns n<%d of T, all %d contracted terms (%.2e of %.2e flop)" % (
+            sm, sn, p.sizes()[3], sub.real_flops(), p.real_flops())
+    else:
+        sub = p
+        a, b, c = W.make_operands(p)
+        sample = "the whole workload"
+    t0 = time.perf_counter()
+    run_oracle(sub, a, b, c, oracle.MODE_TIMED)
+    dt = time.perf_counter() - t0
+    return {"value": sub.real_flops() / dt / 1e9, "unit": "GFLOP/s", "cores": oracle.max_threads(), "kind": "oracle",
+            "sample": sample, "seconds": dt}
+
+
+def parity_after_run(p: W.Problem, dD, steps_done: int, torch):
+    """Sampled check of the timed output of config 2 against the oracle: with beta = 1 and D
+    updated in place, after s steps D = D0 + s * (V T) exactly in exact arithmetic."""
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import oracle
+    from helpers import run_oracle
+    _, M, N, K = p.sizes()
+    rng = np.random.default_rng(p.seed)
+    m_idx = np.unique(np.concatenate([[0, 1, 255, 256, 257, M - 1], rng.integers(0, M, 26)]))
+    n_idx = np.unique(np.concatenate([[0, 127, 128, N - 1], rng.integers(0, N, 12)]))
+    sub, a, b, c = W.config2_sample(p, m_idx, n_idx)
+    one = W.Problem("ab", "f64", sub.A, sub.B, sub.D, alpha=1.0, beta=0.0)
+    ab, S = run_oracle(one, a, b, c, oracle.MODE_TRUTH, want_S=True)
+    expect = c + steps_done * ab
+    lin = (m_idx[:, None] + M * n_idx[None, :]).T.reshape(-1)          # column-major over (x, y)
+    got = dD[torch.from_numpy(lin.astype(np.int64)).to(dD.device)].cpu().numpy()
+    err = np.abs(got - expect) / (steps_done * S + np.abs(c))
+    return {"samples": int(lin.size), "max_normalised_error": float(err.max()), "tolerance": 1e-12,
+            "ok": bool(err.max() <= 1e-12)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--variant", type=int, default=None, help="force a tiled-kernel instantiation")
+    ap.add_argument("--path", type=int, default=None, help="force a kernel path (0 generic, 1 tiled MFMA)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference kernel for scaling rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+
+    import torch
+    import paper_2601_07827_amd as T          # raises if libtcx.so is not built: no fallback
+
+    p = make_problem(args.workload)
+    torch.cuda.set_device(0)
+    dA, dB, dD, _ = device_operands(p, torch)
+    torch.cuda.synchronize()
+
+    h = T.tcx_create_handle()
+    if not T.tcx_handle_has_device(h):
+        sys.exit("bench.py: no gfx950 device")
+    stream = torch.cuda.current_stream()
+    ex = T.tcx_create_executor(h, stream.cuda_stream)
+    ids = W.label_ids(p)
+    infos = [T.tcx_create_tensor_info(h, DT[p.dtype], t.extents, t.strides) for t in (p.A, p.B, p.D)]
+    labs = [[ids[l] for l in t.labels] for t in (p.A, p.B, p.D)]
+    t0 = time.perf_counter()
+    prod = T.tcx_create_product(h, p.opA, infos[0], labs[0], p.opB, infos[1], labs[1], p.opC, infos[2], labs[2],
+                                0, infos[2], labs[2])
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    if args.path is not None:
+        T.tcx_product_set(prod, T.TCX_KEY_FORCE_PATH, args.path)
+    if args.variant is not None:
+        T.tcx_product_set(prod, T.TCX_KEY_VARIANT, args.variant)
+    item = dD.element_size()
+    pA, pB, pD = (t.data_ptr() + s.base * item for t, s in ((dA, p.A), (dB, p.B), (dD, p.D)))
+
+    def step():
+        T.tcx_execute_product(prod, ex, DT[p.dtype], p.alpha, pA, pB, p.beta, pD, pD)
+
+    if args.copy_probe:
+        src = torch.ones(1 << 27, dtype=torch.float64, device="cuda:0")     # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for e0, e1 in events:                       # HIP events on the stream the kernel is launched on
+        e0.record(stream)
+        step()
+        e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = [e0.elapsed_time(e1) for e0, e1 in events]
+    ms_per_step = wall * 1e3 / args.steps
+    flops = p.real_flops()
+    value = flops / (ms_per_step * 1e-3) / 1e9
+
+    avg_kernel_s = float(np.mean(kern_ms)) * 1e-3
+    ai = flops / p.algorithmic_bytes()
+    ridge = PEAK_TFLOPS[p.dtype] * 1e12 / (PEAK_HBM_GBS * 1e9)
+    if ai >= ridge:
+        achieved = flops / avg_kernel_s / 1e12
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[p.dtype], "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_TFLOPS[p.dtype], "traffic": None}
+    else:
+        achieved = p.algorithmic_bytes() / avg_kernel_s / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": achieved / PEAK_HBM_GBS, "traffic": None}
+    roofline["kernel_ms_avg"] = float(np.mean(kern_ms))
+    roofline["kernel_ms_min"] = float(np.min(kern_ms))
+
+    cfg = {"workload": p.name, "sizes_HMNK": list(p.sizes()), "alpha": complex(p.alpha).real, "beta": complex(p.beta).real,
+           "path": T.tcx_product_get(prod, T.TCX_KEY_PATH), "variant": T.tcx_product_get(prod, T.TCX_KEY_VARIANT),
+           "tile": [T.tcx_product_get(prod, k) for k in (T.TCX_KEY_TILE_M, T.TCX_KEY_TILE_N, T.TCX_KEY_TILE_K)],
+           "grid": T.tcx_product_get(prod, T.TCX_KEY_GRID), "plan_ms": plan_ms,
+           "flop_per_step": flops, "algorithmic_bytes_per_step": p.algorithmic_bytes()}
+
+    out = {"metric": "contraction GFLOP/s (fp64/fp32/c128) and % MFMA peak; GB/s for low-AI shapes",
+           "value": value, "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": p.dtype, "data": "synthetic", "config": cfg, "roofline": roofline}
+    if p.name.startswith("cfg2"):
+        out["parity_after_run"] = parity_after_run(p, dD, args.warmup + args.steps, torch)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(p)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

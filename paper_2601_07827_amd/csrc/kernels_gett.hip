@@ -51,6 +51,8 @@ struct Slab {
     static constexpr int LD = KF ? KT + kPadK : MT + kPadMN;
     static constexpr int ELEMS = KF ? MT * LD : KT * LD;
     static_assert(MT * KT % NT == 0, "slab must divide evenly over the workgroup");
+    // lanes run along the rows and a wave covers whole rows' worth: one k index per wave
+    static constexpr bool UNIFORM_K = !KF && MT % 64 == 0 && (NT % MT == 0 || MT % NT == 0);
 
     static __device__ __forceinline__ int row(int e) { return KF ? e / KT : e % MT; }
     static __device__ __forceinline__ int kin(int e) { return KF ? e % KT : e / MT; }
@@ -112,38 +114,57 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
     const T* __restrict__ A = (const T*)g.A + hA;
     const T* __restrict__ B = (const T*)g.B + hB;
 
-    // ---- loop-invariant part of the gather: this thread's row offsets and masks
+    // ---- loop-invariant part of the gather: this thread's row offsets.  Rows past the end of
+    // M or N read a valid (padded) table entry; what they accumulate is never stored.
     int64_t offA[SA::PER], offB[SB::PER];
-    bool okA[SA::PER], okB[SB::PER];
+#pragma unroll
+    for (int i = 0; i < SA::PER; ++i) offA[i] = g.oAM[m0 + SA::row(tid + i * NT)];
+#pragma unroll
+    for (int i = 0; i < SB::PER; ++i) offB[i] = g.oBN[n0 + SB::row(tid + i * NT)];
+
+    // Offsets along K come from the tables one slab ahead of the data loads that use them,
+    // so a data load never waits on a table load issued in the same iteration.  Where the
+    // k index is the same for a whole wave it is made scalar, which turns the table read
+    // into a scalar load.
+    const int nk = g.tilesK;
+    unsigned kinA[SA::PER], kinB[SB::PER];       // this thread's k index inside a slab, per element
 #pragma unroll
     for (int i = 0; i < SA::PER; ++i) {
-        const int r = SA::row(tid + i * NT);
-        offA[i] = g.oAM[m0 + r];
-        okA[i] = m0 + r < g.sizeM;
+        kinA[i] = (unsigned)SA::kin(tid + i * NT);
+        if (SA::UNIFORM_K) kinA[i] = __builtin_amdgcn_readfirstlane(kinA[i]);
     }
 #pragma unroll
     for (int i = 0; i < SB::PER; ++i) {
-        const int r = SB::row(tid + i * NT);
-        offB[i] = g.oBN[n0 + r];
-        okB[i] = n0 + r < g.sizeN;
+        kinB[i] = (unsigned)SB::kin(tid + i * NT);
+        if (SB::UNIFORM_K) kinB[i] = __builtin_amdgcn_readfirstlane(kinB[i]);
     }
+    int64_t kA[SA::PER], kB[SB::PER];
+    auto k_offsets = [&](int kt) {
+        const int64_t* __restrict__ ta = g.oAK + (int64_t)min(kt, nk - 1) * KT;
+        const int64_t* __restrict__ tb = g.oBK + (int64_t)min(kt, nk - 1) * KT;
+#pragma unroll
+        for (int i = 0; i < SA::PER; ++i) kA[i] = ta[kinA[i]];
+#pragma unroll
+        for (int i = 0; i < SB::PER; ++i) kB[i] = tb[kinB[i]];
+    };
 
     T ra[SA::PER], rb[SB::PER];
-    auto gather = [&](int kt) {
-        const int64_t k0 = (int64_t)kt * KT;
-        const int64_t kleft = g.sizeK - k0;
+    // Data loads of slab kt; k_offsets(kt) must have been issued before.  Unconditional: the
+    // tables are padded with offsets of valid elements.
+    auto gather = [&]() {
 #pragma unroll
-        for (int i = 0; i < SA::PER; ++i) {
-            const int kk = SA::kin(tid + i * NT);
-            const T v = A[offA[i] + g.oAK[k0 + kk]];
-            ra[i] = (okA[i] && kk < kleft) ? v : T(0);
-        }
+        for (int i = 0; i < SA::PER; ++i) ra[i] = A[offA[i] + kA[i]];
 #pragma unroll
-        for (int i = 0; i < SB::PER; ++i) {
-            const int kk = SB::kin(tid + i * NT);
-            const T v = B[offB[i] + g.oBK[k0 + kk]];
-            rb[i] = (okB[i] && kk < kleft) ? v : T(0);
-        }
+        for (int i = 0; i < SB::PER; ++i) rb[i] = B[offB[i] + kB[i]];
+    };
+    // The last slab of a ragged K holds padded k entries whose (valid, arbitrary) values must
+    // not be summed: zero them after the load.
+    auto mask_last = [&]() {
+        const unsigned kleft = (unsigned)(g.sizeK - (int64_t)(nk - 1) * KT);
+#pragma unroll
+        for (int i = 0; i < SA::PER; ++i) ra[i] = kinA[i] < kleft ? ra[i] : T(0);
+#pragma unroll
+        for (int i = 0; i < SB::PER; ++i) rb[i] = kinB[i] < kleft ? rb[i] : T(0);
     };
     auto stage = [&](int buf) {
         T* sa = lds + buf * (SA::ELEMS + SB::ELEMS);
@@ -180,20 +201,34 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
         }
     };
 
-    // ---- main loop: gather slab kt+1 into registers while the MFMAs run on slab kt
-    const int nk = g.tilesK;
-    gather(0);
+    // ---- main loop: the data loads of slab kt+1 and the table loads of slab kt+2 are in
+    // flight while the MFMAs run on slab kt.  The last two slabs are peeled so that the loop
+    // body is one straight path.
+    const bool ragged_k = g.sizeK % KT != 0;
+    k_offsets(0);
+    gather();
+    k_offsets(1);
+    if (ragged_k && nk == 1) mask_last();
     stage(0);
     __syncthreads();
     int buf = 0;
-    for (int kt = 0; kt < nk; ++kt) {
-        const bool more = kt + 1 < nk;
-        if (more) gather(kt + 1);
+    for (int kt = 0; kt + 2 < nk; ++kt) {
+        gather();                 // slab kt+1
+        k_offsets(kt + 2);
         compute(buf);
-        if (more) stage(buf ^ 1);
+        stage(buf ^ 1);
         __syncthreads();
         buf ^= 1;
     }
+    if (nk >= 2) {
+        gather();                 // slab nk-1
+        compute(buf);
+        if (ragged_k) mask_last();
+        stage(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+    compute(buf);
 
     // ---- epilogue: D = alpha * acc + beta * C, scattered through D's offset tables
     const T alpha = (T)g.s.alpha_re, beta = (T)g.s.beta_re;

@@ -27,29 +27,54 @@ _M1 = np.uint64(0xBF58476D1CE4E5B9)
 _M2 = np.uint64(0x94D049BB133111EB)
 
 
-def mix64(seed: int, tag: int, idx: np.ndarray) -> np.ndarray:
-    """64-bit hash of (seed, tag, idx); idx is an integer array (any shape)."""
+def _mix64_block(key, z):
+    """In place on a uint64 block (fresh pages are expensive on some hosts, so no temporaries
+    beyond one block-sized scratch)."""
+    t = np.empty_like(z)
+    with np.errstate(over="ignore"):
+        z += key
+        np.right_shift(z, np.uint64(30), out=t); z ^= t; z *= _M1
+        np.right_shift(z, np.uint64(27), out=t); z ^= t; z *= _M2
+        np.right_shift(z, np.uint64(31), out=t); z ^= t
+    return z
+
+
+def _hashed(seed: int, tag: int, idx: np.ndarray, out_dtype, finish) -> np.ndarray:
+    """finish(hash block) evaluated block by block over idx; returns an array shaped like idx."""
     with np.errstate(over="ignore"):
         key = np.uint64((int(seed) * 8 + int(tag) + 1) & 0xFFFFFFFFFFFFFFFF) * _GOLD
-        z = idx.astype(np.uint64) + key
-        z = (z ^ (z >> np.uint64(30))) * _M1
-        z = (z ^ (z >> np.uint64(27))) * _M2
-        z = z ^ (z >> np.uint64(31))
-    return z
+    idx = np.asarray(idx)
+    out = np.empty(idx.shape, dtype=out_dtype)
+    flat_in, flat_out = idx.reshape(-1), out.reshape(-1)
+    if flat_in.shape[0] and not np.shares_memory(flat_out, out):
+        raise ValueError("index array must be reshapeable without a copy")
+    block = 1 << 20
+    for lo in range(0, flat_in.shape[0], block):
+        z = flat_in[lo:lo + block].astype(np.uint64)          # a copy
+        flat_out[lo:lo + block] = finish(_mix64_block(key, z))
+    return out
+
+
+def mix64(seed: int, tag: int, idx: np.ndarray) -> np.ndarray:
+    """64-bit hash of (seed, tag, idx); idx is an integer array (any shape)."""
+    return _hashed(seed, tag, idx, np.uint64, lambda h: h)
 
 
 def uniform_pm1(seed: int, tag: int, idx: np.ndarray, dtype) -> np.ndarray:
     """Uniform on [-1, 1): 53 random bits for float64, 24 for float32 (both exact)."""
     dtype = np.dtype(dtype)
     if dtype == np.complex128:
-        re = uniform_pm1(seed, tag, idx.astype(np.uint64) * np.uint64(2), np.float64)
-        im = uniform_pm1(seed, tag, idx.astype(np.uint64) * np.uint64(2) + np.uint64(1), np.float64)
-        return re + 1j * im
-    h = mix64(seed, tag, idx)
+        out = np.empty(np.shape(idx), dtype=np.complex128)
+        two = np.asarray(idx).astype(np.uint64) * np.uint64(2)
+        out.real = uniform_pm1(seed, tag, two, np.float64)
+        out.imag = uniform_pm1(seed, tag, two + np.uint64(1), np.float64)
+        return out
     if dtype == np.float64:
-        return (h >> np.uint64(11)).astype(np.float64) * 2.0 ** -52 - 1.0
+        return _hashed(seed, tag, idx, np.float64,
+                       lambda h: (h >> np.uint64(11)).astype(np.float64) * 2.0 ** -52 - 1.0)
     if dtype == np.float32:
-        return ((h >> np.uint64(40)).astype(np.float32) * np.float32(2.0 ** -23) - np.float32(1.0)).astype(np.float32)
+        return _hashed(seed, tag, idx, np.float32,
+                       lambda h: (h >> np.uint64(40)).astype(np.float32) * np.float32(2.0 ** -23) - np.float32(1.0))
     raise ValueError(dtype)
 
 
@@ -357,3 +382,28 @@ def torch_uniform_pm1(seed: int, tag: int, start: int, count: int, dtype, device
         else:
             out[lo:lo + n] = lsr(z, 40).to(torch.float32) * 2.0 ** -23 - 1.0
     return out
+
+
+# --------------------------------------------------------------------------------------
+# sampled sub-problems of config 2 (the full tensors never exist on the host)
+# --------------------------------------------------------------------------------------
+def config2_sample(p: Problem, m_idx: np.ndarray, n_idx: np.ndarray):
+    """Rows m_idx of V (as an |m_idx| x |K| matrix), columns n_idx of T and the matching
+    entries of the initial D of a config-2 style problem, generated straight from the
+    counter-based generator.  Returns (sub_problem, bufA, bufB, bufC); the sub-problem is
+    D_s[x,y] = alpha * sum_k A_s[x,k] B_s[k,y] + beta * C_s[x,y], column-major, k running
+    over the fused (c,d) index in V's order."""
+    _, M, N, K = p.sizes()
+    m_idx = np.asarray(m_idx, dtype=np.uint64)
+    n_idx = np.asarray(n_idx, dtype=np.uint64)
+    k = np.arange(K, dtype=np.uint64)
+    # logical linear indices: V[m, k] -> m + M*k ; T[k, n] -> k + K*n ; D[m, n] -> m + M*n.
+    # Index arrays are built slow-index-first so that their C-order flattening is the
+    # column-major buffer of the sub-tensor.
+    a = uniform_pm1(p.seed, TAG_A, np.uint64(M) * k[:, None] + m_idx[None, :], np.float64).reshape(-1)
+    b = uniform_pm1(p.seed, TAG_B, np.uint64(K) * n_idx[:, None] + k[None, :], np.float64).reshape(-1)
+    c = uniform_pm1(p.seed, TAG_C, np.uint64(M) * n_idx[:, None] + m_idx[None, :], np.float64).reshape(-1)
+    e = dict(x=len(m_idx), y=len(n_idx), k=K)
+    sub = Problem(p.name + "_sample", "f64", tensor("xk", e), tensor("ky", e), tensor("xy", e),
+                  alpha=p.alpha, beta=p.beta, seed=p.seed)
+    return sub, a, b, c
