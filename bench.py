@@ -26,6 +26,10 @@ import workloads as W  # noqa: E402
 
 PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3, "c128": 78.6}     # MI355X dense matrix peaks
 PEAK_HBM_GBS = 8000.0
+# L2 <-> fabric bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
+# command, scaled by a streaming probe kernel (profiles/gett_f64_256x128x16_cfg2.md); keyed
+# by (workload, path, variant) so a figure is only reported for the kernel it was taken on.
+MEASURED_TRAFFIC_BYTES = {("cfg2_f64_ppladder_v192_o64", 1, 0): 110.06e9 + 1.208e9}
 DT = {"f32": 0, "f64": 1, "c128": 3}
 
 
@@ -98,7 +102,7 @@ def main():
     ap.add_argument("--variant", type=int, default=None, help="force a tiled-kernel instantiation")
     ap.add_argument("--path", type=int, default=None, help="force a kernel path (0 generic, 1 tiled MFMA)")
     ap.add_argument("--copy-probe", action="store_true",
-                    help="also run one plain 1 GiB device copy (reference kernel for scaling rocprofv3 byte counters)")
+                    help="also run one plain 1 GiB streaming kernel (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -134,9 +138,9 @@ def main():
         T.tcx_execute_product(prod, ex, DT[p.dtype], p.alpha, pA, pB, p.beta, pD, pD)
 
     if args.copy_probe:
-        src = torch.ones(1 << 27, dtype=torch.float64, device="cuda:0")     # 1 GiB read + 1 GiB written
+        src = torch.ones(1 << 27, dtype=torch.float64, device="cuda:0")     # fill kernel: 1 GiB written
         dst = torch.empty_like(src)
-        dst.copy_(src)
+        torch.add(src, 1.0, out=dst)                                        # 1 GiB read + 1 GiB written
         torch.cuda.synchronize()
         del src, dst
     for _ in range(args.warmup):
@@ -166,6 +170,8 @@ def main():
         achieved = p.algorithmic_bytes() / avg_kernel_s / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": achieved / PEAK_HBM_GBS, "traffic": None}
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(
+        (p.name, T.tcx_product_get(prod, T.TCX_KEY_PATH), T.tcx_product_get(prod, T.TCX_KEY_VARIANT)))
     roofline["kernel_ms_avg"] = float(np.mean(kern_ms))
     roofline["kernel_ms_min"] = float(np.min(kern_ms))
 
