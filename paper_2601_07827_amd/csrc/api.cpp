@@ -73,16 +73,22 @@ template <class T> tcx_error_t retire(intptr_t* h, uint32_t magic) {
 
 int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
-// Largest tile whose grid still covers the chip; the smallest shape if none does.
+// Cost model for the tile shape: rounds of workgroups over the chip x padded tile area /
+// the shape's relative efficiency.  Large tiles win when there are enough of them; small
+// problems fall to small tiles that still fill the CUs.
 int choose_variant(const Analysis& an, int num_cu) {
     const int n = gett_num_variants(an.dtype);
-    const int want = num_cu > 0 ? num_cu : 256;
+    const int64_t cus = num_cu > 0 ? num_cu : 256;
+    int best = 0;
+    double best_cost = 0;
     for (int v = 0; v < n; ++v) {
         const GettVariant s = gett_variant(an.dtype, v);
         const int64_t tiles = ((an.sizeM + s.mt_m - 1) / s.mt_m) * ((an.sizeN + s.mt_n - 1) / s.mt_n) * an.sizeH;
-        if (tiles >= want) return v;
+        const int64_t rounds = (tiles + cus - 1) / cus;
+        const double cost = (double)rounds * s.mt_m * s.mt_n / s.efficiency;
+        if (v == 0 || cost < best_cost) { best = v; best_cost = cost; }
     }
-    return n - 1;
+    return best;
 }
 
 void fill_generic(const Analysis& an, GenericArgs* g) {
@@ -305,7 +311,7 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
     if (!p) return TCX_ERR_INVALID_HANDLE;
     const Analysis& an = p->an;
     const bool tiled = an.path == TCX_PATH_GETT_MFMA;
-    const GettVariant s = tiled ? gett_variant(an.dtype, p->variant) : GettVariant{0, 0, 0, 256};
+    const GettVariant s = tiled ? gett_variant(an.dtype, p->variant) : GettVariant{0, 0, 0, 256, 0.f};
     switch (key) {
         case TCX_KEY_PATH: return put_i64(an.path, value, nbytes);
         case TCX_KEY_SIZE_H: return put_i64(an.sizeH, value, nbytes);

@@ -75,6 +75,7 @@ struct GettArgs {
 
 struct GettVariant {
     int mt_m, mt_n, kt, threads;
+    float efficiency;    // relative main-loop speed per unit tile area, for the planner's cost model
 };
 
 // Generic fallback: every mode of D (H, M, N together, D-fastest first) and every K mode.

@@ -1,0 +1,315 @@
+"""Host-only checks of the C-ABI library: it loads without a GPU, exports every symbol the
+header declares, reports each error class before any HIP call, follows the paper's
+conventions (Sec. "Error Handling": codes + text, outputs by pointer, destroy nulls the
+handle), agrees with the oracle's independent validation, and the index analyser produces
+the expected fused shapes.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2601_07827_amd as T
+import workloads as W
+from helpers import desc, random_problem
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = open(os.path.join(ROOT, "include", "tcx.h")).read()
+
+
+def test_library_exports_every_declared_symbol():
+    declared = sorted(set(re.findall(r"^(?:tcx_error_t|int|size_t)\s+(tcx_[a-z_]+)\s*\(", HEADER, re.M)))
+    assert len(declared) >= 17
+    lib = ctypes.CDLL(T.binding.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), "libtcx.so lacks %s" % name
+    assert sorted(T.binding.EXPORTS) == declared
+
+
+def test_header_constants_match_binding():
+    for name, value in re.findall(r"\b(TCX_[A-Z0-9_]+)\s*=\s*(\d+)", HEADER):
+        assert getattr(T, name) == int(value), name
+
+
+def test_explain_error_and_check_success():
+    assert T.tcx_check_success(0) and not T.tcx_check_success(T.TCX_ERR_D_ALIASING)
+    texts = {T.tcx_explain_error(c) for c in range(19)}
+    assert len(texts) == 19 and all(texts)
+    assert "unknown" in T.tcx_explain_error(12345)
+    # truncation keeps a NUL and returns the full length
+    buf = ctypes.create_string_buffer(8)
+    need = T.raw().tcx_explain_error(T.TCX_ERR_CD_MISMATCH, 8, buf)
+    assert need > 8 and len(buf.value) == 7
+
+
+@pytest.fixture()
+def handle():
+    h = T.tcx_create_handle()
+    yield h
+    T.tcx_destroy_handle(h)
+
+
+def _code(fn, *a):
+    try:
+        fn(*a)
+    except T.TcxError as e:
+        return e.code
+    return 0
+
+
+def test_handle_lifecycle_and_null_conventions(handle):
+    lib = T.raw()
+    assert lib.tcx_create_handle(None) == T.TCX_ERR_NULL_ARG
+    assert lib.tcx_destroy_handle(None) == T.TCX_ERR_NULL_ARG
+    h2 = ctypes.c_ssize_t(T.tcx_create_handle())
+    assert lib.tcx_destroy_handle(ctypes.byref(h2)) == 0 and h2.value == 0        # destroy nulls the handle
+    assert lib.tcx_destroy_handle(ctypes.byref(h2)) == T.TCX_ERR_INVALID_HANDLE
+    stale = ctypes.c_ssize_t(123456)
+    assert lib.tcx_destroy_handle(ctypes.byref(stale)) == T.TCX_ERR_INVALID_HANDLE
+    # a tensor-info handle is not a library handle
+    ti = T.tcx_create_tensor_info(handle, T.TCX_F64, [2], [1])
+    assert _code(T.tcx_create_executor, ti, 0) == T.TCX_ERR_INVALID_HANDLE
+    assert _code(T.tcx_destroy_product, ti) == T.TCX_ERR_INVALID_HANDLE
+    assert T.tcx_destroy_tensor_info(ti) == 0
+
+
+def test_tensor_info_errors_and_roundtrip(handle):
+    assert _code(T.tcx_create_tensor_info, handle, 7, [2], [1]) == T.TCX_ERR_BAD_DTYPE
+    assert _code(T.tcx_create_tensor_info, handle, 2, [2], [1]) == T.TCX_ERR_BAD_DTYPE      # complex64 reserved
+    assert _code(T.tcx_create_tensor_info, handle, T.TCX_F64, [1] * 33, [1] * 33) == T.TCX_ERR_BAD_NMODE
+    assert _code(T.tcx_create_tensor_info, handle, T.TCX_F64, [3, 0], [1, 3]) == T.TCX_ERR_BAD_EXTENT
+    assert _code(T.tcx_create_tensor_info, handle, T.TCX_F64, [3, -2], [1, 3]) == T.TCX_ERR_BAD_EXTENT
+    assert _code(T.tcx_create_tensor_info, 0, T.TCX_F64, [3], [1]) == T.TCX_ERR_INVALID_HANDLE
+    ti = T.tcx_create_tensor_info(handle, T.TCX_C128, [3, 4, 5], [20, -5, 1])
+    assert T.tcx_tensor_info_get(ti) == (T.TCX_C128, [3, 4, 5], [20, -5, 1])
+    scalar = T.tcx_create_tensor_info(handle, T.TCX_F32, [], [])
+    assert T.tcx_tensor_info_get(scalar) == (T.TCX_F32, [], [])
+    T.tcx_destroy_tensor_info(ti)
+    T.tcx_destroy_tensor_info(scalar)
+
+
+def _product_code(handle, A, B, C, D, ops=(0, 0, 0, 0), dtypes=(1, 1, 1, 1), prec=0):
+    infos = [T.tcx_create_tensor_info(handle, dt, t[0], t[1]) for dt, t in zip(dtypes, (A, B, C, D))]
+    try:
+        p = T.tcx_create_product(handle, ops[0], infos[0], A[2], ops[1], infos[1], B[2], ops[2], infos[2], C[2],
+                                 ops[3], infos[3], D[2], prec)
+        T.tcx_destroy_product(p)
+        return 0
+    except T.TcxError as e:
+        return e.code
+    finally:
+        for i in infos:
+            T.tcx_destroy_tensor_info(i)
+
+
+def test_product_validation_errors(handle):
+    ext = dict(m=3, n=4, k=5, x=2)
+    ids = dict(m=1, n=2, k=3, x=4)
+    t = lambda labels, **kw: desc(W.tensor(labels, ext, **kw), ids)
+    A, B, D = t("mk"), t("kn"), t("mn")
+    assert _product_code(handle, A, B, D, D) == 0
+    assert _product_code(handle, ([3, 6], [1, 3], [1, 3]), B, D, D) == T.TCX_ERR_EXTENT_MISMATCH       # appendix test 26
+    assert _product_code(handle, A, B, t("nm"), D) == T.TCX_ERR_CD_MISMATCH                           # appendix test 27
+    assert _product_code(handle, A, B, t("mn", strides=dict(m=1, n=4)), D) == T.TCX_ERR_CD_MISMATCH
+    assert _product_code(handle, A, B, t("nm", strides=dict(m=1, n=3)), D) == 0                        # same layout, listed differently
+    al = t("mn", strides=dict(m=1, n=2))
+    assert _product_code(handle, A, B, al, al) == T.TCX_ERR_D_ALIASING                                # appendix test 28
+    z = t("mn", strides=dict(m=0, n=1))
+    assert _product_code(handle, A, B, z, z) == T.TCX_ERR_D_ALIASING
+    assert _product_code(handle, t("mkx"), B, D, D) == T.TCX_ERR_ISOLATED_INDEX                       # Case 4
+    assert _product_code(handle, A, B, t("mnx"), t("mnx")) == T.TCX_ERR_ISOLATED_INDEX                # Case 5
+    assert _product_code(handle, A, B, D, D, dtypes=(1, 0, 1, 1)) == T.TCX_ERR_DTYPE_MIX
+    assert _product_code(handle, A, B, D, D, ops=(0, 0, 0, 1)) == T.TCX_ERR_UNSUPPORTED_OP            # opD must be identity
+    assert _product_code(handle, A, B, D, D, ops=(5, 0, 0, 0)) == T.TCX_ERR_UNSUPPORTED_OP
+    assert _product_code(handle, A, B, D, D, prec=3) == T.TCX_ERR_UNSUPPORTED_PRECISION
+    # zero stride in an input is a broadcast and is legal
+    assert _product_code(handle, t("mk", strides=dict(m=0, k=1)), B, D, D) == 0
+    # repeated label inside a tensor (Case 3) is accepted; with unequal extents it is not
+    assert _product_code(handle, ([5, 3, 5], [1, 5, 15], [3, 1, 3]), B, D, D) == 0
+    assert _product_code(handle, ([5, 3, 4], [1, 5, 15], [3, 1, 3]), B, D, D) == T.TCX_ERR_EXTENT_MISMATCH
+
+
+def test_config3_literal_stride_reading_is_rejected_as_aliasing(handle):
+    p = W.config3()
+    ids = W.label_ids(p)
+    bad = ([37, 53, 61], [1, 37, 2], [ids[l] for l in "abc"])
+    assert _product_code(handle, desc(p.A, ids), desc(p.B, ids), bad, bad, dtypes=(0, 0, 0, 0)) == T.TCX_ERR_D_ALIASING
+
+
+ORACLE_TO_TCX = {oracle.V_OK: 0, oracle.V_EXTENT_MISMATCH: T.TCX_ERR_EXTENT_MISMATCH,
+                 oracle.V_CD_MISMATCH: T.TCX_ERR_CD_MISMATCH, oracle.V_D_ALIASING: T.TCX_ERR_D_ALIASING,
+                 oracle.V_ISOLATED: T.TCX_ERR_ISOLATED_INDEX}
+
+
+def test_library_and_oracle_agree_on_validity(handle):
+    """Random problems, each possibly broken in one way; the two independent validators must
+    put it in the same class."""
+    rng = np.random.default_rng(2601)
+    seen = set()
+    for i in range(300):
+        p = random_problem(rng, "f64", max_group=2, max_extent=4, allow_neg=(i % 2 == 0))
+        ids = W.label_ids(p)
+        A, B, D = [list(map(list, desc(t, ids))) for t in (p.A, p.B, p.D)]
+        C = [list(D[0]), list(D[1]), list(D[2])]
+        kind = i % 6
+        if kind == 1 and A[0]:
+            A[0][int(rng.integers(len(A[0])))] += 1                      # extent mismatch (or isolated if unique)
+        elif kind == 2 and D[0]:
+            j = int(rng.integers(len(D[0])))
+            C[1][j] = C[1][j] * 2 + 1                                    # C laid out differently
+        elif kind == 3 and len(D[0]) >= 2:
+            D[1][0] = D[1][1]
+            C[1][0] = C[1][1]                                            # two modes of D share a stride
+        elif kind == 4:
+            A[0].append(2); A[1].append(1000); A[2].append(999)          # label only in A
+        elif kind == 5:
+            for t_ in (C, D):
+                t_[0].append(2); t_[1].append(5000); t_[2].append(998)   # label only in D
+        v = oracle.validate(tuple(A), tuple(B), tuple(C), tuple(D))
+        code = _product_code(handle, A, B, C, D)
+        assert code == ORACLE_TO_TCX[v], (i, kind, A, B, C, D, oracle.V_NAMES[v], code)
+        seen.add(v)
+    assert seen == set(ORACLE_TO_TCX)
+
+
+def test_execute_argument_checks_without_a_device(handle):
+    ext = dict(m=3, n=4, k=5)
+    ids = dict(m=1, n=2, k=3)
+    infos = [T.tcx_create_tensor_info(handle, T.TCX_F64, *desc(W.tensor(l, ext), ids)[:2]) for l in ("mk", "kn", "mn")]
+    labs = [[ids[c] for c in l] for l in ("mk", "kn", "mn")]
+    prod = T.tcx_create_product(handle, 0, infos[0], labs[0], 0, infos[1], labs[1], 0, infos[2], labs[2], 0, infos[2], labs[2])
+    ex = T.tcx_create_executor(handle, 0)
+    lib = T.raw()
+    one = ctypes.c_double(1.0)
+    zero = ctypes.c_double(0.0)
+    p1, p0 = ctypes.cast(ctypes.pointer(one), ctypes.c_void_p), ctypes.cast(ctypes.pointer(zero), ctypes.c_void_p)
+    fake = ctypes.c_void_p(4096)
+    assert lib.tcx_execute_product(prod, ex, None, None, fake, fake, p0, None, fake) == T.TCX_ERR_NULL_ARG   # alpha
+    assert lib.tcx_execute_product(prod, ex, None, p1, fake, fake, p0, None, None) == T.TCX_ERR_NULL_ARG     # D
+    assert lib.tcx_execute_product(prod, ex, None, p1, None, fake, p0, None, fake) == T.TCX_ERR_NULL_ARG     # A with alpha != 0
+    assert lib.tcx_execute_product(prod, ex, None, p1, fake, fake, p1, None, fake) == T.TCX_ERR_NULL_ARG     # C with beta != 0
+    assert lib.tcx_execute_product(prod, 0, None, p1, fake, fake, p0, None, fake) == T.TCX_ERR_INVALID_HANDLE
+    assert lib.tcx_execute_product(ex, ex, None, p1, fake, fake, p0, None, fake) == T.TCX_ERR_INVALID_HANDLE
+    if not T.tcx_handle_has_device(handle):
+        # beta == 0 with C == NULL is legal; without a GPU the call stops at NO_DEVICE, before any launch
+        assert lib.tcx_execute_product(prod, ex, None, p1, fake, fake, p0, None, fake) == T.TCX_ERR_NO_DEVICE
+    for i in infos:
+        T.tcx_destroy_tensor_info(i)
+    assert T.tcx_destroy_product(prod) == 0 and T.tcx_destroy_executor(ex) == 0
+
+
+def test_product_get_conventions(handle):
+    p = W.config1()
+    ids = W.label_ids(p)
+    infos = [T.tcx_create_tensor_info(handle, T.TCX_F64, t.extents, t.strides) for t in (p.A, p.B, p.D)]
+    labs = [[ids[l] for l in t.labels] for t in (p.A, p.B, p.D)]
+    prod = T.tcx_create_product(handle, 0, infos[0], labs[0], 0, infos[1], labs[1], 0, infos[2], labs[2], 0, infos[2], labs[2])
+    lib = T.raw()
+    v = ctypes.c_int64(0)
+    n = ctypes.c_size_t(4)
+    assert lib.tcx_product_get(prod, T.TCX_KEY_SIZE_M, ctypes.byref(v), ctypes.byref(n)) == T.TCX_ERR_BUFFER_TOO_SMALL
+    assert n.value == 8
+    assert lib.tcx_product_get(prod, 999, ctypes.byref(v), ctypes.byref(n)) == T.TCX_ERR_BAD_KEY
+    assert lib.tcx_product_get(prod, T.TCX_KEY_SIZE_M, ctypes.byref(v), None) == T.TCX_ERR_NULL_ARG
+    assert T.tcx_product_get(prod, T.TCX_KEY_SIZE_M) == 576
+    assert _code(T.tcx_product_set, prod, T.TCX_KEY_VARIANT, 99) == T.TCX_ERR_UNSUPPORTED_OP
+    T.tcx_destroy_product(prod)
+    for i in infos:
+        T.tcx_destroy_tensor_info(i)
+
+
+# ---- the analyser's fused shapes for the five configurations -----------------------------------
+def _plan(handle, p):
+    ids = W.label_ids(p)
+    dt = {"f32": 0, "f64": 1, "c128": 3}[p.dtype]
+    infos = [T.tcx_create_tensor_info(handle, dt, t.extents, t.strides) for t in (p.A, p.B, p.D)]
+    labs = [[ids[l] for l in t.labels] for t in (p.A, p.B, p.D)]
+    prod = T.tcx_create_product(handle, p.opA, infos[0], labs[0], p.opB, infos[1], labs[1], p.opC, infos[2], labs[2],
+                                0, infos[2], labs[2])
+    for i in infos:
+        T.tcx_destroy_tensor_info(i)
+    out = {k: T.tcx_product_get(prod, getattr(T, "TCX_KEY_" + k)) for k in
+           ("PATH", "SIZE_H", "SIZE_M", "SIZE_N", "SIZE_K", "MODES_H", "MODES_M", "MODES_N", "MODES_K",
+            "A_K_FASTEST", "B_K_FASTEST", "D_N_FASTEST", "TILE_M", "TILE_N", "TILE_K", "GRID")}
+    T.tcx_destroy_product(prod)
+    return out
+
+
+def test_analyser_config1(handle):
+    a = _plan(handle, W.config1())
+    # nothing fuses: (a,i), (b,j), (c,d); modes are (extent, strideA, strideB, strideD), fastest first
+    assert a["MODES_M"] == [(24, 1, 0, 1), (24, 576, 0, 576)]
+    assert a["MODES_N"] == [(24, 0, 24, 24), (24, 0, 13824, 13824)]
+    assert a["MODES_K"] == [(24, 24, 1, 0), (24, 13824, 576, 0)]
+    assert (a["A_K_FASTEST"], a["B_K_FASTEST"], a["D_N_FASTEST"]) == (0, 1, 0)
+    assert a["PATH"] == T.TCX_PATH_GETT_MFMA
+
+
+def test_analyser_config2_is_one_gemm(handle):
+    a = _plan(handle, W.config2())
+    assert a["MODES_M"] == [(36864, 1, 0, 1)]
+    assert a["MODES_K"] == [(36864, 36864, 1, 0)]
+    assert a["MODES_N"] == [(4096, 0, 36864, 36864)]
+    assert a["MODES_H"] == []
+    assert (a["A_K_FASTEST"], a["B_K_FASTEST"], a["D_N_FASTEST"]) == (0, 1, 0)
+    assert (a["TILE_M"], a["TILE_N"], a["TILE_K"], a["GRID"]) == (256, 128, 16, 4608)
+
+
+def test_analyser_config3(handle):
+    a = _plan(handle, W.config3())
+    # A: e=1, b=41, a=2173, d=80401; B: e=1, c=41, d=2501; D: c=2, a=122, b=4514.  Nothing fuses.
+    assert a["MODES_K"] == [(41, 1, 1, 0), (29, 80401, 2501, 0)]
+    assert a["MODES_N"] == [(61, 0, 41, 2)]
+    assert sorted(a["MODES_M"]) == sorted([(37, 2173, 0, 122), (53, 41, 0, 4514)])
+    assert (a["A_K_FASTEST"], a["B_K_FASTEST"], a["D_N_FASTEST"]) == (1, 1, 1)
+    assert (a["SIZE_M"], a["SIZE_N"], a["SIZE_K"]) == (1961, 61, 1189)
+
+
+def test_analyser_config4(handle):
+    a = _plan(handle, W.config4())
+    assert a["MODES_H"] == [(512, 1, 1, 1)]
+    assert a["MODES_M"] == [(96, 49152, 0, 512)]
+    assert a["MODES_N"] == [(96, 0, 49152, 49152)]
+    assert a["MODES_K"] == [(96, 512, 512, 0)]
+    b = _plan(handle, W.config4(h_slowest=True))
+    assert b["MODES_H"] == [(512, 9216, 9216, 9216)]
+    assert b["MODES_K"] == [(96, 1, 1, 0)] and b["MODES_M"] == [(96, 96, 0, 1)]
+
+
+def test_analyser_config5_fuses_only_where_the_layouts_agree(handle):
+    p = W.config5()
+    a = _plan(handle, p)
+    assert (a["SIZE_M"], a["SIZE_N"], a["SIZE_K"]) == (1024, 1024, 1024)
+    for key, tensors in (("MODES_M", (1, 3)), ("MODES_N", (2, 3)), ("MODES_K", (1, 2))):
+        modes = a[key]
+        prod = 1
+        for m in modes:
+            prod *= m[0]
+            assert m[0] in (4, 16, 64, 256, 1024)
+            for t in tensors:
+                assert m[t] != 0
+        assert prod == 1024
+        # no fusable pair is left
+        for x in modes:
+            for y in modes:
+                if x is not y:
+                    assert not all(y[t] == x[t] * x[0] for t in (1, 2, 3))
+
+
+def test_analyser_drops_extent_one_and_merges_repeated_labels(handle):
+    ids = dict(k=1, i=2, j=3, u=4)
+    # A[k,i,k,u] with u of extent 1; strides (1, 4, 12, 48) -> merged k stride 13
+    A = ([4, 3, 4, 1], [1, 4, 12, 48], [1, 2, 1, 4])
+    B = ([4, 5, 1], [1, 4, 20], [1, 3, 4])
+    D = ([5, 3], [1, 5], [3, 2])
+    infos = [T.tcx_create_tensor_info(handle, T.TCX_F64, t[0], t[1]) for t in (A, B, D)]
+    prod = T.tcx_create_product(handle, 0, infos[0], A[2], 0, infos[1], B[2], 0, infos[2], D[2], 0, infos[2], D[2])
+    assert T.tcx_product_get(prod, T.TCX_KEY_MODES_K) == [(4, 13, 1, 0)]
+    assert T.tcx_product_get(prod, T.TCX_KEY_MODES_M) == [(3, 4, 0, 5)]
+    assert T.tcx_product_get(prod, T.TCX_KEY_MODES_N) == [(5, 0, 4, 1)]
+    assert T.tcx_product_get(prod, T.TCX_KEY_MODES_H) == []
+    T.tcx_destroy_product(prod)
+    for i in infos:
+        T.tcx_destroy_tensor_info(i)

@@ -18,8 +18,7 @@ GENERIC, GETT = 0, 1
 def _paths_for(p):
     from gpu_helpers import DT  # noqa: F401
     paths = [(GENERIC, None)]
-    if p.dtype in ("f64", "f32"):
-        paths += [(GETT, v) for v in range(4)]
+    paths += [(GETT, v) for v in range(3 if p.dtype == "c128" else 4)]
     return paths
 
 
@@ -64,9 +63,7 @@ def test_random_problems(dtype):
         p = random_problem(rng, dtype, max_group=3, max_extent=6, allow_neg=(i % 3 == 0), name="rand%d_%s" % (i, dtype))
         a, b, c = W.make_operands(p)
         truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
-        paths = [(GENERIC, None)]
-        if dtype != "c128":
-            paths.append((GETT, 2 + i % 2))
+        paths = [(GENERIC, None), (GETT, (1 + i % 2) if dtype == "c128" else (2 + i % 2))]
         for path, variant in paths:
             _check(p, a, b, c, path, variant, truth=truth, S=S)
 
@@ -104,3 +101,33 @@ def test_full_size_integer_inputs_bit_exact(p):
     a, b, c = W.make_operands(p, "ints")
     p2 = W.Problem(p.name + "_ints", p.dtype, p.A, p.B, p.D, alpha=2.0, beta=(0.5 if p.beta != 0 else 0.0), seed=p.seed)
     _check(p2, a, b, c, None, None, exact=True)
+
+
+@pytest.mark.parametrize("dist", ["uniform", "ints"])
+def test_config2_full_size_sampled(dist):
+    """Configuration 2 at its full size (10.9 GB V, generated on the device by the torch twin of
+    the counter-based generator), in the launch configuration bench.py times.  512 sampled
+    outputs -- tile-boundary rows and columns plus random ones -- each a full 36864-term sum
+    evaluated by the oracle.  Integer-valued inputs must match bit for bit."""
+    import torch
+    import bench
+    from gpu_helpers import GpuProduct, say
+    p = W.config2()
+    say("%s full size, dist=%s" % (p.name, dist))
+    dA, dB, dD, _ = bench.device_operands(p, torch, dist)
+    # the device generator reproduces the host generator
+    probe = np.array([0, 1, 12345678, p.A.size - 1], dtype=np.uint64)
+    gen = W.DISTRIBUTIONS[dist]
+    assert np.array_equal(dA[torch.from_numpy(probe.astype(np.int64)).cuda()].cpu().numpy(), gen(p.seed, W.TAG_A, probe, np.float64))
+    gp = GpuProduct(p)
+    try:
+        assert (gp.get(gp.T.TCX_KEY_PATH), gp.get(gp.T.TCX_KEY_TILE_M), gp.get(gp.T.TCX_KEY_TILE_N)) == (1, 256, 128)
+        gp.execute(dA, dB, dD, dD)
+        torch.cuda.synchronize()
+        res = bench.parity_after_run(p, dD, 1, torch, dist)
+    finally:
+        gp.close()
+    assert res["samples"] >= 400
+    assert res["ok"], res
+    if dist == "ints":
+        assert res["bit_exact"], res

@@ -24,6 +24,24 @@ def test_torch_generator_matches_numpy_bit_for_bit():
             assert np.array_equal(t, W.uniform_pm1(W.BASE_SEED + 2, W.TAG_A, idx, ndt))
 
 
+def test_torch_integer_generator_matches_numpy():
+    idx = np.arange(777, 777 + 3000, dtype=np.uint64)
+    t = W.torch_uniform_pm1(5, W.TAG_B, 777, 3000, torch.float64, "cpu", dist="ints").numpy()
+    assert np.array_equal(t, W.small_ints(5, W.TAG_B, idx, np.float64))
+    assert t.min() == -4 and t.max() == 4
+
+
+def test_config2_sample_matches_the_full_tensors():
+    pf = W.config2(v=6, o=3)
+    A, B, C = W.make_operands(pf)
+    Am, Bm, Cm = A.reshape((36, 36), order="F"), B.reshape((36, 9), order="F"), C.reshape((36, 9), order="F")
+    sub, a, b, c = W.config2_sample(pf, np.array([0, 5, 35]), np.array([1, 8]))
+    assert np.array_equal(a.reshape((3, 36), order="F"), Am[[0, 5, 35], :])
+    assert np.array_equal(b.reshape((36, 2), order="F"), Bm[:, [1, 8]])
+    assert np.array_equal(c.reshape((3, 2), order="F"), Cm[[0, 5, 35]][:, [1, 8]])
+    assert sub.sizes() == (1, 3, 2, 36)
+
+
 def test_values_follow_logical_index_not_memory_order():
     e = dict(a=3, b=4, c=5)
     t1 = W.tensor("abc", e)

@@ -359,9 +359,10 @@ def _as_i64(u: int) -> int:
     return u - (1 << 64) if u >= (1 << 63) else u
 
 
-def torch_uniform_pm1(seed: int, tag: int, start: int, count: int, dtype, device, out=None):
-    """uniform_pm1(seed, tag, arange(start, start+count)) as a torch tensor on `device`,
-    bit-identical to the numpy version (wrapping 64-bit integer arithmetic, exact conversion)."""
+def torch_uniform_pm1(seed: int, tag: int, start: int, count: int, dtype, device, out=None, dist="uniform"):
+    """uniform_pm1 (or small_ints for dist="ints") of (seed, tag, arange(start, start+count)) as a
+    torch tensor on `device`, bit-identical to the numpy version (wrapping 64-bit integer
+    arithmetic, exact conversion)."""
     import torch
     assert dtype in (torch.float64, torch.float32)
     key = _as_i64(((int(seed) * 8 + int(tag) + 1) & 0xFFFFFFFFFFFFFFFF) * 0x9E3779B97F4A7C15)
@@ -377,7 +378,9 @@ def torch_uniform_pm1(seed: int, tag: int, start: int, count: int, dtype, device
         z = (z ^ lsr(z, 30)) * _as_i64(0xBF58476D1CE4E5B9)
         z = (z ^ lsr(z, 27)) * _as_i64(0x94D049BB133111EB)
         z = z ^ lsr(z, 31)
-        if dtype == torch.float64:
+        if dist == "ints":
+            out[lo:lo + n] = (torch.remainder(lsr(z, 33), 9) - 4).to(dtype)
+        elif dtype == torch.float64:
             out[lo:lo + n] = lsr(z, 11).to(torch.float64) * 2.0 ** -52 - 1.0
         else:
             out[lo:lo + n] = lsr(z, 40).to(torch.float32) * 2.0 ** -23 - 1.0
@@ -387,7 +390,7 @@ def torch_uniform_pm1(seed: int, tag: int, start: int, count: int, dtype, device
 # --------------------------------------------------------------------------------------
 # sampled sub-problems of config 2 (the full tensors never exist on the host)
 # --------------------------------------------------------------------------------------
-def config2_sample(p: Problem, m_idx: np.ndarray, n_idx: np.ndarray):
+def config2_sample(p: Problem, m_idx: np.ndarray, n_idx: np.ndarray, dist: str = "uniform"):
     """Rows m_idx of V (as an |m_idx| x |K| matrix), columns n_idx of T and the matching
     entries of the initial D of a config-2 style problem, generated straight from the
     counter-based generator.  Returns (sub_problem, bufA, bufB, bufC); the sub-problem is
@@ -400,9 +403,10 @@ def config2_sample(p: Problem, m_idx: np.ndarray, n_idx: np.ndarray):
     # logical linear indices: V[m, k] -> m + M*k ; T[k, n] -> k + K*n ; D[m, n] -> m + M*n.
     # Index arrays are built slow-index-first so that their C-order flattening is the
     # column-major buffer of the sub-tensor.
-    a = uniform_pm1(p.seed, TAG_A, np.uint64(M) * k[:, None] + m_idx[None, :], np.float64).reshape(-1)
-    b = uniform_pm1(p.seed, TAG_B, np.uint64(K) * n_idx[:, None] + k[None, :], np.float64).reshape(-1)
-    c = uniform_pm1(p.seed, TAG_C, np.uint64(M) * n_idx[:, None] + m_idx[None, :], np.float64).reshape(-1)
+    gen = DISTRIBUTIONS[dist]
+    a = gen(p.seed, TAG_A, np.uint64(M) * k[:, None] + m_idx[None, :], np.float64).reshape(-1)
+    b = gen(p.seed, TAG_B, np.uint64(K) * n_idx[:, None] + k[None, :], np.float64).reshape(-1)
+    c = gen(p.seed, TAG_C, np.uint64(M) * n_idx[:, None] + m_idx[None, :], np.float64).reshape(-1)
     e = dict(x=len(m_idx), y=len(n_idx), k=K)
     sub = Problem(p.name + "_sample", "f64", tensor("xk", e), tensor("ky", e), tensor("xy", e),
                   alpha=p.alpha, beta=p.beta, seed=p.seed)
