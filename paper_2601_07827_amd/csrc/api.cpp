@@ -37,6 +37,10 @@ struct Product {
     int64_t* dev_tables = nullptr;
     size_t dev_offset[6] = {0, 0, 0, 0, 0, 0};
     GenericArgs generic{};
+    // bandwidth path: plan and its device tables (one allocation)
+    StreamPlan stream;
+    unsigned char* dev_stream = nullptr;
+    size_t stream_off[4] = {0, 0, 0, 0};   // rowAB, dD, itemsA, itemsB
 };
 struct Status {
     int64_t path = 0, variant = 0, grid = 0, block = 0, tile_m = 0, tile_n = 0, tile_k = 0, hip_error = 0;
@@ -140,6 +144,37 @@ tcx_error_t build_tables(Product* p) {
             (void)hipGetLastError();
             (void)hipFree(p->dev_tables);
             p->dev_tables = nullptr;
+            return TCX_ERR_LAUNCH;
+        }
+    return TCX_SUCCESS;
+}
+
+int elem_bytes(int dtype) { return dtype == TCX_F32 ? 4 : dtype == TCX_F64 ? 8 : 16; }
+
+tcx_error_t build_stream(Product* p) {
+    try {
+        p->stream = plan_stream(p->an, elem_bytes(p->an.dtype));
+    } catch (const std::bad_alloc&) {
+        return TCX_ERR_ALLOC;
+    }
+    if (!p->stream.ok) return TCX_ERR_UNSUPPORTED_OP;
+    if (!p->handle.has_device) return TCX_SUCCESS;
+    const StreamPlan& sp = p->stream;
+    const size_t bytes[4] = {sp.rowAB.size() * sizeof(uint32_t), sp.dD.size() * sizeof(int64_t),
+                             sp.itemsA.size() * sizeof(StreamItem), sp.itemsB.size() * sizeof(StreamItem)};
+    const void* src[4] = {sp.rowAB.data(), sp.dD.data(), sp.itemsA.data(), sp.itemsB.data()};
+    size_t total = 0;
+    for (int i = 0; i < 4; ++i) { p->stream_off[i] = total; total += (bytes[i] + 255) / 256 * 256; }
+    if (hipMalloc((void**)&p->dev_stream, total) != hipSuccess) {
+        p->dev_stream = nullptr;
+        (void)hipGetLastError();
+        return TCX_ERR_ALLOC;
+    }
+    for (int i = 0; i < 4; ++i)
+        if (hipMemcpy(p->dev_stream + p->stream_off[i], src[i], bytes[i], hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipGetLastError();
+            (void)hipFree(p->dev_stream);
+            p->dev_stream = nullptr;
             return TCX_ERR_LAUNCH;
         }
     return TCX_SUCCESS;
@@ -287,7 +322,9 @@ tcx_error_t tcx_create_product(tcx_handle_t handle, tcx_op_t opA, tcx_tensor_inf
                               (int)opB, (int)opC, (int)opD, (int)precision, &p->an);
     if (err == TCX_SUCCESS) {
         fill_generic(p->an, &p->generic);
-        if (p->an.path == TCX_PATH_GETT_MFMA) {
+        if (stream_preferred(p->an, elem_bytes(p->an.dtype)) && build_stream(p) == TCX_SUCCESS) {
+            p->an.path = TCX_PATH_BANDWIDTH;
+        } else if (p->an.path == TCX_PATH_GETT_MFMA) {
             p->variant = choose_variant(p->an, h->num_cu);
             err = build_tables(p);
         }
@@ -303,6 +340,7 @@ tcx_error_t tcx_destroy_product(tcx_product_t* product) {
     Product* p = lookup<Product>(*product, MAGIC_PRODUCT);
     if (!p) return TCX_ERR_INVALID_HANDLE;
     if (p->dev_tables) { (void)hipFree(p->dev_tables); p->dev_tables = nullptr; }
+    if (p->dev_stream) { (void)hipFree(p->dev_stream); p->dev_stream = nullptr; }
     return retire<Product>(product, MAGIC_PRODUCT);
 }
 
@@ -322,7 +360,7 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
         case TCX_KEY_NMODES_M: return put_i64((int64_t)an.M.size(), value, nbytes);
         case TCX_KEY_NMODES_N: return put_i64((int64_t)an.N.size(), value, nbytes);
         case TCX_KEY_NMODES_K: return put_i64((int64_t)an.K.size(), value, nbytes);
-        case TCX_KEY_TILE_M: return put_i64(s.mt_m, value, nbytes);
+        case TCX_KEY_TILE_M: return put_i64(an.path == TCX_PATH_BANDWIDTH ? p->stream.tile : s.mt_m, value, nbytes);
         case TCX_KEY_TILE_N: return put_i64(s.mt_n, value, nbytes);
         case TCX_KEY_TILE_K: return put_i64(s.kt, value, nbytes);
         case TCX_KEY_GRID:
@@ -361,6 +399,14 @@ tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* valu
             p->an.path = TCX_PATH_GETT_MFMA;
             return TCX_SUCCESS;
         }
+        if (v == TCX_PATH_BANDWIDTH) {
+            if (!p->stream.ok) {
+                const tcx_error_t err = build_stream(p);
+                if (err != TCX_SUCCESS) return err;
+            }
+            p->an.path = TCX_PATH_BANDWIDTH;
+            return TCX_SUCCESS;
+        }
         return TCX_ERR_UNSUPPORTED_OP;
     }
     if (key == TCX_KEY_VARIANT) {
@@ -396,7 +442,26 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
     int64_t grid = 0;
     int block = 0;
     const bool tiled = p->an.path == TCX_PATH_GETT_MFMA && read_ab && p->dev_tables;
-    if (tiled) {
+    const bool streamed = p->an.path == TCX_PATH_BANDWIDTH && read_ab && p->dev_stream;
+    if (streamed) {
+        const StreamPlan& sp = p->stream;
+        StreamArgs g{};
+        g.A = A; g.B = B; g.C = C; g.D = D;
+        g.rowAB = (const uint32_t*)(p->dev_stream + p->stream_off[0]);
+        g.dD = (const int64_t*)(p->dev_stream + p->stream_off[1]);
+        g.itemsA = (const StreamItem*)(p->dev_stream + p->stream_off[2]);
+        g.itemsB = (const StreamItem*)(p->dev_stream + p->stream_off[3]);
+        g.nItemsA = (int32_t)sp.itemsA.size(); g.nItemsB = (int32_t)sp.itemsB.size();
+        g.tile = sp.tile; g.inner = sp.inner; g.chunk = sp.chunk; g.K = sp.K; g.rowsA = sp.rowsA; g.rowsB = sp.rowsB;
+        g.split_extent = sp.split_extent; g.num_tiles = sp.num_tiles; g.n_outer = sp.n_outer;
+        for (int i = 0; i < sp.n_outer; ++i) { g.oExt[i] = sp.oExt[i]; g.oSA[i] = sp.oSA[i]; g.oSB[i] = sp.oSB[i]; g.oSD[i] = sp.oSD[i]; }
+        g.s = s;
+        g.opA = p->an.opA; g.opB = p->an.opB; g.opC = p->an.opC;
+        g.read_c = read_c;
+        hip_err = launch_stream(p->an.dtype, g, sp.lds_bytes, p->handle.num_cu, (void*)e->stream, &grid, &block);
+        st.path = TCX_PATH_BANDWIDTH;
+        st.tile_m = sp.tile; st.tile_n = 0; st.tile_k = sp.K;
+    } else if (tiled) {
         const GettVariant v = gett_variant(p->an.dtype, p->variant);
         GettArgs g{};
         g.A = A; g.B = B; g.C = C; g.D = D;

@@ -102,3 +102,67 @@ int launch_gett(int dtype, int variant, bool a_kf, bool b_kf, bool d_nf, const G
                 int64_t* grid, int* block);
 
 }  // namespace tcx
+
+// ---- bandwidth (streaming) path ---------------------------------------------------------------
+// Output-stationary: a workgroup owns a tile made of D's fastest modes (so its stores are one
+// contiguous stretch of D wherever D is), stages the few elements of A and B that the tile
+// needs through LDS with loads that follow A's and B's own memory order, and streams D out.
+namespace tcx {
+
+constexpr int kMaxOuterModes = 32;
+constexpr int kStreamThreads = 256;
+
+struct StreamItem {        // one element to stage: where it comes from and where it goes
+    int64_t src;           // element offset relative to the tile's base in A (or B)
+    uint32_t slot;         // LDS slot = row * K + k
+    uint32_t digit;        // index along the split mode (for masking the ragged last chunk)
+};
+
+struct StreamPlan {
+    bool ok = false;
+    int32_t tile = 0;          // output elements per full tile = inner * chunk
+    int32_t inner = 0;         // product of the tile modes below the split mode
+    int32_t chunk = 0;         // indices of the split mode per tile
+    int64_t split_extent = 1;  // extent of the split mode (1 if none)
+    int32_t rowsA = 0, rowsB = 0, K = 0;
+    int32_t split_in_A = 0, split_in_B = 0;   // does A (B) carry the split mode
+    int64_t num_tiles = 0;
+    // outer loop: the split mode's chunks first, then the remaining D modes
+    int32_t n_outer = 0;
+    int64_t oExt[kMaxOuterModes], oSA[kMaxOuterModes], oSB[kMaxOuterModes], oSD[kMaxOuterModes];
+    // host tables
+    std::vector<uint32_t> rowAB;     // [tile]: rowA | rowB << 16
+    std::vector<int64_t> dD;         // [tile]: D offset relative to the tile base
+    std::vector<StreamItem> itemsA, itemsB;
+    size_t lds_bytes = 0;
+};
+
+struct StreamArgs {
+    const void* A;
+    const void* B;
+    const void* C;
+    void* D;
+    const uint32_t* rowAB;
+    const int64_t* dD;
+    const StreamItem* itemsA;
+    const StreamItem* itemsB;
+    int32_t nItemsA, nItemsB;
+    int32_t tile, inner, chunk, K, rowsA, rowsB;
+    int64_t split_extent;
+    int64_t num_tiles;
+    int32_t n_outer;
+    int64_t oExt[kMaxOuterModes], oSA[kMaxOuterModes], oSB[kMaxOuterModes], oSD[kMaxOuterModes];
+    Scalars s;
+    int32_t opA, opB, opC;
+    int32_t read_c;
+};
+
+// Host: lay out the streaming plan for an analysed product (stream_plan.cpp).
+StreamPlan plan_stream(const Analysis& an, int elem_bytes);
+// Arithmetic intensity test + size limits: should this product take the streaming path?
+bool stream_preferred(const Analysis& an, int elem_bytes);
+
+int launch_stream(int dtype, const StreamArgs& args, size_t lds_bytes, int num_cu, void* stream, int64_t* grid,
+                  int* block);
+
+}  // namespace tcx

@@ -303,15 +303,16 @@ def config3(scale: float = 1.0, d_layout: str = "R1") -> Problem:
                    seed=BASE_SEED + 3)
 
 
-def config4(h: int = 512, n: int = 96, h_slowest: bool = False) -> Problem:
+def config4(h: int = 512, n: int = 96, h_slowest: bool = False, k: Optional[int] = None) -> Problem:
     """complex128 batched: D[h,i,j] = sum_k conj(A[h,k,i]) B[h,k,j] + 0.5 C[h,i,j]."""
-    e = dict(h=h, i=n, j=n, k=n)
+    e = dict(h=h, i=n, j=n, k=n if k is None else k)
     if h_slowest:
         A, B, D = tensor("hki", e, memory_order="kih"), tensor("hkj", e, memory_order="kjh"), \
             tensor("hij", e, memory_order="ijh")
     else:
         A, B, D = tensor("hki", e), tensor("hkj", e), tensor("hij", e)
-    return Problem("cfg4_c128_batched_h%d_n%d%s" % (h, n, "_hslow" if h_slowest else ""), "c128", A, B, D,
+    return Problem("cfg4_c128_batched_h%d_n%d%s%s" % (h, n, "_hslow" if h_slowest else "", "" if k is None else "_k%d" % k),
+                   "c128", A, B, D,
                    alpha=1.0, beta=0.5, opA=1, seed=BASE_SEED + 4)
 
 
@@ -338,6 +339,32 @@ def config5(extent: int = 4, nshared: int = 5, nfree: int = 5, perm_seed: Option
     D = tensor(ms + ns, e, memory_order=shuffled(ms + ns, 2))
     return Problem("cfg5_f64_network_e%d_k%d_f%d_p%d" % (extent, nshared, nfree, pseed), "f64", A, B, D,
                    alpha=1.0, beta=0.0, seed=seed, dist="normal")
+
+
+def hadamard(nmodes: int = 4, extent: int = 128, permuted: bool = False, dtype: str = "f64", beta: float = 0.0) -> Problem:
+    """Pure Hadamard product D[h..] = A[h..] * B[h..] (+ beta C): every label in all three tensors.
+    `permuted`: A, B and D each store the modes in a different order."""
+    labs = ["h%d" % i for i in range(nmodes)]
+    e = dict.fromkeys(labs, extent)
+    if permuted:
+        A, B, D = tensor(labs, e, memory_order=labs[1:] + labs[:1]), tensor(labs, e, memory_order=labs[::-1]), tensor(labs, e)
+    else:
+        A, B, D = tensor(labs, e), tensor(labs, e), tensor(labs, e)
+    return Problem("hadamard_%s_%dx%d%s" % (dtype, nmodes, extent, "_perm" if permuted else ""), dtype, A, B, D,
+                   alpha=1.0, beta=beta, seed=BASE_SEED + 13)
+
+
+def low_intensity_shapes(full: bool = True) -> List[Problem]:
+    """Supplementary shapes whose algorithmic flop/byte is far below the ridge, so HBM bounds them:
+    a one-label contraction and an outer product of high-rank small-extent tensors (random
+    mode orders, as configuration 5), a pure Hadamard product, and configuration 4 with 4
+    contracted terms."""
+    if full:
+        return [config5(extent=4, nshared=1, nfree=7), config5(extent=4, nshared=0, nfree=7),
+                hadamard(4, 128), hadamard(4, 128, permuted=True), config4(h=512, n=96, k=4)]
+    return [config5(extent=4, nshared=1, nfree=3), config5(extent=3, nshared=0, nfree=4),
+            hadamard(3, 20), hadamard(3, 17, permuted=True, beta=0.5), hadamard(2, 9, dtype="c128", permuted=True),
+            config4(h=24, n=20, k=4), config4(h=5, n=33, k=2, h_slowest=True), config3(0.3)]
 
 
 def configs_full() -> List[Problem]:
