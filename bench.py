@@ -35,21 +35,39 @@ DT = {"f32": 0, "f64": 1, "c128": 3}
 
 def make_problem(name: str) -> W.Problem:
     table = {"cfg1": W.config1, "cfg2": W.config2, "cfg3": W.config3, "cfg4": W.config4, "cfg5": W.config5,
-             "cfg3r2": lambda: W.config3(d_layout="R2"), "cfg4hs": lambda: W.config4(h_slowest=True)}
+             "cfg3r2": lambda: W.config3(d_layout="R2"), "cfg4hs": lambda: W.config4(h_slowest=True),
+             # supplementary HBM-bound shapes
+             "s1": lambda: W.config5(extent=4, nshared=1, nfree=7), "s2": lambda: W.config5(extent=4, nshared=0, nfree=7),
+             "s3": lambda: W.hadamard(4, 128), "s3p": lambda: W.hadamard(4, 128, permuted=True),
+             "s3b": lambda: W.hadamard(4, 128, beta=0.5), "s4": lambda: W.config4(h=512, n=96, k=4)}
     return table[name]()
 
 
-def device_operands(p: W.Problem, torch, dist: str = "uniform"):
-    """Inputs resident in HBM.  Config 2 is generated on the device (10.9 GB for V) with the
-    torch twin of the counter-based generator; the small configurations come from the host."""
+def _device_tensor(spec: W.TensorSpec, seed, tag, torch, tdtype, dist):
+    """Strided tensor generated on the device: values keyed on the logical index, placed by strides."""
     dev = "cuda:0"
-    if p.name.startswith("cfg2"):
-        a = W.torch_uniform_pm1(p.seed, W.TAG_A, 0, p.A.size, torch.float64, dev, dist=dist)
-        b = W.torch_uniform_pm1(p.seed, W.TAG_B, 0, p.B.size, torch.float64, dev, dist=dist)
-        d = W.torch_uniform_pm1(p.seed, W.TAG_C, 0, p.D.size, torch.float64, dev, dist=dist)
-        return a, b, d, None
-    ha, hb, hc = W.make_operands(p)
-    return torch.from_numpy(ha).to(dev), torch.from_numpy(hb).to(dev), torch.from_numpy(hc).to(dev), (ha, hb, hc)
+    if tdtype == torch.complex128:
+        flat = torch.view_as_complex(W.torch_uniform_pm1(seed, tag, 0, 2 * spec.count, torch.float64, dev, dist=dist).view(-1, 2))
+    else:
+        flat = W.torch_uniform_pm1(seed, tag, 0, spec.count, tdtype, dev, dist=dist)
+    contiguous = list(spec.strides) == [int(np.prod(spec.extents[:i], dtype=np.int64)) for i in range(len(spec.extents))]
+    if contiguous and spec.size == spec.count:
+        return flat
+    buf = torch.full((spec.size,), -777.0, dtype=tdtype, device=dev)
+    n = len(spec.extents)
+    logical = flat.view(*reversed(spec.extents)).permute(*reversed(range(n)))      # index [i0, i1, ..], i0 fastest
+    buf.as_strided(spec.extents, spec.strides, spec.base).copy_(logical)
+    return buf
+
+
+def device_operands(p: W.Problem, torch, dist: str = "uniform"):
+    """Inputs resident in HBM, generated on the device with the torch twin of the counter-based
+    generator (bit-identical to the host generator for uniform and integer values)."""
+    tdt = {"f32": torch.float32, "f64": torch.float64, "c128": torch.complex128}[p.dtype]
+    a = _device_tensor(p.A, p.seed, W.TAG_A, torch, tdt, dist)
+    b = _device_tensor(p.B, p.seed, W.TAG_B, torch, tdt, dist)
+    d = _device_tensor(p.D, p.seed, W.TAG_C, torch, tdt, dist)
+    return a, b, d, None
 
 
 def cpu_baseline(p: W.Problem):

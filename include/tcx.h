@@ -158,7 +158,8 @@ typedef enum {
 
 /* Read a property of the plan.  *nbytes: in = capacity of value, out = bytes written. */
 tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, size_t* nbytes);
-/* Override a plan decision (TCX_KEY_FORCE_PATH, TCX_KEY_VARIANT).  Returns
+/* Override a plan decision: TCX_KEY_FORCE_PATH, or TCX_KEY_VARIANT (tiled path: index of the tile
+ * shape; bandwidth path: 0 = flat tiles only, 1 = register-blocked tiles where possible).  Returns
  * TCX_ERR_UNSUPPORTED_OP if the plan cannot run that way. */
 tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* value, size_t nbytes);
 

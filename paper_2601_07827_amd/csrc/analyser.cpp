@@ -187,7 +187,7 @@ tcx_error_t analyse(const TensorDesc& A, const int64_t* labA, const TensorDesc& 
     // real work; everything else runs on the generic kernel.
     const int64_t table_limit = (int64_t)1 << 27;
     const bool tables_ok = r.sizeM <= table_limit && r.sizeN <= table_limit && r.sizeK <= table_limit;
-    const bool tiled = tables_ok && (int)r.H.size() <= kMaxHModes && r.sizeM * r.sizeN >= 256 && r.sizeK >= 8;
+    const bool tiled = tables_ok && (int)r.H.size() <= kMaxHModes && r.sizeM * r.sizeN >= 256 && r.sizeK >= 2;
     r.path = tiled ? TCX_PATH_GETT_MFMA : TCX_PATH_GENERIC;
     r.variant = -1;   // chosen by the API layer from the compiled instantiations
     *out = r;

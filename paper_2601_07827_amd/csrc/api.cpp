@@ -40,7 +40,7 @@ struct Product {
     // bandwidth path: plan and its device tables (one allocation)
     StreamPlan stream;
     unsigned char* dev_stream = nullptr;
-    size_t stream_off[4] = {0, 0, 0, 0};   // rowAB, dD, itemsA, itemsB
+    size_t stream_off[6] = {0, 0, 0, 0, 0, 0};   // rowAB, dD, itemsA, itemsB, tabLo, tabHi
 };
 struct Status {
     int64_t path = 0, variant = 0, grid = 0, block = 0, tile_m = 0, tile_n = 0, tile_k = 0, hip_error = 0;
@@ -151,26 +151,28 @@ tcx_error_t build_tables(Product* p) {
 
 int elem_bytes(int dtype) { return dtype == TCX_F32 ? 4 : dtype == TCX_F64 ? 8 : 16; }
 
-tcx_error_t build_stream(Product* p) {
+tcx_error_t build_stream(Product* p, bool allow_blocked = true) {
+    if (p->dev_stream) { (void)hipFree(p->dev_stream); p->dev_stream = nullptr; }
     try {
-        p->stream = plan_stream(p->an, elem_bytes(p->an.dtype));
+        p->stream = plan_stream(p->an, elem_bytes(p->an.dtype), allow_blocked);
     } catch (const std::bad_alloc&) {
         return TCX_ERR_ALLOC;
     }
     if (!p->stream.ok) return TCX_ERR_UNSUPPORTED_OP;
     if (!p->handle.has_device) return TCX_SUCCESS;
     const StreamPlan& sp = p->stream;
-    const size_t bytes[4] = {sp.rowAB.size() * sizeof(uint32_t), sp.dD.size() * sizeof(int64_t),
-                             sp.itemsA.size() * sizeof(StreamItem), sp.itemsB.size() * sizeof(StreamItem)};
-    const void* src[4] = {sp.rowAB.data(), sp.dD.data(), sp.itemsA.data(), sp.itemsB.data()};
+    const size_t bytes[6] = {sp.rowAB.size() * sizeof(uint32_t), sp.dD.size() * sizeof(int64_t),
+                             sp.itemsA.size() * sizeof(StreamItem), sp.itemsB.size() * sizeof(StreamItem),
+                             sp.tabLo.size() * sizeof(int64_t), sp.tabHi.size() * sizeof(int64_t)};
+    const void* src[6] = {sp.rowAB.data(), sp.dD.data(), sp.itemsA.data(), sp.itemsB.data(), sp.tabLo.data(), sp.tabHi.data()};
     size_t total = 0;
-    for (int i = 0; i < 4; ++i) { p->stream_off[i] = total; total += (bytes[i] + 255) / 256 * 256; }
+    for (int i = 0; i < 6; ++i) { p->stream_off[i] = total; total += (bytes[i] + 255) / 256 * 256; }
     if (hipMalloc((void**)&p->dev_stream, total) != hipSuccess) {
         p->dev_stream = nullptr;
         (void)hipGetLastError();
         return TCX_ERR_ALLOC;
     }
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 6; ++i)
         if (hipMemcpy(p->dev_stream + p->stream_off[i], src[i], bytes[i], hipMemcpyHostToDevice) != hipSuccess) {
             (void)hipGetLastError();
             (void)hipFree(p->dev_stream);
@@ -322,7 +324,12 @@ tcx_error_t tcx_create_product(tcx_handle_t handle, tcx_op_t opA, tcx_tensor_inf
                               (int)opB, (int)opC, (int)opD, (int)precision, &p->an);
     if (err == TCX_SUCCESS) {
         fill_generic(p->an, &p->generic);
-        if (stream_preferred(p->an, elem_bytes(p->an.dtype)) && build_stream(p) == TCX_SUCCESS) {
+        // Routing.  Low arithmetic intensity goes to the streaming path when its tile re-reads
+        // little operand data per output; otherwise the tiled MFMA path if the free index
+        // space can fill MFMA tiles; otherwise streaming if it applies at all; else generic.
+        const bool low_ai = stream_preferred(p->an, elem_bytes(p->an.dtype));
+        const bool stream_ok = low_ai && build_stream(p) == TCX_SUCCESS;
+        if (stream_ok && (p->stream.staged_per_output <= 0.5 || p->an.path != TCX_PATH_GETT_MFMA)) {
             p->an.path = TCX_PATH_BANDWIDTH;
         } else if (p->an.path == TCX_PATH_GETT_MFMA) {
             p->variant = choose_variant(p->an, h->num_cu);
@@ -361,7 +368,7 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
         case TCX_KEY_NMODES_N: return put_i64((int64_t)an.N.size(), value, nbytes);
         case TCX_KEY_NMODES_K: return put_i64((int64_t)an.K.size(), value, nbytes);
         case TCX_KEY_TILE_M: return put_i64(an.path == TCX_PATH_BANDWIDTH ? p->stream.tile : s.mt_m, value, nbytes);
-        case TCX_KEY_TILE_N: return put_i64(s.mt_n, value, nbytes);
+        case TCX_KEY_TILE_N: return put_i64(an.path == TCX_PATH_BANDWIDTH ? p->stream.regA * p->stream.regB : s.mt_n, value, nbytes);
         case TCX_KEY_TILE_K: return put_i64(s.kt, value, nbytes);
         case TCX_KEY_GRID:
             return put_i64(tiled ? ((an.sizeM + s.mt_m - 1) / s.mt_m) * ((an.sizeN + s.mt_n - 1) / s.mt_n) * an.sizeH
@@ -371,7 +378,8 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
         case TCX_KEY_A_K_FASTEST: return put_i64(an.a_k_fastest, value, nbytes);
         case TCX_KEY_B_K_FASTEST: return put_i64(an.b_k_fastest, value, nbytes);
         case TCX_KEY_D_N_FASTEST: return put_i64(an.d_n_fastest, value, nbytes);
-        case TCX_KEY_VARIANT: return put_i64(tiled ? p->variant : 0, value, nbytes);
+        case TCX_KEY_VARIANT:
+            return put_i64(tiled ? p->variant : (an.path == TCX_PATH_BANDWIDTH && p->stream.blocked) ? 1 : 0, value, nbytes);
         case TCX_KEY_MODES_M: return put_modes(an.M, value, nbytes);
         case TCX_KEY_MODES_N: return put_modes(an.N, value, nbytes);
         case TCX_KEY_MODES_K: return put_modes(an.K, value, nbytes);
@@ -408,6 +416,11 @@ tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* valu
             return TCX_SUCCESS;
         }
         return TCX_ERR_UNSUPPORTED_OP;
+    }
+    if (key == TCX_KEY_VARIANT && p->an.path == TCX_PATH_BANDWIDTH) {
+        // 0: flat tiles only, 1: register-blocked tiles where the shape allows them
+        if (v != 0 && v != 1) return TCX_ERR_UNSUPPORTED_OP;
+        return build_stream(p, v == 1);
     }
     if (key == TCX_KEY_VARIANT) {
         if (p->an.path != TCX_PATH_GETT_MFMA || v < 0 || v >= gett_num_variants(p->an.dtype)) return TCX_ERR_UNSUPPORTED_OP;
@@ -453,14 +466,18 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
         g.itemsB = (const StreamItem*)(p->dev_stream + p->stream_off[3]);
         g.nItemsA = (int32_t)sp.itemsA.size(); g.nItemsB = (int32_t)sp.itemsB.size();
         g.tile = sp.tile; g.inner = sp.inner; g.chunk = sp.chunk; g.K = sp.K; g.rowsA = sp.rowsA; g.rowsB = sp.rowsB;
-        g.split_extent = sp.split_extent; g.num_tiles = sp.num_tiles; g.n_outer = sp.n_outer;
-        for (int i = 0; i < sp.n_outer; ++i) { g.oExt[i] = sp.oExt[i]; g.oSA[i] = sp.oSA[i]; g.oSB[i] = sp.oSB[i]; g.oSD[i] = sp.oSD[i]; }
+        g.regA = sp.regA; g.regB = sp.regB; g.rowStepA = sp.rowStepA; g.rowStepB = sp.rowStepB;
+        for (int i = 0; i < kStreamRegBlock; ++i) { g.dRegA[i] = sp.dRegA[i]; g.dRegB[i] = sp.dRegB[i]; }
+        g.split_extent = sp.split_extent; g.num_tiles = sp.num_tiles; g.outer_lo = sp.outer_lo;
+        g.tabLo = (const int64_t*)(p->dev_stream + p->stream_off[4]);
+        g.tabHi = (const int64_t*)(p->dev_stream + p->stream_off[5]);
         g.s = s;
         g.opA = p->an.opA; g.opB = p->an.opB; g.opC = p->an.opC;
         g.read_c = read_c;
-        hip_err = launch_stream(p->an.dtype, g, sp.lds_bytes, p->handle.num_cu, (void*)e->stream, &grid, &block);
+        hip_err = launch_stream(p->an.dtype, sp.blocked, g, sp.lds_bytes, p->handle.num_cu, (void*)e->stream, &grid, &block);
         st.path = TCX_PATH_BANDWIDTH;
-        st.tile_m = sp.tile; st.tile_n = 0; st.tile_k = sp.K;
+        st.variant = sp.blocked ? 1 : 0;
+        st.tile_m = sp.tile; st.tile_n = sp.regA * sp.regB; st.tile_k = sp.K;
     } else if (tiled) {
         const GettVariant v = gett_variant(p->an.dtype, p->variant);
         GettArgs g{};

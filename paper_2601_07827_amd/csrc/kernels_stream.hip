@@ -22,9 +22,9 @@ template <> struct SNum<double> {
     static __device__ __forceinline__ double ld(const double* p, int64_t o, int) { return p[o]; }
     static __device__ __forceinline__ double zero() { return 0.0; }
     static __device__ __forceinline__ double fma(double a, double b, double c) { return __builtin_fma(a, b, c); }
-    static __device__ __forceinline__ double out(const Scalars& s, double acc, bool rc, const double* C, int64_t o, int) {
+    static __device__ __forceinline__ double out(const Scalars& s, double acc, bool rc, double c, int) {
         double d = s.alpha_re * acc;
-        if (rc) d += s.beta_re * C[o];
+        if (rc) d += s.beta_re * c;
         return d;
     }
 };
@@ -32,9 +32,9 @@ template <> struct SNum<float> {
     static __device__ __forceinline__ float ld(const float* p, int64_t o, int) { return p[o]; }
     static __device__ __forceinline__ float zero() { return 0.0f; }
     static __device__ __forceinline__ float fma(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
-    static __device__ __forceinline__ float out(const Scalars& s, float acc, bool rc, const float* C, int64_t o, int) {
+    static __device__ __forceinline__ float out(const Scalars& s, float acc, bool rc, float c, int) {
         float d = (float)s.alpha_re * acc;
-        if (rc) d += (float)s.beta_re * C[o];
+        if (rc) d += (float)s.beta_re * c;
         return d;
     }
 };
@@ -52,10 +52,9 @@ template <> struct SNum<double2> {
         c.y = __builtin_fma(a.y, b.x, c.y);
         return c;
     }
-    static __device__ __forceinline__ double2 out(const Scalars& s, double2 acc, bool rc, const double2* C, int64_t o, int opC) {
+    static __device__ __forceinline__ double2 out(const Scalars& s, double2 acc, bool rc, double2 c, int opC) {
         double2 d{s.alpha_re * acc.x - s.alpha_im * acc.y, s.alpha_re * acc.y + s.alpha_im * acc.x};
         if (rc) {
-            double2 c = C[o];
             if (opC == TCX_OP_CONJ) c.y = -c.y;
             d.x += s.beta_re * c.x - s.beta_im * c.y;
             d.y += s.beta_re * c.y + s.beta_im * c.x;
@@ -66,65 +65,248 @@ template <> struct SNum<double2> {
 
 // KC > 0: the number of contracted terms is the compile-time constant KC (inner loop unrolled);
 // KC == 0: any K.
+//
+// Every tile has the same shape, so a thread's share of the lookup tables (which elements it
+// stages, which outputs it forms) is the same for every tile: it is read once into registers
+// before the tile loop.  Inside the loop a thread issues all its global loads back to back.
 template <class T, int KC>
 __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs g) {
     using N_ = SNum<T>;
+    constexpr int PER = kStreamPerThread;
+    constexpr unsigned NEVER = 0xffffu;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     T* sA = (T*)lds_raw;
     T* sB = sA + (size_t)g.rowsA * g.K;
     const int K = KC > 0 ? KC : g.K;
     const int tid = threadIdx.x;
 
-    for (int64_t tile = blockIdx.x; tile < g.num_tiles; tile += gridDim.x) {
-        // outer index -> base offsets of this tile (uniform over the workgroup)
-        int64_t rem = tile, baseA = 0, baseB = 0, baseD = 0, first = 0;
-        for (int i = 0; i < g.n_outer; ++i) {
-            const int64_t q = rem / g.oExt[i], idx = rem - q * g.oExt[i];
-            rem = q;
-            if (i == 0) first = idx;
-            baseA += idx * g.oSA[i];
-            baseB += idx * g.oSB[i];
-            baseD += idx * g.oSD[i];
-        }
-        // the split mode's last chunk may be ragged
-        const int64_t left = g.split_extent - first * g.chunk;
-        const unsigned digits = (unsigned)(left < g.chunk ? left : g.chunk);
-        const int valid = g.inner * (int)digits;
+    int64_t srcA[PER], srcB[PER], offD[PER];
+    unsigned packA[PER], packB[PER], rab[PER];       // pack = digit << 16 | LDS slot
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int p = tid + i * kStreamThreads;
+        srcA[i] = 0; srcB[i] = 0; offD[i] = 0;
+        packA[i] = packB[i] = NEVER << 16;
+        rab[i] = 0;
+        if (p < g.nItemsA) { const StreamItem it = g.itemsA[p]; srcA[i] = it.src; packA[i] = it.digit << 16 | it.slot; }
+        if (p < g.nItemsB) { const StreamItem it = g.itemsB[p]; srcB[i] = it.src; packB[i] = it.digit << 16 | it.slot; }
+        if (p < g.tile) { rab[i] = g.rowAB[p]; offD[i] = g.dD[p]; }
+    }
 
+    // Tile index -> base offsets through two small plan-time tables (low / high part of the
+    // outer index), one division per tile instead of one per outer mode.
+    struct Where {
+        int64_t a, b, d;
+        unsigned digits;      // valid indices along the split mode (the last chunk may be ragged)
+    };
+    auto locate = [&](int64_t tile) {
+        const int64_t hi = tile / g.outer_lo, lo = tile - hi * g.outer_lo;
+        const int64_t* pl = g.tabLo + lo * 4;
+        const int64_t* ph = g.tabHi + hi * 4;
+        return Where{pl[0] + ph[0], pl[1] + ph[1], pl[2] + ph[2], (unsigned)pl[3]};
+    };
+    T va[PER], vb[PER], vc[PER];
+    auto fetch = [&](const Where& w) {       // global loads of a tile's operands (and its C), all in flight together
+        const T* A = (const T*)g.A + w.a;
+        const T* B = (const T*)g.B + w.b;
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if ((packA[i] >> 16) < w.digits) va[i] = N_::ld(A, srcA[i], g.opA);
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if ((packB[i] >> 16) < w.digits) vb[i] = N_::ld(B, srcB[i], g.opB);
+        if (g.read_c) {
+            const T* C = (const T*)g.C + w.d;
+            const int valid = g.inner * (int)w.digits;
+#pragma unroll
+            for (int i = 0; i < PER; ++i)
+                if (tid + i * kStreamThreads < valid) vc[i] = C[offD[i]];
+        }
+    };
+
+    // Three tiles are in flight per workgroup: `cur` is computed from LDS, the operands of
+    // `nxt` travel from memory, and the table rows of the tile after that are being fetched.
+    int64_t tile = blockIdx.x;
+    if (tile >= g.num_tiles) return;
+    const int64_t step = gridDim.x;
+    Where cur = locate(tile);
+    fetch(cur);
+    Where nxt = cur;
+    if (tile + step < g.num_tiles) nxt = locate(tile + step);
+    while (true) {
         __syncthreads();          // the previous tile's reads of LDS are done
-        const T* A = (const T*)g.A + baseA;
-        const T* B = (const T*)g.B + baseB;
-        for (int p = tid; p < g.nItemsA; p += kStreamThreads) {
-            const StreamItem it = g.itemsA[p];
-            if (it.digit < digits) sA[it.slot] = N_::ld(A, it.src, g.opA);
-        }
-        for (int p = tid; p < g.nItemsB; p += kStreamThreads) {
-            const StreamItem it = g.itemsB[p];
-            if (it.digit < digits) sB[it.slot] = N_::ld(B, it.src, g.opB);
-        }
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if ((packA[i] >> 16) < cur.digits) sA[packA[i] & 0xffffu] = va[i];
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if ((packB[i] >> 16) < cur.digits) sB[packB[i] & 0xffffu] = vb[i];
         __syncthreads();
 
-        const T* C = (const T*)g.C + baseD;
-        T* D = (T*)g.D + baseD;
-        for (int e = tid; e < valid; e += kStreamThreads) {
-            const unsigned rab = g.rowAB[e];
-            const int64_t off = g.dD[e];
-            const T* a = sA + (size_t)(rab & 0xffffu) * K;
-            const T* b = sB + (size_t)(rab >> 16) * K;
-            T acc = N_::zero();
-            if (KC > 0) {
+        // C of this tile arrived with its operands; keep it while the next tile's loads reuse vc
+        T cv[PER];
 #pragma unroll
-                for (int k = 0; k < KC; ++k) acc = N_::fma(a[k], b[k], acc);
-            } else {
-                for (int k = 0; k < K; ++k) acc = N_::fma(a[k], b[k], acc);
-            }
-            D[off] = N_::out(g.s, acc, g.read_c != 0, C, off, g.opC);
+        for (int i = 0; i < PER; ++i) cv[i] = vc[i];
+        const bool more = tile + step < g.num_tiles;
+        Where after = nxt;
+        if (more) {
+            fetch(nxt);
+            if (tile + 2 * step < g.num_tiles) after = locate(tile + 2 * step);
         }
+
+        const int valid = g.inner * (int)cur.digits;
+        T* D = (T*)g.D + cur.d;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int e = tid + i * kStreamThreads;
+            if (e < valid) {
+                const T* a = sA + (size_t)(rab[i] & 0xffffu) * K;
+                const T* b = sB + (size_t)(rab[i] >> 16) * K;
+                T acc = N_::zero();
+                if (KC > 0) {
+#pragma unroll
+                    for (int k = 0; k < KC; ++k) acc = N_::fma(a[k], b[k], acc);
+                } else {
+                    for (int k = 0; k < K; ++k) acc = N_::fma(a[k], b[k], acc);
+                }
+                D[offD[i]] = N_::out(g.s, acc, g.read_c != 0, cv[i], g.opC);
+            }
+        }
+        if (!more) break;
+        tile += step;
+        cur = nxt;
+        nxt = after;
+    }
+}
+
+// Blocked tiles: thread `tid` owns lane index tid of the tile and a regA x regB block of outputs
+// (free indices of A times free indices of B held in registers): regA + regB operand rows are
+// read from LDS for regA * regB outputs.  No chunk is ragged here (the planner takes divisors).
+template <class T, int KC>
+__global__ __launch_bounds__(kStreamThreads) void stream_blocked_kernel(StreamArgs g) {
+    using N_ = SNum<T>;
+    constexpr int PER = kStreamPerThread;
+    constexpr int RB = kStreamRegBlock;
+    constexpr unsigned NEVER = 0xffffu;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    T* sA = (T*)lds_raw;
+    T* sB = sA + (size_t)g.rowsA * KC;
+    const int tid = threadIdx.x;
+
+    int64_t srcA[PER], srcB[PER];
+    unsigned slotA[PER], slotB[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int p = tid + i * kStreamThreads;
+        srcA[i] = 0; srcB[i] = 0;
+        slotA[i] = slotB[i] = NEVER;
+        if (p < g.nItemsA) { const StreamItem it = g.itemsA[p]; srcA[i] = it.src; slotA[i] = it.slot; }
+        if (p < g.nItemsB) { const StreamItem it = g.itemsB[p]; srcB[i] = it.src; slotB[i] = it.slot; }
+    }
+    const bool lane_ok = tid < g.tile;
+    const unsigned rab = lane_ok ? g.rowAB[tid] : 0u;
+    const int64_t offL = lane_ok ? g.dD[tid] : 0;
+
+    struct Where {
+        int64_t a, b, d;
+    };
+    auto locate = [&](int64_t tile) {
+        const int64_t hi = tile / g.outer_lo, lo = tile - hi * g.outer_lo;
+        const int64_t* pl = g.tabLo + lo * 4;
+        const int64_t* ph = g.tabHi + hi * 4;
+        return Where{pl[0] + ph[0], pl[1] + ph[1], pl[2] + ph[2]};
+    };
+    T va[PER], vb[PER];
+    auto fetch = [&](const Where& w) {
+        const T* A = (const T*)g.A + w.a;
+        const T* B = (const T*)g.B + w.b;
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (slotA[i] != NEVER) va[i] = N_::ld(A, srcA[i], g.opA);
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (slotB[i] != NEVER) vb[i] = N_::ld(B, srcB[i], g.opB);
+    };
+
+    int64_t tile = blockIdx.x;
+    if (tile >= g.num_tiles) return;
+    const int64_t step = gridDim.x;
+    Where cur = locate(tile);
+    fetch(cur);
+    Where nxt = cur;
+    if (tile + step < g.num_tiles) nxt = locate(tile + step);
+    while (true) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (slotA[i] != NEVER) sA[slotA[i]] = va[i];
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (slotB[i] != NEVER) sB[slotB[i]] = vb[i];
+        __syncthreads();
+
+        const bool more = tile + step < g.num_tiles;
+        Where after = nxt;
+        if (more) {
+            fetch(nxt);
+            if (tile + 2 * step < g.num_tiles) after = locate(tile + 2 * step);
+        }
+
+        if (lane_ok) {
+            const T* C = (const T*)g.C + cur.d + offL;
+            T* D = (T*)g.D + cur.d + offL;
+            T a[RB][KC], b[RB][KC];
+#pragma unroll
+            for (int r = 0; r < RB; ++r)
+                if (r < g.regA) {
+                    const T* row = sA + (size_t)((rab & 0xffffu) + r * g.rowStepA) * KC;
+#pragma unroll
+                    for (int k = 0; k < KC; ++k) a[r][k] = row[k];
+                }
+#pragma unroll
+            for (int r = 0; r < RB; ++r)
+                if (r < g.regB) {
+                    const T* row = sB + (size_t)((rab >> 16) + r * g.rowStepB) * KC;
+#pragma unroll
+                    for (int k = 0; k < KC; ++k) b[r][k] = row[k];
+                }
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                if (rb < g.regB) {
+                    T cv[RB];
+                    if (g.read_c) {
+#pragma unroll
+                        for (int ra = 0; ra < RB; ++ra)
+                            if (ra < g.regA) cv[ra] = C[g.dRegA[ra] + g.dRegB[rb]];
+                    }
+#pragma unroll
+                    for (int ra = 0; ra < RB; ++ra)
+                        if (ra < g.regA) {
+                            T acc = N_::zero();
+#pragma unroll
+                            for (int k = 0; k < KC; ++k) acc = N_::fma(a[ra][k], b[rb][k], acc);
+                            D[g.dRegA[ra] + g.dRegB[rb]] = N_::out(g.s, acc, g.read_c != 0, cv[ra], g.opC);
+                        }
+                }
+        }
+        if (!more) break;
+        tile += step;
+        cur = nxt;
+        nxt = after;
     }
 }
 
 template <class T>
-hipError_t launch_k(const StreamArgs& a, size_t lds, unsigned blocks, hipStream_t st) {
+hipError_t launch_k(bool blocked, const StreamArgs& a, size_t lds, unsigned blocks, hipStream_t st) {
+    if (blocked) {
+        switch (a.K) {
+            case 1: stream_blocked_kernel<T, 1><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
+            case 2: stream_blocked_kernel<T, 2><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
+            case 4: stream_blocked_kernel<T, 4><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
+            default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
     switch (a.K) {
         case 1: stream_kernel<T, 1><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
         case 2: stream_kernel<T, 2><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
@@ -137,8 +319,8 @@ hipError_t launch_k(const StreamArgs& a, size_t lds, unsigned blocks, hipStream_
 
 }  // namespace
 
-int launch_stream(int dtype, const StreamArgs& args, size_t lds_bytes, int num_cu, void* stream, int64_t* grid,
-                  int* block) {
+int launch_stream(int dtype, bool blocked, const StreamArgs& args, size_t lds_bytes, int num_cu, void* stream,
+                  int64_t* grid, int* block) {
     // persistent-style grid: enough workgroups to fill every CU several times over, each
     // walking the tile list with a grid stride
     const int64_t cap = (int64_t)(num_cu > 0 ? num_cu : 256) * 8;
@@ -148,9 +330,9 @@ int launch_stream(int dtype, const StreamArgs& args, size_t lds_bytes, int num_c
     if (blocks <= 0) return (int)hipErrorInvalidConfiguration;
     hipStream_t st = (hipStream_t)stream;
     switch (dtype) {
-        case TCX_F64: return (int)launch_k<double>(args, lds_bytes, (unsigned)blocks, st);
-        case TCX_F32: return (int)launch_k<float>(args, lds_bytes, (unsigned)blocks, st);
-        case TCX_C128: return (int)launch_k<double2>(args, lds_bytes, (unsigned)blocks, st);
+        case TCX_F64: return (int)launch_k<double>(blocked, args, lds_bytes, (unsigned)blocks, st);
+        case TCX_F32: return (int)launch_k<float>(blocked, args, lds_bytes, (unsigned)blocks, st);
+        case TCX_C128: return (int)launch_k<double2>(blocked, args, lds_bytes, (unsigned)blocks, st);
         default: return (int)hipErrorInvalidValue;
     }
 }

@@ -1,5 +1,11 @@
 // Planner of the bandwidth (streaming) path: picks the output tile from D's fastest modes and
 // builds the per-tile lookup tables.  Pure host code.
+//
+// A tile is a list of pieces.  A piece takes `count` consecutive indices of one D mode.  LANE
+// pieces (D's fastest modes) form the index that runs across the threads, so stores are
+// contiguous in D; REG_A / REG_B pieces are free modes of A / of B that each thread walks in
+// registers, so an operand row fetched from LDS is reused for several outputs ("blocked"
+// tiles).  What a piece leaves of its mode becomes an outer mode that the grid walks.
 #include <algorithm>
 #include <cstdlib>
 
@@ -13,7 +19,192 @@ struct DMode {
     bool inA, inB;
 };
 
+enum Role { LANE = 0, REG_A = 1, REG_B = 2 };
+
+struct Piece {
+    int mode;        // index into the D-ordered mode list
+    int64_t count;   // indices taken per tile
+    int64_t mult;    // index = digit * mult (+ what other pieces / the outer loop add)
+    int role;
+};
+
 inline int64_t iabs64(int64_t x) { return x < 0 ? -x : x; }
+
+int64_t largest_divisor_at_most(int64_t n, int64_t cap) {
+    for (int64_t c = std::min(n, cap); c > 1; --c)
+        if (n % c == 0) return c;
+    return 1;
+}
+
+// Fill every table of `p` from the chosen pieces.  `ragged`: the last LANE piece may not divide
+// its mode (flat tiles only); its digit is recorded so the kernel can mask the last chunk.
+bool build(const std::vector<DMode>& dm, const std::vector<Piece>& pieces, bool ragged, const Analysis& an, int elem_bytes,
+           StreamPlan* out) {
+    StreamPlan p;
+    const int K = (int)an.sizeK;
+    p.K = K;
+    // sizes
+    int64_t lanes = 1, ra = 1, rb = 1, rowsA_lane = 1, rowsB_lane = 1;
+    for (const Piece& pc : pieces) {
+        if (pc.role == LANE) {
+            lanes *= pc.count;
+            if (dm[(size_t)pc.mode].inA) rowsA_lane *= pc.count;
+            if (dm[(size_t)pc.mode].inB) rowsB_lane *= pc.count;
+        } else if (pc.role == REG_A) {
+            ra *= pc.count;
+        } else {
+            rb *= pc.count;
+        }
+    }
+    const int64_t rowsA = rowsA_lane * ra, rowsB = rowsB_lane * rb;
+    const int64_t cap = (int64_t)kStreamThreads * kStreamPerThread;      // what a workgroup's registers hold
+    const size_t lds = (size_t)(rowsA + rowsB) * (size_t)K * (size_t)elem_bytes;
+    const bool blocked = ra * rb > 1;
+    if (lds > 64 * 1024 || rowsA * K > cap || rowsB * K > cap || rowsA > 65535 || rowsB > 65535) return false;
+    if (blocked ? lanes > kStreamThreads : lanes > cap) return false;
+    if (ra > kStreamRegBlock || rb > kStreamRegBlock) return false;
+
+    p.blocked = blocked;
+    p.tile = (int32_t)lanes;
+    p.regA = (int32_t)ra; p.regB = (int32_t)rb;
+    p.rowsA = (int32_t)rowsA; p.rowsB = (int32_t)rowsB;
+    p.rowStepA = (int32_t)rowsA_lane; p.rowStepB = (int32_t)rowsB_lane;
+    p.lds_bytes = lds;
+
+    // the ragged piece, if any, is the last LANE piece
+    int last_lane = -1;
+    for (size_t i = 0; i < pieces.size(); ++i)
+        if (pieces[i].role == LANE) last_lane = (int)i;
+    const bool has_split = ragged && last_lane >= 0 && pieces[(size_t)last_lane].count < dm[(size_t)pieces[(size_t)last_lane].mode].m.extent;
+    p.chunk = has_split ? (int32_t)pieces[(size_t)last_lane].count : 1;
+    p.split_extent = has_split ? dm[(size_t)pieces[(size_t)last_lane].mode].m.extent : 1;
+    p.inner = (int32_t)(lanes / p.chunk);
+
+    // lane tables: walk the LANE pieces, first fastest
+    std::vector<const Piece*> lp, apieces, bpieces;
+    for (const Piece& pc : pieces) if (pc.role == LANE) lp.push_back(&pc);
+    p.rowAB.assign((size_t)lanes, 0);
+    p.dD.assign((size_t)lanes, 0);
+    {
+        std::vector<int64_t> idx(lp.size(), 0);
+        for (int64_t l = 0; l < lanes; ++l) {
+            int64_t rA = 0, rB = 0, wa = 1, wb = 1, offD = 0;
+            for (size_t i = 0; i < lp.size(); ++i) {
+                const DMode& d = dm[(size_t)lp[i]->mode];
+                offD += idx[i] * lp[i]->mult * d.m.sD;
+                if (d.inA) { rA += idx[i] * wa; wa *= lp[i]->count; }
+                if (d.inB) { rB += idx[i] * wb; wb *= lp[i]->count; }
+            }
+            p.rowAB[(size_t)l] = (uint32_t)rA | ((uint32_t)rB << 16);
+            p.dD[(size_t)l] = offD;
+            for (size_t i = 0; i < lp.size(); ++i) {
+                if (++idx[i] < lp[i]->count) break;
+                idx[i] = 0;
+            }
+        }
+    }
+    // register-block offsets in D
+    auto reg_offsets = [&](int role, int64_t n, int64_t* dst) {
+        std::vector<const Piece*> rp;
+        for (const Piece& pc : pieces) if (pc.role == role) rp.push_back(&pc);
+        std::vector<int64_t> idx(rp.size(), 0);
+        for (int64_t r = 0; r < n; ++r) {
+            int64_t off = 0;
+            for (size_t i = 0; i < rp.size(); ++i) off += idx[i] * rp[i]->mult * dm[(size_t)rp[i]->mode].m.sD;
+            dst[r] = off;
+            for (size_t i = 0; i < rp.size(); ++i) {
+                if (++idx[i] < rp[i]->count) break;
+                idx[i] = 0;
+            }
+        }
+    };
+    for (int i = 0; i < kStreamRegBlock; ++i) p.dRegA[i] = p.dRegB[i] = 0;
+    reg_offsets(REG_A, ra, p.dRegA);
+    reg_offsets(REG_B, rb, p.dRegB);
+
+    // staging lists.  Rows are numbered over the pieces the operand carries: LANE pieces first
+    // (as in the lane tables), then its REG pieces.
+    const std::vector<int64_t> kA = offset_table(an.K, 0, 0), kB = offset_table(an.K, 1, 0);
+    auto items = [&](bool forA, int64_t rows, const std::vector<int64_t>& kOff) {
+        std::vector<const Piece*> op;
+        for (const Piece& pc : pieces)
+            if (pc.role == LANE && (forA ? dm[(size_t)pc.mode].inA : dm[(size_t)pc.mode].inB)) op.push_back(&pc);
+        for (const Piece& pc : pieces)
+            if (pc.role == (forA ? REG_A : REG_B)) op.push_back(&pc);
+        std::vector<StreamItem> v;
+        v.reserve((size_t)rows * (size_t)K);
+        std::vector<int64_t> idx(op.size(), 0);
+        for (int64_t r = 0; r < rows; ++r) {
+            int64_t src = 0;
+            uint32_t digit = 0;
+            for (size_t i = 0; i < op.size(); ++i) {
+                const Mode& m = dm[(size_t)op[i]->mode].m;
+                src += idx[i] * op[i]->mult * (forA ? m.sA : m.sB);
+                if (has_split && op[i] == &pieces[(size_t)last_lane]) digit = (uint32_t)idx[i];
+            }
+            for (int k = 0; k < K; ++k) v.push_back({src + kOff[(size_t)k], (uint32_t)(r * K + k), digit});
+            for (size_t i = 0; i < op.size(); ++i) {
+                if (++idx[i] < op[i]->count) break;
+                idx[i] = 0;
+            }
+        }
+        // sorted by source so that neighbouring lanes read neighbouring addresses whatever the
+        // operand's own mode order is
+        std::stable_sort(v.begin(), v.end(), [](const StreamItem& a, const StreamItem& b) { return a.src < b.src; });
+        return v;
+    };
+    p.itemsA = items(true, rowsA, kA);
+    p.itemsB = items(false, rowsB, kB);
+
+    // outer modes: what the pieces leave of every D mode, the ragged mode first (its chunk index
+    // decides how much of the last tile is valid)
+    std::vector<int64_t> taken(dm.size(), 1);
+    for (const Piece& pc : pieces) taken[(size_t)pc.mode] *= pc.count;
+    struct Outer { int64_t ext, sA, sB, sD; };
+    std::vector<Outer> outer;
+    auto push_outer = [&](size_t i) {
+        const Mode& m = dm[i].m;
+        const int64_t ext = (m.extent + taken[i] - 1) / taken[i];
+        if (ext > 1 || (has_split && (int)i == pieces[(size_t)last_lane].mode)) outer.push_back({ext, m.sA * taken[i], m.sB * taken[i], m.sD * taken[i]});
+    };
+    if (has_split) push_outer((size_t)pieces[(size_t)last_lane].mode);
+    for (size_t i = 0; i < dm.size(); ++i)
+        if (!(has_split && (int)i == pieces[(size_t)last_lane].mode)) push_outer(i);
+    p.num_tiles = 1;
+    for (const Outer& o : outer) p.num_tiles *= o.ext;
+
+    // two-level table of tile base offsets: the first outer modes (product near the square
+    // root of the tile count) form the low part, the rest the high part
+    size_t nlo = 0;
+    p.outer_lo = 1;
+    while (nlo < outer.size() && p.outer_lo * p.outer_lo < p.num_tiles) p.outer_lo *= outer[nlo++].ext;
+    if (has_split && nlo == 0) { nlo = 1; p.outer_lo = outer[0].ext; }
+    auto table = [&](size_t first, size_t last, bool with_digits) {
+        int64_t n = 1;
+        for (size_t i = first; i < last; ++i) n *= outer[i].ext;
+        std::vector<int64_t> t((size_t)n * 4, 0);
+        std::vector<int64_t> ix(std::max<size_t>(1, last - first), 0);
+        for (int64_t r = 0; r < n; ++r) {
+            for (size_t i = first; i < last; ++i) {
+                t[(size_t)r * 4 + 0] += ix[i - first] * outer[i].sA;
+                t[(size_t)r * 4 + 1] += ix[i - first] * outer[i].sB;
+                t[(size_t)r * 4 + 2] += ix[i - first] * outer[i].sD;
+            }
+            if (with_digits) t[(size_t)r * 4 + 3] = has_split ? std::min<int64_t>(p.chunk, p.split_extent - ix[0] * p.chunk) : 1;
+            for (size_t i = first; i < last; ++i) {
+                if (++ix[i - first] < outer[i].ext) break;
+                ix[i - first] = 0;
+            }
+        }
+        return t;
+    };
+    p.tabLo = table(0, nlo, true);
+    p.tabHi = table(nlo, outer.size(), false);
+    p.staged_per_output = (double)(p.itemsA.size() + p.itemsB.size()) / (double)(lanes * ra * rb);
+    p.ok = true;
+    *out = std::move(p);
+    return true;
+}
 
 }  // namespace
 
@@ -26,7 +217,7 @@ bool stream_preferred(const Analysis& an, int elem_bytes) {
     return an.sizeK <= 32 && flop / bytes < ridge;
 }
 
-StreamPlan plan_stream(const Analysis& an, int elem_bytes) {
+StreamPlan plan_stream(const Analysis& an, int elem_bytes, bool allow_blocked) {
     StreamPlan p;
     if (an.sizeK > 64) return p;
     // every mode that indexes D, D-fastest first
@@ -37,87 +228,94 @@ StreamPlan plan_stream(const Analysis& an, int elem_bytes) {
     std::stable_sort(dm.begin(), dm.end(), [](const DMode& a, const DMode& b) { return iabs64(a.m.sD) < iabs64(b.m.sD); });
     const int K = (int)an.sizeK;
 
-    for (int target = 2048; target >= 64 && !p.ok; target /= 2) {
-        // whole modes while they fit, then a chunk of the next one
-        size_t nfull = 0;
-        int64_t inner = 1;
-        while (nfull < dm.size() && inner * dm[nfull].m.extent <= target) inner *= dm[nfull++].m.extent;
-        int64_t chunk = 1, split_extent = 1;
-        const bool has_split = nfull < dm.size() && inner < target;
-        if (has_split) {
-            split_extent = dm[nfull].m.extent;
-            chunk = std::min<int64_t>(split_extent, std::max<int64_t>(1, target / inner));
-        }
-        int64_t rowsA = 1, rowsB = 1;
-        for (size_t i = 0; i < nfull; ++i) {
-            if (dm[i].inA) rowsA *= dm[i].m.extent;
-            if (dm[i].inB) rowsB *= dm[i].m.extent;
-        }
-        if (has_split && dm[nfull].inA) rowsA *= chunk;
-        if (has_split && dm[nfull].inB) rowsB *= chunk;
-        const int64_t tile = inner * chunk;
-        const size_t lds = (size_t)(rowsA + rowsB) * K * elem_bytes;
-        if (lds > 60 * 1024 || rowsA > 65535 || rowsB > 65535) continue;
-
-        p.tile = (int32_t)tile; p.inner = (int32_t)inner; p.chunk = (int32_t)chunk; p.split_extent = split_extent;
-        p.rowsA = (int32_t)rowsA; p.rowsB = (int32_t)rowsB; p.K = K;
-        p.split_in_A = has_split && dm[nfull].inA; p.split_in_B = has_split && dm[nfull].inB;
-        p.lds_bytes = lds;
-
-        // tile-local tables: walk the tile in D order (first tile mode fastest)
-        std::vector<DMode> tm(dm.begin(), dm.begin() + (long)nfull);
-        if (has_split) { DMode s = dm[nfull]; s.m.extent = chunk; tm.push_back(s); }
-        p.rowAB.assign((size_t)tile, 0);
-        p.dD.assign((size_t)tile, 0);
-        std::vector<int64_t> rowSrcA((size_t)rowsA, 0), rowSrcB((size_t)rowsB, 0);
-        std::vector<uint32_t> rowDigA((size_t)rowsA, 0), rowDigB((size_t)rowsB, 0);
-        std::vector<int64_t> idx(tm.size(), 0);
-        for (int64_t e = 0; e < tile; ++e) {
-            int64_t ra = 0, rb = 0, wa = 1, wb = 1, offA = 0, offB = 0, offD = 0;
-            for (size_t i = 0; i < tm.size(); ++i) {
-                offD += idx[i] * tm[i].m.sD;
-                if (tm[i].inA) { ra += idx[i] * wa; wa *= tm[i].m.extent; offA += idx[i] * tm[i].m.sA; }
-                if (tm[i].inB) { rb += idx[i] * wb; wb *= tm[i].m.extent; offB += idx[i] * tm[i].m.sB; }
+    // ---- blocked tile: up to 256 lanes along D's fastest modes (whole modes or divisors, so no
+    // chunk is ragged), then up to 4 x 4 register-blocked indices of free modes of A and of B.
+    // If the operand rows of such a tile do not fit a workgroup's registers / LDS, smaller
+    // lane counts and register blocks are tried, most operand reuse first.
+    if (allow_blocked && (K == 1 || K == 2 || K == 4)) {
+        static const int kTry[][2] = {{256, 4}, {128, 4}, {256, 2}, {64, 4}, {128, 2}};
+        for (const auto& t : kTry) {
+            const int64_t lane_cap = t[0], reg_cap = t[1];
+            std::vector<Piece> pieces;
+            std::vector<int64_t> left(dm.size());       // what is still untaken of each mode
+            std::vector<int64_t> mult(dm.size(), 1);
+            for (size_t i = 0; i < dm.size(); ++i) left[i] = dm[i].m.extent;
+            int64_t lanes = 1;
+            size_t pos = 0;
+            for (; pos < dm.size(); ++pos) {
+                const int64_t c = largest_divisor_at_most(left[pos], lane_cap / lanes);
+                if (c <= 1) break;
+                pieces.push_back({(int)pos, c, 1, LANE});
+                lanes *= c; left[pos] /= c; mult[pos] *= c;
+                if (left[pos] > 1) break;
             }
-            p.rowAB[(size_t)e] = (uint32_t)ra | ((uint32_t)rb << 16);
-            p.dD[(size_t)e] = offD;
-            rowSrcA[(size_t)ra] = offA; rowSrcB[(size_t)rb] = offB;
-            const uint32_t dig = has_split ? (uint32_t)idx.back() : 0;
-            if (p.split_in_A) rowDigA[(size_t)ra] = dig;
-            if (p.split_in_B) rowDigB[(size_t)rb] = dig;
-            for (size_t i = 0; i < tm.size(); ++i) {
-                if (++idx[i] < tm[i].m.extent) break;
-                idx[i] = 0;
+            int64_t ra = 1, rb = 1;
+            for (size_t i = pos; i < dm.size() && i < pos + 8; ++i) {
+                if (left[i] <= 1 || dm[i].inA == dm[i].inB) continue;      // hyper modes give no reuse
+                int64_t& r = dm[i].inA ? ra : rb;
+                const int64_t c = largest_divisor_at_most(left[i], reg_cap / r);
+                if (c <= 1) continue;
+                pieces.push_back({(int)i, c, mult[i], dm[i].inA ? REG_A : REG_B});
+                r *= c; left[i] /= c; mult[i] *= c;
+            }
+            if (ra * rb > 1 && lanes >= 64 && build(dm, pieces, false, an, elem_bytes, &p)) return p;
+        }
+    }
+
+    // ---- flat tile.  It starts with a run of D's fastest mode; if A's or B's own fastest mode is
+    // a different mode of D, a run of that mode is taken too, so that all three tensors are
+    // touched in runs of whole cache lines (LDS does the transposition).  The rest of the tile
+    // is filled with D's next modes; only the last piece may be ragged.
+    const int64_t run = std::max<int64_t>(4, 128 / elem_bytes);
+    auto fastest_of = [&](bool forA) {
+        int best = -1;
+        for (size_t i = 0; i < dm.size(); ++i) {
+            if (!(forA ? dm[i].inA : dm[i].inB)) continue;
+            const int64_t s = iabs64(forA ? dm[i].m.sA : dm[i].m.sB);
+            if (s == 0) continue;
+            if (best < 0 || s < iabs64(forA ? dm[(size_t)best].m.sA : dm[(size_t)best].m.sB)) best = (int)i;
+        }
+        // a contracted mode may be faster still; then the operand is read in runs along K anyway
+        for (const Mode& k : an.K)
+            if (best >= 0 && iabs64(forA ? k.sA : k.sB) != 0 &&
+                iabs64(forA ? k.sA : k.sB) < iabs64(forA ? dm[(size_t)best].m.sA : dm[(size_t)best].m.sB) && an.sizeK >= 4)
+                return -1;
+        return best;
+    };
+    std::vector<int> fast;          // distinct D modes that must contribute a run
+    if (!dm.empty()) fast.push_back(0);
+    for (int f : {fastest_of(true), fastest_of(false)})
+        if (f >= 0 && std::find(fast.begin(), fast.end(), f) == fast.end()) fast.push_back(f);
+    for (int target = kStreamThreads * kStreamPerThread; target >= 64; target /= 2) {
+        std::vector<Piece> pieces;
+        std::vector<int64_t> left(dm.size());
+        for (size_t i = 0; i < dm.size(); ++i) left[i] = dm[i].m.extent;
+        int64_t lanes = 1;
+        if (fast.size() > 1) {
+            // equal shares of the tile for each run, at least a cache line where the extent allows
+            int64_t share = 1;
+            while ((share * 2) * (share * 2) * (fast.size() > 2 ? share * 2 : 1) <= target) share *= 2;
+            share = std::max(share, std::min<int64_t>(run, target));
+            for (int f : fast) {
+                const int64_t c = largest_divisor_at_most(left[(size_t)f], std::min<int64_t>(share, target / lanes));
+                if (c <= 1) continue;
+                pieces.push_back({f, c, 1, LANE});
+                lanes *= c; left[(size_t)f] /= c;
             }
         }
-        // staging lists: (row, k) -> source offset; sorted by source so neighbouring lanes read
-        // neighbouring addresses whatever the operand's own mode order is
-        const std::vector<int64_t> kA = offset_table(an.K, 0, 0), kB = offset_table(an.K, 1, 0);
-        auto items = [&](const std::vector<int64_t>& rowSrc, const std::vector<uint32_t>& dig, const std::vector<int64_t>& kOff) {
-            std::vector<StreamItem> v;
-            v.reserve(rowSrc.size() * (size_t)K);
-            for (size_t r = 0; r < rowSrc.size(); ++r)
-                for (int k = 0; k < K; ++k) v.push_back({rowSrc[r] + kOff[(size_t)k], (uint32_t)(r * (size_t)K + (size_t)k), dig[r]});
-            std::stable_sort(v.begin(), v.end(), [](const StreamItem& a, const StreamItem& b) { return a.src < b.src; });
-            return v;
-        };
-        p.itemsA = items(rowSrcA, rowDigA, kA);
-        p.itemsB = items(rowSrcB, rowDigB, kB);
-
-        // outer loop modes: chunks of the split mode, then the rest of D's modes
-        p.n_outer = 0;
-        p.num_tiles = 1;
-        auto push_outer = [&](int64_t ext, int64_t sA, int64_t sB, int64_t sD) {
-            p.oExt[p.n_outer] = ext; p.oSA[p.n_outer] = sA; p.oSB[p.n_outer] = sB; p.oSD[p.n_outer] = sD;
-            ++p.n_outer;
-            p.num_tiles *= ext;
-        };
-        if (has_split) {
-            const Mode& s = dm[nfull].m;
-            push_outer((split_extent + chunk - 1) / chunk, s.sA * chunk, s.sB * chunk, s.sD * chunk);
+        for (size_t i = 0; i < dm.size() && lanes < target; ++i) {
+            if (left[i] <= 1) continue;
+            const bool untouched = left[i] == dm[i].m.extent;
+            if (untouched && lanes * left[i] <= target) {
+                pieces.push_back({(int)i, left[i], 1, LANE});
+                lanes *= left[i]; left[i] = 1;
+            } else if (untouched) {
+                const int64_t chunk = std::min<int64_t>(left[i], std::max<int64_t>(1, target / lanes));
+                if (chunk > 1) { pieces.push_back({(int)i, chunk, 1, LANE}); lanes *= chunk; }
+                break;          // a ragged piece must be the last one
+            }
         }
-        for (size_t i = nfull + (has_split ? 1 : 0); i < dm.size(); ++i) push_outer(dm[i].m.extent, dm[i].m.sA, dm[i].m.sB, dm[i].m.sD);
-        p.ok = p.n_outer <= kMaxOuterModes;
+        if (build(dm, pieces, true, an, elem_bytes, &p)) return p;
     }
     return p;
 }

@@ -109,8 +109,9 @@ int launch_gett(int dtype, int variant, bool a_kf, bool b_kf, bool d_nf, const G
 // needs through LDS with loads that follow A's and B's own memory order, and streams D out.
 namespace tcx {
 
-constexpr int kMaxOuterModes = 32;
 constexpr int kStreamThreads = 256;
+constexpr int kStreamRegBlock = 4;    // a thread's register block is at most 4 x 4 outputs
+constexpr int kStreamPerThread = 8;   // table entries a thread keeps in registers: tile, staged items <= 2048
 
 struct StreamItem {        // one element to stage: where it comes from and where it goes
     int64_t src;           // element offset relative to the tile's base in A (or B)
@@ -120,21 +121,25 @@ struct StreamItem {        // one element to stage: where it comes from and wher
 
 struct StreamPlan {
     bool ok = false;
-    int32_t tile = 0;          // output elements per full tile = inner * chunk
-    int32_t inner = 0;         // product of the tile modes below the split mode
-    int32_t chunk = 0;         // indices of the split mode per tile
-    int64_t split_extent = 1;  // extent of the split mode (1 if none)
+    bool blocked = false;      // threads own a regA x regB register block of outputs
+    int32_t tile = 0;          // lane indices per tile (flat: outputs per full tile = inner * chunk)
+    int32_t inner = 0;         // flat tiles: product of the tile modes below the split mode
+    int32_t chunk = 1;         // flat tiles: indices of the split mode per tile
+    int64_t split_extent = 1;  // flat tiles: extent of the split mode (1 if none)
     int32_t rowsA = 0, rowsB = 0, K = 0;
-    int32_t split_in_A = 0, split_in_B = 0;   // does A (B) carry the split mode
+    int32_t regA = 1, regB = 1;            // register block (blocked tiles)
+    int32_t rowStepA = 0, rowStepB = 0;    // row increment per register index
+    int64_t dRegA[kStreamRegBlock], dRegB[kStreamRegBlock];   // D offset per register index
     int64_t num_tiles = 0;
-    // outer loop: the split mode's chunks first, then the remaining D modes
-    int32_t n_outer = 0;
-    int64_t oExt[kMaxOuterModes], oSA[kMaxOuterModes], oSB[kMaxOuterModes], oSD[kMaxOuterModes];
     // host tables
-    std::vector<uint32_t> rowAB;     // [tile]: rowA | rowB << 16
-    std::vector<int64_t> dD;         // [tile]: D offset relative to the tile base
+    std::vector<uint32_t> rowAB;     // [tile]: rowA | rowB << 16 of a lane index
+    std::vector<int64_t> dD;         // [tile]: D offset of a lane index relative to the tile base
     std::vector<StreamItem> itemsA, itemsB;
+    // tile index -> base offsets: tile = lo + outer_lo * hi; rows are (offA, offB, offD, digits)
+    int64_t outer_lo = 1;
+    std::vector<int64_t> tabLo, tabHi;
     size_t lds_bytes = 0;
+    double staged_per_output = 0;    // operand elements staged per output element (traffic overhead)
 };
 
 struct StreamArgs {
@@ -148,21 +153,24 @@ struct StreamArgs {
     const StreamItem* itemsB;
     int32_t nItemsA, nItemsB;
     int32_t tile, inner, chunk, K, rowsA, rowsB;
+    int32_t regA, regB, rowStepA, rowStepB;
+    int64_t dRegA[kStreamRegBlock], dRegB[kStreamRegBlock];
     int64_t split_extent;
     int64_t num_tiles;
-    int32_t n_outer;
-    int64_t oExt[kMaxOuterModes], oSA[kMaxOuterModes], oSB[kMaxOuterModes], oSD[kMaxOuterModes];
+    int64_t outer_lo;          // number of rows of tabLo
+    const int64_t* tabLo;      // [outer_lo][4]
+    const int64_t* tabHi;      // [num_tiles / outer_lo][4]
     Scalars s;
     int32_t opA, opB, opC;
     int32_t read_c;
 };
 
 // Host: lay out the streaming plan for an analysed product (stream_plan.cpp).
-StreamPlan plan_stream(const Analysis& an, int elem_bytes);
+StreamPlan plan_stream(const Analysis& an, int elem_bytes, bool allow_blocked = true);
 // Arithmetic intensity test + size limits: should this product take the streaming path?
 bool stream_preferred(const Analysis& an, int elem_bytes);
 
-int launch_stream(int dtype, const StreamArgs& args, size_t lds_bytes, int num_cu, void* stream, int64_t* grid,
-                  int* block);
+int launch_stream(int dtype, bool blocked, const StreamArgs& args, size_t lds_bytes, int num_cu, void* stream,
+                  int64_t* grid, int* block);
 
 }  // namespace tcx

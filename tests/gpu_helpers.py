@@ -75,7 +75,7 @@ def run_gpu(p: W.Problem, bufA, bufB, bufC, force_path=None, variant=None, alpha
         torch.cuda.synchronize()
         if force_path is not None and (alpha is None or alpha != 0):
             assert gp.last_path == force_path, "the forced path did not run"
-        if variant is not None:
+        if variant is not None and force_path != 2:
             assert gp.last_variant == variant
         return dD.cpu().numpy()
     finally:

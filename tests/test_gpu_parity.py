@@ -31,9 +31,9 @@ def _check(p, a, b, c, path, variant, exact=False, truth=None, S=None):
         truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
     try:
         got = run_gpu(p, a, b, c, force_path=path, variant=variant)
-    except Exception as exc:                       # the streaming path declines large |K|
-        if path == STREAM and getattr(exc, "code", None) == 11 and p.sizes()[3] > 64:
-            say("  (streaming path not applicable: |K| = %d)" % p.sizes()[3])
+    except Exception as exc:                       # the streaming path may decline large |K| (operand rows must fit LDS)
+        if path == STREAM and getattr(exc, "code", None) == 11 and p.sizes()[3] > 8:
+            say("  (streaming path declined: |K| = %d)" % p.sizes()[3])
             return
         raise
     assert gaps_untouched(p, c, got), "elements outside (extents, strides) of D were modified"
@@ -100,14 +100,14 @@ def test_low_intensity_shapes_all_paths(p):
     path, the tiled path and the generic path against the oracle; bit-exact on integer inputs."""
     a, b, c = W.make_operands(p)
     truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
-    for path, variant in [(GENERIC, None), (GETT, None), (STREAM, None), (None, None)]:
+    for path, variant in [(GENERIC, None), (GETT, None), (STREAM, None), (STREAM, 0), (None, None)]:
         _check(p, a, b, c, path, variant, truth=truth, S=S)
     a, b, c = W.make_operands(p, "ints")
     p2 = W.Problem(p.name + "_ints", p.dtype, p.A, p.B, p.D, alpha=-2.0, beta=(4.0 if p.beta != 0 else 0.0),
                    opA=p.opA, opB=p.opB, opC=p.opC, seed=p.seed)
     truth, S = run_oracle(p2, a, b, c, oracle.MODE_TRUTH, want_S=True)
-    for path in (GETT, STREAM):
-        _check(p2, a, b, c, path, None, exact=True, truth=truth, S=S)
+    for path, variant in ((GETT, None), (STREAM, None), (STREAM, 0)):
+        _check(p2, a, b, c, path, variant, exact=True, truth=truth, S=S)
 
 
 FULL = [W.config1(), W.config3(), W.config3(d_layout="R2"), W.config4(), W.config4(h_slowest=True), W.config5()]
