@@ -36,6 +36,7 @@ DT = {"f32": 0, "f64": 1, "c128": 3}
 def make_problem(name: str) -> W.Problem:
     table = {"cfg1": W.config1, "cfg2": W.config2, "cfg3": W.config3, "cfg4": W.config4, "cfg5": W.config5,
              "cfg3r2": lambda: W.config3(d_layout="R2"), "cfg4hs": lambda: W.config4(h_slowest=True),
+             "gemm1k": lambda: W.config2(v=32, o=32),      # contiguous 1024^3 product, same size as cfg5
              # supplementary HBM-bound shapes
              "s1": lambda: W.config5(extent=4, nshared=1, nfree=7), "s2": lambda: W.config5(extent=4, nshared=0, nfree=7),
              "s3": lambda: W.hadamard(4, 128), "s3p": lambda: W.hadamard(4, 128, permuted=True),
@@ -121,7 +122,8 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--variant", type=int, default=None, help="force a tiled-kernel instantiation")
-    ap.add_argument("--path", type=int, default=None, help="force a kernel path (0 generic, 1 tiled MFMA)")
+    ap.add_argument("--path", type=int, default=None, help="force a kernel path (0 generic, 1 tiled MFMA, 2 streaming)")
+    ap.add_argument("--split-k", type=int, default=None, help="force the number of parts of the contracted range (tiled path)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB streaming kernel (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -152,6 +154,8 @@ def main():
         T.tcx_product_set(prod, T.TCX_KEY_FORCE_PATH, args.path)
     if args.variant is not None:
         T.tcx_product_set(prod, T.TCX_KEY_VARIANT, args.variant)
+    if args.split_k is not None:
+        T.tcx_product_set(prod, T.TCX_KEY_SPLIT_K, args.split_k)
     item = dD.element_size()
     pA, pB, pD = (t.data_ptr() + s.base * item for t, s in ((dA, p.A), (dB, p.B), (dD, p.D)))
 
@@ -204,6 +208,7 @@ def main():
     cfg = {"workload": p.name, "sizes_HMNK": list(p.sizes()), "alpha": complex(p.alpha).real, "beta": complex(p.beta).real,
            "path": T.tcx_product_get(prod, T.TCX_KEY_PATH), "variant": T.tcx_product_get(prod, T.TCX_KEY_VARIANT),
            "tile": [T.tcx_product_get(prod, k) for k in (T.TCX_KEY_TILE_M, T.TCX_KEY_TILE_N, T.TCX_KEY_TILE_K)],
+           "split_k": T.tcx_product_get(prod, T.TCX_KEY_SPLIT_K),
            "grid": T.tcx_product_get(prod, T.TCX_KEY_GRID), "plan_ms": plan_ms,
            "flop_per_step": flops, "algorithmic_bytes_per_step": p.algorithmic_bytes()}
 

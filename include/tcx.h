@@ -35,8 +35,10 @@
  *    address are left bit-unchanged.
  *  - tcx_execute_product enqueues work on the executor's stream and returns; argument
  *    errors are reported synchronously, before anything is enqueued.
- *  - Objects are immutable after creation; concurrent execution of one product on
- *    different executors is allowed.
+ *  - Objects are immutable after creation (tcx_product_set aside).  A product whose plan cuts
+ *    the contracted range into parts (TCX_KEY_SPLIT_K > 1) owns a device workspace for the
+ *    partial sums: executions of that one product must not overlap in time.  Other products
+ *    may be executed concurrently on different executors.
  */
 #ifndef TCX_H
 #define TCX_H
@@ -148,7 +150,8 @@ enum {
     TCX_KEY_MODES_N = 21,
     TCX_KEY_MODES_K = 22,
     TCX_KEY_MODES_H = 23,
-    TCX_KEY_FORCE_PATH = 24    /* tcx_product_set only: force a tcx_path_t (testing, tuning) */
+    TCX_KEY_FORCE_PATH = 24,   /* tcx_product_set only: force a tcx_path_t (testing, tuning) */
+    TCX_KEY_SPLIT_K = 25       /* tiled path: number of parts the contracted range is cut into (1 = unsplit) */
 };
 typedef enum {
     TCX_PATH_GENERIC = 0,      /* one thread per element of D, loops over the contracted index space */

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <mutex>
@@ -32,6 +33,9 @@ struct Product {
     Handle handle;
     Analysis an;
     int variant = 0;                 // index into the tiled kernel instantiations
+    int splitK = 1;                  // parts the K slabs are divided into (tiled path)
+    void* workspace = nullptr;       // split-K partial accumulators, device memory owned by the plan
+    size_t workspace_bytes = 0;
     // offset tables, host copies and one device allocation holding all six
     std::vector<int64_t> tables[6];  // oAM oAK oBN oBK oDM oDN
     int64_t* dev_tables = nullptr;
@@ -77,22 +81,37 @@ template <class T> tcx_error_t retire(intptr_t* h, uint32_t magic) {
 
 int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
-// Cost model for the tile shape: rounds of workgroups over the chip x padded tile area /
-// the shape's relative efficiency.  Large tiles win when there are enough of them; small
-// problems fall to small tiles that still fill the CUs.
-int choose_variant(const Analysis& an, int num_cu) {
+int64_t tiles_of(const Analysis& an, const GettVariant& s) {
+    return ((an.sizeM + s.mt_m - 1) / s.mt_m) * ((an.sizeN + s.mt_n - 1) / s.mt_n) * an.sizeH;
+}
+
+// Cost model for tile shape and split-K, in microseconds.  A workgroup's time is its slabs at
+// the shape's fraction of the CU's matrix peak plus a fixed prologue/epilogue; the grid runs
+// in rounds over the CUs; split-K adds a second launch and the traffic of the partial
+// accumulators.  Large tiles win when there are enough of them; small problems are cut
+// along K to fill the chip.
+void choose_plan(const Analysis& an, int num_cu, int* variant, int* splitK) {
     const int n = gett_num_variants(an.dtype);
-    const int64_t cus = num_cu > 0 ? num_cu : 256;
-    int best = 0;
-    double best_cost = 0;
+    const double cus = num_cu > 0 ? num_cu : 256;
+    const double cu_flops = (an.dtype == TCX_F32 ? 157.3e12 : 78.6e12) / 256.0;
+    const double flop_per_mac = an.dtype == TCX_C128 ? 8.0 : 2.0;
+    const int ebytes = an.dtype == TCX_F32 ? 4 : an.dtype == TCX_F64 ? 8 : 16;
+    double best = -1;
     for (int v = 0; v < n; ++v) {
         const GettVariant s = gett_variant(an.dtype, v);
-        const int64_t tiles = ((an.sizeM + s.mt_m - 1) / s.mt_m) * ((an.sizeN + s.mt_n - 1) / s.mt_n) * an.sizeH;
-        const int64_t rounds = (tiles + cus - 1) / cus;
-        const double cost = (double)rounds * s.mt_m * s.mt_n / s.efficiency;
-        if (v == 0 || cost < best_cost) { best = v; best_cost = cost; }
+        const double tiles = (double)tiles_of(an, s);
+        const int64_t nk = (an.sizeK + s.kt - 1) / s.kt;
+        const double slab_us = flop_per_mac * s.mt_m * s.mt_n * s.kt / (cu_flops * s.efficiency) * 1e6;
+        for (int64_t want : {1, 2, 3, 4, 6, 8, 12, 16}) {
+            if (want > nk) break;
+            const int64_t per = (nk + want - 1) / want;
+            const int64_t S = (nk + per - 1) / per;
+            const double rounds = std::ceil(tiles * (double)S / cus);
+            double us = rounds * ((double)per * slab_us + 2.5);
+            if (S > 1) us += 4.0 + (2.0 * S + 1.0) * tiles * s.acc_reals * (ebytes > 8 ? 8 : ebytes) / 5e12 * 1e6;
+            if (best < 0 || us < best) { best = us; *variant = v; *splitK = (int)S; }
+        }
     }
-    return best;
 }
 
 void fill_generic(const Analysis& an, GenericArgs* g) {
@@ -146,6 +165,23 @@ tcx_error_t build_tables(Product* p) {
             p->dev_tables = nullptr;
             return TCX_ERR_LAUNCH;
         }
+    return TCX_SUCCESS;
+}
+
+// (Re)allocate the split-K workspace for the plan's current shape and split count.
+tcx_error_t ensure_workspace(Product* p) {
+    if (p->splitK <= 1 || !p->handle.has_device) return TCX_SUCCESS;
+    const GettVariant s = gett_variant(p->an.dtype, p->variant);
+    const size_t real_bytes = p->an.dtype == TCX_F32 ? 4 : 8;
+    const size_t need = (size_t)tiles_of(p->an, s) * (size_t)p->splitK * (size_t)s.acc_reals * real_bytes;
+    if (need <= p->workspace_bytes) return TCX_SUCCESS;
+    if (p->workspace) { (void)hipFree(p->workspace); p->workspace = nullptr; p->workspace_bytes = 0; }
+    if (hipMalloc(&p->workspace, need) != hipSuccess) {
+        (void)hipGetLastError();
+        p->workspace = nullptr;
+        return TCX_ERR_ALLOC;
+    }
+    p->workspace_bytes = need;
     return TCX_SUCCESS;
 }
 
@@ -332,8 +368,9 @@ tcx_error_t tcx_create_product(tcx_handle_t handle, tcx_op_t opA, tcx_tensor_inf
         if (stream_ok && (p->stream.staged_per_output <= 0.5 || p->an.path != TCX_PATH_GETT_MFMA)) {
             p->an.path = TCX_PATH_BANDWIDTH;
         } else if (p->an.path == TCX_PATH_GETT_MFMA) {
-            p->variant = choose_variant(p->an, h->num_cu);
+            choose_plan(p->an, h->num_cu, &p->variant, &p->splitK);
             err = build_tables(p);
+            if (err == TCX_SUCCESS && ensure_workspace(p) != TCX_SUCCESS) p->splitK = 1;   // no memory: run unsplit
         }
         p->an.variant = p->variant;
     }
@@ -348,6 +385,7 @@ tcx_error_t tcx_destroy_product(tcx_product_t* product) {
     if (!p) return TCX_ERR_INVALID_HANDLE;
     if (p->dev_tables) { (void)hipFree(p->dev_tables); p->dev_tables = nullptr; }
     if (p->dev_stream) { (void)hipFree(p->dev_stream); p->dev_stream = nullptr; }
+    if (p->workspace) { (void)hipFree(p->workspace); p->workspace = nullptr; }
     return retire<Product>(product, MAGIC_PRODUCT);
 }
 
@@ -356,7 +394,7 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
     if (!p) return TCX_ERR_INVALID_HANDLE;
     const Analysis& an = p->an;
     const bool tiled = an.path == TCX_PATH_GETT_MFMA;
-    const GettVariant s = tiled ? gett_variant(an.dtype, p->variant) : GettVariant{0, 0, 0, 256, 0.f};
+    const GettVariant s = tiled ? gett_variant(an.dtype, p->variant) : GettVariant{0, 0, 0, 256, 0.f, 0};
     switch (key) {
         case TCX_KEY_PATH: return put_i64(an.path, value, nbytes);
         case TCX_KEY_SIZE_H: return put_i64(an.sizeH, value, nbytes);
@@ -371,13 +409,12 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
         case TCX_KEY_TILE_N: return put_i64(an.path == TCX_PATH_BANDWIDTH ? p->stream.regA * p->stream.regB : s.mt_n, value, nbytes);
         case TCX_KEY_TILE_K: return put_i64(s.kt, value, nbytes);
         case TCX_KEY_GRID:
-            return put_i64(tiled ? ((an.sizeM + s.mt_m - 1) / s.mt_m) * ((an.sizeN + s.mt_n - 1) / s.mt_n) * an.sizeH
-                                 : (an.sizeH * an.sizeM * an.sizeN + 255) / 256,
-                           value, nbytes);
+            return put_i64(tiled ? tiles_of(an, s) * p->splitK : (an.sizeH * an.sizeM * an.sizeN + 255) / 256, value, nbytes);
         case TCX_KEY_BLOCK: return put_i64(s.threads, value, nbytes);
         case TCX_KEY_A_K_FASTEST: return put_i64(an.a_k_fastest, value, nbytes);
         case TCX_KEY_B_K_FASTEST: return put_i64(an.b_k_fastest, value, nbytes);
         case TCX_KEY_D_N_FASTEST: return put_i64(an.d_n_fastest, value, nbytes);
+        case TCX_KEY_SPLIT_K: return put_i64(tiled ? p->splitK : 1, value, nbytes);
         case TCX_KEY_VARIANT:
             return put_i64(tiled ? p->variant : (an.path == TCX_PATH_BANDWIDTH && p->stream.blocked) ? 1 : 0, value, nbytes);
         case TCX_KEY_MODES_M: return put_modes(an.M, value, nbytes);
@@ -400,9 +437,10 @@ tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* valu
         if (v == TCX_PATH_GETT_MFMA) {
             if (gett_num_variants(p->an.dtype) == 0 || (int)p->an.H.size() > kMaxHModes) return TCX_ERR_UNSUPPORTED_OP;
             if (p->tables[0].empty()) {
-                p->variant = choose_variant(p->an, p->handle.num_cu);
+                choose_plan(p->an, p->handle.num_cu, &p->variant, &p->splitK);
                 const tcx_error_t err = build_tables(p);
                 if (err != TCX_SUCCESS) return err;
+                if (ensure_workspace(p) != TCX_SUCCESS) p->splitK = 1;
             }
             p->an.path = TCX_PATH_GETT_MFMA;
             return TCX_SUCCESS;
@@ -426,7 +464,16 @@ tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* valu
         if (p->an.path != TCX_PATH_GETT_MFMA || v < 0 || v >= gett_num_variants(p->an.dtype)) return TCX_ERR_UNSUPPORTED_OP;
         p->variant = (int)v;
         p->an.variant = (int)v;
+        p->splitK = 1;                       // a forced shape starts unsplit; set TCX_KEY_SPLIT_K afterwards
         return TCX_SUCCESS;
+    }
+    if (key == TCX_KEY_SPLIT_K) {
+        if (p->an.path != TCX_PATH_GETT_MFMA || v < 1 || v > 64) return TCX_ERR_UNSUPPORTED_OP;
+        const GettVariant sh = gett_variant(p->an.dtype, p->variant);
+        const int64_t nk = (p->an.sizeK + sh.kt - 1) / sh.kt;
+        const int64_t per = (nk + v - 1) / v;
+        p->splitK = (int)((nk + per - 1) / per);        // no part may be empty
+        return ensure_workspace(p);
     }
     return TCX_ERR_BAD_KEY;
 }
@@ -496,6 +543,8 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
         g.s = s;
         g.opA = p->an.opA; g.opB = p->an.opB; g.opC = p->an.opC;
         g.read_c = read_c;
+        g.splitK = p->splitK;
+        g.workspace = p->workspace;
         hip_err = launch_gett(p->an.dtype, p->variant, p->an.a_k_fastest, p->an.b_k_fastest, p->an.d_n_fastest, g,
                               (void*)e->stream, &grid, &block);
         st.path = TCX_PATH_GETT_MFMA; st.variant = p->variant;

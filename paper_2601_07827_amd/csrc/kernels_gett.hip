@@ -47,6 +47,24 @@ template <> struct Mfma<float> {
 // the epilogue combines alpha, beta, the accumulator and op(C) --------------------------------
 template <class R> struct RealPolicy {
     using elem = R;
+    using real = R;
+    template <int FM, int FN> static constexpr int acc_reals() { return FM * FN * 4; }
+    template <int FM, int FN, class A> static __device__ __forceinline__ void spill(const A (&acc)[FM][FN], R* dst, int pitch) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) dst[(size_t)((i * FN + j) * 4 + v) * pitch] = acc[i][j].v[v];
+    }
+    template <int FM, int FN, class A> static __device__ __forceinline__ void accumulate(A (&acc)[FM][FN], const R* src, int pitch) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[i][j].v[v] += src[(size_t)((i * FN + j) * 4 + v) * pitch];
+    }
     using MF = Mfma<R>;
     using vec = typename MF::vec;
     struct acc_t {
@@ -73,6 +91,30 @@ template <class R> struct RealPolicy {
 // is flipped), so the main loop does not depend on the ops.
 struct ComplexPolicy {
     using elem = double2;
+    using real = double;
+    template <int FM, int FN> static constexpr int acc_reals() { return FM * FN * 8; }
+    template <int FM, int FN, class A> static __device__ __forceinline__ void spill(const A (&acc)[FM][FN], double* dst, int pitch) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    dst[(size_t)((i * FN + j) * 8 + v) * pitch] = acc[i][j].re[v];
+                    dst[(size_t)((i * FN + j) * 8 + 4 + v) * pitch] = acc[i][j].im[v];
+                }
+    }
+    template <int FM, int FN, class A> static __device__ __forceinline__ void accumulate(A (&acc)[FM][FN], const double* src, int pitch) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    acc[i][j].re[v] += src[(size_t)((i * FN + j) * 8 + v) * pitch];
+                    acc[i][j].im[v] += src[(size_t)((i * FN + j) * 8 + 4 + v) * pitch];
+                }
+    }
     using MF = Mfma<double>;
     using vec = double4_t;
     struct acc_t {
@@ -135,7 +177,84 @@ struct Slab {
     static __device__ __forceinline__ int frag_index(int r, int kk) { return KF ? r * LD + kk : kk * LD + r; }
 };
 
-template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF>
+// Keeps reads of an accumulator away from the MFMA that wrote it last.  On gfx950 a 16x16x4
+// fp64 MFMA writes its result registers over 16 passes; the wait states this compiler inserts
+// between such an MFMA and a following non-MFMA read of its result assume 8 (the last-written
+// quarter of the accumulator was observed stale when a wave owns a single accumulator and the
+// compiler moves it between register files right after the MFMA).  With several accumulators
+// per wave the other MFMAs provide the distance; where a wave has only one or two, and once
+// before every epilogue, 24 idle issue slots are inserted by hand.  They idle only this wave.
+__device__ __forceinline__ void settle_accumulators() {
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// Consecutive workgroup ids go round-robin over the 8 XCDs; remap so that each XCD (private
+// 4 MB L2) works on one contiguous stretch of the tile order.
+__device__ __forceinline__ int64_t xcd_contiguous(int64_t id, int64_t nb) {
+    const int64_t per = nb / 8;
+    return id < per * 8 ? (id % 8) * per + id / 8 : id;
+}
+
+struct Tile {
+    int64_t m0, n0;          // first row / column of the tile in the linearised M, N index
+    int64_t hA, hB, hD;      // base offsets from the hyper index
+};
+
+// Tile number -> tile coordinates.  Tiles are walked in bands of 8 tile-rows; the hyper index
+// is the slowest (Eq. case2: an independent product per value of H).
+__device__ __forceinline__ Tile locate_tile(int64_t t_all, const GettArgs& g, int mt_m, int mt_n) {
+    const int64_t tiles_per_h = (int64_t)g.tilesM * g.tilesN;
+    const int64_t h = t_all / tiles_per_h;
+    const int t = (int)(t_all - h * tiles_per_h);
+    constexpr int BAND = 8;
+    const int band = t / (BAND * g.tilesN);
+    const int first_m = band * BAND;
+    const int band_rows = min(BAND, g.tilesM - first_m);
+    const int in_band = t - band * BAND * g.tilesN;
+    Tile r;
+    r.m0 = (int64_t)(first_m + in_band % band_rows) * mt_m;
+    r.n0 = (int64_t)(in_band / band_rows) * mt_n;
+    r.hA = r.hB = r.hD = 0;
+    int64_t rem = h;
+    for (int i = 0; i < g.nH; ++i) {
+        const int64_t q = rem / g.hExt[i], idx = rem - q * g.hExt[i];
+        rem = q;
+        r.hA += idx * g.hSA[i];
+        r.hB += idx * g.hSB[i];
+        r.hD += idx * g.hSD[i];
+    }
+    return r;
+}
+
+// alpha/beta epilogue of one thread's accumulators: strided scatter through D's offset tables.
+template <class P, int FM, int FN, int WT_M, int WT_N, bool DNF>
+__device__ __forceinline__ void scatter(const typename P::acc_t (&acc)[FM][FN], const GettArgs& g, const Tile& tile,
+                                        int wm, int wn, int lane) {
+    using T = typename P::elem;
+    using MF = typename P::MF;
+    const T* __restrict__ C = (const T*)g.C + tile.hD;
+    T* __restrict__ D = (T*)g.D + tile.hD;
+    const int fr = lane & 15;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int rr = MF::row_of(lane, v);
+                const int ml = wm * WT_M + i * 16 + (DNF ? rr : fr);
+                const int nl = wn * WT_N + j * 16 + (DNF ? fr : rr);
+                if (tile.m0 + ml < g.sizeM && tile.n0 + nl < g.sizeN)
+                    P::store(D, C, g.oDM[tile.m0 + ml] + g.oDN[tile.n0 + nl], acc[i][j], v, g.s, g.read_c != 0, g.opC);
+            }
+}
+
+// DEPTH: how many slabs ahead of the MFMAs the global loads run (a ring of DEPTH register sets).
+// Large tiles spend longer on a slab than a load takes and need 1; small tiles need more bytes
+// in flight to cover the same latency.
+template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF, int DEPTH>
 __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
     using T = typename P::elem;
     using acc_t = typename P::acc_t;
@@ -154,38 +273,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
     const int wave = tid >> 6;
     const int wm = wave % WGM, wn = wave / WGM;
 
-    // ---- which tile: consecutive workgroup ids go round-robin over the 8 XCDs, so give
-    // each XCD one contiguous stretch of the tile order (its own L2 then sees neighbouring
-    // tiles), and walk tiles in bands of 8 tile-rows.
-    int64_t lid = blockIdx.x;
-    {
-        const int64_t nb = gridDim.x, per = nb / 8;
-        if (lid < per * 8) lid = (lid % 8) * per + lid / 8;
-    }
-    const int64_t tiles_per_h = (int64_t)g.tilesM * g.tilesN;
-    const int64_t h = lid / tiles_per_h;
-    const int t = (int)(lid - h * tiles_per_h);
-    constexpr int BAND = 8;
-    const int band = t / (BAND * g.tilesN);
-    const int first_m = band * BAND;
-    const int band_rows = min(BAND, g.tilesM - first_m);
-    const int in_band = t - band * BAND * g.tilesN;
-    const int tm = first_m + in_band % band_rows;
-    const int tn = in_band / band_rows;
-    const int64_t m0 = (int64_t)tm * MT_M, n0 = (int64_t)tn * MT_N;
-
-    // ---- hyper index -> base offsets (Eq. case2: an independent product per value of H)
-    int64_t hA = 0, hB = 0, hD = 0;
-    {
-        int64_t rem = h;
-        for (int i = 0; i < g.nH; ++i) {
-            const int64_t q = rem / g.hExt[i], idx = rem - q * g.hExt[i];
-            rem = q;
-            hA += idx * g.hSA[i];
-            hB += idx * g.hSB[i];
-            hD += idx * g.hSD[i];
-        }
-    }
+    // ---- which tile, and which part of K (split-K: consecutive ids are the parts of one tile)
+    const int64_t lid = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int split = (int)(lid % g.splitK);
+    const Tile tile = locate_tile(lid / g.splitK, g, MT_M, MT_N);
+    const int64_t m0 = tile.m0, n0 = tile.n0, hA = tile.hA, hB = tile.hB, hD = tile.hD;
     const T* __restrict__ A = (const T*)g.A + hA;
     const T* __restrict__ B = (const T*)g.B + hB;
 
@@ -223,33 +315,33 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
         for (int i = 0; i < SB::PER; ++i) kB[i] = tb[kinB[i]];
     };
 
-    T ra[SA::PER], rb[SB::PER];
+    T ra[DEPTH][SA::PER], rb[DEPTH][SB::PER];
     const unsigned conjA = g.opA == TCX_OP_CONJ ? 0x80000000u : 0u;
     const unsigned conjB = g.opB == TCX_OP_CONJ ? 0x80000000u : 0u;
-    // Data loads of slab kt; k_offsets(kt) must have been issued before.  Unconditional: the
-    // tables are padded with offsets of valid elements.
-    auto gather = [&]() {
+    // Data loads of one slab into ring slot `slot`; its k_offsets() must have been issued
+    // before.  Unconditional: the tables are padded with offsets of valid elements.
+    auto gather = [&](int slot) {
 #pragma unroll
-        for (int i = 0; i < SA::PER; ++i) ra[i] = P::load(A, offA[i] + kA[i], conjA);
+        for (int i = 0; i < SA::PER; ++i) ra[slot][i] = P::load(A, offA[i] + kA[i], conjA);
 #pragma unroll
-        for (int i = 0; i < SB::PER; ++i) rb[i] = P::load(B, offB[i] + kB[i], conjB);
+        for (int i = 0; i < SB::PER; ++i) rb[slot][i] = P::load(B, offB[i] + kB[i], conjB);
     };
     // The last slab of a ragged K holds padded k entries whose (valid, arbitrary) values must
     // not be summed: zero them after the load.
-    auto mask_last = [&]() {
+    auto mask_last = [&](int slot) {
         const unsigned kleft = (unsigned)(g.sizeK - (int64_t)(nk - 1) * KT);
 #pragma unroll
-        for (int i = 0; i < SA::PER; ++i) ra[i] = kinA[i] < kleft ? ra[i] : P::zero();
+        for (int i = 0; i < SA::PER; ++i) ra[slot][i] = kinA[i] < kleft ? ra[slot][i] : P::zero();
 #pragma unroll
-        for (int i = 0; i < SB::PER; ++i) rb[i] = kinB[i] < kleft ? rb[i] : P::zero();
+        for (int i = 0; i < SB::PER; ++i) rb[slot][i] = kinB[i] < kleft ? rb[slot][i] : P::zero();
     };
-    auto stage = [&](int buf) {
+    auto stage = [&](int slot, int buf) {
         T* sa = lds + buf * (SA::ELEMS + SB::ELEMS);
         T* sb = sa + SA::ELEMS;
 #pragma unroll
-        for (int i = 0; i < SA::PER; ++i) sa[SA::lds_index(tid + i * NT)] = ra[i];
+        for (int i = 0; i < SA::PER; ++i) sa[SA::lds_index(tid + i * NT)] = ra[slot][i];
 #pragma unroll
-        for (int i = 0; i < SB::PER; ++i) sb[SB::lds_index(tid + i * NT)] = rb[i];
+        for (int i = 0; i < SB::PER; ++i) sb[SB::lds_index(tid + i * NT)] = rb[slot][i];
     };
 
     acc_t acc[FM][FN];
@@ -274,79 +366,256 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
 #pragma unroll
                 for (int j = 0; j < FN; ++j) P::template mac<DNF>(fa[i], fb[j], acc[i][j]);
         }
+        if (FM * FN <= 2) settle_accumulators();
     };
 
     // ---- main loop: the data loads of slab kt+1 and the table loads of slab kt+2 are in
     // flight while the MFMAs run on slab kt.  The last two slabs are peeled so that the loop
     // body is one straight path.
     const bool ragged_k = g.sizeK % KT != 0;
-    k_offsets(0);
-    gather();
-    k_offsets(1);
-    if (ragged_k && nk == 1) mask_last();
-    stage(0);
+    const int per_split = (nk + g.splitK - 1) / g.splitK;
+    const int kb = split * per_split, ke = min(nk, kb + per_split);      // this workgroup's slabs [kb, ke)
+    // Prologue: fill the ring with slabs kb .. kb+DEPTH-1 (slab numbers past the end are clamped
+    // by k_offsets to the last slab: harmless loads that are never staged).
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+        k_offsets(kb + d);
+        gather(d);
+    }
+    k_offsets(kb + DEPTH);
+    if (ragged_k && kb == nk - 1) mask_last(0);
+    stage(0, 0);
     __syncthreads();
     int buf = 0;
-    for (int kt = 0; kt + 2 < nk; ++kt) {
-        gather();                 // slab kt+1
-        k_offsets(kt + 2);
-        compute(buf);
-        stage(buf ^ 1);
-        __syncthreads();
-        buf ^= 1;
+    // Steady state, unrolled by DEPTH so that ring slots are compile-time register names.  In
+    // iteration kt slot u holds slab kt (already staged), so it is refilled with slab kt+DEPTH;
+    // slot u+1 holds slab kt+1, issued DEPTH-1 iterations ago, and is staged for the next one.
+    for (int kt = kb; kt < ke - 1; kt += DEPTH) {
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) {
+            if (kt + u >= ke - 1) break;
+            gather(u);                                   // slab kt+u+DEPTH
+            k_offsets(kt + u + DEPTH + 1);
+            compute(buf);                                // slab kt+u
+            if (ragged_k && kt + u + 1 == nk - 1) mask_last((u + 1) % DEPTH);
+            stage((u + 1) % DEPTH, buf ^ 1);             // slab kt+u+1
+            __syncthreads();
+            buf ^= 1;
+        }
     }
-    if (nk >= 2) {
-        gather();                 // slab nk-1
-        compute(buf);
-        if (ragged_k) mask_last();
-        stage(buf ^ 1);
-        __syncthreads();
-        buf ^= 1;
-    }
-    compute(buf);
+    compute(buf);                                        // slab ke-1
+    settle_accumulators();
 
-    // ---- epilogue: D = alpha * acc + beta * C, scattered through D's offset tables
-    const T* __restrict__ C = (const T*)g.C + hD;
-    T* __restrict__ D = (T*)g.D + hD;
+    // ---- epilogue.  With split-K the raw accumulators go to the workspace, one coalesced
+    // stretch per accumulator register; the reduction kernel sums the parts in a fixed order
+    // and applies alpha, beta and the scatter.
+    if (g.splitK > 1) {
+        typename P::real* ws = (typename P::real*)g.workspace + (size_t)lid * (NT * P::template acc_reals<FM, FN>());
+        P::template spill<FM, FN>(acc, ws + tid, NT);
+    } else {
+        scatter<P, FM, FN, WT_M, WT_N, DNF>(acc, g, tile, wm, wn, lane);
+    }
+}
+
+// Second kernel of a split-K product: one workgroup per tile, same thread-to-element mapping as
+// the main kernel.  Parts are summed in the order 0, 1, ..., splitK-1, so the result does not
+// depend on scheduling.
+template <class P, int MT_M, int MT_N, int WGM, int WGN, bool DNF>
+__global__ __launch_bounds__(WGM* WGN * 64) void gett_reduce_kernel(GettArgs g) {
+    constexpr int NT = WGM * WGN * 64;
+    constexpr int WT_M = MT_M / WGM, WT_N = MT_N / WGN;
+    constexpr int FM = WT_M / 16, FN = WT_N / 16;
+    using acc_t = typename P::acc_t;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int64_t t_all = blockIdx.x;
+    const Tile tile = locate_tile(t_all, g, MT_M, MT_N);
+    acc_t acc[FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
+        for (int j = 0; j < FN; ++j) P::clear(acc[i][j]);
+    constexpr size_t PART = (size_t)NT * P::template acc_reals<FM, FN>();
+    const typename P::real* ws = (const typename P::real*)g.workspace + (size_t)t_all * g.splitK * PART + tid;
+    for (int sp = 0; sp < g.splitK; ++sp) P::template accumulate<FM, FN>(acc, ws + (size_t)sp * PART, NT);
+    scatter<P, FM, FN, WT_M, WT_N, DNF>(acc, g, tile, wm, wn, lane);
+}
+
+// ---- direct kernel for small tiles --------------------------------------------------------------
+// When a product has few tiles the LDS pipeline above spends most of its time in barriers and
+// in the latency between a slab's global loads and its use.  This kernel has no LDS and no
+// barrier: every wave loads its own MFMA fragments from the strided tensors straight into
+// registers -- lane (row = lane % 16, q = lane / 16) of a 16x16x4 block holds one element of a
+// row of the tile, which is exactly one gathered load -- two chunks of K ahead of the MFMAs
+// that consume them.  Waves that share rows of A or columns of B re-read them through the L1.
+// Inside a chunk of 4*CH contracted indices lane group q owns the CH consecutive indices
+// q*CH .. q*CH+CH-1 (the order in which a contraction index is summed is free as long as both
+// operands agree), so an operand whose fastest mode is contracted is read in short runs.
+template <class P, int FM, int FN, int CH, bool DNF>
+__global__ __launch_bounds__(256) void gett_direct_kernel(GettArgs g) {
+    using T = typename P::elem;
+    using acc_t = typename P::acc_t;
+    constexpr int WGM = 2, WGN = 2, NT = 256;
+    constexpr int WT_M = FM * 16, WT_N = FN * 16, MT_M = WGM * WT_M, MT_N = WGN * WT_N;
+    constexpr int KC = 4 * CH;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int fr = lane & 15, fq = lane >> 4;
+
+    const int64_t lid = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int split = (int)(lid % g.splitK);
+    const Tile tile = locate_tile(lid / g.splitK, g, MT_M, MT_N);
+    const T* __restrict__ A = (const T*)g.A + tile.hA;
+    const T* __restrict__ B = (const T*)g.B + tile.hB;
+    const unsigned conjA = g.opA == TCX_OP_CONJ ? 0x80000000u : 0u;
+    const unsigned conjB = g.opB == TCX_OP_CONJ ? 0x80000000u : 0u;
+
+    int64_t rowA[FM], rowB[FN];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int rr = MF::row_of(lane, v);
-                const int ml = wm * WT_M + i * 16 + (DNF ? rr : fr);
-                const int nl = wn * WT_N + j * 16 + (DNF ? fr : rr);
-                if (m0 + ml < g.sizeM && n0 + nl < g.sizeN)
-                    P::store(D, C, g.oDM[m0 + ml] + g.oDN[n0 + nl], acc[i][j], v, g.s, g.read_c != 0, g.opC);
+    for (int i = 0; i < FM; ++i) rowA[i] = g.oAM[tile.m0 + wm * WT_M + i * 16 + fr];
+#pragma unroll
+    for (int j = 0; j < FN; ++j) rowB[j] = g.oBN[tile.n0 + wn * WT_N + j * 16 + fr];
+
+    const int nk = g.tilesK;                                   // chunks of KC contracted indices
+    const int per_split = (nk + g.splitK - 1) / g.splitK;
+    const int kb = split * per_split, ke = min(nk, kb + per_split);
+    const bool ragged_k = g.sizeK % KC != 0;
+
+    int64_t ka[2][CH], kbo[2][CH];       // K offsets of this lane's indices, two chunks
+    T da[2][CH][FM], db[2][CH][FN];      // fragments, two chunks
+    acc_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) P::clear(acc[i][j]);
+
+    auto koffs = [&](int buf, int c) {
+        const int64_t base = (int64_t)min(c, nk - 1) * KC + fq * CH;
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            ka[buf][j] = g.oAK[base + j];
+            kbo[buf][j] = g.oBK[base + j];
+        }
+    };
+    auto loads = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+#pragma unroll
+            for (int i = 0; i < FM; ++i) da[buf][j][i] = P::load(A, rowA[i] + ka[buf][j], conjA);
+#pragma unroll
+            for (int i = 0; i < FN; ++i) db[buf][j][i] = P::load(B, rowB[i] + kbo[buf][j], conjB);
+        }
+    };
+    auto mask = [&](int buf, int c) {          // last chunk of a ragged K: padded indices must add nothing
+#pragma unroll
+        for (int j = 0; j < CH; ++j)
+            if ((int64_t)c * KC + fq * CH + j >= g.sizeK) {
+#pragma unroll
+                for (int i = 0; i < FM; ++i) da[buf][j][i] = P::zero();
+#pragma unroll
+                for (int i = 0; i < FN; ++i) db[buf][j][i] = P::zero();
             }
+    };
+    auto mfmas = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j)
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int jn = 0; jn < FN; ++jn) P::template mac<DNF>(da[buf][j][i], db[buf][j][jn], acc[i][jn]);
+        if (FM * FN <= 2) settle_accumulators();
+    };
+
+    // register pipeline: fragments of chunk c+1 and K offsets of chunk c+2 are in flight while
+    // the MFMAs of chunk c run; the loop is unrolled by two so that buffer indices are static
+    koffs(0, kb);
+    koffs(1, kb + 1);
+    loads(0);
+    if (ragged_k && kb == nk - 1) mask(0, kb);
+    int c = kb;
+    while (true) {
+        if (c + 1 < ke) {
+            loads(1);
+            koffs(0, c + 2);
+            if (ragged_k && c + 1 == nk - 1) mask(1, c + 1);
+        }
+        mfmas(0);
+        if (++c >= ke) break;
+        if (c + 1 < ke) {
+            loads(0);
+            koffs(1, c + 2);
+            if (ragged_k && c + 1 == nk - 1) mask(0, c + 1);
+        }
+        mfmas(1);
+        if (++c >= ke) break;
+    }
+    settle_accumulators();
+
+    if (g.splitK > 1) {
+        typename P::real* ws = (typename P::real*)g.workspace + (size_t)lid * (NT * P::template acc_reals<FM, FN>());
+        P::template spill<FM, FN>(acc, ws + tid, NT);
+    } else {
+        scatter<P, FM, FN, WT_M, WT_N, DNF>(acc, g, tile, wm, wn, lane);
+    }
 }
 
 // ---- instantiation tables -------------------------------------------------------------------
 struct Shape {
     int mt_m, mt_n, kt, wgm, wgn;
     float efficiency;      // relative speed of the main loop per unit of tile area (planner's cost model)
+    int ch;                // 0: LDS-staged kernel; > 0: direct kernel with chunks of 4*ch contracted indices
+    int depth;             // LDS-staged kernel: slabs of global loads in flight
 };
 constexpr Shape kRealShapes[] = {
-    {256, 128, 16, 4, 2, 1.00f},
-    {128, 128, 16, 2, 2, 0.80f},
-    {64, 64, 16, 2, 2, 0.55f},
-    {32, 32, 16, 2, 2, 0.25f},
+    {256, 128, 16, 4, 2, 1.00f, 0, 1},
+    {128, 128, 16, 2, 2, 0.80f, 0, 2},
+    {64, 64, 16, 2, 2, 0.55f, 0, 3},
+    {32, 32, 16, 2, 2, 0.25f, 0, 3},
+    {128, 64, 16, 2, 2, 0.75f, 4, 0},
+    {64, 64, 16, 2, 2, 0.65f, 4, 0},
+    {32, 32, 16, 2, 2, 0.35f, 4, 0},
+    {64, 64, 16, 2, 4, 0.55f, 0, 2},
+    {64, 64, 16, 4, 4, 0.55f, 0, 2},
 };
 constexpr Shape kComplexShapes[] = {
-    {96, 96, 8, 2, 2, 1.00f},
-    {64, 64, 8, 2, 2, 0.85f},
-    {32, 32, 8, 2, 2, 0.40f},
+    {96, 96, 8, 2, 2, 1.00f, 0, 2},
+    {64, 64, 8, 2, 2, 0.85f, 0, 2},
+    {32, 32, 8, 2, 2, 0.40f, 0, 3},
+    {96, 96, 8, 2, 2, 1.00f, 2, 0},
+    {64, 64, 8, 2, 2, 0.85f, 2, 0},
 };
 constexpr int kNumRealShapes = sizeof(kRealShapes) / sizeof(Shape);
 constexpr int kNumComplexShapes = sizeof(kComplexShapes) / sizeof(Shape);
 
+constexpr Shape shape_at(bool complex_table, int i) {
+    return complex_table ? kComplexShapes[i < kNumComplexShapes ? i : 0] : kRealShapes[i < kNumRealShapes ? i : 0];
+}
+
 template <class P, int S, bool AKF, bool BKF, bool DNF>
 hipError_t launch_one(const GettArgs& a, int64_t blocks, hipStream_t st) {
-    constexpr Shape s = std::is_same<P, ComplexPolicy>::value ? kComplexShapes[S] : kRealShapes[S];
-    gett_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF>
-        <<<dim3((unsigned)blocks), dim3(s.wgm * s.wgn * 64), 0, st>>>(a);
-    return hipGetLastError();
+    constexpr Shape s = shape_at(std::is_same<P, ComplexPolicy>::value, S);
+    if constexpr (s.ch > 0) {
+        // the direct kernel gathers per lane; the operands' orientation does not enter
+        if constexpr (!AKF && !BKF)
+            gett_direct_kernel<P, s.mt_m / 32, s.mt_n / 32, s.ch, DNF><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(a);
+        else
+            return launch_one<P, S, false, false, DNF>(a, blocks, st);
+    } else {
+        gett_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.depth>
+            <<<dim3((unsigned)blocks), dim3(s.wgm * s.wgn * 64), 0, st>>>(a);
+    }
+    hipError_t err = hipGetLastError();
+    if (err == hipSuccess && a.splitK > 1) {
+        gett_reduce_kernel<P, s.mt_m, s.mt_n, s.wgm, s.wgn, DNF>
+            <<<dim3((unsigned)(blocks / a.splitK)), dim3(s.wgm * s.wgn * 64), 0, st>>>(a);
+        err = hipGetLastError();
+    }
+    return err;
 }
 
 template <class P, int S>
@@ -371,6 +640,11 @@ hipError_t launch_real_shape(int variant, bool akf, bool bkf, bool dnf, const Ge
         case 1: return launch_flags<P, 1>(akf, bkf, dnf, a, blocks, st);
         case 2: return launch_flags<P, 2>(akf, bkf, dnf, a, blocks, st);
         case 3: return launch_flags<P, 3>(akf, bkf, dnf, a, blocks, st);
+        case 4: return launch_flags<P, 4>(akf, bkf, dnf, a, blocks, st);
+        case 5: return launch_flags<P, 5>(akf, bkf, dnf, a, blocks, st);
+        case 6: return launch_flags<P, 6>(akf, bkf, dnf, a, blocks, st);
+        case 7: return launch_flags<P, 7>(akf, bkf, dnf, a, blocks, st);
+        case 8: return launch_flags<P, 8>(akf, bkf, dnf, a, blocks, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -380,6 +654,8 @@ hipError_t launch_complex_shape(int variant, bool akf, bool bkf, bool dnf, const
         case 0: return launch_flags<ComplexPolicy, 0>(akf, bkf, dnf, a, blocks, st);
         case 1: return launch_flags<ComplexPolicy, 1>(akf, bkf, dnf, a, blocks, st);
         case 2: return launch_flags<ComplexPolicy, 2>(akf, bkf, dnf, a, blocks, st);
+        case 3: return launch_flags<ComplexPolicy, 3>(akf, bkf, dnf, a, blocks, st);
+        case 4: return launch_flags<ComplexPolicy, 4>(akf, bkf, dnf, a, blocks, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -403,13 +679,15 @@ GettVariant gett_variant(int dtype, int variant) {
     int n = 0;
     const Shape* t = shapes_of(dtype, &n);
     const Shape s = t[variant];
-    return {s.mt_m, s.mt_n, s.kt, s.wgm * s.wgn * 64, s.efficiency};
+    const int planes = dtype == TCX_C128 ? 2 : 1;
+    return {s.mt_m, s.mt_n, s.kt, s.wgm * s.wgn * 64, s.efficiency, s.mt_m * s.mt_n * planes};
 }
 
 int launch_gett(int dtype, int variant, bool a_kf, bool b_kf, bool d_nf, const GettArgs& args, void* stream,
                 int64_t* grid, int* block) {
     if (variant < 0 || variant >= gett_num_variants(dtype)) return (int)hipErrorInvalidValue;
-    const int64_t blocks = (int64_t)args.tilesM * args.tilesN * args.sizeH;
+    if (args.splitK < 1 || (args.splitK > 1 && !args.workspace)) return (int)hipErrorInvalidValue;
+    const int64_t blocks = (int64_t)args.tilesM * args.tilesN * args.sizeH * args.splitK;
     *grid = blocks;
     *block = gett_variant(dtype, variant).threads;
     if (blocks <= 0 || blocks > 0x7fffffff) return (int)hipErrorInvalidConfiguration;

@@ -71,11 +71,14 @@ struct GettArgs {
     Scalars s;
     int32_t opA, opB, opC;
     int32_t read_c;      // beta != 0
+    int32_t splitK;      // >= 1: number of parts the K slabs are divided into
+    void* workspace;     // splitK > 1: [tiles * splitK][accumulator reals of a tile], owned by the plan
 };
 
 struct GettVariant {
     int mt_m, mt_n, kt, threads;
     float efficiency;    // relative main-loop speed per unit tile area, for the planner's cost model
+    int acc_reals;       // real accumulator values per tile (split-K workspace per part)
 };
 
 // Generic fallback: every mode of D (H, M, N together, D-fastest first) and every K mode.

@@ -19,7 +19,7 @@ def say(msg: str):
 class GpuProduct:
     """Plan for one Problem: tensor infos + product + executor on torch's current stream."""
 
-    def __init__(self, p: W.Problem, force_path=None, variant=None):
+    def __init__(self, p: W.Problem, force_path=None, variant=None, split_k=None):
         import torch
         import paper_2601_07827_amd as T
         self.T, self.p = T, p
@@ -39,6 +39,8 @@ class GpuProduct:
             T.tcx_product_set(self.prod, T.TCX_KEY_FORCE_PATH, force_path)
         if variant is not None:
             T.tcx_product_set(self.prod, T.TCX_KEY_VARIANT, variant)
+        if split_k is not None:
+            T.tcx_product_set(self.prod, T.TCX_KEY_SPLIT_K, split_k)
 
     def get(self, key):
         return self.T.tcx_product_get(self.prod, key)
@@ -64,10 +66,11 @@ class GpuProduct:
         self.T.tcx_destroy_handle(self.h)
 
 
-def run_gpu(p: W.Problem, bufA, bufB, bufC, force_path=None, variant=None, alpha=None, beta=None, c_null=False):
+def run_gpu(p: W.Problem, bufA, bufB, bufC, force_path=None, variant=None, alpha=None, beta=None, c_null=False,
+            split_k=None):
     """D buffer (numpy) after D := alpha op(A) op(B) + beta op(C), computed in place over a copy of bufC."""
     import torch
-    gp = GpuProduct(p, force_path, variant)
+    gp = GpuProduct(p, force_path, variant, split_k)
     try:
         dA, dB = torch.from_numpy(bufA).cuda(), torch.from_numpy(bufB).cuda()
         dD = torch.from_numpy(bufC.copy()).cuda()

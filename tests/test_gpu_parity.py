@@ -18,19 +18,19 @@ GENERIC, GETT, STREAM = 0, 1, 2
 def _paths_for(p):
     from gpu_helpers import DT  # noqa: F401
     paths = [(GENERIC, None)]
-    paths += [(GETT, v) for v in range(3 if p.dtype == "c128" else 4)]
+    paths += [(GETT, v) for v in range(5 if p.dtype == "c128" else 9)]
     if p.sizes()[3] <= 64:
         paths.append((STREAM, None))
     return paths
 
 
-def _check(p, a, b, c, path, variant, exact=False, truth=None, S=None):
+def _check(p, a, b, c, path, variant, exact=False, truth=None, S=None, split_k=None):
     from gpu_helpers import run_gpu, say
-    say("%s path=%s variant=%s exact=%s" % (p.name, path, variant, exact))
+    say("%s path=%s variant=%s split_k=%s exact=%s" % (p.name, path, variant, split_k, exact))
     if truth is None:
         truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
     try:
-        got = run_gpu(p, a, b, c, force_path=path, variant=variant)
+        got = run_gpu(p, a, b, c, force_path=path, variant=variant, split_k=split_k)
     except Exception as exc:                       # the streaming path may decline large |K| (operand rows must fit LDS)
         if path == STREAM and getattr(exc, "code", None) == 11 and p.sizes()[3] > 8:
             say("  (streaming path declined: |K| = %d)" % p.sizes()[3])
@@ -50,6 +50,8 @@ def test_reduced_configs_all_paths(p):
     truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
     for path, variant in _paths_for(p):
         _check(p, a, b, c, path, variant, truth=truth, S=S)
+        if path == GETT:            # the contracted range cut into parts, reduced by the second kernel
+            _check(p, a, b, c, path, variant, truth=truth, S=S, split_k=2 + variant)
     # the plan's own choice
     _check(p, a, b, c, None, None, truth=truth, S=S)
 
@@ -62,6 +64,8 @@ def test_reduced_configs_integer_inputs_bit_exact(p):
     truth, S = run_oracle(p2, a, b, c, oracle.MODE_TRUTH, want_S=True)
     for path, variant in _paths_for(p2) + [(None, None)]:
         _check(p2, a, b, c, path, variant, exact=True, truth=truth, S=S)
+        if path == GETT:
+            _check(p2, a, b, c, path, variant, exact=True, truth=truth, S=S, split_k=3)
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32", "c128"])
@@ -71,9 +75,10 @@ def test_random_problems(dtype):
         p = random_problem(rng, dtype, max_group=3, max_extent=6, allow_neg=(i % 3 == 0), name="rand%d_%s" % (i, dtype))
         a, b, c = W.make_operands(p)
         truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
-        paths = [(GENERIC, None), (GETT, (1 + i % 2) if dtype == "c128" else (2 + i % 2)), (STREAM, None)]
+        paths = [(GENERIC, None), (GETT, (1 + i % 4) if dtype == "c128" else (2 + i % 5)), (STREAM, None)]
         for path, variant in paths:
             _check(p, a, b, c, path, variant, truth=truth, S=S)
+        _check(p, a, b, c, GETT, paths[1][1], truth=truth, S=S, split_k=2 + i % 3)
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32", "c128"])
@@ -124,7 +129,20 @@ def test_full_size_configs(p):
 def test_full_size_integer_inputs_bit_exact(p):
     a, b, c = W.make_operands(p, "ints")
     p2 = W.Problem(p.name + "_ints", p.dtype, p.A, p.B, p.D, alpha=2.0, beta=(0.5 if p.beta != 0 else 0.0), seed=p.seed)
-    _check(p2, a, b, c, None, None, exact=True)
+    truth, S = run_oracle(p2, a, b, c, oracle.MODE_TRUTH, want_S=True)
+    _check(p2, a, b, c, None, None, exact=True, truth=truth, S=S)
+    _check(p2, a, b, c, GETT, 1, exact=True, truth=truth, S=S, split_k=4)
+    _check(p2, a, b, c, GETT, 2, exact=True, truth=truth, S=S, split_k=1)
+
+
+def test_split_k_is_deterministic():
+    """Two executions of a split-K plan give the same bits (parts are summed in a fixed order)."""
+    from gpu_helpers import run_gpu
+    p = W.config1()
+    a, b, c = W.make_operands(p)
+    r1 = run_gpu(p, a, b, c, force_path=GETT, variant=2, split_k=6)
+    r2 = run_gpu(p, a, b, c, force_path=GETT, variant=2, split_k=6)
+    assert np.array_equal(r1, r2)
 
 
 @pytest.mark.parametrize("dist", ["uniform", "ints"])
