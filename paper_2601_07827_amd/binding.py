@@ -14,6 +14,14 @@ from typing import Optional, Sequence
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtcx.so")
 
+# PyTorch-ROCm ships its own HIP runtime.  A process that holds device memory through torch must
+# let torch load that runtime first: if libtcx.so pulled in the system's libamdhip64 before it,
+# torch would afterwards find no GPU.  Processes that do not use torch are unaffected.
+try:
+    import torch  # noqa: F401
+except ImportError:
+    pass
+
 if not os.path.exists(LIB_PATH):
     raise ImportError("libtcx.so is not built: run `python -m paper_2601_07827_amd.build` "
                       "(hipcc --offload-arch=gfx950); there is no CPU fallback")

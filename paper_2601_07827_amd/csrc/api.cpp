@@ -102,13 +102,17 @@ void choose_plan(const Analysis& an, int num_cu, int* variant, int* splitK) {
         const double tiles = (double)tiles_of(an, s);
         const int64_t nk = (an.sizeK + s.kt - 1) / s.kt;
         const double slab_us = flop_per_mac * s.mt_m * s.mt_n * s.kt / (cu_flops * s.efficiency) * 1e6;
-        for (int64_t want : {1, 2, 3, 4, 6, 8, 12, 16}) {
+        for (int64_t want : {1, 2, 3, 4, 6, 8}) {
             if (want > nk) break;
             const int64_t per = (nk + want - 1) / want;
             const int64_t S = (nk + per - 1) / per;
-            const double rounds = std::ceil(tiles * (double)S / cus);
-            double us = rounds * ((double)per * slab_us + 2.5);
-            if (S > 1) us += 4.0 + (2.0 * S + 1.0) * tiles * s.acc_reals * (ebytes > 8 ? 8 : ebytes) / 5e12 * 1e6;
+            // small tiles leave room for several workgroups per CU, which then share its matrix
+            // pipe: the time of a round does not shrink, but a partial last round costs less
+            const double resident = std::max(1.0, std::min(4.0, 65536.0 / ((double)s.mt_m * s.mt_n * (ebytes > 8 ? 2 : 1))));
+            const double slots = cus * resident;
+            const double rounds = std::ceil(tiles * (double)S / slots);
+            double us = rounds * resident * (double)per * slab_us + 6.0;
+            if (S > 1) us += 3.0 + (2.0 * S + 1.0) * tiles * s.acc_reals * (ebytes > 8 ? 8 : ebytes) / 6e12 * 1e6;
             if (best < 0 || us < best) { best = us; *variant = v; *splitK = (int)S; }
         }
     }

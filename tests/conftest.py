@@ -1,6 +1,8 @@
 import os
 import sys
 
+import torch  # noqa: F401  -- before anything loads libtcx.so: torch must bring up its own HIP runtime first
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
