@@ -33,10 +33,18 @@ MEASURED_TRAFFIC_BYTES = {("cfg2_f64_ppladder_v192_o64", 1, 0): 110.06e9 + 1.208
 DT = {"f32": 0, "f64": 1, "c128": 3}
 
 
+def _gemm(m, n, k) -> W.Problem:
+    """Plain column-major matrix product (calibration shape)."""
+    e = dict(m=m, n=n, k=k)
+    return W.Problem("gemm_%dx%dx%d" % (m, n, k), "f64", W.tensor("mk", e), W.tensor("kn", e), W.tensor("mn", e),
+                     alpha=1.0, beta=0.0, seed=W.BASE_SEED + 20)
+
+
 def make_problem(name: str) -> W.Problem:
     table = {"cfg1": W.config1, "cfg2": W.config2, "cfg3": W.config3, "cfg4": W.config4, "cfg5": W.config5,
              "cfg3r2": lambda: W.config3(d_layout="R2"), "cfg4hs": lambda: W.config4(h_slowest=True),
              "gemm1k": lambda: W.config2(v=32, o=32),      # contiguous 1024^3 product, same size as cfg5
+             "gemmk16": lambda: _gemm(1024, 1024, 16), "gemmk256": lambda: _gemm(1024, 1024, 256),
              # supplementary HBM-bound shapes
              "s1": lambda: W.config5(extent=4, nshared=1, nfree=7), "s2": lambda: W.config5(extent=4, nshared=0, nfree=7),
              "s3": lambda: W.hadamard(4, 128), "s3p": lambda: W.hadamard(4, 128, permuted=True),

@@ -77,11 +77,10 @@ template <class R> struct RealPolicy {
         c.v = DNF ? MF::mac(a, b, c.v)      // rows = m, lanes along n
                   : MF::mac(b, a, c.v);     // rows = n, lanes along m
     }
-    static __device__ __forceinline__ void store(elem* D, const elem* C, int64_t off, const acc_t& c, int v,
-                                                 const Scalars& s, bool read_c, int) {
+    static __device__ __forceinline__ elem combine(const acc_t& c, int v, const Scalars& s, bool read_c, elem cc, int) {
         R d = (R)s.alpha_re * c.v[v];
-        if (read_c) d += (R)s.beta_re * C[off];
-        D[off] = d;
+        if (read_c) d += (R)s.beta_re * cc;
+        return d;
     }
 };
 
@@ -142,18 +141,16 @@ struct ComplexPolicy {
             c.im = MF::mac(b.x, a.y, c.im);
         }
     }
-    static __device__ __forceinline__ void store(elem* D, const elem* C, int64_t off, const acc_t& c, int v,
-                                                 const Scalars& s, bool read_c, int opC) {
+    static __device__ __forceinline__ elem combine(const acc_t& c, int v, const Scalars& s, bool read_c, elem cc, int opC) {
         const double re = c.re[v], im = c.im[v];
         double dr = s.alpha_re * re - s.alpha_im * im;
         double di = s.alpha_re * im + s.alpha_im * re;
         if (read_c) {
-            elem cc = C[off];
             if (opC == TCX_OP_CONJ) cc.y = -cc.y;
             dr += s.beta_re * cc.x - s.beta_im * cc.y;
             di += s.beta_re * cc.y + s.beta_im * cc.x;
         }
-        D[off] = double2{dr, di};
+        return double2{dr, di};
     }
 };
 
@@ -229,6 +226,8 @@ __device__ __forceinline__ Tile locate_tile(int64_t t_all, const GettArgs& g, in
 }
 
 // alpha/beta epilogue of one thread's accumulators: strided scatter through D's offset tables.
+// The reads of C for a whole row of fragments are issued together before any of them is used,
+// so a thread pays the memory latency FM times rather than once per element.
 template <class P, int FM, int FN, int WT_M, int WT_N, bool DNF>
 __device__ __forceinline__ void scatter(const typename P::acc_t (&acc)[FM][FN], const GettArgs& g, const Tile& tile,
                                         int wm, int wn, int lane) {
@@ -237,8 +236,12 @@ __device__ __forceinline__ void scatter(const typename P::acc_t (&acc)[FM][FN], 
     const T* __restrict__ C = (const T*)g.C + tile.hD;
     T* __restrict__ D = (T*)g.D + tile.hD;
     const int fr = lane & 15;
+    const bool read_c = g.read_c != 0;
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < FM; ++i) {
+        int64_t off[FN][4];
+        bool ok[FN][4];
+        T cval[FN][4];
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -246,9 +249,23 @@ __device__ __forceinline__ void scatter(const typename P::acc_t (&acc)[FM][FN], 
                 const int rr = MF::row_of(lane, v);
                 const int ml = wm * WT_M + i * 16 + (DNF ? rr : fr);
                 const int nl = wn * WT_N + j * 16 + (DNF ? fr : rr);
-                if (tile.m0 + ml < g.sizeM && tile.n0 + nl < g.sizeN)
-                    P::store(D, C, g.oDM[tile.m0 + ml] + g.oDN[tile.n0 + nl], acc[i][j], v, g.s, g.read_c != 0, g.opC);
+                ok[j][v] = tile.m0 + ml < g.sizeM && tile.n0 + nl < g.sizeN;
+                off[j][v] = g.oDM[tile.m0 + ml] + g.oDN[tile.n0 + nl];      // padded tables: always a valid entry
+                cval[j][v] = P::zero();
             }
+        if (read_c) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (ok[j][v]) cval[j][v] = C[off[j][v]];
+        }
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (ok[j][v]) D[off[j][v]] = P::combine(acc[i][j], v, g.s, read_c, cval[j][v], g.opC);
+    }
 }
 
 // DEPTH: how many slabs ahead of the MFMAs the global loads run (a ring of DEPTH register sets).
@@ -266,7 +283,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
     using MF = typename P::MF;
     static_assert(KT % 4 == 0 && WT_M % 16 == 0 && WT_N % 16 == 0, "tile shape");
 
-    __shared__ T lds[2 * (SA::ELEMS + SB::ELEMS)];
+    // three slabs of LDS: see the main loop
+    __shared__ T lds[3 * (SA::ELEMS + SB::ELEMS)];
+    static_assert(sizeof(T) * 3 * (SA::ELEMS + SB::ELEMS) <= 160 * 1024, "LDS budget of a CU");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -351,11 +370,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
         for (int j = 0; j < FN; ++j) P::clear(acc[i][j]);
 
     const int fr = lane & 15, fq = lane >> 4;
-    auto compute = [&](int buf) {
+    auto compute = [&](int buf, int ks_begin, int ks_end) {
         const T* sa = lds + buf * (SA::ELEMS + SB::ELEMS);
         const T* sb = sa + SA::ELEMS;
 #pragma unroll
-        for (int ks = 0; ks < KT; ks += 4) {
+        for (int ks = ks_begin; ks < ks_end; ks += 4) {
             T fa[FM], fb[FN];
 #pragma unroll
             for (int i = 0; i < FM; ++i) fa[i] = sa[SA::frag_index(wm * WT_M + i * 16 + fr, ks + fq)];
@@ -369,12 +388,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
         if (FM * FN <= 2) settle_accumulators();
     };
 
-    // ---- main loop: the data loads of slab kt+1 and the table loads of slab kt+2 are in
-    // flight while the MFMAs run on slab kt.  The last two slabs are peeled so that the loop
-    // body is one straight path.
+    // ---- main loop.  Global loads run DEPTH slabs ahead in registers.  LDS holds three slabs
+    // and the workgroup barrier sits in the MIDDLE of a slab's MFMAs: slab kt+1 is written to
+    // LDS after the first half of slab kt and is first read a whole half-slab after the
+    // barrier, so no wave ever idles at a slab boundary waiting for LDS data, and a wave
+    // that waits at the barrier does so while the other waves of its SIMD still have MFMAs
+    // to issue.  The third buffer makes that safe: the buffer being written was last read two
+    // slabs ago, which every wave finished before it reached the previous barrier.
     const bool ragged_k = g.sizeK % KT != 0;
     const int per_split = (nk + g.splitK - 1) / g.splitK;
     const int kb = split * per_split, ke = min(nk, kb + per_split);      // this workgroup's slabs [kb, ke)
+    constexpr int KH = (KT / 8) * 4 > 0 ? (KT / 8) * 4 : 4;              // first "half" of a slab, a multiple of 4
     // Prologue: fill the ring with slabs kb .. kb+DEPTH-1 (slab numbers past the end are clamped
     // by k_offsets to the last slab: harmless loads that are never staged).
 #pragma unroll
@@ -394,16 +418,18 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
 #pragma unroll
         for (int u = 0; u < DEPTH; ++u) {
             if (kt + u >= ke - 1) break;
+            const int next = buf == 2 ? 0 : buf + 1;
             gather(u);                                   // slab kt+u+DEPTH
             k_offsets(kt + u + DEPTH + 1);
-            compute(buf);                                // slab kt+u
+            compute(buf, 0, KH);                         // slab kt+u, first half
             if (ragged_k && kt + u + 1 == nk - 1) mask_last((u + 1) % DEPTH);
-            stage((u + 1) % DEPTH, buf ^ 1);             // slab kt+u+1
+            stage((u + 1) % DEPTH, next);                // slab kt+u+1
             __syncthreads();
-            buf ^= 1;
+            compute(buf, KH, KT);                        // slab kt+u, second half
+            buf = next;
         }
     }
-    compute(buf);                                        // slab ke-1
+    compute(buf, 0, KT);                                 // slab ke-1
     settle_accumulators();
 
     // ---- epilogue.  With split-K the raw accumulators go to the workspace, one coalesced
@@ -590,6 +616,8 @@ constexpr Shape kComplexShapes[] = {
     {32, 32, 8, 2, 2, 0.20f, 0, 3},
     {96, 96, 8, 2, 2, 0.45f, 2, 0},
     {64, 64, 8, 2, 2, 0.25f, 2, 0},
+    {96, 48, 8, 2, 1, 0.45f, 0, 2},
+    {48, 96, 8, 1, 2, 0.45f, 0, 2},
 };
 constexpr int kNumRealShapes = sizeof(kRealShapes) / sizeof(Shape);
 constexpr int kNumComplexShapes = sizeof(kComplexShapes) / sizeof(Shape);
@@ -658,6 +686,8 @@ hipError_t launch_complex_shape(int variant, bool akf, bool bkf, bool dnf, const
         case 2: return launch_flags<ComplexPolicy, 2>(akf, bkf, dnf, a, blocks, st);
         case 3: return launch_flags<ComplexPolicy, 3>(akf, bkf, dnf, a, blocks, st);
         case 4: return launch_flags<ComplexPolicy, 4>(akf, bkf, dnf, a, blocks, st);
+        case 5: return launch_flags<ComplexPolicy, 5>(akf, bkf, dnf, a, blocks, st);
+        case 6: return launch_flags<ComplexPolicy, 6>(akf, bkf, dnf, a, blocks, st);
         default: return hipErrorInvalidValue;
     }
 }
