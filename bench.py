@@ -132,6 +132,8 @@ def main():
     ap.add_argument("--variant", type=int, default=None, help="force a tiled-kernel instantiation")
     ap.add_argument("--path", type=int, default=None, help="force a kernel path (0 generic, 1 tiled MFMA, 2 streaming)")
     ap.add_argument("--split-k", type=int, default=None, help="force the number of parts of the contracted range (tiled path)")
+    ap.add_argument("--perm-seeds", type=int, default=0,
+                    help="cfg5 only: also time this many other permutation seeds (its speed depends on the draw)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB streaming kernel (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -219,6 +221,28 @@ def main():
            "split_k": T.tcx_product_get(prod, T.TCX_KEY_SPLIT_K),
            "grid": T.tcx_product_get(prod, T.TCX_KEY_GRID), "plan_ms": plan_ms,
            "flop_per_step": flops, "algorithmic_bytes_per_step": p.algorithmic_bytes()}
+
+    if args.perm_seeds and args.workload == "cfg5":
+        times = []
+        for ps in range(args.perm_seeds):
+            q = W.config5(perm_seed=1000 + ps)
+            qa, qb, qd, _ = device_operands(q, torch)
+            qi = [T.tcx_create_tensor_info(h, DT[q.dtype], t.extents, t.strides) for t in (q.A, q.B, q.D)]
+            ql = [[W.label_ids(q)[l] for l in t.labels] for t in (q.A, q.B, q.D)]
+            qp = T.tcx_create_product(h, 0, qi[0], ql[0], 0, qi[1], ql[1], 0, qi[2], ql[2], 0, qi[2], ql[2])
+            for _ in range(3):
+                T.tcx_execute_product(qp, ex, DT[q.dtype], q.alpha, qa.data_ptr(), qb.data_ptr(), q.beta, 0, qd.data_ptr())
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(51)]
+            ev[0].record(stream)
+            for it in range(50):
+                T.tcx_execute_product(qp, ex, DT[q.dtype], q.alpha, qa.data_ptr(), qb.data_ptr(), q.beta, 0, qd.data_ptr())
+                ev[it + 1].record(stream)
+            torch.cuda.synchronize()
+            # the median launch: a single stall of the box (tens of ms, now and then) would own a mean
+            times.append(float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(50)])) * 1e3)
+            T.tcx_destroy_product(qp)
+        cfg["perm_seed_us"] = {"min": float(np.min(times)), "median": float(np.median(times)), "max": float(np.max(times)),
+                               "n": len(times)}
 
     out = {"metric": "contraction GFLOP/s (fp64/fp32/c128) and % MFMA peak; GB/s for low-AI shapes",
            "value": value, "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -18,7 +18,7 @@ GENERIC, GETT, STREAM = 0, 1, 2
 def _paths_for(p):
     from gpu_helpers import DT  # noqa: F401
     paths = [(GENERIC, None)]
-    paths += [(GETT, v) for v in range(5 if p.dtype == "c128" else 9)]
+    paths += [(GETT, v) for v in range(7 if p.dtype == "c128" else 9)]
     if p.sizes()[3] <= 64:
         paths.append((STREAM, None))
     return paths
@@ -75,7 +75,7 @@ def test_random_problems(dtype):
         p = random_problem(rng, dtype, max_group=3, max_extent=6, allow_neg=(i % 3 == 0), name="rand%d_%s" % (i, dtype))
         a, b, c = W.make_operands(p)
         truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
-        paths = [(GENERIC, None), (GETT, (1 + i % 4) if dtype == "c128" else (2 + i % 5)), (STREAM, None)]
+        paths = [(GENERIC, None), (GETT, (1 + i % 6) if dtype == "c128" else (2 + i % 7)), (STREAM, None)]
         for path, variant in paths:
             _check(p, a, b, c, path, variant, truth=truth, S=S)
         _check(p, a, b, c, GETT, paths[1][1], truth=truth, S=S, split_k=2 + i % 3)
@@ -113,6 +113,21 @@ def test_low_intensity_shapes_all_paths(p):
     truth, S = run_oracle(p2, a, b, c, oracle.MODE_TRUTH, want_S=True)
     for path, variant in ((GETT, None), (STREAM, None), (STREAM, 0)):
         _check(p2, a, b, c, path, variant, exact=True, truth=truth, S=S)
+
+
+LOW_AI_LARGE = [W.config5(extent=4, nshared=1, nfree=7), W.config4(h=512, n=96, k=4),
+                W.hadamard(4, 64, permuted=True, beta=0.5), W.config5(extent=4, nshared=0, nfree=6)]
+
+
+@pytest.mark.parametrize("p", LOW_AI_LARGE, ids=lambda p: p.name)
+def test_low_intensity_shapes_large(p):
+    """The streaming path at sizes far beyond one tile (the rank-14 output of the one-label
+    contraction has 4^14 elements), whole output compared, on the plan's own path and on the
+    streaming path forced."""
+    a, b, c = W.make_operands(p, "uniform")
+    truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+    _check(p, a, b, c, None, None, truth=truth, S=S)
+    _check(p, a, b, c, STREAM, None, truth=truth, S=S)
 
 
 FULL = [W.config1(), W.config3(), W.config3(d_layout="R2"), W.config4(), W.config4(h_slowest=True), W.config5()]
