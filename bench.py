@@ -134,6 +134,9 @@ def main():
     ap.add_argument("--split-k", type=int, default=None, help="force the number of parts of the contracted range (tiled path)")
     ap.add_argument("--perm-seeds", type=int, default=0,
                     help="cfg5 only: also time this many other permutation seeds (its speed depends on the draw)")
+    ap.add_argument("--cold", type=int, default=0,
+                    help="rotate through this many distinct copies of the operands (choose enough to exceed the "
+                         "256 MB Infinity Cache) so that every step reads its inputs from HBM")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB streaming kernel (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -169,8 +172,18 @@ def main():
     item = dD.element_size()
     pA, pB, pD = (t.data_ptr() + s.base * item for t, s in ((dA, p.A), (dB, p.B), (dD, p.D)))
 
+    sets = [(pA, pB, pD)]
+    keep = []
+    for _ in range(max(0, args.cold - 1)):                # device-side copies: same values, other addresses
+        cA, cB, cD = dA.clone(), dB.clone(), dD.clone()
+        keep.append((cA, cB, cD))
+        sets.append(tuple(t.data_ptr() + s.base * item for t, s in ((cA, p.A), (cB, p.B), (cD, p.D))))
+    counter = [0]
+
     def step():
-        T.tcx_execute_product(prod, ex, DT[p.dtype], p.alpha, pA, pB, p.beta, pD, pD)
+        a, b, d = sets[counter[0] % len(sets)]
+        counter[0] += 1
+        T.tcx_execute_product(prod, ex, DT[p.dtype], p.alpha, a, b, p.beta, d, d)
 
     if args.copy_probe:
         src = torch.ones(1 << 27, dtype=torch.float64, device="cuda:0")     # fill kernel: 1 GiB written
@@ -221,6 +234,22 @@ def main():
            "split_k": T.tcx_product_get(prod, T.TCX_KEY_SPLIT_K),
            "grid": T.tcx_product_get(prod, T.TCX_KEY_GRID), "plan_ms": plan_ms,
            "flop_per_step": flops, "algorithmic_bytes_per_step": p.algorithmic_bytes()}
+
+    cfg["buffers"] = "cache-resident (one operand set)" if len(sets) == 1 else \
+        "cold: rotating over %d operand sets, %.0f MB in total" % (len(sets), len(sets) * p.algorithmic_bytes() / 1e6)
+    if avg_kernel_s < 1e-3:
+        # what a back-to-back launch of an (almost) empty kernel costs on this stream: the floor
+        # under any sub-millisecond figure above
+        one = torch.zeros(1, device="cuda:0")
+        for _ in range(20):
+            one.zero_()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(200):
+            one.zero_()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        roofline["launch_floor_us"] = e0.elapsed_time(e1) / 200 * 1e3
 
     if args.perm_seeds and args.workload == "cfg5":
         times = []
