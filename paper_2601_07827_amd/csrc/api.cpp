@@ -40,6 +40,12 @@ struct Product {
     std::vector<int64_t> tables[6];  // oAM oAK oBN oBK oDM oDN
     int64_t* dev_tables = nullptr;
     size_t dev_offset[6] = {0, 0, 0, 0, 0, 0};
+    // tile-relative 32-bit gather tables of the LDS-staged tiled kernels (built for the plan's
+    // tile shape; one device allocation): per operand rowrel, rowbase, kofs, krel, kbase
+    unsigned char* dev_narrow = nullptr;
+    size_t narrow_off[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    int narrow_variant = -1;         // tile shape the narrow tables were built for (-1: none)
+    bool periodic[2] = {false, false};   // A, B: relative k offsets repeat from slab to slab
     GenericArgs generic{};
     // bandwidth path: plan and its device tables (one allocation)
     StreamPlan stream;
@@ -190,6 +196,132 @@ tcx_error_t ensure_workspace(Product* p) {
 }
 
 int elem_bytes(int dtype) { return dtype == TCX_F32 ? 4 : dtype == TCX_F64 ? 8 : 16; }
+
+// Gather tables of the LDS-staged tiled kernels.  An operand element's address is split as
+//   base(workgroup) + rowbase[tile] + { kofs[k]  |  kbase[slab] + krel[k] } + rowrel[row],
+// all in bytes, where rowbase / kbase are the smallest offsets inside a tile's rows / a slab's
+// contracted indices.  rowrel and krel are then small non-negative numbers and fit 32 bits
+// (checked here), so a load is "64-bit scalar base + 32-bit per-lane offset": no 64-bit vector
+// arithmetic and half the registers per offset.  kofs serves operands whose lanes run along the
+// rows (one k per wave: its offset is a scalar); kbase + krel serves lanes that run along k.
+struct NarrowOperand {
+    std::vector<uint32_t> rowrel, krel;
+    std::vector<int64_t> rowbase, kofs, kbase;
+    bool periodic = true;      // every slab has the relative k offsets of the first (and |K| is whole slabs)
+};
+
+bool narrow_operand(const std::vector<int64_t>& rows, int64_t nrows, int mt, const std::vector<int64_t>& ks, int64_t nk,
+                    int kt, int64_t esize, NarrowOperand* out) {
+    const int64_t tiles = (nrows + mt - 1) / mt, slabs = (nk + kt - 1) / kt;
+    out->rowrel.assign((size_t)(tiles * mt), 0);
+    out->rowbase.assign((size_t)tiles, 0);
+    out->krel.assign((size_t)(slabs * kt), 0);
+    out->kbase.assign((size_t)slabs, 0);
+    out->kofs.assign((size_t)(slabs * kt), 0);
+    uint64_t max_row = 0, max_k = 0;
+    for (int64_t t = 0; t < tiles; ++t) {
+        const int64_t lo = t * mt, hi = std::min(nrows, lo + mt);
+        int64_t base = rows[(size_t)lo];
+        for (int64_t r = lo; r < hi; ++r) base = std::min(base, rows[(size_t)r]);
+        out->rowbase[(size_t)t] = base * esize;
+        for (int64_t r = lo; r < lo + mt; ++r) {                 // rows past the end repeat the tile's first row
+            const uint64_t rel = (uint64_t)(rows[(size_t)(r < hi ? r : lo)] - base) * (uint64_t)esize;
+            if (rel > 0xffffffffull) return false;
+            out->rowrel[(size_t)r] = (uint32_t)rel;
+            max_row = std::max(max_row, rel);
+        }
+    }
+    for (int64_t sl = 0; sl < slabs; ++sl) {
+        const int64_t lo = sl * kt, hi = std::min(nk, lo + kt);
+        int64_t base = ks[(size_t)lo];
+        for (int64_t k = lo; k < hi; ++k) base = std::min(base, ks[(size_t)k]);
+        out->kbase[(size_t)sl] = base * esize;
+        for (int64_t k = lo; k < lo + kt; ++k) {                 // indices past the end repeat the slab's first
+            const int64_t off = ks[(size_t)(k < hi ? k : lo)];
+            const uint64_t rel = (uint64_t)(off - base) * (uint64_t)esize;
+            if (rel > 0xffffffffull) return false;
+            out->krel[(size_t)k] = (uint32_t)rel;
+            out->kofs[(size_t)k] = off * esize;
+            max_k = std::max(max_k, rel);
+        }
+    }
+    out->periodic = nk % kt == 0;
+    for (int64_t k = kt; k < slabs * kt && out->periodic; ++k)
+        if (out->krel[(size_t)k] != out->krel[(size_t)(k % kt)]) out->periodic = false;
+    return max_row + max_k <= 0xffffffffull;                     // the kernel adds the two in 32 bits
+}
+
+// Builds the narrow tables for tile shape `variant`; TCX_ERR_UNSUPPORTED_OP if a tile of that
+// shape spans 4 GB or more of an operand.
+tcx_error_t build_narrow(Product* p, int variant) {
+    const GettVariant s = gett_variant(p->an.dtype, variant);
+    if (p->narrow_variant == variant) return TCX_SUCCESS;
+    const int64_t es = elem_bytes(p->an.dtype);
+    NarrowOperand a, b;
+    try {
+        if (!narrow_operand(p->tables[0], p->an.sizeM, s.mt_m, p->tables[1], p->an.sizeK, s.kt, es, &a) ||
+            !narrow_operand(p->tables[2], p->an.sizeN, s.mt_n, p->tables[3], p->an.sizeK, s.kt, es, &b))
+            return TCX_ERR_UNSUPPORTED_OP;
+        // the two-phase kernel has no masked slab, and precomputes the per-lane k offsets of
+        // an operand whose lanes run along k
+        if (s.pingpong && (p->an.sizeK % s.kt != 0 || (p->an.a_k_fastest && !a.periodic) || (p->an.b_k_fastest && !b.periodic)))
+            return TCX_ERR_UNSUPPORTED_OP;
+        p->periodic[0] = a.periodic;
+        p->periodic[1] = b.periodic;
+    } catch (const std::bad_alloc&) {
+        return TCX_ERR_ALLOC;
+    }
+    p->narrow_variant = -1;
+    if (!p->handle.has_device) return TCX_SUCCESS;
+    if (p->dev_narrow) { (void)hipFree(p->dev_narrow); p->dev_narrow = nullptr; }
+    const void* src[10] = {a.rowrel.data(), a.rowbase.data(), a.kofs.data(), a.krel.data(), a.kbase.data(),
+                           b.rowrel.data(), b.rowbase.data(), b.kofs.data(), b.krel.data(), b.kbase.data()};
+    const size_t bytes[10] = {a.rowrel.size() * 4, a.rowbase.size() * 8, a.kofs.size() * 8, a.krel.size() * 4, a.kbase.size() * 8,
+                              b.rowrel.size() * 4, b.rowbase.size() * 8, b.kofs.size() * 8, b.krel.size() * 4, b.kbase.size() * 8};
+    size_t total = 0;
+    for (int i = 0; i < 10; ++i) { p->narrow_off[i] = total; total += (bytes[i] + 255) / 256 * 256; }
+    if (hipMalloc((void**)&p->dev_narrow, total) != hipSuccess) {
+        p->dev_narrow = nullptr;
+        (void)hipGetLastError();
+        return TCX_ERR_ALLOC;
+    }
+    for (int i = 0; i < 10; ++i)
+        if (bytes[i] && hipMemcpy(p->dev_narrow + p->narrow_off[i], src[i], bytes[i], hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipGetLastError();
+            (void)hipFree(p->dev_narrow);
+            p->dev_narrow = nullptr;
+            return TCX_ERR_LAUNCH;
+        }
+    p->narrow_variant = variant;
+    return TCX_SUCCESS;
+}
+
+// Everything the tiled path needs for the plan's current tile shape.  If a tile of that shape
+// spans too much of an operand for 32-bit relative offsets, smaller shapes are tried.
+tcx_error_t prepare_tiled(Product* p) {
+    if (p->tables[0].empty()) {
+        const tcx_error_t err = build_tables(p);
+        if (err != TCX_SUCCESS) return err;
+    }
+    const int n = gett_num_variants(p->an.dtype);
+    tcx_error_t err = TCX_ERR_UNSUPPORTED_OP;
+    const int first = p->variant, second = gett_variant(p->an.dtype, first).fallback;
+    for (int t = -1; t <= n; ++t) {
+        // order: the plan's shape, the shape it names as its stand-in, then all others
+        const int v = t == -1 ? first : t == 0 ? second : t - 1;
+        if (v < 0 || (t > 0 && (v == first || v == second))) continue;
+        err = gett_variant(p->an.dtype, v).staged ? build_narrow(p, v) : TCX_SUCCESS;
+        if (err == TCX_SUCCESS) {
+            if (v != p->variant) { p->variant = v; p->splitK = 1; }
+            break;
+        }
+        if (err != TCX_ERR_UNSUPPORTED_OP) break;
+    }
+    if (err != TCX_SUCCESS) return err;
+    p->an.variant = p->variant;
+    if (ensure_workspace(p) != TCX_SUCCESS) p->splitK = 1;      // no memory: run unsplit
+    return TCX_SUCCESS;
+}
 
 tcx_error_t build_stream(Product* p, bool allow_blocked = true) {
     if (p->dev_stream) { (void)hipFree(p->dev_stream); p->dev_stream = nullptr; }
@@ -373,8 +505,8 @@ tcx_error_t tcx_create_product(tcx_handle_t handle, tcx_op_t opA, tcx_tensor_inf
             p->an.path = TCX_PATH_BANDWIDTH;
         } else if (p->an.path == TCX_PATH_GETT_MFMA) {
             choose_plan(p->an, h->num_cu, &p->variant, &p->splitK);
-            err = build_tables(p);
-            if (err == TCX_SUCCESS && ensure_workspace(p) != TCX_SUCCESS) p->splitK = 1;   // no memory: run unsplit
+            err = prepare_tiled(p);
+            if (err == TCX_ERR_UNSUPPORTED_OP) { err = TCX_SUCCESS; p->an.path = TCX_PATH_GENERIC; }
         }
         p->an.variant = p->variant;
     }
@@ -388,6 +520,7 @@ tcx_error_t tcx_destroy_product(tcx_product_t* product) {
     Product* p = lookup<Product>(*product, MAGIC_PRODUCT);
     if (!p) return TCX_ERR_INVALID_HANDLE;
     if (p->dev_tables) { (void)hipFree(p->dev_tables); p->dev_tables = nullptr; }
+    if (p->dev_narrow) { (void)hipFree(p->dev_narrow); p->dev_narrow = nullptr; }
     if (p->dev_stream) { (void)hipFree(p->dev_stream); p->dev_stream = nullptr; }
     if (p->workspace) { (void)hipFree(p->workspace); p->workspace = nullptr; }
     return retire<Product>(product, MAGIC_PRODUCT);
@@ -440,12 +573,9 @@ tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* valu
         if (v == TCX_PATH_GENERIC) { p->an.path = TCX_PATH_GENERIC; return TCX_SUCCESS; }
         if (v == TCX_PATH_GETT_MFMA) {
             if (gett_num_variants(p->an.dtype) == 0 || (int)p->an.H.size() > kMaxHModes) return TCX_ERR_UNSUPPORTED_OP;
-            if (p->tables[0].empty()) {
-                choose_plan(p->an, p->handle.num_cu, &p->variant, &p->splitK);
-                const tcx_error_t err = build_tables(p);
-                if (err != TCX_SUCCESS) return err;
-                if (ensure_workspace(p) != TCX_SUCCESS) p->splitK = 1;
-            }
+            if (p->tables[0].empty()) choose_plan(p->an, p->handle.num_cu, &p->variant, &p->splitK);
+            const tcx_error_t err = prepare_tiled(p);
+            if (err != TCX_SUCCESS) return err;
             p->an.path = TCX_PATH_GETT_MFMA;
             return TCX_SUCCESS;
         }
@@ -466,6 +596,10 @@ tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* valu
     }
     if (key == TCX_KEY_VARIANT) {
         if (p->an.path != TCX_PATH_GETT_MFMA || v < 0 || v >= gett_num_variants(p->an.dtype)) return TCX_ERR_UNSUPPORTED_OP;
+        if (gett_variant(p->an.dtype, (int)v).staged) {
+            const tcx_error_t err = build_narrow(p, (int)v);
+            if (err != TCX_SUCCESS) return err;
+        }
         p->variant = (int)v;
         p->an.variant = (int)v;
         p->splitK = 1;                       // a forced shape starts unsplit; set TCX_KEY_SPLIT_K afterwards
@@ -505,7 +639,8 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
     int hip_err = 0;
     int64_t grid = 0;
     int block = 0;
-    const bool tiled = p->an.path == TCX_PATH_GETT_MFMA && read_ab && p->dev_tables;
+    const bool tiled = p->an.path == TCX_PATH_GETT_MFMA && read_ab && p->dev_tables &&
+                       (!gett_variant(p->an.dtype, p->variant).staged || (p->dev_narrow && p->narrow_variant == p->variant));
     const bool streamed = p->an.path == TCX_PATH_BANDWIDTH && read_ab && p->dev_stream;
     if (streamed) {
         const StreamPlan& sp = p->stream;
@@ -536,6 +671,15 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
         g.oAM = p->dev_tables + p->dev_offset[0]; g.oAK = p->dev_tables + p->dev_offset[1];
         g.oBN = p->dev_tables + p->dev_offset[2]; g.oBK = p->dev_tables + p->dev_offset[3];
         g.oDM = p->dev_tables + p->dev_offset[4]; g.oDN = p->dev_tables + p->dev_offset[5];
+        if (p->dev_narrow) {
+            const unsigned char* nb = p->dev_narrow;
+            const size_t* o = p->narrow_off;
+            g.rrA = (const uint32_t*)(nb + o[0]); g.rbA = (const int64_t*)(nb + o[1]); g.kqA = (const int64_t*)(nb + o[2]);
+            g.krA = (const uint32_t*)(nb + o[3]); g.kbA = (const int64_t*)(nb + o[4]);
+            g.rrB = (const uint32_t*)(nb + o[5]); g.rbB = (const int64_t*)(nb + o[6]); g.kqB = (const int64_t*)(nb + o[7]);
+            g.krB = (const uint32_t*)(nb + o[8]); g.kbB = (const int64_t*)(nb + o[9]);
+            g.periodicA = p->periodic[0]; g.periodicB = p->periodic[1];
+        }
         g.sizeM = p->an.sizeM; g.sizeN = p->an.sizeN; g.sizeK = p->an.sizeK; g.sizeH = p->an.sizeH;
         g.tilesM = (int32_t)((g.sizeM + v.mt_m - 1) / v.mt_m);
         g.tilesN = (int32_t)((g.sizeN + v.mt_n - 1) / v.mt_n);

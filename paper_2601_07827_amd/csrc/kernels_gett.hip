@@ -73,6 +73,9 @@ template <class R> struct RealPolicy {
     static __device__ __forceinline__ void clear(acc_t& c) { c.v = vec{0, 0, 0, 0}; }
     static __device__ __forceinline__ elem zero() { return R(0); }
     static __device__ __forceinline__ elem load(const elem* p, int64_t off, unsigned) { return p[off]; }
+    static __device__ __forceinline__ elem load_at(const char* base, uint32_t byte_off, unsigned) {
+        return *(const elem*)(base + byte_off);
+    }
     template <bool DNF> static __device__ __forceinline__ void mac(elem a, elem b, acc_t& c) {
         c.v = DNF ? MF::mac(a, b, c.v)      // rows = m, lanes along n
                   : MF::mac(b, a, c.v);     // rows = n, lanes along m
@@ -123,6 +126,12 @@ struct ComplexPolicy {
     static __device__ __forceinline__ elem zero() { return double2{0.0, 0.0}; }
     static __device__ __forceinline__ elem load(const elem* p, int64_t off, unsigned conj_mask_hi) {
         elem v = p[off];
+        unsigned long long bits = __builtin_bit_cast(unsigned long long, v.y) ^ ((unsigned long long)conj_mask_hi << 32);
+        v.y = __builtin_bit_cast(double, bits);
+        return v;
+    }
+    static __device__ __forceinline__ elem load_at(const char* base, uint32_t byte_off, unsigned conj_mask_hi) {
+        elem v = *(const elem*)(base + byte_off);
         unsigned long long bits = __builtin_bit_cast(unsigned long long, v.y) ^ ((unsigned long long)conj_mask_hi << 32);
         v.y = __builtin_bit_cast(double, bits);
         return v;
@@ -186,6 +195,21 @@ __device__ __forceinline__ void settle_accumulators() {
     asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
 }
+
+// Values that are the same for every lane of a wave but were computed by vector instructions
+// (divisions, table reads): moved to scalar registers, so that what is derived from them (loop
+// counters, base addresses, table reads) is scalar work too.
+__device__ __forceinline__ int wave_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ int64_t wave_uniform(int64_t v) {
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)(uint64_t)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// Read-only plan tables indexed by a wave-uniform number: viewed through the constant address
+// space their reads are scalar loads whatever else the kernel stores.
+template <class T> using const_table = const __attribute__((address_space(4))) T*;
+template <class T> __device__ __forceinline__ const_table<T> scalar_table(const T* p) { return (const_table<T>)(uintptr_t)p; }
 
 // Consecutive workgroup ids go round-robin over the 8 XCDs; remap so that each XCD (private
 // 4 MB L2) works on one contiguous stretch of the tile order.
@@ -271,7 +295,7 @@ __device__ __forceinline__ void scatter(const typename P::acc_t (&acc)[FM][FN], 
 // DEPTH: how many slabs ahead of the MFMAs the global loads run (a ring of DEPTH register sets).
 // Large tiles spend longer on a slab than a load takes and need 1; small tiles need more bytes
 // in flight to cover the same latency.
-template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF, int DEPTH>
+template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF, int DEPTH, bool NARROW>
 __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
     using T = typename P::elem;
     using acc_t = typename P::acc_t;
@@ -294,24 +318,40 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
 
     // ---- which tile, and which part of K (split-K: consecutive ids are the parts of one tile)
     const int64_t lid = xcd_contiguous(blockIdx.x, gridDim.x);
-    const int split = (int)(lid % g.splitK);
+    const int split = wave_uniform((int)(lid % g.splitK));
     const Tile tile = locate_tile(lid / g.splitK, g, MT_M, MT_N);
-    const int64_t m0 = tile.m0, n0 = tile.n0, hA = tile.hA, hB = tile.hB, hD = tile.hD;
-    const T* __restrict__ A = (const T*)g.A + hA;
-    const T* __restrict__ B = (const T*)g.B + hB;
-
-    // ---- loop-invariant part of the gather: this thread's row offsets.  Rows past the end of
-    // M or N read a valid (padded) table entry; what they accumulate is never stored.
+    const int64_t m0 = wave_uniform(tile.m0), n0 = wave_uniform(tile.n0);
+    // ---- gather addressing, two forms.
+    // NARROW: an element's address is a wave-uniform 64-bit base plus a 32-bit per-lane byte
+    // offset (the plan's tile-relative tables), which the hardware adds itself: no 64-bit vector
+    // arithmetic in the loop and one register per offset.  This is the faster form for the
+    // small tiles, whose loops are short of issue slots.
+    // Otherwise: 64-bit element offsets from the plain tables, summed per lane.  The 256 x 128
+    // tile, whose loop is bound by the matrix pipe, measured faster this way.
+    const char* const Ab = (const char*)g.A + (NARROW ? wave_uniform(tile.hA * (int64_t)sizeof(T) + scalar_table(g.rbA)[m0 / MT_M]) : 0);
+    const char* const Bb = (const char*)g.B + (NARROW ? wave_uniform(tile.hB * (int64_t)sizeof(T) + scalar_table(g.rbB)[n0 / MT_N]) : 0);
+    const T* __restrict__ A = (const T*)g.A + tile.hA;
+    const T* __restrict__ B = (const T*)g.B + tile.hB;
+    // Row offsets are loop-invariant.  Rows past the end of M or N read a valid (padded) table
+    // entry; what they accumulate is never stored.
+    uint32_t rrA[SA::PER], rrB[SB::PER];
     int64_t offA[SA::PER], offB[SB::PER];
 #pragma unroll
-    for (int i = 0; i < SA::PER; ++i) offA[i] = g.oAM[m0 + SA::row(tid + i * NT)];
+    for (int i = 0; i < SA::PER; ++i) {
+        if (NARROW) rrA[i] = g.rrA[m0 + SA::row(tid + i * NT)];
+        else offA[i] = g.oAM[m0 + SA::row(tid + i * NT)];
+    }
 #pragma unroll
-    for (int i = 0; i < SB::PER; ++i) offB[i] = g.oBN[n0 + SB::row(tid + i * NT)];
+    for (int i = 0; i < SB::PER; ++i) {
+        if (NARROW) rrB[i] = g.rrB[n0 + SB::row(tid + i * NT)];
+        else offB[i] = g.oBN[n0 + SB::row(tid + i * NT)];
+    }
 
     // Offsets along K come from the tables one slab ahead of the data loads that use them,
     // so a data load never waits on a table load issued in the same iteration.  Where the
-    // k index is the same for a whole wave it is made scalar, which turns the table read
-    // into a scalar load.
+    // k index is the same for a whole wave its offset is a scalar (NARROW: it goes into the
+    // base); otherwise (NARROW) the slab's base is the scalar and each lane adds its k's
+    // relative offset.
     const int nk = g.tilesK;
     unsigned kinA[SA::PER], kinB[SB::PER];       // this thread's k index inside a slab, per element
 #pragma unroll
@@ -324,14 +364,41 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
         kinB[i] = (unsigned)SB::kin(tid + i * NT);
         if (SB::UNIFORM_K) kinB[i] = __builtin_amdgcn_readfirstlane(kinB[i]);
     }
-    int64_t kA[SA::PER], kB[SB::PER];
+    int64_t kqA[SA::PER], kqB[SB::PER];          // NARROW, uniform-k operands: scalar byte offset per element
+    uint32_t krA[SA::PER], krB[SB::PER];         // NARROW, others: per-lane offset relative to the slab's base
+    int64_t kbA = 0, kbB = 0;
+    int64_t kA[SA::PER], kB[SB::PER];            // wide form: element offsets
     auto k_offsets = [&](int kt) {
-        const int64_t* __restrict__ ta = g.oAK + (int64_t)min(kt, nk - 1) * KT;
-        const int64_t* __restrict__ tb = g.oBK + (int64_t)min(kt, nk - 1) * KT;
+        const int64_t at = (int64_t)min(kt, nk - 1) * KT;
+        if (NARROW) {
+            const const_table<int64_t> qa = scalar_table(g.kqA + at), qb = scalar_table(g.kqB + at);
+            const const_table<int64_t> ba = scalar_table(g.kbA), bb = scalar_table(g.kbB);
+            const uint32_t* __restrict__ ta = g.krA + at;
+            const uint32_t* __restrict__ tb = g.krB + at;
+            if (SA::UNIFORM_K) {
 #pragma unroll
-        for (int i = 0; i < SA::PER; ++i) kA[i] = ta[kinA[i]];
+                for (int i = 0; i < SA::PER; ++i) kqA[i] = qa[kinA[i]];
+            } else {
+                kbA = ba[min(kt, nk - 1)];
 #pragma unroll
-        for (int i = 0; i < SB::PER; ++i) kB[i] = tb[kinB[i]];
+                for (int i = 0; i < SA::PER; ++i) krA[i] = ta[kinA[i]];
+            }
+            if (SB::UNIFORM_K) {
+#pragma unroll
+                for (int i = 0; i < SB::PER; ++i) kqB[i] = qb[kinB[i]];
+            } else {
+                kbB = bb[min(kt, nk - 1)];
+#pragma unroll
+                for (int i = 0; i < SB::PER; ++i) krB[i] = tb[kinB[i]];
+            }
+        } else {
+            const int64_t* __restrict__ ta = g.oAK + at;
+            const int64_t* __restrict__ tb = g.oBK + at;
+#pragma unroll
+            for (int i = 0; i < SA::PER; ++i) kA[i] = ta[kinA[i]];
+#pragma unroll
+            for (int i = 0; i < SB::PER; ++i) kB[i] = tb[kinB[i]];
+        }
     };
 
     T ra[DEPTH][SA::PER], rb[DEPTH][SB::PER];
@@ -341,9 +408,29 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
     // before.  Unconditional: the tables are padded with offsets of valid elements.
     auto gather = [&](int slot) {
 #pragma unroll
-        for (int i = 0; i < SA::PER; ++i) ra[slot][i] = P::load(A, offA[i] + kA[i], conjA);
+        for (int i = 0; i < SA::PER; ++i) {
+            if (!NARROW) {
+                ra[slot][i] = P::load(A, offA[i] + kA[i], conjA);
+            } else if (SA::UNIFORM_K) {
+                // the empty statement keeps the compiler from folding the loop-invariant row
+                // offset into a 64-bit per-lane pointer (which would undo the scalar base)
+                asm("" : "+v"(rrA[i]));
+                ra[slot][i] = P::load_at(Ab + kqA[i], rrA[i], conjA);
+            } else {
+                ra[slot][i] = P::load_at(Ab + kbA, rrA[i] + krA[i], conjA);
+            }
+        }
 #pragma unroll
-        for (int i = 0; i < SB::PER; ++i) rb[slot][i] = P::load(B, offB[i] + kB[i], conjB);
+        for (int i = 0; i < SB::PER; ++i) {
+            if (!NARROW) {
+                rb[slot][i] = P::load(B, offB[i] + kB[i], conjB);
+            } else if (SB::UNIFORM_K) {
+                asm("" : "+v"(rrB[i]));
+                rb[slot][i] = P::load_at(Bb + kqB[i], rrB[i], conjB);
+            } else {
+                rb[slot][i] = P::load_at(Bb + kbB, rrB[i] + krB[i], conjB);
+            }
+        }
     };
     // The last slab of a ragged K holds padded k entries whose (valid, arbitrary) values must
     // not be summed: zero them after the load.
@@ -369,36 +456,40 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
 #pragma unroll
         for (int j = 0; j < FN; ++j) P::clear(acc[i][j]);
 
+    // MFMA fragments are read from LDS one k-step (4 contracted indices) ahead of the MFMAs
+    // that consume them, into two register sets used alternately; the last step of a slab reads
+    // the first fragments of the next slab.  A wave's MFMAs then follow each other without
+    // waiting on LDS, whatever the other wave of its SIMD is doing.
     const int fr = lane & 15, fq = lane >> 4;
-    auto compute = [&](int buf, int ks_begin, int ks_end) {
+    constexpr int STEPS = KT / 4;
+    static_assert(STEPS % 2 == 0, "fragment sets alternate per k-step and must line up across slabs");
+    T fa[2][FM], fb[2][FN];
+    auto frag_load = [&](int buf, int step, int set) {
         const T* sa = lds + buf * (SA::ELEMS + SB::ELEMS);
         const T* sb = sa + SA::ELEMS;
 #pragma unroll
-        for (int ks = ks_begin; ks < ks_end; ks += 4) {
-            T fa[FM], fb[FN];
+        for (int i = 0; i < FM; ++i) fa[set][i] = sa[SA::frag_index(wm * WT_M + i * 16 + fr, step * 4 + fq)];
 #pragma unroll
-            for (int i = 0; i < FM; ++i) fa[i] = sa[SA::frag_index(wm * WT_M + i * 16 + fr, ks + fq)];
+        for (int j = 0; j < FN; ++j) fb[set][j] = sb[SB::frag_index(wn * WT_N + j * 16 + fr, step * 4 + fq)];
+    };
+    auto mfmas = [&](int set) {
 #pragma unroll
-            for (int j = 0; j < FN; ++j) fb[j] = sb[SB::frag_index(wn * WT_N + j * 16 + fr, ks + fq)];
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j) P::template mac<DNF>(fa[i], fb[j], acc[i][j]);
-        }
+            for (int j = 0; j < FN; ++j) P::template mac<DNF>(fa[set][i], fb[set][j], acc[i][j]);
         if (FM * FN <= 2) settle_accumulators();
     };
 
     // ---- main loop.  Global loads run DEPTH slabs ahead in registers.  LDS holds three slabs
     // and the workgroup barrier sits in the MIDDLE of a slab's MFMAs: slab kt+1 is written to
-    // LDS after the first half of slab kt and is first read a whole half-slab after the
-    // barrier, so no wave ever idles at a slab boundary waiting for LDS data, and a wave
-    // that waits at the barrier does so while the other waves of its SIMD still have MFMAs
-    // to issue.  The third buffer makes that safe: the buffer being written was last read two
-    // slabs ago, which every wave finished before it reached the previous barrier.
+    // LDS after the first half of slab kt and is first read (by the fragment prefetch of slab
+    // kt's last step) half a slab after the barrier, so a wave that waits at the barrier does
+    // so with its next fragments already in registers.  The third buffer makes that safe: the
+    // buffer being written was last read two slabs ago, which every wave finished before it
+    // reached the previous barrier.
     const bool ragged_k = g.sizeK % KT != 0;
     const int per_split = (nk + g.splitK - 1) / g.splitK;
-    const int kb = split * per_split, ke = min(nk, kb + per_split);      // this workgroup's slabs [kb, ke)
-    constexpr int KH = (KT / 8) * 4 > 0 ? (KT / 8) * 4 : 4;              // first "half" of a slab, a multiple of 4
+    const int kb = wave_uniform(split * per_split), ke = wave_uniform(min(nk, kb + per_split));   // this workgroup's slabs [kb, ke)
     // Prologue: fill the ring with slabs kb .. kb+DEPTH-1 (slab numbers past the end are clamped
     // by k_offsets to the last slab: harmless loads that are never staged).
 #pragma unroll
@@ -411,30 +502,265 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
     stage(0, 0);
     __syncthreads();
     int buf = 0;
+    frag_load(0, 0, 0);
     // Steady state, unrolled by DEPTH so that ring slots are compile-time register names.  In
     // iteration kt slot u holds slab kt (already staged), so it is refilled with slab kt+DEPTH;
     // slot u+1 holds slab kt+1, issued DEPTH-1 iterations ago, and is staged for the next one.
-    for (int kt = kb; kt < ke - 1; kt += DEPTH) {
+    // `last_group` is a compile-time flag: only the final group of iterations can meet the end
+    // of the range or the ragged slab, so the steady-state body is one straight path.
+    auto iteration = [&](int kt, int u, auto last_group) {
+        const int next = buf == 2 ? 0 : buf + 1;
+        gather(u);                                       // slab kt+u+DEPTH
+        k_offsets(kt + u + DEPTH + 1);
 #pragma unroll
-        for (int u = 0; u < DEPTH; ++u) {
-            if (kt + u >= ke - 1) break;
-            const int next = buf == 2 ? 0 : buf + 1;
-            gather(u);                                   // slab kt+u+DEPTH
-            k_offsets(kt + u + DEPTH + 1);
-            compute(buf, 0, KH);                         // slab kt+u, first half
-            if (ragged_k && kt + u + 1 == nk - 1) mask_last((u + 1) % DEPTH);
-            stage((u + 1) % DEPTH, next);                // slab kt+u+1
-            __syncthreads();
-            compute(buf, KH, KT);                        // slab kt+u, second half
-            buf = next;
+        for (int st = 0; st < STEPS; ++st) {
+            if (st + 1 < STEPS) frag_load(buf, st + 1, (st + 1) & 1);
+            else frag_load(next, 0, 0);                  // slab kt+u+1, complete since this slab's barrier
+            mfmas(st & 1);
+            if (st == STEPS / 2 - 1) {
+                if (decltype(last_group)::value && ragged_k && kt + u + 1 == nk - 1) mask_last((u + 1) % DEPTH);
+                stage((u + 1) % DEPTH, next);            // slab kt+u+1
+                __syncthreads();
+            }
         }
+        buf = next;
+    };
+    int kt = kb;
+    for (; kt + DEPTH < ke - 1; kt += DEPTH) {
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) iteration(kt, u, std::false_type{});
     }
-    compute(buf, 0, KT);                                 // slab ke-1
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u) {
+        if (kt + u >= ke - 1) break;
+        iteration(kt, u, std::true_type{});
+    }
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {                 // slab ke-1
+        if (st + 1 < STEPS) frag_load(buf, st + 1, (st + 1) & 1);
+        mfmas(st & 1);
+    }
     settle_accumulators();
 
     // ---- epilogue.  With split-K the raw accumulators go to the workspace, one coalesced
     // stretch per accumulator register; the reduction kernel sums the parts in a fixed order
     // and applies alpha, beta and the scatter.
+    if (g.splitK > 1) {
+        typename P::real* ws = (typename P::real*)g.workspace + (size_t)lid * (NT * P::template acc_reals<FM, FN>());
+        P::template spill<FM, FN>(acc, ws + tid, NT);
+    } else {
+        scatter<P, FM, FN, WT_M, WT_N, DNF>(acc, g, tile, wm, wn, lane);
+    }
+}
+
+// ---- two-phase ("ping-pong") kernel for the large tile -----------------------------------------
+// Measured on gfx950: while one wave issues MFMAs back to back, the other waves of its SIMD cannot
+// issue ANY vector-ALU instruction (integer adds for addresses included); scalar instructions, LDS
+// accesses and global loads of those waves proceed at full speed.  A workgroup barrier once per
+// slab, on the other hand, puts all waves into the same phase: they then do their memory work at
+// the same time and the matrix pipe idles meanwhile.  This kernel therefore
+//  * splits the waves into two groups with one wave of each on every SIMD (wave w and w + half
+//    share a SIMD).  An iteration is a MEMORY phase (copy the slab that has arrived in registers
+//    to LDS, issue the global loads of the slab after it, read the first MFMA fragments) and a
+//    COMPUTE phase (all MFMAs of a slab), each ended by a workgroup barrier; the second group
+//    runs one phase behind the first, so one group is always streaming MFMAs while the other
+//    does its memory work in that shadow;
+//  * keeps the memory phase free of vector-ALU instructions: every per-lane address (global
+//    offsets, LDS write and read addresses for each of the three LDS slabs) is computed once
+//    before the loop; what changes per slab is scalar (base pointers from the plan's tables);
+//    the loop is unrolled by three so that the LDS slab in use is a compile-time constant.
+// Preconditions, checked by the host: |K| is a multiple of KT (no masking in the loop), and an
+// operand whose lanes run along k has the same relative k offsets in every slab.
+// A slab's global loads have a whole iteration to arrive.  Three LDS slabs: slab i+1 is written
+// in phase 2i by the first group and in phase 2i+1 by the second; the buffer it goes to held slab
+// i-2, last read in phase 2i-2; it is first read in phase 2i+2.
+template <class T> __device__ __forceinline__ void lds_store(unsigned byte_addr, T v) {
+    *(__attribute__((address_space(3))) T*)(uintptr_t)byte_addr = v;
+}
+template <class T> __device__ __forceinline__ T lds_load(unsigned byte_addr) {
+    return *(const __attribute__((address_space(3))) T*)(uintptr_t)byte_addr;
+}
+
+template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF>
+__global__ __launch_bounds__(WGM* WGN * 64) void gett_pingpong_kernel(GettArgs g) {
+    using T = typename P::elem;
+    using acc_t = typename P::acc_t;
+    constexpr int NT = WGM * WGN * 64;
+    constexpr int WT_M = MT_M / WGM, WT_N = MT_N / WGN;
+    constexpr int FM = WT_M / 16, FN = WT_N / 16;
+    using SA = Slab<T, MT_M, KT, NT, AKF>;
+    using SB = Slab<T, MT_N, KT, NT, BKF>;
+    constexpr int STEPS = KT / 4;
+    constexpr int SLAB = SA::ELEMS + SB::ELEMS;
+    constexpr unsigned ES = sizeof(T);
+    static_assert(KT % 8 == 0 && WT_M % 16 == 0 && WT_N % 16 == 0, "tile shape");
+    static_assert((WGM * WGN) % 8 == 0, "two groups with a wave on each of the four SIMDs");
+    static_assert(NT % KT == 0 && NT % MT_M == 0 && NT % MT_N == 0, "a thread's slab elements differ by a constant LDS offset");
+    static_assert(AKF || SA::UNIFORM_K, "an operand whose lanes run along the rows needs one k per wave");
+    static_assert(BKF || SB::UNIFORM_K, "an operand whose lanes run along the rows needs one k per wave");
+    static_assert(ES * SLAB < 65536, "LDS offsets inside a slab must fit the instruction's immediate");
+
+    __shared__ T lds[3 * SLAB];
+    static_assert(sizeof(T) * 3 * SLAB <= 160 * 1024, "LDS budget of a CU");
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = wave_uniform(tid >> 6);
+    const int wm = wave % WGM, wn = wave / WGM;
+    const bool second_group = wave >= WGM * WGN / 2;
+
+    const int64_t lid = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int split = wave_uniform((int)(lid % g.splitK));
+    const Tile tile = locate_tile(lid / g.splitK, g, MT_M, MT_N);
+    const int64_t m0 = wave_uniform(tile.m0), n0 = wave_uniform(tile.n0);
+    const char* const Ab = (const char*)g.A + wave_uniform(tile.hA * (int64_t)sizeof(T) + scalar_table(g.rbA)[m0 / MT_M]);
+    const char* const Bb = (const char*)g.B + wave_uniform(tile.hB * (int64_t)sizeof(T) + scalar_table(g.rbB)[n0 / MT_N]);
+    const unsigned conjA = g.opA == TCX_OP_CONJ ? 0x80000000u : 0u;
+    const unsigned conjB = g.opB == TCX_OP_CONJ ? 0x80000000u : 0u;
+
+    // ---- everything per-lane, once.  Global byte offsets of this thread's slab elements
+    // relative to the slab's scalar base: the row part, plus (lanes along k) the k part, which
+    // the host guarantees to be the same in every slab.
+    uint32_t voA[SA::PER], voB[SB::PER];
+    unsigned kinA[SA::PER], kinB[SB::PER];
+#pragma unroll
+    for (int i = 0; i < SA::PER; ++i) {
+        const int e = tid + i * NT;
+        voA[i] = g.rrA[m0 + SA::row(e)] + (AKF ? g.krA[SA::kin(e)] : 0u);
+        kinA[i] = AKF ? 0u : (unsigned)__builtin_amdgcn_readfirstlane(SA::kin(e));
+    }
+#pragma unroll
+    for (int i = 0; i < SB::PER; ++i) {
+        const int e = tid + i * NT;
+        voB[i] = g.rrB[n0 + SB::row(e)] + (BKF ? g.krB[SB::kin(e)] : 0u);
+        kinB[i] = BKF ? 0u : (unsigned)__builtin_amdgcn_readfirstlane(SB::kin(e));
+    }
+    // LDS byte addresses, per LDS slab: where this thread writes its first element of A and of
+    // B, and where it reads its first fragment of A and of B.  Further elements / fragments are
+    // at compile-time offsets from these.
+    const int fr = lane & 15, fq = lane >> 4;
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) T*)lds;
+    unsigned wA[3], wB[3], fA[3], fB[3];
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+        wA[b] = lds0 + ES * (unsigned)(b * SLAB + SA::lds_index(tid));
+        wB[b] = lds0 + ES * (unsigned)(b * SLAB + SA::ELEMS + SB::lds_index(tid));
+        fA[b] = lds0 + ES * (unsigned)(b * SLAB + SA::frag_index(wm * WT_M + fr, fq));
+        fB[b] = lds0 + ES * (unsigned)(b * SLAB + SA::ELEMS + SB::frag_index(wn * WT_N + fr, fq));
+        // opaque to the compiler from here on: kept in registers instead of being recomputed
+        // (with vector-ALU instructions) inside the loop
+        asm volatile("" : "+v"(wA[b]), "+v"(wB[b]), "+v"(fA[b]), "+v"(fB[b]));
+    }
+    constexpr unsigned dWA = ES * (AKF ? (NT / KT) * SA::LD : (NT / MT_M) * SA::LD);   // element i+1 minus element i
+    constexpr unsigned dWB = ES * (BKF ? (NT / KT) * SB::LD : (NT / MT_N) * SB::LD);
+    constexpr unsigned dFA_row = ES * (AKF ? 16 * SA::LD : 16), dFA_step = ES * (AKF ? 4 : 4 * SA::LD);
+    constexpr unsigned dFB_row = ES * (BKF ? 16 * SB::LD : 16), dFB_step = ES * (BKF ? 4 : 4 * SB::LD);
+
+    // ---- per slab, scalar: the base of each load
+    const int nk = g.tilesK;
+    int64_t kqA[SA::PER], kqB[SB::PER];          // lanes along the rows: one byte offset per element's k
+    int64_t kbA = 0, kbB = 0;                    // lanes along k: the slab's base
+    auto k_offsets = [&](int kt) {
+        const int kc = min(kt, nk - 1);
+        if (AKF) {
+            kbA = scalar_table(g.kbA)[kc];
+        } else {
+            const const_table<int64_t> q = scalar_table(g.kqA + (int64_t)kc * KT);
+#pragma unroll
+            for (int i = 0; i < SA::PER; ++i) kqA[i] = q[kinA[i]];
+        }
+        if (BKF) {
+            kbB = scalar_table(g.kbB)[kc];
+        } else {
+            const const_table<int64_t> q = scalar_table(g.kqB + (int64_t)kc * KT);
+#pragma unroll
+            for (int i = 0; i < SB::PER; ++i) kqB[i] = q[kinB[i]];
+        }
+    };
+    T ra[SA::PER], rb[SB::PER];
+    auto gather = [&]() {
+#pragma unroll
+        for (int i = 0; i < SA::PER; ++i) {
+            asm("" : "+v"(voA[i]));              // keeps "scalar base + 32-bit lane offset" from being folded into a 64-bit lane address
+            ra[i] = P::load_at(Ab + (AKF ? kbA : kqA[i]), voA[i], conjA);
+        }
+#pragma unroll
+        for (int i = 0; i < SB::PER; ++i) {
+            asm("" : "+v"(voB[i]));
+            rb[i] = P::load_at(Bb + (BKF ? kbB : kqB[i]), voB[i], conjB);
+        }
+    };
+    auto stage = [&](auto BUF) {
+        constexpr int b = decltype(BUF)::value;
+#pragma unroll
+        for (int i = 0; i < SA::PER; ++i) lds_store<T>(wA[b] + i * dWA, ra[i]);
+#pragma unroll
+        for (int i = 0; i < SB::PER; ++i) lds_store<T>(wB[b] + i * dWB, rb[i]);
+    };
+
+    acc_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) P::clear(acc[i][j]);
+    T fa[2][FM], fb[2][FN];
+    auto frag_load = [&](auto BUF, int step, int set) {
+        constexpr int b = decltype(BUF)::value;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) fa[set][i] = lds_load<T>(fA[b] + i * dFA_row + step * dFA_step);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) fb[set][j] = lds_load<T>(fB[b] + j * dFB_row + step * dFB_step);
+    };
+    auto mfmas = [&](int set) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) P::template mac<DNF>(fa[set][i], fb[set][j], acc[i][j]);
+    };
+
+    const int per_split = (nk + g.splitK - 1) / g.splitK;
+    const int kb = wave_uniform(split * per_split), ke = wave_uniform(min(nk, kb + per_split));
+    const int n = ke - kb;
+    // Prologue: slab kb to LDS, slab kb+1 into registers (slab numbers past the end are clamped:
+    // harmless loads that are never staged).
+    k_offsets(kb);
+    gather();
+    k_offsets(kb + 1);
+    stage(std::integral_constant<int, 0>{});
+    gather();
+    k_offsets(kb + 2);
+    __syncthreads();
+    if (second_group) __builtin_amdgcn_s_barrier();       // one phase behind the first group
+
+    auto round = [&](int i, auto BUF) {
+        constexpr int b = decltype(BUF)::value;
+        // memory phase: no vector-ALU instruction in here
+        if (i + 1 < n) {
+            stage(std::integral_constant<int, (b + 1) % 3>{});   // slab kb+i+1
+            gather();                                            // slab kb+i+2
+            k_offsets(kb + i + 3);
+        }
+        frag_load(BUF, 0, 0);
+        __syncthreads();
+        // compute phase
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st) {
+            if (st + 1 < STEPS) frag_load(BUF, st + 1, (st + 1) & 1);
+            mfmas(st & 1);
+        }
+        __syncthreads();
+    };
+    int i = 0;
+    for (; i + 3 <= n; i += 3) {
+        round(i, std::integral_constant<int, 0>{});
+        round(i + 1, std::integral_constant<int, 1>{});
+        round(i + 2, std::integral_constant<int, 2>{});
+    }
+    if (i < n) round(i, std::integral_constant<int, 0>{});
+    if (i + 1 < n) round(i + 1, std::integral_constant<int, 1>{});
+    if (!second_group) __builtin_amdgcn_s_barrier();      // pairs with the second group's last barrier
+    settle_accumulators();
+
     if (g.splitK > 1) {
         typename P::real* ws = (typename P::real*)g.workspace + (size_t)lid * (NT * P::template acc_reals<FM, FN>());
         P::template spill<FM, FN>(acc, ws + tid, NT);
@@ -596,28 +922,32 @@ struct Shape {
     float efficiency;      // relative speed of the main loop per unit of tile area (planner's cost model)
     int ch;                // 0: LDS-staged kernel; > 0: direct kernel with chunks of 4*ch contracted indices
     int depth;             // LDS-staged kernel: slabs of global loads in flight
+    bool narrow;           // LDS-staged kernel: gather through the 32-bit tile-relative tables
+    bool pingpong = false; // two-phase kernel (needs |K| % kt == 0 and slab-periodic k offsets)
+    int fallback = -1;     // shape to use instead when this one's preconditions fail (-1: any)
 };
 // `efficiency`: measured fraction of a CU's matrix peak that the shape's main loop sustains on
 // MI355X with the CU saturated (256x128: config 2; the others: a 1024^3 product, 576^3, 96^3 x 512).
 constexpr Shape kRealShapes[] = {
-    {256, 128, 16, 4, 2, 0.82f, 0, 1},
-    {128, 128, 16, 2, 2, 0.46f, 0, 2},
-    {64, 64, 16, 2, 2, 0.36f, 0, 3},
-    {32, 32, 16, 2, 2, 0.30f, 0, 3},
-    {128, 64, 16, 2, 2, 0.33f, 4, 0},
-    {64, 64, 16, 2, 2, 0.30f, 4, 0},
-    {32, 32, 16, 2, 2, 0.20f, 4, 0},
-    {64, 64, 16, 2, 4, 0.36f, 0, 2},
-    {64, 64, 16, 4, 4, 0.41f, 0, 2},
+    {256, 128, 16, 4, 2, 0.82f, 0, 1, true, true, 9},
+    {128, 128, 16, 2, 2, 0.46f, 0, 2, true},
+    {64, 64, 16, 2, 2, 0.36f, 0, 3, true},
+    {32, 32, 16, 2, 2, 0.30f, 0, 3, true},
+    {128, 64, 16, 2, 2, 0.33f, 4, 0, false},
+    {64, 64, 16, 2, 2, 0.30f, 4, 0, false},
+    {32, 32, 16, 2, 2, 0.20f, 4, 0, false},
+    {64, 64, 16, 2, 4, 0.36f, 0, 2, true},
+    {64, 64, 16, 4, 4, 0.41f, 0, 2, true},
+    {256, 128, 16, 4, 2, 0.80f, 0, 1, true, false, -1},
 };
 constexpr Shape kComplexShapes[] = {
-    {96, 96, 8, 2, 2, 0.45f, 0, 2},
-    {64, 64, 8, 2, 2, 0.30f, 0, 2},
-    {32, 32, 8, 2, 2, 0.20f, 0, 3},
-    {96, 96, 8, 2, 2, 0.45f, 2, 0},
-    {64, 64, 8, 2, 2, 0.25f, 2, 0},
-    {96, 48, 8, 2, 1, 0.45f, 0, 2},
-    {48, 96, 8, 1, 2, 0.45f, 0, 2},
+    {96, 96, 8, 2, 2, 0.45f, 0, 2, true},
+    {64, 64, 8, 2, 2, 0.30f, 0, 2, true},
+    {32, 32, 8, 2, 2, 0.20f, 0, 3, true},
+    {96, 96, 8, 2, 2, 0.45f, 2, 0, false},
+    {64, 64, 8, 2, 2, 0.25f, 2, 0, false},
+    {96, 48, 8, 2, 1, 0.45f, 0, 2, true},
+    {48, 96, 8, 1, 2, 0.45f, 0, 2, true},
 };
 constexpr int kNumRealShapes = sizeof(kRealShapes) / sizeof(Shape);
 constexpr int kNumComplexShapes = sizeof(kComplexShapes) / sizeof(Shape);
@@ -635,8 +965,12 @@ hipError_t launch_one(const GettArgs& a, int64_t blocks, hipStream_t st) {
             gett_direct_kernel<P, s.mt_m / 32, s.mt_n / 32, s.ch, DNF><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(a);
         else
             return launch_one<P, S, false, false, DNF>(a, blocks, st);
+    } else if constexpr (s.pingpong) {
+        if (a.sizeK % s.kt != 0 || (AKF && !a.periodicA) || (BKF && !a.periodicB)) return hipErrorInvalidValue;
+        gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF>
+            <<<dim3((unsigned)blocks), dim3(s.wgm * s.wgn * 64), 0, st>>>(a);
     } else {
-        gett_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.depth>
+        gett_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.depth, s.narrow>
             <<<dim3((unsigned)blocks), dim3(s.wgm * s.wgn * 64), 0, st>>>(a);
     }
     hipError_t err = hipGetLastError();
@@ -675,6 +1009,7 @@ hipError_t launch_real_shape(int variant, bool akf, bool bkf, bool dnf, const Ge
         case 6: return launch_flags<P, 6>(akf, bkf, dnf, a, blocks, st);
         case 7: return launch_flags<P, 7>(akf, bkf, dnf, a, blocks, st);
         case 8: return launch_flags<P, 8>(akf, bkf, dnf, a, blocks, st);
+        case 9: return launch_flags<P, 9>(akf, bkf, dnf, a, blocks, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -712,7 +1047,7 @@ GettVariant gett_variant(int dtype, int variant) {
     const Shape* t = shapes_of(dtype, &n);
     const Shape s = t[variant];
     const int planes = dtype == TCX_C128 ? 2 : 1;
-    return {s.mt_m, s.mt_n, s.kt, s.wgm * s.wgn * 64, s.efficiency, s.mt_m * s.mt_n * planes};
+    return {s.mt_m, s.mt_n, s.kt, s.wgm * s.wgn * 64, s.efficiency, s.mt_m * s.mt_n * planes, s.ch == 0 && s.narrow, s.pingpong, s.fallback};
 }
 
 int launch_gett(int dtype, int variant, bool a_kf, bool b_kf, bool d_nf, const GettArgs& args, void* stream,

@@ -64,6 +64,19 @@ struct GettArgs {
     const int64_t* oBK;  // [tilesK * KT]
     const int64_t* oDM;  // [tilesM * MT_M]
     const int64_t* oDN;  // [tilesN * MT_N]
+    // LDS-staged kernels gather through tile-relative byte offsets: element address =
+    // operand + hyper offset + rowbase[tile] + (kofs[k] | kbase[slab] + krel[k]) + rowrel[row]
+    const uint32_t* rrA;   // rowrel  [tilesM * MT_M]
+    const int64_t* rbA;    // rowbase [tilesM]
+    const int64_t* kqA;    // kofs    [tilesK * KT]   (lanes along the rows: one scalar per k)
+    const uint32_t* krA;   // krel    [tilesK * KT]   (lanes along k)
+    const int64_t* kbA;    // kbase   [tilesK]
+    const uint32_t* rrB;
+    const int64_t* rbB;
+    const int64_t* kqB;
+    const uint32_t* krB;
+    const int64_t* kbB;
+    int32_t periodicA, periodicB;   // krel is the same in every slab (two-phase kernel, lanes along k)
     int64_t sizeM, sizeN, sizeK, sizeH;
     int32_t tilesM, tilesN, tilesK;
     int32_t nH;
@@ -79,6 +92,9 @@ struct GettVariant {
     int mt_m, mt_n, kt, threads;
     float efficiency;    // relative main-loop speed per unit tile area, for the planner's cost model
     int acc_reals;       // real accumulator values per tile (split-K workspace per part)
+    bool staged;         // kernel gathers through the narrow (32-bit, tile-relative) tables
+    bool pingpong;       // two-phase kernel: needs |K| % kt == 0 and slab-periodic relative k offsets
+    int fallback;        // shape to try first when this one cannot serve the plan (-1: none)
 };
 
 // Generic fallback: every mode of D (H, M, N together, D-fastest first) and every K mode.
