@@ -29,7 +29,12 @@ PEAK_HBM_GBS = 8000.0
 # L2 <-> fabric bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
 # command, scaled by a streaming probe kernel (profiles/gett_f64_256x128x16_cfg2.md); keyed
 # by (workload, path, variant) so a figure is only reported for the kernel it was taken on.
-MEASURED_TRAFFIC_BYTES = {("cfg2_f64_ppladder_v192_o64", 1, 0): 110.06e9 + 1.208e9}
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg2_f64_ppladder_v192_o64", 1, 0): 319.72e9 + 1.34e9,
+    ("cfg5_f64_network_e4_k1_f7_p7832", 2, 1): 35.1e6 + 2147.48e6,         # s1
+    ("cfg5_f64_network_e4_k0_f7_p7832", 2, 1): 5.6e6 + 2147.48e6,          # s2
+    ("hadamard_f64_4x128", 2, 0): None,                                     # s3 / s3b differ by beta: see profiles/
+}
 DT = {"f32": 0, "f64": 1, "c128": 3}
 
 
