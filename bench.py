@@ -26,11 +26,11 @@ import workloads as W  # noqa: E402
 
 PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3, "c128": 78.6}     # MI355X dense matrix peaks
 PEAK_HBM_GBS = 8000.0
-# L2 <-> fabric bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
-# command, scaled by a streaming probe kernel (profiles/gett_f64_256x128x16_cfg2.md); keyed
-# by (workload, path, variant) so a figure is only reported for the kernel it was taken on.
+# L2 <-> fabric bytes per STEP from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
+# command, scaled by a streaming probe kernel (profiles/); keyed by (workload, path, variant) so a
+# figure is only reported for the kernel it was taken on.  The JSON line reports it per launch.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg2_f64_ppladder_v192_o64", 1, 0): 319.72e9 + 1.34e9,
+    ("cfg2_f64_ppladder_v192_o64", 1, 0): 111.63e9 + 1.34e9,               # 18 launches (rounds) per step
     ("cfg5_f64_network_e4_k1_f7_p7832", 2, 1): 35.1e6 + 2147.48e6,         # s1
     ("cfg5_f64_network_e4_k0_f7_p7832", 2, 1): 5.6e6 + 2147.48e6,          # s2
     ("hadamard_f64_4x128", 2, 0): None,                                     # s3 / s3b differ by beta: see profiles/
@@ -227,8 +227,15 @@ def main():
         achieved = p.algorithmic_bytes() / avg_kernel_s / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": achieved / PEAK_HBM_GBS, "traffic": None}
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(
+    # A step may be several launches of the dominant kernel (a long-tile product is enqueued round
+    # by round); the per-launch figures are the step's divided by that count.
+    launches = T.tcx_product_get(prod, T.TCX_KEY_LAUNCHES) - (1 if T.tcx_product_get(prod, T.TCX_KEY_SPLIT_K) > 1 else 0)
+    step_traffic = MEASURED_TRAFFIC_BYTES.get(
         (p.name, T.tcx_product_get(prod, T.TCX_KEY_PATH), T.tcx_product_get(prod, T.TCX_KEY_VARIANT)))
+    roofline["traffic"] = None if step_traffic is None else step_traffic / launches
+    roofline["launches_per_step"] = launches
+    roofline["launch_ms_avg"] = region_ms / args.steps / launches
+    roofline["algorithmic_per_launch"] = (flops if roofline["bound"] == "mfma" else p.algorithmic_bytes()) / launches
     roofline["kernel_ms_avg"] = region_ms / args.steps
     roofline["kernel_ms_min"] = float(np.min(kern_ms))
     roofline["kernel_ms_median"] = float(np.median(kern_ms))
@@ -237,7 +244,8 @@ def main():
            "path": T.tcx_product_get(prod, T.TCX_KEY_PATH), "variant": T.tcx_product_get(prod, T.TCX_KEY_VARIANT),
            "tile": [T.tcx_product_get(prod, k) for k in (T.TCX_KEY_TILE_M, T.TCX_KEY_TILE_N, T.TCX_KEY_TILE_K)],
            "split_k": T.tcx_product_get(prod, T.TCX_KEY_SPLIT_K),
-           "grid": T.tcx_product_get(prod, T.TCX_KEY_GRID), "plan_ms": plan_ms,
+           "grid": T.tcx_product_get(prod, T.TCX_KEY_GRID), "launches_per_step": T.tcx_product_get(prod, T.TCX_KEY_LAUNCHES),
+           "plan_ms": plan_ms,
            "flop_per_step": flops, "algorithmic_bytes_per_step": p.algorithmic_bytes()}
 
     cfg["buffers"] = "cache-resident (one operand set)" if len(sets) == 1 else \

@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -55,6 +56,13 @@ struct Product {
 struct Status {
     int64_t path = 0, variant = 0, grid = 0, block = 0, tile_m = 0, tile_n = 0, tile_k = 0, hip_error = 0;
 };
+
+// Workgroups per launch when a product's grid is enqueued round by round (0: one launch).  Rounds
+// pay off when a tile runs for milliseconds (hundreds of slabs): see the launcher.
+int64_t round_size_of(const Product& p, const GettVariant& s) {
+    const int64_t nk = (p.an.sizeK + s.kt - 1) / s.kt;
+    return (s.pingpong && nk >= 256) ? p.handle.num_cu : 0;
+}
 
 std::mutex g_mu;
 std::unordered_map<intptr_t, uint32_t> g_live;   // handle value -> object type
@@ -552,6 +560,13 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
         case TCX_KEY_B_K_FASTEST: return put_i64(an.b_k_fastest, value, nbytes);
         case TCX_KEY_D_N_FASTEST: return put_i64(an.d_n_fastest, value, nbytes);
         case TCX_KEY_SPLIT_K: return put_i64(tiled ? p->splitK : 1, value, nbytes);
+        case TCX_KEY_LAUNCHES: {
+            if (!tiled) return put_i64(1, value, nbytes);
+            const int64_t blocks = tiles_of(an, s) * p->splitK;
+            const int64_t round = round_size_of(*p, s);
+            return put_i64((round > 0 && p->splitK == 1 && blocks > round ? (blocks + round - 1) / round : 1) + (p->splitK > 1 ? 1 : 0),
+                           value, nbytes);
+        }
         case TCX_KEY_VARIANT:
             return put_i64(tiled ? p->variant : (an.path == TCX_PATH_BANDWIDTH && p->stream.blocked) ? 1 : 0, value, nbytes);
         case TCX_KEY_MODES_M: return put_modes(an.M, value, nbytes);
@@ -693,6 +708,9 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
         g.read_c = read_c;
         g.splitK = p->splitK;
         g.workspace = p->workspace;
+        g.lid_base = 0;
+        // rounds pay off when a tile runs for milliseconds (hundreds of slabs) and there are several rounds
+        g.round_size = (int32_t)round_size_of(*p, v);
         hip_err = launch_gett(p->an.dtype, p->variant, p->an.a_k_fastest, p->an.b_k_fastest, p->an.d_n_fastest, g,
                               (void*)e->stream, &grid, &block);
         st.path = TCX_PATH_GETT_MFMA; st.variant = p->variant;

@@ -14,6 +14,7 @@
 // along D's fastest group (the MFMA operand roles are swapped to make that so).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "tcx_internal.hpp"
@@ -317,7 +318,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
     const int wm = wave % WGM, wn = wave / WGM;
 
     // ---- which tile, and which part of K (split-K: consecutive ids are the parts of one tile)
-    const int64_t lid = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int64_t lid = g.lid_base + xcd_contiguous(blockIdx.x, gridDim.x);
     const int split = wave_uniform((int)(lid % g.splitK));
     const Tile tile = locate_tile(lid / g.splitK, g, MT_M, MT_N);
     const int64_t m0 = wave_uniform(tile.m0), n0 = wave_uniform(tile.n0);
@@ -609,7 +610,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_pingpong_kernel(GettArgs g
     const int wm = wave % WGM, wn = wave / WGM;
     const bool second_group = wave >= WGM * WGN / 2;
 
-    const int64_t lid = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int64_t lid = g.lid_base + xcd_contiguous(blockIdx.x, gridDim.x);
     const int split = wave_uniform((int)(lid % g.splitK));
     const Tile tile = locate_tile(lid / g.splitK, g, MT_M, MT_N);
     const int64_t m0 = wave_uniform(tile.m0), n0 = wave_uniform(tile.n0);
@@ -826,7 +827,7 @@ __global__ __launch_bounds__(256) void gett_direct_kernel(GettArgs g) {
     const int wm = wave % WGM, wn = wave / WGM;
     const int fr = lane & 15, fq = lane >> 4;
 
-    const int64_t lid = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int64_t lid = g.lid_base + xcd_contiguous(blockIdx.x, gridDim.x);
     const int split = (int)(lid % g.splitK);
     const Tile tile = locate_tile(lid / g.splitK, g, MT_M, MT_N);
     const T* __restrict__ A = (const T*)g.A + tile.hA;
@@ -974,8 +975,21 @@ hipError_t launch_one(const GettArgs& a, int64_t blocks, hipStream_t st) {
             return launch_one<P, S, false, false, DNF>(a, blocks, st);
     } else if constexpr (s.pingpong) {
         if (a.sizeK % s.kt != 0 || (AKF && !a.periodicA) || (BKF && !a.periodicB)) return hipErrorInvalidValue;
-        gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF>
-            <<<dim3((unsigned)blocks), dim3(s.wgm * s.wgn * 64), 0, st>>>(a);
+        // Long tiles are launched round by round (one workgroup per CU each): workgroups of a
+        // round that share operand panels through an XCD's L2 start together, whereas in one big
+        // launch the 0.5 - 1 % differences in tile duration between CUs add up from round to
+        // round until the sharers are further apart than the L2 holds.
+        if (a.round_size > 0 && a.splitK == 1 && blocks > a.round_size) {
+            GettArgs r = a;
+            for (int64_t at = 0; at < blocks; at += a.round_size) {
+                r.lid_base = at;
+                gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF>
+                    <<<dim3((unsigned)std::min<int64_t>(a.round_size, blocks - at)), dim3(s.wgm * s.wgn * 64), 0, st>>>(r);
+            }
+        } else {
+            gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF>
+                <<<dim3((unsigned)blocks), dim3(s.wgm * s.wgn * 64), 0, st>>>(a);
+        }
     } else {
         gett_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.depth, s.narrow>
             <<<dim3((unsigned)blocks), dim3(s.wgm * s.wgn * 64), 0, st>>>(a);

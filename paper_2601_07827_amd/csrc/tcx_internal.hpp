@@ -77,6 +77,8 @@ struct GettArgs {
     const uint32_t* krB;
     const int64_t* kbB;
     int32_t periodicA, periodicB;   // krel is the same in every slab (two-phase kernel, lanes along k)
+    int64_t lid_base;      // first tile number of this launch (a product may be launched in rounds)
+    int32_t round_size;    // > 0: launch the grid in rounds of this many workgroups (two-phase kernel)
     int64_t sizeM, sizeN, sizeK, sizeH;
     int32_t tilesM, tilesN, tilesK;
     int32_t nH;
