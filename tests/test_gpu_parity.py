@@ -227,3 +227,29 @@ def test_config2_full_size_sampled(dist):
     assert res["ok"], res
     if dist == "ints":
         assert res["bit_exact"], res
+
+
+@pytest.mark.parametrize("dist", ["uniform", "ints"])
+def test_round_by_round_launch(dist):
+    """A product whose tiles are long (324 slabs) and more numerous than the CUs is enqueued as
+    several launches of the two-phase kernel, the last one partial (378 tiles = 256 + 122).
+    Sampled outputs from both launches against the oracle; integer inputs bit for bit."""
+    import torch
+    import bench
+    from gpu_helpers import GpuProduct, say
+    p = W.config2(v=72, o=48)
+    say("%s, dist=%s" % (p.name, dist))
+    dA, dB, dD, _ = bench.device_operands(p, torch, dist)
+    gp = GpuProduct(p, force_path=GETT, variant=0)        # a forced shape starts unsplit
+    try:
+        assert (gp.get(gp.T.TCX_KEY_PATH), gp.get(gp.T.TCX_KEY_VARIANT), gp.get(gp.T.TCX_KEY_GRID)) == (1, 0, 378)
+        assert gp.get(gp.T.TCX_KEY_LAUNCHES) == 2
+        gp.execute(dA, dB, dD, dD)
+        torch.cuda.synchronize()
+        res = bench.parity_after_run(p, dD, 1, torch, dist)
+    finally:
+        gp.close()
+    assert res["samples"] >= 400
+    assert res["ok"], res
+    if dist == "ints":
+        assert res["bit_exact"], res
