@@ -229,7 +229,7 @@ def main():
                     "frac": achieved / PEAK_HBM_GBS, "traffic": None}
     # A step may be several launches of the dominant kernel (a long-tile product is enqueued round
     # by round); the per-launch figures are the step's divided by that count.
-    launches = T.tcx_product_get(prod, T.TCX_KEY_LAUNCHES) - (1 if T.tcx_product_get(prod, T.TCX_KEY_SPLIT_K) > 1 else 0)
+    launches = max(1, T.tcx_product_get(prod, T.TCX_KEY_LAUNCHES) - (1 if T.tcx_product_get(prod, T.TCX_KEY_SPLIT_K) > 1 else 0))
     step_traffic = MEASURED_TRAFFIC_BYTES.get(
         (p.name, T.tcx_product_get(prod, T.TCX_KEY_PATH), T.tcx_product_get(prod, T.TCX_KEY_VARIANT)))
     roofline["traffic"] = None if step_traffic is None else step_traffic / launches

@@ -104,15 +104,23 @@ int64_t tiles_of(const Analysis& an, const GettVariant& s) {
 // in rounds over the CUs; split-K adds a second launch and the traffic of the partial
 // accumulators.  Large tiles win when there are enough of them; small problems are cut
 // along K to fill the chip.
-void choose_plan(const Analysis& an, int num_cu, int* variant, int* splitK) {
+struct PlanChoice {
+    double us;
+    int variant, splitK;
+};
+
+// Every tile shape with its best split count, cheapest first.
+std::vector<PlanChoice> rank_plans(const Analysis& an, int num_cu) {
+    std::vector<PlanChoice> ranked;
     const int n = gett_num_variants(an.dtype);
     const double cus = num_cu > 0 ? num_cu : 256;
     const double cu_flops = (an.dtype == TCX_F32 ? 157.3e12 : 78.6e12) / 256.0;
     const double flop_per_mac = an.dtype == TCX_C128 ? 8.0 : 2.0;
     const int ebytes = an.dtype == TCX_F32 ? 4 : an.dtype == TCX_F64 ? 8 : 16;
-    double best = -1;
     for (int v = 0; v < n; ++v) {
         const GettVariant s = gett_variant(an.dtype, v);
+        double best = -1;
+        int bestS = 1;
         const double tiles = (double)tiles_of(an, s);
         const int64_t nk = (an.sizeK + s.kt - 1) / s.kt;
         const double slab_us = flop_per_mac * s.mt_m * s.mt_n * s.kt / (cu_flops * s.efficiency) * 1e6;
@@ -122,14 +130,24 @@ void choose_plan(const Analysis& an, int num_cu, int* variant, int* splitK) {
             const int64_t S = (nk + per - 1) / per;
             // small tiles leave room for several workgroups per CU, which then share its matrix
             // pipe: the time of a round does not shrink, but a partial last round costs less
-            const double resident = std::max(1.0, std::min(4.0, 65536.0 / ((double)s.mt_m * s.mt_n * (ebytes > 8 ? 2 : 1))));
+            const double resident = s.dual ? 2.0   // one workgroup per CU, two tiles in it
+                                           : std::max(1.0, std::min(4.0, 65536.0 / ((double)s.mt_m * s.mt_n * (ebytes > 8 ? 2 : 1))));
             const double slots = cus * resident;
             const double rounds = std::ceil(tiles * (double)S / slots);
             double us = rounds * resident * (double)per * slab_us + 6.0;
-            if (S > 1) us += 3.0 + (2.0 * S + 1.0) * tiles * s.acc_reals * (ebytes > 8 ? 8 : ebytes) / 6e12 * 1e6;
-            if (best < 0 || us < best) { best = us; *variant = v; *splitK = (int)S; }
+            if (S > 1 && !(S == 2 && s.pair_in_lds))
+                us += 3.0 + (2.0 * S + 1.0) * tiles * s.acc_reals * (ebytes > 8 ? 8 : ebytes) / 6e12 * 1e6;
+            if (best < 0 || us < best) { best = us; bestS = (int)S; }
         }
+        ranked.push_back({best, v, bestS});
     }
+    std::stable_sort(ranked.begin(), ranked.end(), [](const PlanChoice& x, const PlanChoice& y) { return x.us < y.us; });
+    return ranked;
+}
+
+void choose_plan(const Analysis& an, int num_cu, int* variant, int* splitK) {
+    const std::vector<PlanChoice> r = rank_plans(an, num_cu);
+    if (!r.empty()) { *variant = r[0].variant; *splitK = r[0].splitK; }
 }
 
 void fill_generic(const Analysis& an, GenericArgs* g) {
@@ -190,6 +208,7 @@ tcx_error_t build_tables(Product* p) {
 tcx_error_t ensure_workspace(Product* p) {
     if (p->splitK <= 1 || !p->handle.has_device) return TCX_SUCCESS;
     const GettVariant s = gett_variant(p->an.dtype, p->variant);
+    if (p->splitK == 2 && s.pair_in_lds) return TCX_SUCCESS;
     const size_t real_bytes = p->an.dtype == TCX_F32 ? 4 : 8;
     const size_t need = (size_t)tiles_of(p->an, s) * (size_t)p->splitK * (size_t)s.acc_reals * real_bytes;
     if (need <= p->workspace_bytes) return TCX_SUCCESS;
@@ -272,7 +291,11 @@ tcx_error_t build_narrow(Product* p, int variant) {
             return TCX_ERR_UNSUPPORTED_OP;
         // the two-phase kernel has no masked slab, and precomputes the per-lane k offsets of
         // an operand whose lanes run along k
-        if (s.pingpong && (p->an.sizeK % s.kt != 0 || (p->an.a_k_fastest && !a.periodic) || (p->an.b_k_fastest && !b.periodic)))
+        auto operand_ok = [&](bool k_fastest, bool periodic, int mt) {
+            return k_fastest ? periodic : (mt % 64 == 0 && s.threads % mt == 0);
+        };
+        if (s.pingpong && (p->an.sizeK % s.kt != 0 || !operand_ok(p->an.a_k_fastest, a.periodic, s.mt_m) ||
+                           !operand_ok(p->an.b_k_fastest, b.periodic, s.mt_n)))
             return TCX_ERR_UNSUPPORTED_OP;
         p->periodic[0] = a.periodic;
         p->periodic[1] = b.periodic;
@@ -311,16 +334,18 @@ tcx_error_t prepare_tiled(Product* p) {
         const tcx_error_t err = build_tables(p);
         if (err != TCX_SUCCESS) return err;
     }
-    const int n = gett_num_variants(p->an.dtype);
+    // order: the plan's shape, the shape it names as its stand-in, then the others as the cost
+    // model ranks them (each with its own best split count)
     tcx_error_t err = TCX_ERR_UNSUPPORTED_OP;
     const int first = p->variant, second = gett_variant(p->an.dtype, first).fallback;
-    for (int t = -1; t <= n; ++t) {
-        // order: the plan's shape, the shape it names as its stand-in, then all others
-        const int v = t == -1 ? first : t == 0 ? second : t - 1;
-        if (v < 0 || (t > 0 && (v == first || v == second))) continue;
-        err = gett_variant(p->an.dtype, v).staged ? build_narrow(p, v) : TCX_SUCCESS;
+    std::vector<PlanChoice> order = {{0.0, first, p->splitK}};
+    if (second >= 0) order.push_back({0.0, second, 1});
+    for (const PlanChoice& c : rank_plans(p->an, p->handle.num_cu))
+        if (c.variant != first && c.variant != second) order.push_back(c);
+    for (const PlanChoice& c : order) {
+        err = gett_variant(p->an.dtype, c.variant).staged ? build_narrow(p, c.variant) : TCX_SUCCESS;
         if (err == TCX_SUCCESS) {
-            if (v != p->variant) { p->variant = v; p->splitK = 1; }
+            if (c.variant != p->variant) { p->variant = c.variant; p->splitK = c.splitK; }
             break;
         }
         if (err != TCX_ERR_UNSUPPORTED_OP) break;
@@ -554,17 +579,20 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
         case TCX_KEY_TILE_N: return put_i64(an.path == TCX_PATH_BANDWIDTH ? p->stream.regA * p->stream.regB : s.mt_n, value, nbytes);
         case TCX_KEY_TILE_K: return put_i64(s.kt, value, nbytes);
         case TCX_KEY_GRID:
-            return put_i64(tiled ? tiles_of(an, s) * p->splitK : (an.sizeH * an.sizeM * an.sizeN + 255) / 256, value, nbytes);
-        case TCX_KEY_BLOCK: return put_i64(s.threads, value, nbytes);
+            return put_i64(tiled ? (s.dual ? (tiles_of(an, s) * p->splitK + 1) / 2 : tiles_of(an, s) * p->splitK)
+                                 : (an.sizeH * an.sizeM * an.sizeN + 255) / 256, value, nbytes);
+        case TCX_KEY_BLOCK: return put_i64(s.threads * (tiled && s.dual ? 2 : 1), value, nbytes);
         case TCX_KEY_A_K_FASTEST: return put_i64(an.a_k_fastest, value, nbytes);
         case TCX_KEY_B_K_FASTEST: return put_i64(an.b_k_fastest, value, nbytes);
         case TCX_KEY_D_N_FASTEST: return put_i64(an.d_n_fastest, value, nbytes);
         case TCX_KEY_SPLIT_K: return put_i64(tiled ? p->splitK : 1, value, nbytes);
         case TCX_KEY_LAUNCHES: {
             if (!tiled) return put_i64(1, value, nbytes);
-            const int64_t blocks = tiles_of(an, s) * p->splitK;
+            const int64_t items = tiles_of(an, s) * p->splitK;
+            const int64_t blocks = s.dual ? (items + 1) / 2 : items;
             const int64_t round = round_size_of(*p, s);
-            return put_i64((round > 0 && p->splitK == 1 && blocks > round ? (blocks + round - 1) / round : 1) + (p->splitK > 1 ? 1 : 0),
+            const bool second_kernel = p->splitK > 1 && !(p->splitK == 2 && s.pair_in_lds);
+            return put_i64((round > 0 && p->splitK == 1 && blocks > round ? (blocks + round - 1) / round : 1) + (second_kernel ? 1 : 0),
                            value, nbytes);
         }
         case TCX_KEY_VARIANT:

@@ -77,6 +77,7 @@ template <class R> struct RealPolicy {
     static __device__ __forceinline__ elem load_at(const char* base, uint32_t byte_off, unsigned) {
         return *(const elem*)(base + byte_off);
     }
+    static __device__ __forceinline__ void conj_fix(elem&, unsigned) {}
     template <bool DNF> static __device__ __forceinline__ void mac(elem a, elem b, acc_t& c) {
         c.v = DNF ? MF::mac(a, b, c.v)      // rows = m, lanes along n
                   : MF::mac(b, a, c.v);     // rows = n, lanes along m
@@ -136,6 +137,10 @@ struct ComplexPolicy {
         unsigned long long bits = __builtin_bit_cast(unsigned long long, v.y) ^ ((unsigned long long)conj_mask_hi << 32);
         v.y = __builtin_bit_cast(double, bits);
         return v;
+    }
+    static __device__ __forceinline__ void conj_fix(elem& v, unsigned conj_mask_hi) {
+        unsigned long long bits = __builtin_bit_cast(unsigned long long, v.y) ^ ((unsigned long long)conj_mask_hi << 32);
+        v.y = __builtin_bit_cast(double, bits);
     }
     template <bool DNF> static __device__ __forceinline__ void mac(elem a, elem b, acc_t& c) {
         const double nai = -a.y;
@@ -581,38 +586,82 @@ template <class T> __device__ __forceinline__ void lds_store(unsigned byte_addr,
 template <class T> __device__ __forceinline__ T lds_load(unsigned byte_addr) {
     return *(const __attribute__((address_space(3))) T*)(uintptr_t)byte_addr;
 }
+// complex elements travel as a plain 16-byte vector (one ds_write_b128 / ds_read_b128)
+typedef double plain_double2 __attribute__((ext_vector_type(2)));
+template <> __device__ __forceinline__ void lds_store<double2>(unsigned byte_addr, double2 v) {
+    *(__attribute__((address_space(3))) plain_double2*)(uintptr_t)byte_addr = plain_double2{v.x, v.y};
+}
+template <> __device__ __forceinline__ double2 lds_load<double2>(unsigned byte_addr) {
+    const plain_double2 t = *(const __attribute__((address_space(3))) plain_double2*)(uintptr_t)byte_addr;
+    return double2{t.x, t.y};
+}
 
-template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF>
-__global__ __launch_bounds__(WGM* WGN * 64) void gett_pingpong_kernel(GettArgs g) {
+// DUAL: each of the two wave groups owns a tile of its own (WGM x WGN waves per tile, twice that
+// per workgroup) and stages only its own operands; the groups meet at the phase barriers alone.
+// This brings the schedule to small tiles: a workgroup of eight waves works on two 64 x 64 or
+// 96 x 96 tiles.  Two LDS slabs per group are enough then (a group writes slab i+1 one phase
+// after it last read the buffer).  A workgroup's two items may have different numbers of slabs
+// (split K) or the second may not exist (odd count): both groups run the phase barriers of the
+// longer one.
+// One predicate, used by the kernel, its launcher and the planner alike: the partial sums of a
+// tile (one group's accumulators) fit into the LDS slabs of a dual workgroup.  The slabs' pitch
+// padding is left out, so it can only err towards "does not fit".
+constexpr bool pair_fits_lds(size_t elem_bytes, size_t real_bytes, int planes, int mt_m, int mt_n, int kt) {
+    return real_bytes * planes * mt_m * mt_n <= elem_bytes * 4 * (size_t)(mt_m + mt_n) * kt;
+}
+
+template <int MT, int NTG, bool KF> constexpr bool pingpong_operand_ok() {
+    // lanes along k, or lanes along the rows with one k per wave and rows that repeat per thread
+    return KF || (MT % 64 == 0 && NTG % MT == 0);
+}
+
+template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF, bool DUAL>
+__global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_kernel(GettArgs g) {
     using T = typename P::elem;
     using acc_t = typename P::acc_t;
-    constexpr int NT = WGM * WGN * 64;
+    constexpr int NTG = WGM * WGN * 64;                   // threads that work on one tile
+    constexpr int GROUPS_PER_TILE = DUAL ? 1 : 2;
+    constexpr int NB = DUAL ? 2 : 3;                      // LDS slabs per tile
     constexpr int WT_M = MT_M / WGM, WT_N = MT_N / WGN;
     constexpr int FM = WT_M / 16, FN = WT_N / 16;
-    using SA = Slab<T, MT_M, KT, NT, AKF>;
-    using SB = Slab<T, MT_N, KT, NT, BKF>;
+    using SA = Slab<T, MT_M, KT, NTG, AKF>;
+    using SB = Slab<T, MT_N, KT, NTG, BKF>;
     constexpr int STEPS = KT / 4;
     constexpr int SLAB = SA::ELEMS + SB::ELEMS;
     constexpr unsigned ES = sizeof(T);
     static_assert(KT % 8 == 0 && WT_M % 16 == 0 && WT_N % 16 == 0, "tile shape");
-    static_assert((WGM * WGN) % 8 == 0, "two groups with a wave on each of the four SIMDs");
-    static_assert(NT % KT == 0 && NT % MT_M == 0 && NT % MT_N == 0, "a thread's slab elements differ by a constant LDS offset");
-    static_assert(AKF || SA::UNIFORM_K, "an operand whose lanes run along the rows needs one k per wave");
-    static_assert(BKF || SB::UNIFORM_K, "an operand whose lanes run along the rows needs one k per wave");
+    static_assert((NTG / 64 * (DUAL ? 2 : 1)) % 8 == 0, "two groups with a wave on each of the four SIMDs");
+    static_assert(NTG % KT == 0, "a thread's slab elements differ by a constant LDS offset");
+    static_assert(pingpong_operand_ok<MT_M, NTG, AKF>() && pingpong_operand_ok<MT_N, NTG, BKF>(), "operand orientation");
     static_assert(ES * SLAB < 65536, "LDS offsets inside a slab must fit the instruction's immediate");
 
-    __shared__ T lds[3 * SLAB];
-    static_assert(sizeof(T) * 3 * SLAB <= 160 * 1024, "LDS budget of a CU");
+    __shared__ T lds[(DUAL ? 2 : 1) * NB * SLAB];
+    static_assert(sizeof(T) * (DUAL ? 2 : 1) * NB * SLAB <= 160 * 1024, "LDS budget of a CU");
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = wave_uniform(tid >> 6);
+    const int wave_all = wave_uniform((int)threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const bool second_group = wave_all >= NTG / 64 * (DUAL ? 2 : 1) / 2;
+    const int tid = DUAL ? (int)threadIdx.x % NTG : (int)threadIdx.x;      // thread number inside the tile's group(s)
+    const int wave = DUAL ? wave_all % (NTG / 64) : wave_all;
     const int wm = wave % WGM, wn = wave / WGM;
-    const bool second_group = wave >= WGM * WGN / 2;
 
-    const int64_t lid = g.lid_base + xcd_contiguous(blockIdx.x, gridDim.x);
-    const int split = wave_uniform((int)(lid % g.splitK));
-    const Tile tile = locate_tile(lid / g.splitK, g, MT_M, MT_N);
+    // ---- which item (tile, part of K) this group works on, and how many slabs both items have
+    const int64_t items = (int64_t)g.tilesM * g.tilesN * g.sizeH * g.splitK;
+    const int64_t wg = g.lid_base + xcd_contiguous(blockIdx.x, gridDim.x);
+    const int64_t lid = DUAL ? 2 * wg + (second_group ? 1 : 0) : wg;
+    const int nk = g.tilesK;
+    const int per_split = (nk + g.splitK - 1) / g.splitK;
+    auto slabs_of = [&](int64_t item, int* first) {
+        if (item >= items) { *first = 0; return 0; }
+        const int sp = (int)(item % g.splitK);
+        *first = sp * per_split;
+        return max(0, min(nk, *first + per_split) - *first);
+    };
+    int kb = 0, kb_other = 0;
+    const int n = wave_uniform(slabs_of(lid, &kb));
+    const int n_all = DUAL ? wave_uniform(max(n, slabs_of(lid ^ 1, &kb_other))) : n;
+    kb = wave_uniform(kb);
+    const Tile tile = locate_tile(min(lid, items - 1) / g.splitK, g, MT_M, MT_N);
     const int64_t m0 = wave_uniform(tile.m0), n0 = wave_uniform(tile.n0);
     const char* const Ab = (const char*)g.A + wave_uniform(tile.hA * (int64_t)sizeof(T) + scalar_table(g.rbA)[m0 / MT_M]);
     const char* const Bb = (const char*)g.B + wave_uniform(tile.hB * (int64_t)sizeof(T) + scalar_table(g.rbB)[n0 / MT_N]);
@@ -626,13 +675,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_pingpong_kernel(GettArgs g
     unsigned kinA[SA::PER], kinB[SB::PER];
 #pragma unroll
     for (int i = 0; i < SA::PER; ++i) {
-        const int e = tid + i * NT;
+        const int e = tid + i * NTG;
         voA[i] = g.rrA[m0 + SA::row(e)] + (AKF ? g.krA[SA::kin(e)] : 0u);
         kinA[i] = AKF ? 0u : (unsigned)__builtin_amdgcn_readfirstlane(SA::kin(e));
     }
 #pragma unroll
     for (int i = 0; i < SB::PER; ++i) {
-        const int e = tid + i * NT;
+        const int e = tid + i * NTG;
         voB[i] = g.rrB[n0 + SB::row(e)] + (BKF ? g.krB[SB::kin(e)] : 0u);
         kinB[i] = BKF ? 0u : (unsigned)__builtin_amdgcn_readfirstlane(SB::kin(e));
     }
@@ -640,10 +689,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_pingpong_kernel(GettArgs g
     // B, and where it reads its first fragment of A and of B.  Further elements / fragments are
     // at compile-time offsets from these.
     const int fr = lane & 15, fq = lane >> 4;
-    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) T*)lds;
-    unsigned wA[3], wB[3], fA[3], fB[3];
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) T*)lds +
+                          (DUAL && second_group ? ES * NB * SLAB : 0u);
+    unsigned wA[NB], wB[NB], fA[NB], fB[NB];
 #pragma unroll
-    for (int b = 0; b < 3; ++b) {
+    for (int b = 0; b < NB; ++b) {
         wA[b] = lds0 + ES * (unsigned)(b * SLAB + SA::lds_index(tid));
         wB[b] = lds0 + ES * (unsigned)(b * SLAB + SA::ELEMS + SB::lds_index(tid));
         fA[b] = lds0 + ES * (unsigned)(b * SLAB + SA::frag_index(wm * WT_M + fr, fq));
@@ -652,13 +702,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_pingpong_kernel(GettArgs g
         // (with vector-ALU instructions) inside the loop
         asm volatile("" : "+v"(wA[b]), "+v"(wB[b]), "+v"(fA[b]), "+v"(fB[b]));
     }
-    constexpr unsigned dWA = ES * (AKF ? (NT / KT) * SA::LD : (NT / MT_M) * SA::LD);   // element i+1 minus element i
-    constexpr unsigned dWB = ES * (BKF ? (NT / KT) * SB::LD : (NT / MT_N) * SB::LD);
+    constexpr unsigned dWA = ES * (AKF ? (NTG / KT) * SA::LD : (NTG / MT_M) * SA::LD);   // element i+1 minus element i
+    constexpr unsigned dWB = ES * (BKF ? (NTG / KT) * SB::LD : (NTG / MT_N) * SB::LD);
     constexpr unsigned dFA_row = ES * (AKF ? 16 * SA::LD : 16), dFA_step = ES * (AKF ? 4 : 4 * SA::LD);
     constexpr unsigned dFB_row = ES * (BKF ? 16 * SB::LD : 16), dFB_step = ES * (BKF ? 4 : 4 * SB::LD);
 
     // ---- per slab, scalar: the base of each load
-    const int nk = g.tilesK;
     int64_t kqA[SA::PER], kqB[SB::PER];          // lanes along the rows: one byte offset per element's k
     int64_t kbA = 0, kbB = 0;                    // lanes along k: the slab's base
     auto k_offsets = [&](int kt) {
@@ -678,17 +727,18 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_pingpong_kernel(GettArgs g
             for (int i = 0; i < SB::PER; ++i) kqB[i] = q[kinB[i]];
         }
     };
+    // conjugation is applied to the MFMA fragments in the compute phase (a vector-ALU operation)
     T ra[SA::PER], rb[SB::PER];
     auto gather = [&]() {
 #pragma unroll
         for (int i = 0; i < SA::PER; ++i) {
             asm("" : "+v"(voA[i]));              // keeps "scalar base + 32-bit lane offset" from being folded into a 64-bit lane address
-            ra[i] = P::load_at(Ab + (AKF ? kbA : kqA[i]), voA[i], conjA);
+            ra[i] = P::load_at(Ab + (AKF ? kbA : kqA[i]), voA[i], 0u);
         }
 #pragma unroll
         for (int i = 0; i < SB::PER; ++i) {
             asm("" : "+v"(voB[i]));
-            rb[i] = P::load_at(Bb + (BKF ? kbB : kqB[i]), voB[i], conjB);
+            rb[i] = P::load_at(Bb + (BKF ? kbB : kqB[i]), voB[i], 0u);
         }
     };
     auto stage = [&](auto BUF) {
@@ -714,22 +764,25 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_pingpong_kernel(GettArgs g
     };
     auto mfmas = [&](int set) {
 #pragma unroll
+        for (int i = 0; i < FM; ++i) P::conj_fix(fa[set][i], conjA);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) P::conj_fix(fb[set][j], conjB);
+#pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
             for (int j = 0; j < FN; ++j) P::template mac<DNF>(fa[set][i], fb[set][j], acc[i][j]);
     };
 
-    const int per_split = (nk + g.splitK - 1) / g.splitK;
-    const int kb = wave_uniform(split * per_split), ke = wave_uniform(min(nk, kb + per_split));
-    const int n = ke - kb;
     // Prologue: slab kb to LDS, slab kb+1 into registers (slab numbers past the end are clamped:
     // harmless loads that are never staged).
-    k_offsets(kb);
-    gather();
-    k_offsets(kb + 1);
-    stage(std::integral_constant<int, 0>{});
-    gather();
-    k_offsets(kb + 2);
+    if (n > 0) {
+        k_offsets(kb);
+        gather();
+        k_offsets(kb + 1);
+        stage(std::integral_constant<int, 0>{});
+        gather();
+        k_offsets(kb + 2);
+    }
     __syncthreads();
     if (second_group) __builtin_amdgcn_s_barrier();       // one phase behind the first group
 
@@ -744,34 +797,61 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_pingpong_kernel(GettArgs g
         constexpr int b = decltype(BUF)::value;
         // memory phase: no vector-ALU instruction in here
         if (i + 1 < n) {
-            stage(std::integral_constant<int, (b + 1) % 3>{});   // slab kb+i+1
-            gather();                                            // slab kb+i+2
+            stage(std::integral_constant<int, (b + 1) % NB>{});   // slab kb+i+1
+            gather();                                             // slab kb+i+2
             k_offsets(kb + i + 3);
         }
-        frag_load(BUF, 0, 0);
+        if (i < n) frag_load(BUF, 0, 0);
         phase_end();
         // compute phase
+        if (i < n) {
 #pragma unroll
-        for (int st = 0; st < STEPS; ++st) {
-            if (st + 1 < STEPS) frag_load(BUF, st + 1, (st + 1) & 1);
-            mfmas(st & 1);
+            for (int st = 0; st < STEPS; ++st) {
+                if (st + 1 < STEPS) frag_load(BUF, st + 1, (st + 1) & 1);
+                mfmas(st & 1);
+            }
         }
         phase_end();
     };
     int i = 0;
-    for (; i + 3 <= n; i += 3) {
-        round(i, std::integral_constant<int, 0>{});
-        round(i + 1, std::integral_constant<int, 1>{});
-        round(i + 2, std::integral_constant<int, 2>{});
+    if constexpr (NB == 3) {
+        for (; i + 3 <= n_all; i += 3) {
+            round(i, std::integral_constant<int, 0>{});
+            round(i + 1, std::integral_constant<int, 1>{});
+            round(i + 2, std::integral_constant<int, 2>{});
+        }
+        if (i < n_all) round(i, std::integral_constant<int, 0>{});
+        if (i + 1 < n_all) round(i + 1, std::integral_constant<int, 1>{});
+    } else {
+        for (; i + 2 <= n_all; i += 2) {
+            round(i, std::integral_constant<int, 0>{});
+            round(i + 1, std::integral_constant<int, 1>{});
+        }
+        if (i < n_all) round(i, std::integral_constant<int, 0>{});
     }
-    if (i < n) round(i, std::integral_constant<int, 0>{});
-    if (i + 1 < n) round(i + 1, std::integral_constant<int, 1>{});
     if (!second_group) __builtin_amdgcn_s_barrier();      // pairs with the second group's last barrier
     settle_accumulators();
 
+    // ---- epilogue.  K in two parts with one tile per group: the two items of a workgroup are
+    // the two parts of ONE tile, and the partial sums meet in LDS (first group's + second
+    // group's, a fixed order) instead of going through the workspace and a second kernel.
+    constexpr bool PAIR_FITS = DUAL && pair_fits_lds(sizeof(T), sizeof(typename P::real), sizeof(T) / sizeof(typename P::real), MT_M, MT_N, KT);
+    static_assert(!PAIR_FITS || sizeof(typename P::real) * NTG * P::template acc_reals<FM, FN>() <= sizeof(T) * 2 * NB * SLAB, "partial sums must fit the slabs");
+    if (PAIR_FITS && g.splitK == 2) {
+        typename P::real* part = (typename P::real*)lds;
+        __syncthreads();                                  // every wave has left the main loop: the slabs are free
+        if (second_group) P::template spill<FM, FN>(acc, part + tid, NTG);
+        __syncthreads();
+        if (!second_group) {
+            P::template accumulate<FM, FN>(acc, part + tid, NTG);
+            scatter<P, FM, FN, WT_M, WT_N, DNF>(acc, g, tile, wm, wn, lane);
+        }
+        return;
+    }
+    if (n == 0) return;                                   // a second group without an item
     if (g.splitK > 1) {
-        typename P::real* ws = (typename P::real*)g.workspace + (size_t)lid * (NT * P::template acc_reals<FM, FN>());
-        P::template spill<FM, FN>(acc, ws + tid, NT);
+        typename P::real* ws = (typename P::real*)g.workspace + (size_t)lid * (NTG * P::template acc_reals<FM, FN>());
+        P::template spill<FM, FN>(acc, ws + tid, NTG);
     } else {
         scatter<P, FM, FN, WT_M, WT_N, DNF>(acc, g, tile, wm, wn, lane);
     }
@@ -933,6 +1013,7 @@ struct Shape {
     bool narrow;           // LDS-staged kernel: gather through the 32-bit tile-relative tables
     bool pingpong = false; // two-phase kernel (needs |K| % kt == 0 and slab-periodic k offsets)
     int fallback = -1;     // shape to use instead when this one's preconditions fail (-1: any)
+    bool dual = false;     // two-phase kernel: one tile per wave group (two per workgroup)
 };
 // `efficiency`: measured fraction of a CU's matrix peak that the shape's main loop sustains on
 // MI355X with the CU saturated (256x128: config 2; the others: a 1024^3 product, 576^3, 96^3 x 512).
@@ -947,6 +1028,8 @@ constexpr Shape kRealShapes[] = {
     {64, 64, 16, 2, 4, 0.36f, 0, 2, true},
     {64, 64, 16, 4, 4, 0.41f, 0, 2, true},
     {256, 128, 16, 4, 2, 0.80f, 0, 1, true, false, -1},
+    {64, 64, 16, 2, 2, 0.80f, 0, 1, true, true, -1, true},
+    {128, 64, 16, 2, 2, 0.85f, 0, 1, true, true, -1, true},
 };
 constexpr Shape kComplexShapes[] = {
     {96, 96, 8, 2, 2, 0.45f, 0, 2, true},
@@ -956,6 +1039,7 @@ constexpr Shape kComplexShapes[] = {
     {64, 64, 8, 2, 2, 0.25f, 2, 0, false},
     {96, 48, 8, 2, 1, 0.45f, 0, 2, true},
     {48, 96, 8, 1, 2, 0.45f, 0, 2, true},
+    {96, 96, 8, 2, 2, 0.85f, 0, 1, true, true, 5, true},
 };
 constexpr int kNumRealShapes = sizeof(kRealShapes) / sizeof(Shape);
 constexpr int kNumComplexShapes = sizeof(kComplexShapes) / sizeof(Shape);
@@ -974,28 +1058,39 @@ hipError_t launch_one(const GettArgs& a, int64_t blocks, hipStream_t st) {
         else
             return launch_one<P, S, false, false, DNF>(a, blocks, st);
     } else if constexpr (s.pingpong) {
-        if (a.sizeK % s.kt != 0 || (AKF && !a.periodicA) || (BKF && !a.periodicB)) return hipErrorInvalidValue;
-        // Long tiles are launched round by round (one workgroup per CU each): workgroups of a
-        // round that share operand panels through an XCD's L2 start together, whereas in one big
-        // launch the 0.5 - 1 % differences in tile duration between CUs add up from round to
-        // round until the sharers are further apart than the L2 holds.
-        if (a.round_size > 0 && a.splitK == 1 && blocks > a.round_size) {
-            GettArgs r = a;
-            for (int64_t at = 0; at < blocks; at += a.round_size) {
-                r.lid_base = at;
-                gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF>
-                    <<<dim3((unsigned)std::min<int64_t>(a.round_size, blocks - at)), dim3(s.wgm * s.wgn * 64), 0, st>>>(r);
+        constexpr int NTG = s.wgm * s.wgn * 64;
+        if constexpr (pingpong_operand_ok<s.mt_m, NTG, AKF>() && pingpong_operand_ok<s.mt_n, NTG, BKF>()) {
+            if (a.sizeK % s.kt != 0 || (AKF && !a.periodicA) || (BKF && !a.periodicB)) return hipErrorInvalidValue;
+            constexpr int threads = NTG * (s.dual ? 2 : 1);
+            const int64_t wgs = s.dual ? (blocks + 1) / 2 : blocks;
+            // Long tiles are launched round by round (one workgroup per CU each): workgroups of a
+            // round that share operand panels through an XCD's L2 start together, whereas in one big
+            // launch the 0.5 - 1 % differences in tile duration between CUs add up from round to
+            // round until the sharers are further apart than the L2 holds.
+            if (a.round_size > 0 && a.splitK == 1 && wgs > a.round_size) {
+                GettArgs r = a;
+                for (int64_t at = 0; at < wgs; at += a.round_size) {
+                    r.lid_base = at;
+                    gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual>
+                        <<<dim3((unsigned)std::min<int64_t>(a.round_size, wgs - at)), dim3(threads), 0, st>>>(r);
+                }
+            } else {
+                gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual>
+                    <<<dim3((unsigned)wgs), dim3(threads), 0, st>>>(a);
             }
         } else {
-            gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF>
-                <<<dim3((unsigned)blocks), dim3(s.wgm * s.wgn * 64), 0, st>>>(a);
+            return hipErrorInvalidValue;      // this orientation is not built for the shape: the plan must not choose it
         }
     } else {
         gett_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.depth, s.narrow>
             <<<dim3((unsigned)blocks), dim3(s.wgm * s.wgn * 64), 0, st>>>(a);
     }
     hipError_t err = hipGetLastError();
-    if (err == hipSuccess && a.splitK > 1) {
+    bool reduced = false;
+    if constexpr (s.ch == 0 && s.pingpong)
+        reduced = a.splitK == 2 && s.dual &&
+                  pair_fits_lds(sizeof(typename P::elem), sizeof(typename P::real), sizeof(typename P::elem) / sizeof(typename P::real), s.mt_m, s.mt_n, s.kt);
+    if (err == hipSuccess && a.splitK > 1 && !reduced) {
         gett_reduce_kernel<P, s.mt_m, s.mt_n, s.wgm, s.wgn, DNF>
             <<<dim3((unsigned)(blocks / a.splitK)), dim3(s.wgm * s.wgn * 64), 0, st>>>(a);
         err = hipGetLastError();
@@ -1031,6 +1126,8 @@ hipError_t launch_real_shape(int variant, bool akf, bool bkf, bool dnf, const Ge
         case 7: return launch_flags<P, 7>(akf, bkf, dnf, a, blocks, st);
         case 8: return launch_flags<P, 8>(akf, bkf, dnf, a, blocks, st);
         case 9: return launch_flags<P, 9>(akf, bkf, dnf, a, blocks, st);
+        case 10: return launch_flags<P, 10>(akf, bkf, dnf, a, blocks, st);
+        case 11: return launch_flags<P, 11>(akf, bkf, dnf, a, blocks, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1044,6 +1141,7 @@ hipError_t launch_complex_shape(int variant, bool akf, bool bkf, bool dnf, const
         case 4: return launch_flags<ComplexPolicy, 4>(akf, bkf, dnf, a, blocks, st);
         case 5: return launch_flags<ComplexPolicy, 5>(akf, bkf, dnf, a, blocks, st);
         case 6: return launch_flags<ComplexPolicy, 6>(akf, bkf, dnf, a, blocks, st);
+        case 7: return launch_flags<ComplexPolicy, 7>(akf, bkf, dnf, a, blocks, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1068,16 +1166,20 @@ GettVariant gett_variant(int dtype, int variant) {
     const Shape* t = shapes_of(dtype, &n);
     const Shape s = t[variant];
     const int planes = dtype == TCX_C128 ? 2 : 1;
-    return {s.mt_m, s.mt_n, s.kt, s.wgm * s.wgn * 64, s.efficiency, s.mt_m * s.mt_n * planes, s.ch == 0 && s.narrow, s.pingpong, s.fallback};
+    return {s.mt_m, s.mt_n, s.kt, s.wgm * s.wgn * 64, s.efficiency, s.mt_m * s.mt_n * planes, s.ch == 0 && s.narrow, s.pingpong, s.fallback, s.dual,
+            s.dual && pair_fits_lds(dtype == TCX_F32 ? 4 : dtype == TCX_F64 ? 8 : 16, dtype == TCX_F32 ? 4 : 8, planes, s.mt_m, s.mt_n, s.kt)};
 }
 
 int launch_gett(int dtype, int variant, bool a_kf, bool b_kf, bool d_nf, const GettArgs& args, void* stream,
                 int64_t* grid, int* block) {
     if (variant < 0 || variant >= gett_num_variants(dtype)) return (int)hipErrorInvalidValue;
-    if (args.splitK < 1 || (args.splitK > 1 && !args.workspace)) return (int)hipErrorInvalidValue;
+    if (args.splitK < 1) return (int)hipErrorInvalidValue;
+    if (args.splitK > 1 && !args.workspace && !(args.splitK == 2 && gett_variant(dtype, variant).pair_in_lds))
+        return (int)hipErrorInvalidValue;
     const int64_t blocks = (int64_t)args.tilesM * args.tilesN * args.sizeH * args.splitK;
-    *grid = blocks;
-    *block = gett_variant(dtype, variant).threads;
+    const GettVariant gv = gett_variant(dtype, variant);
+    *grid = gv.dual ? (blocks + 1) / 2 : blocks;
+    *block = gv.threads * (gv.dual ? 2 : 1);
     if (blocks <= 0 || blocks > 0x7fffffff) return (int)hipErrorInvalidConfiguration;
     hipStream_t st = (hipStream_t)stream;
     if (dtype == TCX_F64) return (int)launch_real_shape<RealPolicy<double>>(variant, a_kf, b_kf, d_nf, args, blocks, st);

@@ -91,12 +91,14 @@ struct GettArgs {
 };
 
 struct GettVariant {
-    int mt_m, mt_n, kt, threads;
+    int mt_m, mt_n, kt, threads;   // threads: per TILE (a dual workgroup has twice as many)
     float efficiency;    // relative main-loop speed per unit tile area, for the planner's cost model
     int acc_reals;       // real accumulator values per tile (split-K workspace per part)
     bool staged;         // kernel gathers through the narrow (32-bit, tile-relative) tables
     bool pingpong;       // two-phase kernel: needs |K| % kt == 0 and slab-periodic relative k offsets
     int fallback;        // shape to try first when this one cannot serve the plan (-1: none)
+    bool dual;           // two-phase kernel with one tile per wave group: a workgroup takes two items
+    bool pair_in_lds;    // ... and reduces a two-part split of K inside the workgroup (no workspace, no second kernel)
 };
 
 // Generic fallback: every mode of D (H, M, N together, D-fastest first) and every K mode.

@@ -15,10 +15,13 @@ pytestmark = pytest.mark.gpu
 GENERIC, GETT, STREAM = 0, 1, 2
 
 
+TWO_PHASE = {False: (0, 10, 11), True: (7,)}      # tile shapes served by the two-phase kernel (real, complex)
+
+
 def _paths_for(p):
     from gpu_helpers import DT  # noqa: F401
     paths = [(GENERIC, None)]
-    paths += [(GETT, v) for v in range(7 if p.dtype == "c128" else 10)]
+    paths += [(GETT, v) for v in range(8 if p.dtype == "c128" else 12)]
     if p.sizes()[3] <= 64:
         paths.append((STREAM, None))
     return paths
@@ -35,7 +38,7 @@ def _check(p, a, b, c, path, variant, exact=False, truth=None, S=None, split_k=N
         if path == STREAM and getattr(exc, "code", None) == 11 and p.sizes()[3] > 8:
             say("  (streaming path declined: |K| = %d)" % p.sizes()[3])
             return
-        if path == GETT and variant == 0 and p.dtype != "c128" and getattr(exc, "code", None) == 11:
+        if path == GETT and variant in TWO_PHASE[p.dtype == "c128"] and getattr(exc, "code", None) == 11:
             # the two-phase kernel needs |K| in whole slabs and slab-periodic k offsets
             say("  (two-phase kernel declined this plan)")
             return
@@ -133,25 +136,50 @@ def test_two_phase_kernel(dtype):
     """The two-phase (ping-pong) kernel of the large tile, forced: every operand orientation, slab
     counts that end in each position of its loop unrolled by three, ragged M and N, split K."""
     from gpu_helpers import GpuProduct  # noqa: F401
+    from gpu_helpers import run_gpu, say
     for flags in range(8):
         akf, bkf, dnf = bool(flags & 4), bool(flags & 2), bool(flags & 1)
         for k in (16, 32, 48, 64, 80, 176):
             p = _matrix_product(300, 200, k, akf, bkf, dnf, dtype)
             a, b, c = W.make_operands(p)
             truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
-            from gpu_helpers import run_gpu, say
-            say("%s two-phase" % p.name)
-            got = run_gpu(p, a, b, c, force_path=GETT, variant=0)      # must not be declined: raises otherwise
-            assert normalised_error(p, got, truth, S, c) <= TOLERANCE[p.dtype]
-            if k >= 48:
-                got = run_gpu(p, a, b, c, force_path=GETT, variant=0, split_k=3)
+            for variant in TWO_PHASE[False]:
+                say("%s two-phase shape %d" % (p.name, variant))
+                got = run_gpu(p, a, b, c, force_path=GETT, variant=variant)      # must not be declined: raises otherwise
                 assert normalised_error(p, got, truth, S, c) <= TOLERANCE[p.dtype]
+                for parts in (2, 3) if k >= 48 else ():
+                    # 2 parts: summed inside the workgroup (one tile per wave group) or by the second
+                    # kernel; 3 parts: the two items of a workgroup get different numbers of slabs
+                    got = run_gpu(p, a, b, c, force_path=GETT, variant=variant, split_k=parts)
+                    assert normalised_error(p, got, truth, S, c) <= TOLERANCE[p.dtype]
     # integer inputs: bit-exact
     p = _matrix_product(520, 260, 112, False, True, False, dtype)
     a, b, c = W.make_operands(p, "ints")
     truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
-    got = run_gpu(p, a, b, c, force_path=GETT, variant=0)
-    assert np.array_equal(W.strided_view(got, p.D), W.strided_view(truth, p.D))
+    for variant in TWO_PHASE[False]:
+        for parts in (None, 2):
+            got = run_gpu(p, a, b, c, force_path=GETT, variant=variant, split_k=parts)
+            assert np.array_equal(W.strided_view(got, p.D), W.strided_view(truth, p.D))
+
+
+@pytest.mark.parametrize("h_slowest", [False, True])
+def test_two_phase_kernel_complex(h_slowest):
+    """The two-phase kernel with one 96 x 96 complex tile per wave group: batched conj(A)^T B with
+    an odd number of batches (the last workgroup's second group has no tile), ragged tiles, |K| in
+    whole slabs; also with K split (items of different length in one workgroup) and integer inputs."""
+    from gpu_helpers import run_gpu, say
+    for h, n, k in ((7, 40, 40), (5, 100, 24), (3, 96, 96)):
+        p = W.config4(h=h, n=n, h_slowest=h_slowest, k=k)
+        for dist, exact in (("uniform", False), ("ints", True)):
+            a, b, c = W.make_operands(p, dist)
+            truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+            for split in (None, 2, 3):
+                say("%s two-phase complex dist=%s split=%s" % (p.name, dist, split))
+                got = run_gpu(p, a, b, c, force_path=GETT, variant=TWO_PHASE[True][0], split_k=split)
+                if exact:                                  # 0.5 * integer is exact
+                    assert np.array_equal(W.strided_view(got, p.D), W.strided_view(truth, p.D))
+                else:
+                    assert normalised_error(p, got, truth, S, c) <= TOLERANCE[p.dtype]
 
 
 LOW_AI_LARGE = [W.config5(extent=4, nshared=1, nfree=7), W.config4(h=512, n=96, k=4),
