@@ -615,7 +615,16 @@ template <int MT, int NTG, bool KF> constexpr bool pingpong_operand_ok() {
     return KF || (MT % 64 == 0 && NTG % MT == 0);
 }
 
-template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF, bool DUAL>
+template <int I, int N, class F> __device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// DEPTH: slabs of global loads in flight in registers.  The large tile spends 3.6 us on a slab and
+// needs one; an iteration of the small tiles is shorter than a load takes.
+template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF, bool DUAL, int DEPTH>
 __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_kernel(GettArgs g) {
     using T = typename P::elem;
     using acc_t = typename P::acc_t;
@@ -651,7 +660,7 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
     const int64_t lid = DUAL ? 2 * wg + (second_group ? 1 : 0) : wg;
     const int nk = g.tilesK;
     const int per_split = (nk + g.splitK - 1) / g.splitK;
-    auto slabs_of = [&](int64_t item, int* first) {
+    auto slabs_of = [&](int64_t item, int* first) __attribute__((always_inline)) {
         if (item >= items) { *first = 0; return 0; }
         const int sp = (int)(item % g.splitK);
         *first = sp * per_split;
@@ -710,7 +719,7 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
     // ---- per slab, scalar: the base of each load
     int64_t kqA[SA::PER], kqB[SB::PER];          // lanes along the rows: one byte offset per element's k
     int64_t kbA = 0, kbB = 0;                    // lanes along k: the slab's base
-    auto k_offsets = [&](int kt) {
+    auto k_offsets = [&](int kt) __attribute__((always_inline)) {
         const int kc = min(kt, nk - 1);
         if (AKF) {
             kbA = scalar_table(g.kbA)[kc];
@@ -728,25 +737,26 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
         }
     };
     // conjugation is applied to the MFMA fragments in the compute phase (a vector-ALU operation)
-    T ra[SA::PER], rb[SB::PER];
-    auto gather = [&]() {
+    T ra[DEPTH][SA::PER], rb[DEPTH][SB::PER];     // slab kb+j waits in ring slot j % DEPTH
+    auto gather = [&](auto SLOT) __attribute__((always_inline)) {
+        constexpr int sl = decltype(SLOT)::value;
 #pragma unroll
         for (int i = 0; i < SA::PER; ++i) {
             asm("" : "+v"(voA[i]));              // keeps "scalar base + 32-bit lane offset" from being folded into a 64-bit lane address
-            ra[i] = P::load_at(Ab + (AKF ? kbA : kqA[i]), voA[i], 0u);
+            ra[sl][i] = P::load_at(Ab + (AKF ? kbA : kqA[i]), voA[i], 0u);
         }
 #pragma unroll
         for (int i = 0; i < SB::PER; ++i) {
             asm("" : "+v"(voB[i]));
-            rb[i] = P::load_at(Bb + (BKF ? kbB : kqB[i]), voB[i], 0u);
+            rb[sl][i] = P::load_at(Bb + (BKF ? kbB : kqB[i]), voB[i], 0u);
         }
     };
-    auto stage = [&](auto BUF) {
-        constexpr int b = decltype(BUF)::value;
+    auto stage = [&](auto BUF, auto SLOT) __attribute__((always_inline)) {
+        constexpr int b = decltype(BUF)::value, sl = decltype(SLOT)::value;
 #pragma unroll
-        for (int i = 0; i < SA::PER; ++i) lds_store<T>(wA[b] + i * dWA, ra[i]);
+        for (int i = 0; i < SA::PER; ++i) lds_store<T>(wA[b] + i * dWA, ra[sl][i]);
 #pragma unroll
-        for (int i = 0; i < SB::PER; ++i) lds_store<T>(wB[b] + i * dWB, rb[i]);
+        for (int i = 0; i < SB::PER; ++i) lds_store<T>(wB[b] + i * dWB, rb[sl][i]);
     };
 
     acc_t acc[FM][FN];
@@ -755,14 +765,14 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
 #pragma unroll
         for (int j = 0; j < FN; ++j) P::clear(acc[i][j]);
     T fa[2][FM], fb[2][FN];
-    auto frag_load = [&](auto BUF, int step, int set) {
+    auto frag_load = [&](auto BUF, int step, int set) __attribute__((always_inline)) {
         constexpr int b = decltype(BUF)::value;
 #pragma unroll
         for (int i = 0; i < FM; ++i) fa[set][i] = lds_load<T>(fA[b] + i * dFA_row + step * dFA_step);
 #pragma unroll
         for (int j = 0; j < FN; ++j) fb[set][j] = lds_load<T>(fB[b] + j * dFB_row + step * dFB_step);
     };
-    auto mfmas = [&](int set) {
+    auto mfmas = [&](int set) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < FM; ++i) P::conj_fix(fa[set][i], conjA);
 #pragma unroll
@@ -773,62 +783,59 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
             for (int j = 0; j < FN; ++j) P::template mac<DNF>(fa[set][i], fb[set][j], acc[i][j]);
     };
 
-    // Prologue: slab kb to LDS, slab kb+1 into registers (slab numbers past the end are clamped:
-    // harmless loads that are never staged).
+    // Prologue: slab kb to LDS, slabs kb+1 .. kb+DEPTH into the ring (slab numbers past the end
+    // are clamped: harmless loads that are never staged).
     if (n > 0) {
         k_offsets(kb);
-        gather();
+        gather(std::integral_constant<int, 0>{});
         k_offsets(kb + 1);
-        stage(std::integral_constant<int, 0>{});
-        gather();
-        k_offsets(kb + 2);
+        stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        static_for<0, DEPTH>([&](auto D) __attribute__((always_inline)) {
+            gather(std::integral_constant<int, (1 + decltype(D)::value) % DEPTH>{});      // slab kb+1+D
+            k_offsets(kb + 2 + decltype(D)::value);
+        });
     }
     __syncthreads();
     if (second_group) __builtin_amdgcn_s_barrier();       // one phase behind the first group
 
     // A phase ends with the workgroup barrier; the compiler may move nothing across it (MFMAs
     // only touch registers, so the barrier alone would not hold them in their phase).
-    auto phase_end = [&]() {
+    auto phase_end = [&]() __attribute__((always_inline)) {
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto round = [&](int i, auto BUF) {
-        constexpr int b = decltype(BUF)::value;
+    // The loop is unrolled so that the LDS slab and the ring slot are compile-time constants:
+    // iteration i has IDX = i % UNROLL.
+    constexpr int UNROLL = NB * DEPTH / (NB % DEPTH == 0 ? DEPTH : DEPTH % NB == 0 ? NB : 1);
+    static_assert(UNROLL % NB == 0 && UNROLL % DEPTH == 0, "unroll factor");
+    auto round = [&](int i, auto IDX) __attribute__((always_inline)) {
+        using BUF = std::integral_constant<int, decltype(IDX)::value % NB>;
+        using NEXT_BUF = std::integral_constant<int, (decltype(IDX)::value + 1) % NB>;
+        using NEXT_SLOT = std::integral_constant<int, (decltype(IDX)::value + 1) % DEPTH>;
         // memory phase: no vector-ALU instruction in here
         if (i + 1 < n) {
-            stage(std::integral_constant<int, (b + 1) % NB>{});   // slab kb+i+1
-            gather();                                             // slab kb+i+2
-            k_offsets(kb + i + 3);
+            stage(NEXT_BUF{}, NEXT_SLOT{});               // slab kb+i+1
+            gather(NEXT_SLOT{});                          // slab kb+i+1+DEPTH
+            k_offsets(kb + i + 2 + DEPTH);
         }
-        if (i < n) frag_load(BUF, 0, 0);
+        if (i < n) frag_load(BUF{}, 0, 0);
         phase_end();
         // compute phase
         if (i < n) {
 #pragma unroll
             for (int st = 0; st < STEPS; ++st) {
-                if (st + 1 < STEPS) frag_load(BUF, st + 1, (st + 1) & 1);
+                if (st + 1 < STEPS) frag_load(BUF{}, st + 1, (st + 1) & 1);
                 mfmas(st & 1);
             }
         }
         phase_end();
     };
     int i = 0;
-    if constexpr (NB == 3) {
-        for (; i + 3 <= n_all; i += 3) {
-            round(i, std::integral_constant<int, 0>{});
-            round(i + 1, std::integral_constant<int, 1>{});
-            round(i + 2, std::integral_constant<int, 2>{});
-        }
-        if (i < n_all) round(i, std::integral_constant<int, 0>{});
-        if (i + 1 < n_all) round(i + 1, std::integral_constant<int, 1>{});
-    } else {
-        for (; i + 2 <= n_all; i += 2) {
-            round(i, std::integral_constant<int, 0>{});
-            round(i + 1, std::integral_constant<int, 1>{});
-        }
-        if (i < n_all) round(i, std::integral_constant<int, 0>{});
-    }
+    for (; i + UNROLL <= n_all; i += UNROLL) static_for<0, UNROLL>([&](auto IDX) __attribute__((always_inline)) { round(i + decltype(IDX)::value, IDX); });
+    static_for<0, UNROLL - 1>([&](auto IDX) __attribute__((always_inline)) {
+        if (i + decltype(IDX)::value < n_all) round(i + decltype(IDX)::value, IDX);
+    });
     if (!second_group) __builtin_amdgcn_s_barrier();      // pairs with the second group's last barrier
     settle_accumulators();
 
@@ -1029,7 +1036,7 @@ constexpr Shape kRealShapes[] = {
     {64, 64, 16, 4, 4, 0.41f, 0, 2, true},
     {256, 128, 16, 4, 2, 0.80f, 0, 1, true, false, -1},
     {64, 64, 16, 2, 2, 0.80f, 0, 1, true, true, -1, true},
-    {128, 64, 16, 2, 2, 0.85f, 0, 1, true, true, -1, true},
+    {128, 64, 16, 2, 2, 0.85f, 0, 2, true, true, -1, true},
 };
 constexpr Shape kComplexShapes[] = {
     {96, 96, 8, 2, 2, 0.45f, 0, 2, true},
@@ -1071,11 +1078,11 @@ hipError_t launch_one(const GettArgs& a, int64_t blocks, hipStream_t st) {
                 GettArgs r = a;
                 for (int64_t at = 0; at < wgs; at += a.round_size) {
                     r.lid_base = at;
-                    gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual>
+                    gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual, s.depth>
                         <<<dim3((unsigned)std::min<int64_t>(a.round_size, wgs - at)), dim3(threads), 0, st>>>(r);
                 }
             } else {
-                gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual>
+                gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual, s.depth>
                     <<<dim3((unsigned)wgs), dim3(threads), 0, st>>>(a);
             }
         } else {

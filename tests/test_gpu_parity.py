@@ -246,8 +246,14 @@ def test_config2_full_size_sampled(dist):
     gp = GpuProduct(p)
     try:
         assert (gp.get(gp.T.TCX_KEY_PATH), gp.get(gp.T.TCX_KEY_TILE_M), gp.get(gp.T.TCX_KEY_TILE_N)) == (1, 256, 128)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(torch.cuda.current_stream())
         gp.execute(dA, dB, dD, dD)
+        e1.record(torch.cuda.current_stream())
         torch.cuda.synchronize()
+        # a guard against the kernel silently losing its registers to scratch memory (it then runs
+        # forty times longer and still computes the right numbers): 1.1e13 flop at 25 % of peak
+        assert e0.elapsed_time(e1) < 600.0, "configuration 2 took %.0f ms" % e0.elapsed_time(e1)
         res = bench.parity_after_run(p, dD, 1, torch, dist)
     finally:
         gp.close()
