@@ -73,7 +73,7 @@ enum {
     TCX_ERR_D_ALIASING = 8,          /* two index tuples of D share an address (appendix test 28) */
     TCX_ERR_ISOLATED_INDEX = 9,      /* Case 4 / Case 5 label (Eq. FreeD, Note 7) */
     TCX_ERR_DTYPE_MIX = 10,          /* the four tensors do not share one dtype */
-    TCX_ERR_UNSUPPORTED_OP = 11,     /* op value unknown, or opD != identity */
+    TCX_ERR_UNSUPPORTED_OP = 11,     /* op value unknown, or opD != identity; from tcx_product_set: this plan cannot take the path, tile shape or split */
     TCX_ERR_UNSUPPORTED_PRECISION = 12,
     TCX_ERR_ALLOC = 13,              /* host or device allocation failed */
     TCX_ERR_LAUNCH = 14,             /* the HIP runtime refused a launch or copy; see the status object */

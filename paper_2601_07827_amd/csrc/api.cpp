@@ -61,7 +61,7 @@ struct Status {
 // pay off when a tile runs for milliseconds (hundreds of slabs): see the launcher.
 int64_t round_size_of(const Product& p, const GettVariant& s) {
     const int64_t nk = (p.an.sizeK + s.kt - 1) / s.kt;
-    return (s.pingpong && nk >= 256) ? p.handle.num_cu : 0;
+    return (s.pingpong && nk >= 256) ? (p.handle.num_cu > 0 ? p.handle.num_cu : 256) : 0;   // a plan-only handle assumes 256 CUs
 }
 
 std::mutex g_mu;
@@ -414,7 +414,7 @@ const char* const kMessages[] = {
     "two index tuples of tensor D address the same element",
     "a label occurs in only one of A, B, D (isolated index: reduction or broadcast is not supported)",
     "the four tensors do not share one data type",
-    "unsupported element-wise operation (opD must be the identity)",
+    "unsupported: an element-wise operation (opD must be the identity), or a path / tile shape / split that this plan cannot take",
     "unsupported computational precision",
     "memory allocation failed",
     "the HIP runtime reported an error; query TCX_KEY_HIP_ERROR on the status object",

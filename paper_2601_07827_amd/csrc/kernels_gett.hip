@@ -301,7 +301,7 @@ __device__ __forceinline__ void scatter(const typename P::acc_t (&acc)[FM][FN], 
 // DEPTH: how many slabs ahead of the MFMAs the global loads run (a ring of DEPTH register sets).
 // Large tiles spend longer on a slab than a load takes and need 1; small tiles need more bytes
 // in flight to cover the same latency.
-template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF, int DEPTH, bool NARROW>
+template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF, int DEPTH>
 __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
     using T = typename P::elem;
     using acc_t = typename P::acc_t;
@@ -327,37 +327,23 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
     const int split = wave_uniform((int)(lid % g.splitK));
     const Tile tile = locate_tile(lid / g.splitK, g, MT_M, MT_N);
     const int64_t m0 = wave_uniform(tile.m0), n0 = wave_uniform(tile.n0);
-    // ---- gather addressing, two forms.
-    // NARROW: an element's address is a wave-uniform 64-bit base plus a 32-bit per-lane byte
-    // offset (the plan's tile-relative tables), which the hardware adds itself: no 64-bit vector
-    // arithmetic in the loop and one register per offset.  This is the faster form for the
-    // small tiles, whose loops are short of issue slots.
-    // Otherwise: 64-bit element offsets from the plain tables, summed per lane.  The 256 x 128
-    // tile, whose loop is bound by the matrix pipe, measured faster this way.
-    const char* const Ab = (const char*)g.A + (NARROW ? wave_uniform(tile.hA * (int64_t)sizeof(T) + scalar_table(g.rbA)[m0 / MT_M]) : 0);
-    const char* const Bb = (const char*)g.B + (NARROW ? wave_uniform(tile.hB * (int64_t)sizeof(T) + scalar_table(g.rbB)[n0 / MT_N]) : 0);
-    const T* __restrict__ A = (const T*)g.A + tile.hA;
-    const T* __restrict__ B = (const T*)g.B + tile.hB;
-    // Row offsets are loop-invariant.  Rows past the end of M or N read a valid (padded) table
-    // entry; what they accumulate is never stored.
+    // ---- gather addressing.  An element's address is a wave-uniform 64-bit base plus a 32-bit
+    // per-lane byte offset (the plan's tile-relative tables), which the hardware adds itself: no
+    // 64-bit vector arithmetic in the loop and one register per offset.
+    const char* const Ab = (const char*)g.A + wave_uniform(tile.hA * (int64_t)sizeof(T) + scalar_table(g.rbA)[m0 / MT_M]);
+    const char* const Bb = (const char*)g.B + wave_uniform(tile.hB * (int64_t)sizeof(T) + scalar_table(g.rbB)[n0 / MT_N]);
+    // Row offsets are loop-invariant.  Rows past the end of M or N repeat a valid row of the
+    // tile; what they accumulate is never stored.
     uint32_t rrA[SA::PER], rrB[SB::PER];
-    int64_t offA[SA::PER], offB[SB::PER];
 #pragma unroll
-    for (int i = 0; i < SA::PER; ++i) {
-        if (NARROW) rrA[i] = g.rrA[m0 + SA::row(tid + i * NT)];
-        else offA[i] = g.oAM[m0 + SA::row(tid + i * NT)];
-    }
+    for (int i = 0; i < SA::PER; ++i) rrA[i] = g.rrA[m0 + SA::row(tid + i * NT)];
 #pragma unroll
-    for (int i = 0; i < SB::PER; ++i) {
-        if (NARROW) rrB[i] = g.rrB[n0 + SB::row(tid + i * NT)];
-        else offB[i] = g.oBN[n0 + SB::row(tid + i * NT)];
-    }
+    for (int i = 0; i < SB::PER; ++i) rrB[i] = g.rrB[n0 + SB::row(tid + i * NT)];
 
     // Offsets along K come from the tables one slab ahead of the data loads that use them,
     // so a data load never waits on a table load issued in the same iteration.  Where the
-    // k index is the same for a whole wave its offset is a scalar (NARROW: it goes into the
-    // base); otherwise (NARROW) the slab's base is the scalar and each lane adds its k's
-    // relative offset.
+    // k index is the same for a whole wave its offset is a scalar that goes into the base;
+    // otherwise the slab's base is the scalar and each lane adds its k's relative offset.
     const int nk = g.tilesK;
     unsigned kinA[SA::PER], kinB[SB::PER];       // this thread's k index inside a slab, per element
 #pragma unroll
@@ -370,40 +356,31 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
         kinB[i] = (unsigned)SB::kin(tid + i * NT);
         if (SB::UNIFORM_K) kinB[i] = __builtin_amdgcn_readfirstlane(kinB[i]);
     }
-    int64_t kqA[SA::PER], kqB[SB::PER];          // NARROW, uniform-k operands: scalar byte offset per element
-    uint32_t krA[SA::PER], krB[SB::PER];         // NARROW, others: per-lane offset relative to the slab's base
+    int64_t kqA[SA::PER], kqB[SB::PER];          // uniform-k operands: scalar byte offset per element
+    uint32_t krA[SA::PER], krB[SB::PER];         // others: per-lane offset relative to the slab's base
     int64_t kbA = 0, kbB = 0;
-    int64_t kA[SA::PER], kB[SB::PER];            // wide form: element offsets
     auto k_offsets = [&](int kt) {
-        const int64_t at = (int64_t)min(kt, nk - 1) * KT;
-        if (NARROW) {
-            const const_table<int64_t> qa = scalar_table(g.kqA + at), qb = scalar_table(g.kqB + at);
-            const const_table<int64_t> ba = scalar_table(g.kbA), bb = scalar_table(g.kbB);
-            const uint32_t* __restrict__ ta = g.krA + at;
-            const uint32_t* __restrict__ tb = g.krB + at;
-            if (SA::UNIFORM_K) {
+        const int kc = min(kt, nk - 1);
+        const int64_t at = (int64_t)kc * KT;
+        if (SA::UNIFORM_K) {
+            const const_table<int64_t> q = scalar_table(g.kqA + at);
 #pragma unroll
-                for (int i = 0; i < SA::PER; ++i) kqA[i] = qa[kinA[i]];
-            } else {
-                kbA = ba[min(kt, nk - 1)];
-#pragma unroll
-                for (int i = 0; i < SA::PER; ++i) krA[i] = ta[kinA[i]];
-            }
-            if (SB::UNIFORM_K) {
-#pragma unroll
-                for (int i = 0; i < SB::PER; ++i) kqB[i] = qb[kinB[i]];
-            } else {
-                kbB = bb[min(kt, nk - 1)];
-#pragma unroll
-                for (int i = 0; i < SB::PER; ++i) krB[i] = tb[kinB[i]];
-            }
+            for (int i = 0; i < SA::PER; ++i) kqA[i] = q[kinA[i]];
         } else {
-            const int64_t* __restrict__ ta = g.oAK + at;
-            const int64_t* __restrict__ tb = g.oBK + at;
+            const uint32_t* __restrict__ t = g.krA + at;
+            kbA = scalar_table(g.kbA)[kc];
 #pragma unroll
-            for (int i = 0; i < SA::PER; ++i) kA[i] = ta[kinA[i]];
+            for (int i = 0; i < SA::PER; ++i) krA[i] = t[kinA[i]];
+        }
+        if (SB::UNIFORM_K) {
+            const const_table<int64_t> q = scalar_table(g.kqB + at);
 #pragma unroll
-            for (int i = 0; i < SB::PER; ++i) kB[i] = tb[kinB[i]];
+            for (int i = 0; i < SB::PER; ++i) kqB[i] = q[kinB[i]];
+        } else {
+            const uint32_t* __restrict__ t = g.krB + at;
+            kbB = scalar_table(g.kbB)[kc];
+#pragma unroll
+            for (int i = 0; i < SB::PER; ++i) krB[i] = t[kinB[i]];
         }
     };
 
@@ -415,9 +392,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
     auto gather = [&](int slot) {
 #pragma unroll
         for (int i = 0; i < SA::PER; ++i) {
-            if (!NARROW) {
-                ra[slot][i] = P::load(A, offA[i] + kA[i], conjA);
-            } else if (SA::UNIFORM_K) {
+            if (SA::UNIFORM_K) {
                 // the empty statement keeps the compiler from folding the loop-invariant row
                 // offset into a 64-bit per-lane pointer (which would undo the scalar base)
                 asm("" : "+v"(rrA[i]));
@@ -428,9 +403,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
         }
 #pragma unroll
         for (int i = 0; i < SB::PER; ++i) {
-            if (!NARROW) {
-                rb[slot][i] = P::load(B, offB[i] + kB[i], conjB);
-            } else if (SB::UNIFORM_K) {
+            if (SB::UNIFORM_K) {
                 asm("" : "+v"(rrB[i]));
                 rb[slot][i] = P::load_at(Bb + kqB[i], rrB[i], conjB);
             } else {
@@ -1089,7 +1062,7 @@ hipError_t launch_one(const GettArgs& a, int64_t blocks, hipStream_t st) {
             return hipErrorInvalidValue;      // this orientation is not built for the shape: the plan must not choose it
         }
     } else {
-        gett_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.depth, s.narrow>
+        gett_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.depth>
             <<<dim3((unsigned)blocks), dim3(s.wgm * s.wgn * 64), 0, st>>>(a);
     }
     hipError_t err = hipGetLastError();

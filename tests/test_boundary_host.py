@@ -232,7 +232,8 @@ def _plan(handle, p):
         T.tcx_destroy_tensor_info(i)
     out = {k: T.tcx_product_get(prod, getattr(T, "TCX_KEY_" + k)) for k in
            ("PATH", "SIZE_H", "SIZE_M", "SIZE_N", "SIZE_K", "MODES_H", "MODES_M", "MODES_N", "MODES_K",
-            "A_K_FASTEST", "B_K_FASTEST", "D_N_FASTEST", "TILE_M", "TILE_N", "TILE_K", "GRID")}
+            "A_K_FASTEST", "B_K_FASTEST", "D_N_FASTEST", "TILE_M", "TILE_N", "TILE_K", "GRID", "BLOCK", "VARIANT",
+            "SPLIT_K", "LAUNCHES")}
     T.tcx_destroy_product(prod)
     return out
 
@@ -313,3 +314,39 @@ def test_analyser_drops_extent_one_and_merges_repeated_labels(handle):
     T.tcx_destroy_product(prod)
     for i in infos:
         T.tcx_destroy_tensor_info(i)
+
+
+def test_planner_routes_each_configuration(handle):
+    """Which kernel form the plan takes (a plan-only handle assumes 256 CUs).  The two-phase kernel
+    needs |K| in whole slabs and, for an operand whose lanes run along k, the same relative k
+    offsets in every slab; plans that fail this fall back to the classic staged kernel."""
+    c2 = _plan(handle, W.config2())
+    # one 256x128 tile per workgroup, eight waves, 4608 workgroups enqueued in 18 rounds of 256
+    assert (c2["VARIANT"], c2["BLOCK"], c2["GRID"], c2["SPLIT_K"], c2["LAUNCHES"]) == (0, 512, 4608, 1, 18)
+    c5 = _plan(handle, W.config5())
+    # 256 tiles of 64x64, K in two halves = 512 items, two per workgroup, summed inside it: one launch
+    assert (c5["TILE_M"], c5["TILE_N"], c5["BLOCK"], c5["GRID"], c5["SPLIT_K"], c5["LAUNCHES"]) == (64, 64, 512, 256, 2, 1)
+    c4 = _plan(handle, W.config4())
+    # 512 batches, one 96x96 complex tile each, two per workgroup
+    assert (c4["TILE_M"], c4["TILE_N"], c4["TILE_K"], c4["BLOCK"], c4["GRID"], c4["LAUNCHES"]) == (96, 96, 8, 512, 256, 1)
+    c1 = _plan(handle, W.config1())
+    # B's lanes run along k = (c, d) with extent 24: slabs of 16 do not repeat -> classic kernel, split K + reduction
+    assert c1["BLOCK"] == 256 and c1["SPLIT_K"] > 1 and c1["LAUNCHES"] == 2
+    c3 = _plan(handle, W.config3())
+    assert c3["BLOCK"] == 256 and c3["SIZE_K"] % c3["TILE_K"] != 0          # ragged K: never the two-phase kernel
+
+
+def test_forcing_a_shape_the_plan_cannot_take_is_refused(handle):
+    p = W.config1()
+    ids = W.label_ids(p)
+    infos = [T.tcx_create_tensor_info(handle, 1, t.extents, t.strides) for t in (p.A, p.B, p.D)]
+    labs = [[ids[l] for l in t.labels] for t in (p.A, p.B, p.D)]
+    prod = T.tcx_create_product(handle, 0, infos[0], labs[0], 0, infos[1], labs[1], 0, infos[2], labs[2], 0, infos[2], labs[2])
+    before = T.tcx_product_get(prod, T.TCX_KEY_VARIANT)
+    with pytest.raises(T.TcxError) as e:
+        T.tcx_product_set(prod, T.TCX_KEY_VARIANT, 0)            # two-phase 256x128: needs slab-periodic k offsets
+    assert e.value.code == T.TCX_ERR_UNSUPPORTED_OP
+    assert T.tcx_product_get(prod, T.TCX_KEY_VARIANT) == before   # the plan is unchanged
+    T.tcx_product_set(prod, T.TCX_KEY_VARIANT, 2)                # a classic shape is fine
+    assert T.tcx_product_get(prod, T.TCX_KEY_VARIANT) == 2 and T.tcx_product_get(prod, T.TCX_KEY_SPLIT_K) == 1
+    T.tcx_destroy_product(prod)
