@@ -156,6 +156,70 @@ bool build(const std::vector<DMode>& dm, const std::vector<Piece>& pieces, bool 
     p.itemsA = items(true, rowsA, kA);
     p.itemsB = items(false, rowsB, kB);
 
+    // LDS bank conflicts of a flat tile.  Rows are numbered in D's lane order, so the lanes read
+    // consecutive rows; the staging writes go in the operand's own address order, which for a
+    // permuted operand is a large power-of-two stride in row numbers: every lane of a quarter
+    // wave would hit the same bank.  Rows are therefore spread out, r -> r + (r >> s1) * p1 +
+    // (r >> s2) * p2, with the pair of skews that a simulation of both access patterns (16
+    // lanes per cycle, 32 banks of 4 bytes) finds cheapest; LDS grows by at most a quarter.
+    if (!blocked) {
+        const int words = std::max(1, elem_bytes / 4);
+        auto cost_of = [&](const std::vector<uint32_t>& rows_in_issue_order) {
+            // rows_in_issue_order: the row each consecutive lane touches, instruction after instruction
+            int64_t cycles = 0;
+            int hits[32];
+            for (size_t at = 0; at < rows_in_issue_order.size(); at += 16) {
+                for (int b = 0; b < 32; ++b) hits[b] = 0;
+                int worst = 0;
+                for (size_t l = at; l < std::min(at + 16, rows_in_issue_order.size()); ++l) {
+                    const int b = (int)(((int64_t)rows_in_issue_order[l] * K * words) % 32);
+                    worst = std::max(worst, ++hits[b]);
+                }
+                cycles += worst;
+            }
+            return cycles;
+        };
+        auto spread = [&](std::vector<StreamItem>& its, bool forA, int64_t* rows) {
+            std::vector<uint32_t> readers((size_t)lanes), writers(its.size());
+            auto remap = [](uint32_t r, int s1, int p1, int s2, int p2) {
+                return r + (s1 >= 0 ? (r >> s1) * (uint32_t)p1 : 0u) + (s2 >= 0 ? (r >> s2) * (uint32_t)p2 : 0u);
+            };
+            int best[4] = {-1, 0, -1, 0};
+            int64_t best_cost = -1;
+            static const int kShift[] = {-1, 2, 3, 4, 5, 6, 7, 8};
+            for (int s1 : kShift)
+                for (int s2 : kShift) {
+                    if (s2 >= 0 && s2 <= s1) continue;
+                    for (int p1 = (s1 >= 0 ? 1 : 0); p1 <= (s1 >= 0 ? 2 : 0); ++p1)
+                        for (int p2 = (s2 >= 0 ? 1 : 0); p2 <= (s2 >= 0 ? 2 : 0); ++p2) {
+                            const uint32_t top = remap((uint32_t)*rows - 1, s1, p1, s2, p2) + 1;
+                            if (top > 65535 || (int64_t)top * 4 > *rows * 5) continue;
+                            for (int64_t l = 0; l < lanes; ++l) {
+                                const uint32_t r = forA ? (p.rowAB[(size_t)l] & 0xffffu) : (p.rowAB[(size_t)l] >> 16);
+                                readers[(size_t)l] = remap(r, s1, p1, s2, p2);
+                            }
+                            for (size_t i = 0; i < its.size(); ++i) writers[i] = remap(its[i].slot / (uint32_t)K, s1, p1, s2, p2);
+                            const int64_t c = cost_of(readers) + cost_of(writers);
+                            if (best_cost < 0 || c < best_cost) { best_cost = c; best[0] = s1; best[1] = p1; best[2] = s2; best[3] = p2; }
+                        }
+                }
+            if (best[0] < 0 && best[2] < 0) return;
+            for (StreamItem& it : its) it.slot = remap(it.slot / (uint32_t)K, best[0], best[1], best[2], best[3]) * (uint32_t)K + it.slot % (uint32_t)K;
+            for (int64_t l = 0; l < lanes; ++l) {
+                uint32_t& w = p.rowAB[(size_t)l];
+                const uint32_t a = w & 0xffffu, b = w >> 16;
+                w = forA ? (remap(a, best[0], best[1], best[2], best[3]) | (b << 16)) : (a | (remap(b, best[0], best[1], best[2], best[3]) << 16));
+            }
+            *rows = remap((uint32_t)*rows - 1, best[0], best[1], best[2], best[3]) + 1;
+        };
+        int64_t padA = rowsA, padB = rowsB;
+        spread(p.itemsA, true, &padA);
+        spread(p.itemsB, false, &padB);
+        p.rowsA = (int32_t)padA; p.rowsB = (int32_t)padB;
+        p.lds_bytes = (size_t)(padA + padB) * (size_t)K * (size_t)elem_bytes;
+        if (p.lds_bytes > 64 * 1024) return false;
+    }
+
     // outer modes: what the pieces leave of every D mode, the ragged mode first (its chunk index
     // decides how much of the last tile is valid)
     std::vector<int64_t> taken(dm.size(), 1);
@@ -296,12 +360,21 @@ StreamPlan plan_stream(const Analysis& an, int elem_bytes, bool allow_blocked) {
             int64_t share = 1;
             while ((share * 2) * (share * 2) * (fast.size() > 2 ? share * 2 : 1) <= target) share *= 2;
             share = std::max(share, std::min<int64_t>(run, target));
-            for (int f : fast) {
+            // Sizes are handed out to the operands' runs first and to D's run last: a read
+            // that covers half a 128-byte line still fetches the whole line, whereas 64-byte
+            // stores cost nothing extra.  The pieces keep D's run first (consecutive lanes write
+            // consecutive elements).
+            std::vector<int64_t> size(fast.size(), 1);
+            for (size_t q = 0; q < fast.size(); ++q) {
+                const size_t at = (q + 1) % fast.size();          // order: the operands' runs, then D's run (index 0)
+                const int f = fast[at];
                 const int64_t c = largest_divisor_at_most(left[(size_t)f], std::min<int64_t>(share, target / lanes));
                 if (c <= 1) continue;
-                pieces.push_back({f, c, 1, LANE});
+                size[at] = c;
                 lanes *= c; left[(size_t)f] /= c;
             }
+            for (size_t q = 0; q < fast.size(); ++q)
+                if (size[q] > 1) pieces.push_back({fast[q], size[q], 1, LANE});
         }
         for (size_t i = 0; i < dm.size() && lanes < target; ++i) {
             if (left[i] <= 1) continue;
