@@ -38,10 +38,10 @@ MEASURED_TRAFFIC_BYTES = {
 DT = {"f32": 0, "f64": 1, "c128": 3}
 
 
-def _gemm(m, n, k) -> W.Problem:
+def _gemm(m, n, k, dtype="f64") -> W.Problem:
     """Plain column-major matrix product (calibration shape)."""
     e = dict(m=m, n=n, k=k)
-    return W.Problem("gemm_%dx%dx%d" % (m, n, k), "f64", W.tensor("mk", e), W.tensor("kn", e), W.tensor("mn", e),
+    return W.Problem("gemm_%s_%dx%dx%d" % (dtype, m, n, k), dtype, W.tensor("mk", e), W.tensor("kn", e), W.tensor("mn", e),
                      alpha=1.0, beta=0.0, seed=W.BASE_SEED + 20)
 
 
@@ -50,6 +50,8 @@ def make_problem(name: str) -> W.Problem:
              "cfg3r2": lambda: W.config3(d_layout="R2"), "cfg4hs": lambda: W.config4(h_slowest=True),
              "gemm1k": lambda: W.config2(v=32, o=32),      # contiguous 1024^3 product, same size as cfg5
              "gemmk16": lambda: _gemm(1024, 1024, 16), "gemmk256": lambda: _gemm(1024, 1024, 256),
+             # large plain products in both real dtypes (fp32 has no large configuration of its own)
+             "gemm8k": lambda: _gemm(8192, 8192, 16384), "gemm8kf": lambda: _gemm(8192, 8192, 16384, "f32"),
              # supplementary HBM-bound shapes
              "s1": lambda: W.config5(extent=4, nshared=1, nfree=7), "s2": lambda: W.config5(extent=4, nshared=0, nfree=7),
              "s3": lambda: W.hadamard(4, 128), "s3p": lambda: W.hadamard(4, 128, permuted=True),
