@@ -12,6 +12,15 @@
 // ([k][m] or [m][k]); only the MFMA fragment read differs.  Accumulation is register
 // blocked over 16x16x4 MFMA tiles; the alpha/beta epilogue scatters to strided D with lanes
 // along D's fastest group (the MFMA operand roles are swapped to make that so).
+//
+// Three kernels share the pieces above:
+//   gett_pingpong_kernel  two wave groups alternate a memory phase and a compute phase, the
+//                         memory phase free of vector-ALU instructions (the fast one; needs |K|
+//                         in whole slabs and slab-periodic k offsets);
+//   gett_kernel           one barrier per slab in the middle of its MFMAs, register ring of
+//                         global loads (every plan the first cannot take);
+//   gett_direct_kernel    no LDS, no barrier (few short tiles);
+// plus gett_reduce_kernel, which sums split-K parts in a fixed order.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>

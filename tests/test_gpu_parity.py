@@ -16,7 +16,7 @@ GENERIC, GETT, STREAM = 0, 1, 2
 
 
 TWO_PHASE = {False: (0, 10, 11), True: (7,)}      # tile shapes served by the two-phase kernel (real, complex)
-TWO_PHASE_SLAB = {0: 16, 10: 16, 11: 16, 12: 32}     # contracted indices per slab of the real shapes
+TWO_PHASE_SLAB = {0: 16, 10: 16, 11: 16}             # contracted indices per slab of the real shapes
 
 
 def _paths_for(p):
