@@ -165,6 +165,36 @@ def test_two_phase_kernel(dtype):
             assert np.array_equal(W.strided_view(got, p.D), W.strided_view(truth, p.D))
 
 
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+def test_two_phase_kernel_batches_and_negative_strides(dtype):
+    """Real batched products (a hyper label, slowest or fastest in memory) and operands stored
+    backwards along k, along the rows, or both, on every two-phase shape; padded leading dimensions."""
+    from gpu_helpers import run_gpu, say
+    cases = []
+    e = {"h": 5, "m": 150, "n": 100, "k": 64}
+    # batch slowest / batch fastest
+    cases.append(("batch_slowest", W.tensor("hmk", e, memory_order="mkh"), W.tensor("hkn", e, memory_order="knh"),
+                  W.tensor("hmn", e, memory_order="mnh")))
+    cases.append(("batch_fastest", W.tensor("hmk", e, memory_order="hkm"), W.tensor("hkn", e, memory_order="hkn"),
+                  W.tensor("hmn", e, memory_order="hmn")))
+    # reversed storage: negative strides along k (A), along n (B), along m (D); padded leading dimension in A
+    e2 = {"m": 200, "n": 136, "k": 96}
+    cases.append(("reversed", W.tensor("mk", e2, strides={"m": 1, "k": -210}), W.tensor("kn", e2, strides={"k": 1, "n": -96}),
+                  W.tensor("mn", e2, strides={"m": -1, "n": 200})))
+    cases.append(("reversed_k_fast", W.tensor("mk", e2, strides={"m": 100, "k": -1}), W.tensor("kn", e2, strides={"k": -1, "n": 97}),
+                  W.tensor("mn", e2, strides={"m": 136, "n": -1})))
+    for name, A, B, D in cases:
+        p = W.Problem("two_phase_%s_%s" % (name, dtype), dtype, A, B, D, alpha=-0.75, beta=1.5, seed=W.BASE_SEED + 22)
+        a, b, c = W.make_operands(p)
+        truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+        for variant in TWO_PHASE[False]:
+            for parts in (None, 2, 3):
+                say("%s shape %d parts %s" % (p.name, variant, parts))
+                got = run_gpu(p, a, b, c, force_path=GETT, variant=variant, split_k=parts)
+                assert gaps_untouched(p, c, got)
+                assert normalised_error(p, got, truth, S, c) <= TOLERANCE[p.dtype]
+
+
 @pytest.mark.parametrize("h_slowest", [False, True])
 def test_two_phase_kernel_complex(h_slowest):
     """The two-phase kernel with one 96 x 96 complex tile per wave group: batched conj(A)^T B with
