@@ -234,7 +234,7 @@ int elem_bytes(int dtype) { return dtype == TCX_F32 ? 4 : dtype == TCX_F64 ? 8 :
 struct NarrowOperand {
     std::vector<uint32_t> rowrel, krel;
     std::vector<int64_t> rowbase, kofs, kbase;
-    bool periodic = true;      // every slab has the relative k offsets of the first (and |K| is whole slabs)
+    bool periodic = true;      // every whole slab has the relative k offsets of the first
 };
 
 bool narrow_operand(const std::vector<int64_t>& rows, int64_t nrows, int mt, const std::vector<int64_t>& ks, int64_t nk,
@@ -272,8 +272,8 @@ bool narrow_operand(const std::vector<int64_t>& rows, int64_t nrows, int mt, con
             max_k = std::max(max_k, rel);
         }
     }
-    out->periodic = nk % kt == 0;
-    for (int64_t k = kt; k < slabs * kt && out->periodic; ++k)
+    out->periodic = true;
+    for (int64_t k = kt; k < nk / kt * kt && out->periodic; ++k)        // whole slabs only
         if (out->krel[(size_t)k] != out->krel[(size_t)(k % kt)]) out->periodic = false;
     return max_row + max_k <= 0xffffffffull;                     // the kernel adds the two in 32 bits
 }
@@ -289,13 +289,11 @@ tcx_error_t build_narrow(Product* p, int variant) {
         if (!narrow_operand(p->tables[0], p->an.sizeM, s.mt_m, p->tables[1], p->an.sizeK, s.kt, es, &a) ||
             !narrow_operand(p->tables[2], p->an.sizeN, s.mt_n, p->tables[3], p->an.sizeK, s.kt, es, &b))
             return TCX_ERR_UNSUPPORTED_OP;
-        // the two-phase kernel has no masked slab, and precomputes the per-lane k offsets of
-        // an operand whose lanes run along k
+        // the two-phase kernel precomputes the per-lane k offsets of an operand whose lanes run along k
         auto operand_ok = [&](bool k_fastest, bool periodic, int mt) {
             return k_fastest ? periodic : (mt % 64 == 0 && s.threads % mt == 0);
         };
-        if (s.pingpong && (p->an.sizeK % s.kt != 0 || !operand_ok(p->an.a_k_fastest, a.periodic, s.mt_m) ||
-                           !operand_ok(p->an.b_k_fastest, b.periodic, s.mt_n)))
+        if (s.pingpong && (!operand_ok(p->an.a_k_fastest, a.periodic, s.mt_m) || !operand_ok(p->an.b_k_fastest, b.periodic, s.mt_n)))
             return TCX_ERR_UNSUPPORTED_OP;
         p->periodic[0] = a.periodic;
         p->periodic[1] = b.periodic;

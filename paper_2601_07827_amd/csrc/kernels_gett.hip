@@ -557,8 +557,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
 //    offsets, LDS write and read addresses for each of the three LDS slabs) is computed once
 //    before the loop; what changes per slab is scalar (base pointers from the plan's tables);
 //    the loop is unrolled by three so that the LDS slab in use is a compile-time constant.
-// Preconditions, checked by the host: |K| is a multiple of KT (no masking in the loop), and an
-// operand whose lanes run along k has the same relative k offsets in every slab.
+// Preconditions, checked by the host: an operand whose lanes run along k has the same relative k
+// offsets in every whole slab, and an operand whose lanes run along the rows has a tile extent
+// that is a multiple of 64.
 // A slab's global loads have a whole iteration to arrive.  Three LDS slabs: slab i+1 is written
 // in phase 2i by the first group and in phase 2i+1 by the second; the buffer it goes to held slab
 // i-2, last read in phase 2i-2; it is first read in phase 2i+2.
@@ -606,7 +607,12 @@ template <int I, int N, class F> __device__ __forceinline__ void static_for(F&& 
 
 // DEPTH: slabs of global loads in flight in registers.  The large tile spends 3.6 us on a slab and
 // needs one; an iteration of the small tiles is shorter than a load takes.
-template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF, bool DUAL, int DEPTH>
+// RAGGED: |K| is not a multiple of KT.  A separate instantiation, so that the steady state of
+// the common case carries none of it: the last slab's lanes along k take their offsets from the
+// table (padded entries address a valid element) instead of the slab-periodic ones, and what the
+// padded entries load is zeroed before it goes to LDS -- vector-ALU work in a memory phase, once
+// per tile.
+template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF, bool DUAL, int DEPTH, bool RAGGED>
 __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_kernel(GettArgs g) {
     using T = typename P::elem;
     using acc_t = typename P::acc_t;
@@ -720,8 +726,28 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
     };
     // conjugation is applied to the MFMA fragments in the compute phase (a vector-ALU operation)
     T ra[DEPTH][SA::PER], rb[DEPTH][SB::PER];     // slab kb+j waits in ring slot j % DEPTH
-    auto gather = [&](auto SLOT) __attribute__((always_inline)) {
+    const unsigned kleft = (unsigned)(g.sizeK - (int64_t)(nk - 1) * KT);          // valid indices of the last slab
+    auto gather = [&](auto SLOT, int slab) __attribute__((always_inline)) {
         constexpr int sl = decltype(SLOT)::value;
+        if constexpr (RAGGED) {
+            if (slab >= nk - 1) {
+                // the ragged slab (or a clamped slab past the end): offsets of lanes along k from the table
+#pragma unroll
+                for (int i = 0; i < SA::PER; ++i) {
+                    uint32_t vo = voA[i];
+                    if (AKF) vo += g.krA[(int64_t)(nk - 1) * KT + SA::kin(tid + i * NTG)] - g.krA[SA::kin(tid + i * NTG)];
+                    ra[sl][i] = P::load_at(Ab + (AKF ? kbA : kqA[i]), vo, 0u);
+                }
+#pragma unroll
+                for (int i = 0; i < SB::PER; ++i) {
+                    uint32_t vo = voB[i];
+                    if (BKF) vo += g.krB[(int64_t)(nk - 1) * KT + SB::kin(tid + i * NTG)] - g.krB[SB::kin(tid + i * NTG)];
+                    rb[sl][i] = P::load_at(Bb + (BKF ? kbB : kqB[i]), vo, 0u);
+                }
+                return;
+            }
+        }
+        // steady state: no vector-ALU instruction
 #pragma unroll
         for (int i = 0; i < SA::PER; ++i) {
             asm("" : "+v"(voA[i]));              // keeps "scalar base + 32-bit lane offset" from being folded into a 64-bit lane address
@@ -733,8 +759,18 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
             rb[sl][i] = P::load_at(Bb + (BKF ? kbB : kqB[i]), voB[i], 0u);
         }
     };
-    auto stage = [&](auto BUF, auto SLOT) __attribute__((always_inline)) {
+    auto stage = [&](auto BUF, auto SLOT, int slab) __attribute__((always_inline)) {
         constexpr int b = decltype(BUF)::value, sl = decltype(SLOT)::value;
+        if constexpr (RAGGED) {
+            if (slab == nk - 1) {
+#pragma unroll
+                for (int i = 0; i < SA::PER; ++i)
+                    if ((unsigned)SA::kin(tid + i * NTG) >= kleft) ra[sl][i] = P::zero();
+#pragma unroll
+                for (int i = 0; i < SB::PER; ++i)
+                    if ((unsigned)SB::kin(tid + i * NTG) >= kleft) rb[sl][i] = P::zero();
+            }
+        }
 #pragma unroll
         for (int i = 0; i < SA::PER; ++i) lds_store<T>(wA[b] + i * dWA, ra[sl][i]);
 #pragma unroll
@@ -769,11 +805,11 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
     // are clamped: harmless loads that are never staged).
     if (n > 0) {
         k_offsets(kb);
-        gather(std::integral_constant<int, 0>{});
+        gather(std::integral_constant<int, 0>{}, kb);
         k_offsets(kb + 1);
-        stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, kb);
         static_for<0, DEPTH>([&](auto D) __attribute__((always_inline)) {
-            gather(std::integral_constant<int, (1 + decltype(D)::value) % DEPTH>{});      // slab kb+1+D
+            gather(std::integral_constant<int, (1 + decltype(D)::value) % DEPTH>{}, kb + 1 + decltype(D)::value);
             k_offsets(kb + 2 + decltype(D)::value);
         });
     }
@@ -797,8 +833,8 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
         using NEXT_SLOT = std::integral_constant<int, (decltype(IDX)::value + 1) % DEPTH>;
         // memory phase: no vector-ALU instruction in here
         if (i + 1 < n) {
-            stage(NEXT_BUF{}, NEXT_SLOT{});               // slab kb+i+1
-            gather(NEXT_SLOT{});                          // slab kb+i+1+DEPTH
+            stage(NEXT_BUF{}, NEXT_SLOT{}, kb + i + 1);
+            gather(NEXT_SLOT{}, kb + i + 1 + DEPTH);
             k_offsets(kb + i + 2 + DEPTH);
         }
         if (i < n) frag_load(BUF{}, 0, 0);
@@ -1049,9 +1085,18 @@ hipError_t launch_one(const GettArgs& a, int64_t blocks, hipStream_t st) {
     } else if constexpr (s.pingpong) {
         constexpr int NTG = s.wgm * s.wgn * 64;
         if constexpr (pingpong_operand_ok<s.mt_m, NTG, AKF>() && pingpong_operand_ok<s.mt_n, NTG, BKF>()) {
-            if (a.sizeK % s.kt != 0 || (AKF && !a.periodicA) || (BKF && !a.periodicB)) return hipErrorInvalidValue;
+            if ((AKF && !a.periodicA) || (BKF && !a.periodicB)) return hipErrorInvalidValue;
             constexpr int threads = NTG * (s.dual ? 2 : 1);
             const int64_t wgs = s.dual ? (blocks + 1) / 2 : blocks;
+            const bool ragged = a.sizeK % s.kt != 0;
+            auto launch = [&](const GettArgs& r, int64_t count) {
+                if (ragged)
+                    gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual, s.depth, true>
+                        <<<dim3((unsigned)count), dim3(threads), 0, st>>>(r);
+                else
+                    gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual, s.depth, false>
+                        <<<dim3((unsigned)count), dim3(threads), 0, st>>>(r);
+            };
             // Long tiles are launched round by round (one workgroup per CU each): workgroups of a
             // round that share operand panels through an XCD's L2 start together, whereas in one big
             // launch the 0.5 - 1 % differences in tile duration between CUs add up from round to
@@ -1060,12 +1105,10 @@ hipError_t launch_one(const GettArgs& a, int64_t blocks, hipStream_t st) {
                 GettArgs r = a;
                 for (int64_t at = 0; at < wgs; at += a.round_size) {
                     r.lid_base = at;
-                    gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual, s.depth>
-                        <<<dim3((unsigned)std::min<int64_t>(a.round_size, wgs - at)), dim3(threads), 0, st>>>(r);
+                    launch(r, std::min<int64_t>(a.round_size, wgs - at));
                 }
             } else {
-                gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual, s.depth>
-                    <<<dim3((unsigned)wgs), dim3(threads), 0, st>>>(a);
+                launch(a, wgs);
             }
         } else {
             return hipErrorInvalidValue;      // this orientation is not built for the shape: the plan must not choose it

@@ -318,8 +318,8 @@ def test_analyser_drops_extent_one_and_merges_repeated_labels(handle):
 
 def test_planner_routes_each_configuration(handle):
     """Which kernel form the plan takes (a plan-only handle assumes 256 CUs).  The two-phase kernel
-    needs |K| in whole slabs and, for an operand whose lanes run along k, the same relative k
-    offsets in every slab; plans that fail this fall back to the classic staged kernel."""
+    needs, for an operand whose lanes run along k, the same relative k offsets in every whole slab;
+    plans that fail this fall back to the classic staged kernel."""
     c2 = _plan(handle, W.config2())
     # one 256x128 tile per workgroup, eight waves, 4608 workgroups enqueued in 18 rounds of 256
     assert (c2["VARIANT"], c2["BLOCK"], c2["GRID"], c2["SPLIT_K"], c2["LAUNCHES"]) == (0, 512, 4608, 1, 18)
@@ -333,7 +333,7 @@ def test_planner_routes_each_configuration(handle):
     # B's lanes run along k = (c, d) with extent 24: slabs of 16 do not repeat -> classic kernel, split K + reduction
     assert c1["BLOCK"] == 256 and c1["SPLIT_K"] > 1 and c1["LAUNCHES"] == 2
     c3 = _plan(handle, W.config3())
-    assert c3["BLOCK"] == 256 and c3["SIZE_K"] % c3["TILE_K"] != 0          # ragged K: never the two-phase kernel
+    assert c3["BLOCK"] == 256                                               # K = (e41, d29): slabs of 16 do not repeat
 
 
 def test_forcing_a_shape_the_plan_cannot_take_is_refused(handle):

@@ -16,7 +16,6 @@ GENERIC, GETT, STREAM = 0, 1, 2
 
 
 TWO_PHASE = {False: (0, 10, 11), True: (7,)}      # tile shapes served by the two-phase kernel (real, complex)
-TWO_PHASE_SLAB = {0: 16, 10: 16, 11: 16}             # contracted indices per slab of the real shapes
 
 
 def _paths_for(p):
@@ -140,13 +139,11 @@ def test_two_phase_kernel(dtype):
     from gpu_helpers import run_gpu, say
     for flags in range(8):
         akf, bkf, dnf = bool(flags & 4), bool(flags & 2), bool(flags & 1)
-        for k in (16, 32, 48, 64, 80, 96, 160, 176):
+        for k in (16, 32, 48, 64, 80, 96, 160, 176, 5, 23, 40, 100, 171):     # whole slabs, and ragged last slabs
             p = _matrix_product(300, 200, k, akf, bkf, dnf, dtype)
             a, b, c = W.make_operands(p)
             truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
             for variant in TWO_PHASE[False]:
-                if k % TWO_PHASE_SLAB[variant]:
-                    continue                                  # needs |K| in whole slabs
                 say("%s two-phase shape %d" % (p.name, variant))
                 got = run_gpu(p, a, b, c, force_path=GETT, variant=variant)      # must not be declined: raises otherwise
                 assert normalised_error(p, got, truth, S, c) <= TOLERANCE[p.dtype]
@@ -198,10 +195,10 @@ def test_two_phase_kernel_batches_and_negative_strides(dtype):
 @pytest.mark.parametrize("h_slowest", [False, True])
 def test_two_phase_kernel_complex(h_slowest):
     """The two-phase kernel with one 96 x 96 complex tile per wave group: batched conj(A)^T B with
-    an odd number of batches (the last workgroup's second group has no tile), ragged tiles, |K| in
-    whole slabs; also with K split (items of different length in one workgroup) and integer inputs."""
+    an odd number of batches (the last workgroup's second group has no tile), ragged tiles, whole and
+    ragged slabs of K; also with K split (items of different length in one workgroup) and integer inputs."""
     from gpu_helpers import run_gpu, say
-    for h, n, k in ((7, 40, 40), (5, 100, 24), (3, 96, 96)):
+    for h, n, k in ((7, 40, 40), (5, 100, 24), (3, 96, 96), (4, 50, 21), (2, 96, 3)):
         p = W.config4(h=h, n=n, h_slowest=h_slowest, k=k)
         for dist, exact in (("uniform", False), ("ints", True)):
             a, b, c = W.make_operands(p, dist)
