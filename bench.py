@@ -247,6 +247,7 @@ def main():
            "tile": [T.tcx_product_get(prod, k) for k in (T.TCX_KEY_TILE_M, T.TCX_KEY_TILE_N, T.TCX_KEY_TILE_K)],
            "split_k": T.tcx_product_get(prod, T.TCX_KEY_SPLIT_K),
            "grid": T.tcx_product_get(prod, T.TCX_KEY_GRID), "launches_per_step": T.tcx_product_get(prod, T.TCX_KEY_LAUNCHES),
+           "gather_width": T.tcx_product_get(prod, T.TCX_KEY_GATHER_WIDTH),
            "plan_ms": plan_ms,
            "flop_per_step": flops, "algorithmic_bytes_per_step": p.algorithmic_bytes()}
 

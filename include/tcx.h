@@ -152,7 +152,8 @@ enum {
     TCX_KEY_MODES_H = 23,
     TCX_KEY_FORCE_PATH = 24,   /* tcx_product_set only: force a tcx_path_t (testing, tuning) */
     TCX_KEY_SPLIT_K = 25,      /* tiled path: number of parts the contracted range is cut into (1 = unsplit) */
-    TCX_KEY_LAUNCHES = 26      /* read-only: kernel launches one execution enqueues (rounds of a long-tile product; +1 for the split-K reduction) */
+    TCX_KEY_LAUNCHES = 26,     /* read-only: kernel launches one execution enqueues (rounds of a long-tile product; +1 for the split-K reduction) */
+    TCX_KEY_GATHER_WIDTH = 27  /* read-only: elements one gather load of the tiled kernel brings (2: neighbouring pairs of 8-byte elements; a status reports what the execution used, which also depends on the operand pointers being 16-byte aligned) */
 };
 typedef enum {
     TCX_PATH_GENERIC = 0,      /* one thread per element of D, loops over the contracted index space */

@@ -39,7 +39,8 @@ TCX_PATH_GENERIC, TCX_PATH_GETT_MFMA, TCX_PATH_BANDWIDTH = 0, 1, 2
 (TCX_KEY_PATH, TCX_KEY_SIZE_H, TCX_KEY_SIZE_M, TCX_KEY_SIZE_N, TCX_KEY_SIZE_K, TCX_KEY_NMODES_H, TCX_KEY_NMODES_M,
  TCX_KEY_NMODES_N, TCX_KEY_NMODES_K, TCX_KEY_TILE_M, TCX_KEY_TILE_N, TCX_KEY_TILE_K, TCX_KEY_GRID, TCX_KEY_BLOCK,
  TCX_KEY_A_K_FASTEST, TCX_KEY_B_K_FASTEST, TCX_KEY_D_N_FASTEST, TCX_KEY_VARIANT, TCX_KEY_HIP_ERROR, TCX_KEY_MODES_M,
- TCX_KEY_MODES_N, TCX_KEY_MODES_K, TCX_KEY_MODES_H, TCX_KEY_FORCE_PATH, TCX_KEY_SPLIT_K, TCX_KEY_LAUNCHES) = range(1, 27)
+ TCX_KEY_MODES_N, TCX_KEY_MODES_K, TCX_KEY_MODES_H, TCX_KEY_FORCE_PATH, TCX_KEY_SPLIT_K, TCX_KEY_LAUNCHES,
+ TCX_KEY_GATHER_WIDTH) = range(1, 28)
 TCX_MAX_MODES = 32
 
 EXPORTS = [

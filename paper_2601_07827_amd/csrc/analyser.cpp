@@ -164,11 +164,51 @@ tcx_error_t analyse(const TensorDesc& A, const int64_t* labA, const TensorDesc& 
     r.a_k_fastest = aK < aM;
     r.b_k_fastest = bK < bN;
     r.d_n_fastest = dN < dM;
-    // M is shared by A and D: follow D's order if D's fastest mode is an M mode (coalesced
-    // stores), else A's.  N likewise with B.  K: follow whichever input is K-fastest; if
-    // both are, the larger operand; if neither, A.
-    sort_by(&r.M, !r.d_n_fastest ? 2 : 0);
-    sort_by(&r.N, r.d_n_fastest ? 2 : 1);
+    // Order inside each group.  A tile takes the first modes of M and of N as its rows and
+    // columns, a slab the first modes of K, so what matters is which modes come first: the
+    // fastest modes of each tensor that make up a 128-byte line should lie inside the tile, or
+    // every access to that tensor touches a line for one element.  M: D's line modes first (by
+    // D's stride: consecutive lanes store consecutive elements), then A's line modes, then the
+    // rest by the stride of the tensor whose fastest mode the group holds (D if D's fastest mode
+    // is an M mode, else A).  N likewise with B.  K: the line modes of whichever input is
+    // K-fastest (both: the larger operand first), then the rest by that input's stride.
+    const int64_t line = 128 / (r.dtype == TCX_F32 ? 4 : r.dtype == TCX_F64 ? 8 : 16);
+    auto line_strides = [&](int which) {
+        // strides (in tensor `which`) of its fastest modes, up to a line's worth of elements
+        std::vector<std::pair<int64_t, int64_t>> se;
+        for (const std::vector<Mode>* g : {&r.H, &r.M, &r.N, &r.K})
+            for (const Mode& m : *g)
+                if (m.*kStride[which] != 0) se.push_back({iabs(m.*kStride[which]), m.extent});
+        std::sort(se.begin(), se.end());
+        std::vector<int64_t> out;
+        int64_t have = 1;
+        for (const auto& p : se) {
+            if (have >= line) break;
+            out.push_back(p.first);
+            have *= p.second;
+        }
+        return out;
+    };
+    auto order = [&](std::vector<Mode>* g, std::initializer_list<int> first, int rest) {
+        std::vector<Mode> left = *g, done;
+        for (int which : first) {
+            const std::vector<int64_t> ls = line_strides(which);
+            sort_by(&left, which);
+            for (size_t i = 0; i < left.size();) {
+                if (std::find(ls.begin(), ls.end(), iabs(left[i].*kStride[which])) != ls.end()) {
+                    done.push_back(left[i]);
+                    left.erase(left.begin() + (long)i);
+                } else {
+                    ++i;
+                }
+            }
+        }
+        sort_by(&left, rest);
+        done.insert(done.end(), left.begin(), left.end());
+        *g = done;
+    };
+    order(&r.M, {2, 0}, !r.d_n_fastest ? 2 : 0);
+    order(&r.N, {2, 1}, r.d_n_fastest ? 2 : 1);
     int k_anchor = 0;
     if (r.a_k_fastest && r.b_k_fastest) {
         const int64_t sizeA = r.sizeM * r.sizeK, sizeB = r.sizeN * r.sizeK;
@@ -176,7 +216,8 @@ tcx_error_t analyse(const TensorDesc& A, const int64_t* labA, const TensorDesc& 
     } else if (r.b_k_fastest) {
         k_anchor = 1;
     }
-    sort_by(&r.K, k_anchor);
+    if (k_anchor == 0) order(&r.K, {0, 1}, 0);
+    else order(&r.K, {1, 0}, 1);
     sort_by(&r.H, 2);
 
     if ((int)(r.H.size() + r.M.size() + r.N.size()) > kMaxGenericModes || (int)r.K.size() > kMaxGenericModes)

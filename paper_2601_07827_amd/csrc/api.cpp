@@ -47,6 +47,8 @@ struct Product {
     size_t narrow_off[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     int narrow_variant = -1;         // tile shape the narrow tables were built for (-1: none)
     bool periodic[2] = {false, false};   // A, B: relative k offsets repeat from slab to slab
+    bool pairs = false;                  // both operands can be gathered two neighbouring elements at a time
+    int pair_step[2] = {0, 0};           // ... element x along the lanes is paired with x + step
     GenericArgs generic{};
     // bandwidth path: plan and its device tables (one allocation)
     StreamPlan stream;
@@ -54,7 +56,7 @@ struct Product {
     size_t stream_off[6] = {0, 0, 0, 0, 0, 0};   // rowAB, dD, itemsA, itemsB, tabLo, tabHi
 };
 struct Status {
-    int64_t path = 0, variant = 0, grid = 0, block = 0, tile_m = 0, tile_n = 0, tile_k = 0, hip_error = 0;
+    int64_t path = 0, variant = 0, grid = 0, block = 0, tile_m = 0, tile_n = 0, tile_k = 0, hip_error = 0, gather_width = 1;
 };
 
 // Workgroups per launch when a product's grid is enqueued round by round (0: one launch).  Rounds
@@ -102,7 +104,9 @@ int64_t tiles_of(const Analysis& an, const GettVariant& s) {
 // Cost model for tile shape and split-K, in microseconds.  A workgroup's time is its slabs at
 // the shape's fraction of the CU's matrix peak plus a fixed prologue/epilogue; the grid runs
 // in rounds over the CUs; split-K adds a second launch and the traffic of the partial
-// accumulators.  Large tiles win when there are enough of them; small problems are cut
+// accumulators, and writing D (about 4 TB/s) is exposed in full where a CU holds one workgroup,
+// so that every CU stores at the same time, and half hidden behind other workgroups' main
+// loops otherwise.  Large tiles win when there are enough of them; small problems are cut
 // along K to fill the chip.
 struct PlanChoice {
     double us;
@@ -117,6 +121,7 @@ std::vector<PlanChoice> rank_plans(const Analysis& an, int num_cu) {
     const double cu_flops = (an.dtype == TCX_F32 ? 157.3e12 : 78.6e12) / 256.0;
     const double flop_per_mac = an.dtype == TCX_C128 ? 8.0 : 2.0;
     const int ebytes = an.dtype == TCX_F32 ? 4 : an.dtype == TCX_F64 ? 8 : 16;
+    const double store_us = (double)an.sizeH * an.sizeM * an.sizeN * ebytes / 4e12 * 1e6;
     for (int v = 0; v < n; ++v) {
         const GettVariant s = gett_variant(an.dtype, v);
         double best = -1;
@@ -134,7 +139,7 @@ std::vector<PlanChoice> rank_plans(const Analysis& an, int num_cu) {
                                            : std::max(1.0, std::min(4.0, 65536.0 / ((double)s.mt_m * s.mt_n * (ebytes > 8 ? 2 : 1))));
             const double slots = cus * resident;
             const double rounds = std::ceil(tiles * (double)S / slots);
-            double us = rounds * resident * (double)per * slab_us + 6.0;
+            double us = rounds * resident * (double)per * slab_us + 6.0 + store_us * (s.pingpong ? 1.0 : 0.5);
             if (S > 1 && !(S == 2 && s.pair_in_lds))
                 us += 3.0 + (2.0 * S + 1.0) * tiles * s.acc_reals * (ebytes > 8 ? 8 : ebytes) / 6e12 * 1e6;
             if (best < 0 || us < best) { best = us; bestS = (int)S; }
@@ -297,6 +302,33 @@ tcx_error_t build_narrow(Product* p, int variant) {
             return TCX_ERR_UNSUPPORTED_OP;
         p->periodic[0] = a.periodic;
         p->periodic[1] = b.periodic;
+        // Paired gather loads (8-byte elements, two-phase kernel with one tile per wave group):
+        // whole tiles and slabs, slab-periodic k offsets, and a step ps (a power of two) along the
+        // direction the operand's lanes run such that every element x with (x / ps) even and its
+        // partner x + ps are contiguous, x being 16-byte aligned relative to the operand's pointer
+        // (whose own alignment is looked at when the product is executed).  Returns ps, 0 if none.
+        auto pair_step = [&](const NarrowOperand& o, bool k_fastest, int64_t nrows, int mt, int which) -> int {
+            if (!o.periodic || nrows % mt != 0 || p->an.sizeK % s.kt != 0) return 0;
+            for (const Mode& h : p->an.H)
+                if ((which == 0 ? h.sA : h.sB) % 2 != 0) return 0;
+            for (int64_t v : o.rowbase) if (v % 16 != 0) return 0;
+            for (int64_t v : o.kbase) if (v % 16 != 0) return 0;
+            const std::vector<uint32_t>& along = k_fastest ? o.krel : o.rowrel;
+            const std::vector<uint32_t>& across = k_fastest ? o.rowrel : o.krel;
+            for (uint32_t v : across) if (v % 16 != 0) return 0;
+            const int unit = k_fastest ? s.kt : mt;               // pairs stay inside a slab / a tile
+            for (int ps = 1; 2 * ps <= unit; ps *= 2) {
+                if (unit % (2 * ps) != 0) break;
+                bool ok = true;
+                for (size_t x = 0; x < along.size() && ok; ++x)
+                    if ((x / (size_t)ps) % 2 == 0) ok = along[x] % 16 == 0 && along[x + (size_t)ps] == along[x] + 8;
+                if (ok) return ps;
+            }
+            return 0;
+        };
+        p->pair_step[0] = pair_step(a, p->an.a_k_fastest, p->an.sizeM, s.mt_m, 0);
+        p->pair_step[1] = pair_step(b, p->an.b_k_fastest, p->an.sizeN, s.mt_n, 1);
+        p->pairs = s.pingpong && s.dual && es == 8 && p->pair_step[0] > 0 && p->pair_step[1] > 0;
     } catch (const std::bad_alloc&) {
         return TCX_ERR_ALLOC;
     }
@@ -593,6 +625,7 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
             return put_i64((round > 0 && p->splitK == 1 && blocks > round ? (blocks + round - 1) / round : 1) + (second_kernel ? 1 : 0),
                            value, nbytes);
         }
+        case TCX_KEY_GATHER_WIDTH: return put_i64(tiled && s.pingpong && s.dual && p->pairs ? 2 : 1, value, nbytes);
         case TCX_KEY_VARIANT:
             return put_i64(tiled ? p->variant : (an.path == TCX_PATH_BANDWIDTH && p->stream.blocked) ? 1 : 0, value, nbytes);
         case TCX_KEY_MODES_M: return put_modes(an.M, value, nbytes);
@@ -720,6 +753,8 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
             g.rrB = (const uint32_t*)(nb + o[5]); g.rbB = (const int64_t*)(nb + o[6]); g.kqB = (const int64_t*)(nb + o[7]);
             g.krB = (const uint32_t*)(nb + o[8]); g.kbB = (const int64_t*)(nb + o[9]);
             g.periodicA = p->periodic[0]; g.periodicB = p->periodic[1];
+            g.pair = p->pairs && (((uintptr_t)A | (uintptr_t)B) & 15) == 0;
+            g.psA = p->pair_step[0]; g.psB = p->pair_step[1];
         }
         g.sizeM = p->an.sizeM; g.sizeN = p->an.sizeN; g.sizeK = p->an.sizeK; g.sizeH = p->an.sizeH;
         g.tilesM = (int32_t)((g.sizeM + v.mt_m - 1) / v.mt_m);
@@ -740,6 +775,7 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
         hip_err = launch_gett(p->an.dtype, p->variant, p->an.a_k_fastest, p->an.b_k_fastest, p->an.d_n_fastest, g,
                               (void*)e->stream, &grid, &block);
         st.path = TCX_PATH_GETT_MFMA; st.variant = p->variant;
+        st.gather_width = g.pair && v.pingpong && v.dual && g.sizeK % v.kt == 0 ? 2 : 1;
         st.tile_m = v.mt_m; st.tile_n = v.mt_n; st.tile_k = v.kt;
     } else {
         GenericArgs g = p->generic;
@@ -769,6 +805,7 @@ tcx_error_t tcx_status_get(tcx_status_t status, int32_t key, void* value, size_t
         case TCX_KEY_TILE_N: return put_i64(s->tile_n, value, nbytes);
         case TCX_KEY_TILE_K: return put_i64(s->tile_k, value, nbytes);
         case TCX_KEY_HIP_ERROR: return put_i64(s->hip_error, value, nbytes);
+        case TCX_KEY_GATHER_WIDTH: return put_i64(s->gather_width, value, nbytes);
         default: return TCX_ERR_BAD_KEY;
     }
 }

@@ -181,13 +181,15 @@ struct ComplexPolicy {
 constexpr int kPadMN = 16;   // [k][mn] rows: the four k-rows of a fragment land on distinct banks
 constexpr int kPadK = 1;     // [mn][k] rows: odd row pitch spreads the 16 rows of a fragment
 
-// One operand's slab: MT rows (m or n) by KT contracted indices.
-template <class T, int MT, int KT, int NT, bool KF>
+// One operand's slab: MT rows (m or n) by KT contracted indices.  A thread stages PER items of
+// VEC elements each (VEC = 2: the kernel pairs the elements up itself and does not use row(),
+// kin() and lds_index()).
+template <class T, int MT, int KT, int NT, bool KF, int VEC = 1>
 struct Slab {
-    static constexpr int PER = MT * KT / NT;                       // elements per thread per slab
+    static constexpr int PER = MT * KT / NT / VEC;                 // items per thread per slab
     static constexpr int LD = KF ? KT + kPadK : MT + kPadMN;
     static constexpr int ELEMS = KF ? MT * LD : KT * LD;
-    static_assert(MT * KT % NT == 0, "slab must divide evenly over the workgroup");
+    static_assert(MT * KT % (NT * VEC) == 0 && MT % VEC == 0 && KT % VEC == 0, "slab must divide evenly over the workgroup");
     // lanes run along the rows and a wave covers whole rows' worth: one k index per wave
     static constexpr bool UNIFORM_K = !KF && MT % 64 == 0 && (NT % MT == 0 || MT % NT == 0);
 
@@ -579,6 +581,11 @@ template <> __device__ __forceinline__ double2 lds_load<double2>(unsigned byte_a
     return double2{t.x, t.y};
 }
 
+// what one gather load brings: an element, or two neighbouring real elements
+template <class T, int VEC> struct staged_item { using type = T; };
+template <> struct staged_item<double, 2> { using type = plain_double2; };
+template <> struct staged_item<float, 2> { typedef float type __attribute__((ext_vector_type(2))); };
+
 // DUAL: each of the two wave groups owns a tile of its own (WGM x WGN waves per tile, twice that
 // per workgroup) and stages only its own operands; the groups meet at the phase barriers alone.
 // This brings the schedule to small tiles: a workgroup of eight waves works on two 64 x 64 or
@@ -607,32 +614,53 @@ template <int I, int N, class F> __device__ __forceinline__ void static_for(F&& 
 
 // DEPTH: slabs of global loads in flight in registers.  The large tile spends 3.6 us on a slab and
 // needs one; an iteration of the small tiles is shorter than a load takes.
+// LATE (small tiles, DEPTH >= 2): a slab's global loads are issued in the compute phase, between
+// the MFMAs, instead of in the memory phase.  A CU's address unit takes about 16 cycles per
+// gather load of 64 addresses; for a 64 x 64 x 16 tile that made the memory phase longer than
+// the compute phase (about 1300 against 1000 cycles).  Loads need no vector-ALU slot, and the
+// matrix pipe works off the MFMAs already issued while the wave waits for the address unit.
 // RAGGED: |K| is not a multiple of KT.  A separate instantiation, so that the steady state of
 // the common case carries none of it: the last slab's lanes along k take their offsets from the
 // table (padded entries address a valid element) instead of the slab-periodic ones, and what the
 // padded entries load is zeroed before it goes to LDS -- vector-ALU work in a memory phase, once
 // per tile.
-template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF, bool DUAL, int DEPTH, bool RAGGED>
+// VEC = 2 (8-byte elements, whole tiles and slabs only): a gather load brings two elements that
+// are neighbours in memory.  Along the direction its lanes run (k if the operand is K-fastest,
+// else the tile's rows) element x is paired with x + ps, where ps (GettArgs::psA / psB, a power
+// of two) is the step at which the host found every such pair contiguous and 16-byte aligned:
+// 1 if the operand's fastest mode comes first in the tile, more if other modes of the tile lie
+// in between.  The two halves go to LDS with one write each.  The address unit of a CU takes a
+// gather load of 64 different addresses in about 16 cycles whatever its width, so on small
+// tiles, whose memory phase is as long as the compute phase, the number of load instructions is
+// what counts.  Both operands take the slab-periodic form of the k offsets (one scalar base per
+// slab), whichever way their lanes run.
+template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF, bool DUAL, int DEPTH, bool RAGGED, bool LATE = false, int VEC = 1>
 __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_kernel(GettArgs g) {
     using T = typename P::elem;
+    using V = typename staged_item<T, VEC>::type;
     using acc_t = typename P::acc_t;
+    constexpr bool PAIR = VEC > 1;
+    constexpr bool ALANES_K = AKF || PAIR, BLANES_K = BKF || PAIR;      // per-lane k offsets, one scalar base per slab
+    static_assert(!(PAIR && RAGGED), "paired loads need whole slabs");
+    static_assert(!LATE || DEPTH >= 2, "loads issued in a compute phase need a phase more to arrive");
     constexpr int NTG = WGM * WGN * 64;                   // threads that work on one tile
     constexpr int GROUPS_PER_TILE = DUAL ? 1 : 2;
     constexpr int NB = DUAL ? 2 : 3;                      // LDS slabs per tile
     constexpr int WT_M = MT_M / WGM, WT_N = MT_N / WGN;
     constexpr int FM = WT_M / 16, FN = WT_N / 16;
-    using SA = Slab<T, MT_M, KT, NTG, AKF>;
-    using SB = Slab<T, MT_N, KT, NTG, BKF>;
+    using SA = Slab<T, MT_M, KT, NTG, AKF, VEC>;
+    using SB = Slab<T, MT_N, KT, NTG, BKF, VEC>;
     constexpr int STEPS = KT / 4;
     constexpr int SLAB = SA::ELEMS + SB::ELEMS;
     constexpr unsigned ES = sizeof(T);
     static_assert(KT % 8 == 0 && WT_M % 16 == 0 && WT_N % 16 == 0, "tile shape");
     static_assert((NTG / 64 * (DUAL ? 2 : 1)) % 8 == 0, "two groups with a wave on each of the four SIMDs");
     static_assert(NTG % KT == 0, "a thread's slab elements differ by a constant LDS offset");
-    static_assert(pingpong_operand_ok<MT_M, NTG, AKF>() && pingpong_operand_ok<MT_N, NTG, BKF>(), "operand orientation");
+    static_assert(PAIR || (pingpong_operand_ok<MT_M, NTG, AKF>() && pingpong_operand_ok<MT_N, NTG, BKF>()), "operand orientation");
+    static_assert(!PAIR || ((AKF || NTG % (MT_M / VEC) == 0) && (BKF || NTG % (MT_N / VEC) == 0)), "a thread's items differ by a constant LDS offset");
     static_assert(ES * SLAB < 65536, "LDS offsets inside a slab must fit the instruction's immediate");
 
-    __shared__ T lds[(DUAL ? 2 : 1) * NB * SLAB];
+    __shared__ __attribute__((aligned(16))) T lds[(DUAL ? 2 : 1) * NB * SLAB];
     static_assert(sizeof(T) * (DUAL ? 2 : 1) * NB * SLAB <= 160 * 1024, "LDS budget of a CU");
 
     const int wave_all = wave_uniform((int)threadIdx.x >> 6);
@@ -670,17 +698,24 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
     // the host guarantees to be the same in every slab.
     uint32_t voA[SA::PER], voB[SB::PER];
     unsigned kinA[SA::PER], kinB[SB::PER];
+    // (row, k) of item e of a slab; paired items: x-th pair along the lanes -> its first element
+    const int psA = PAIR ? g.psA : 1, psB = PAIR ? g.psB : 1;
+    auto first_of_pair = [](int x, int ps) __attribute__((always_inline)) { return x % ps + 2 * ps * (x / ps); };
+    auto rowA_of = [&](int e) __attribute__((always_inline)) { return !PAIR ? SA::row(e) : AKF ? e / (KT / 2) : first_of_pair(e % (MT_M / 2), psA); };
+    auto kinA_of = [&](int e) __attribute__((always_inline)) { return !PAIR ? SA::kin(e) : AKF ? first_of_pair(e % (KT / 2), psA) : e / (MT_M / 2); };
+    auto rowB_of = [&](int e) __attribute__((always_inline)) { return !PAIR ? SB::row(e) : BKF ? e / (KT / 2) : first_of_pair(e % (MT_N / 2), psB); };
+    auto kinB_of = [&](int e) __attribute__((always_inline)) { return !PAIR ? SB::kin(e) : BKF ? first_of_pair(e % (KT / 2), psB) : e / (MT_N / 2); };
 #pragma unroll
     for (int i = 0; i < SA::PER; ++i) {
         const int e = tid + i * NTG;
-        voA[i] = g.rrA[m0 + SA::row(e)] + (AKF ? g.krA[SA::kin(e)] : 0u);
-        kinA[i] = AKF ? 0u : (unsigned)__builtin_amdgcn_readfirstlane(SA::kin(e));
+        voA[i] = g.rrA[m0 + rowA_of(e)] + (ALANES_K ? g.krA[kinA_of(e)] : 0u);
+        kinA[i] = ALANES_K ? 0u : (unsigned)__builtin_amdgcn_readfirstlane(SA::kin(e));
     }
 #pragma unroll
     for (int i = 0; i < SB::PER; ++i) {
         const int e = tid + i * NTG;
-        voB[i] = g.rrB[n0 + SB::row(e)] + (BKF ? g.krB[SB::kin(e)] : 0u);
-        kinB[i] = BKF ? 0u : (unsigned)__builtin_amdgcn_readfirstlane(SB::kin(e));
+        voB[i] = g.rrB[n0 + rowB_of(e)] + (BLANES_K ? g.krB[kinB_of(e)] : 0u);
+        kinB[i] = BLANES_K ? 0u : (unsigned)__builtin_amdgcn_readfirstlane(SB::kin(e));
     }
     // LDS byte addresses, per LDS slab: where this thread writes its first element of A and of
     // B, and where it reads its first fragment of A and of B.  Further elements / fragments are
@@ -689,18 +724,22 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) T*)lds +
                           (DUAL && second_group ? ES * NB * SLAB : 0u);
     unsigned wA[NB], wB[NB], fA[NB], fB[NB];
+    unsigned wA2[NB], wB2[NB];                            // paired items: where the second element goes
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-        wA[b] = lds0 + ES * (unsigned)(b * SLAB + SA::lds_index(tid));
-        wB[b] = lds0 + ES * (unsigned)(b * SLAB + SA::ELEMS + SB::lds_index(tid));
+        wA[b] = lds0 + ES * (unsigned)(b * SLAB + SA::frag_index(rowA_of(tid), kinA_of(tid)));
+        wB[b] = lds0 + ES * (unsigned)(b * SLAB + SA::ELEMS + SB::frag_index(rowB_of(tid), kinB_of(tid)));
+        wA2[b] = wA[b] + ES * (unsigned)psA;
+        wB2[b] = wB[b] + ES * (unsigned)psB;
+        if constexpr (PAIR) asm volatile("" : "+v"(wA2[b]), "+v"(wB2[b]));
         fA[b] = lds0 + ES * (unsigned)(b * SLAB + SA::frag_index(wm * WT_M + fr, fq));
         fB[b] = lds0 + ES * (unsigned)(b * SLAB + SA::ELEMS + SB::frag_index(wn * WT_N + fr, fq));
         // opaque to the compiler from here on: kept in registers instead of being recomputed
         // (with vector-ALU instructions) inside the loop
         asm volatile("" : "+v"(wA[b]), "+v"(wB[b]), "+v"(fA[b]), "+v"(fB[b]));
     }
-    constexpr unsigned dWA = ES * (AKF ? (NTG / KT) * SA::LD : (NTG / MT_M) * SA::LD);   // element i+1 minus element i
-    constexpr unsigned dWB = ES * (BKF ? (NTG / KT) * SB::LD : (NTG / MT_N) * SB::LD);
+    constexpr unsigned dWA = ES * (AKF ? (NTG * VEC / KT) * SA::LD : (NTG * VEC / MT_M) * SA::LD);   // item i+1 minus item i
+    constexpr unsigned dWB = ES * (BKF ? (NTG * VEC / KT) * SB::LD : (NTG * VEC / MT_N) * SB::LD);
     constexpr unsigned dFA_row = ES * (AKF ? 16 * SA::LD : 16), dFA_step = ES * (AKF ? 4 : 4 * SA::LD);
     constexpr unsigned dFB_row = ES * (BKF ? 16 * SB::LD : 16), dFB_step = ES * (BKF ? 4 : 4 * SB::LD);
 
@@ -709,14 +748,14 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
     int64_t kbA = 0, kbB = 0;                    // lanes along k: the slab's base
     auto k_offsets = [&](int kt) __attribute__((always_inline)) {
         const int kc = min(kt, nk - 1);
-        if (AKF) {
+        if (ALANES_K) {
             kbA = scalar_table(g.kbA)[kc];
         } else {
             const const_table<int64_t> q = scalar_table(g.kqA + (int64_t)kc * KT);
 #pragma unroll
             for (int i = 0; i < SA::PER; ++i) kqA[i] = q[kinA[i]];
         }
-        if (BKF) {
+        if (BLANES_K) {
             kbB = scalar_table(g.kbB)[kc];
         } else {
             const const_table<int64_t> q = scalar_table(g.kqB + (int64_t)kc * KT);
@@ -725,21 +764,24 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
         }
     };
     // conjugation is applied to the MFMA fragments in the compute phase (a vector-ALU operation)
-    T ra[DEPTH][SA::PER], rb[DEPTH][SB::PER];     // slab kb+j waits in ring slot j % DEPTH
+    V ra[DEPTH][SA::PER], rb[DEPTH][SB::PER];     // slab kb+j waits in ring slot j % DEPTH
     const unsigned kleft = (unsigned)(g.sizeK - (int64_t)(nk - 1) * KT);          // valid indices of the last slab
-    auto gather = [&](auto SLOT, int slab) __attribute__((always_inline)) {
+    // `part` of `parts`: the loads are issued in portions (item i belongs to portion i % parts)
+    auto gather = [&](auto SLOT, int slab, int part, int parts) __attribute__((always_inline)) {
         constexpr int sl = decltype(SLOT)::value;
         if constexpr (RAGGED) {
             if (slab >= nk - 1) {
                 // the ragged slab (or a clamped slab past the end): offsets of lanes along k from the table
 #pragma unroll
                 for (int i = 0; i < SA::PER; ++i) {
+                    if (i % parts != part) continue;
                     uint32_t vo = voA[i];
                     if (AKF) vo += g.krA[(int64_t)(nk - 1) * KT + SA::kin(tid + i * NTG)] - g.krA[SA::kin(tid + i * NTG)];
                     ra[sl][i] = P::load_at(Ab + (AKF ? kbA : kqA[i]), vo, 0u);
                 }
 #pragma unroll
                 for (int i = 0; i < SB::PER; ++i) {
+                    if (i % parts != part) continue;
                     uint32_t vo = voB[i];
                     if (BKF) vo += g.krB[(int64_t)(nk - 1) * KT + SB::kin(tid + i * NTG)] - g.krB[SB::kin(tid + i * NTG)];
                     rb[sl][i] = P::load_at(Bb + (BKF ? kbB : kqB[i]), vo, 0u);
@@ -750,13 +792,17 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
         // steady state: no vector-ALU instruction
 #pragma unroll
         for (int i = 0; i < SA::PER; ++i) {
+            if (i % parts != part) continue;
             asm("" : "+v"(voA[i]));              // keeps "scalar base + 32-bit lane offset" from being folded into a 64-bit lane address
-            ra[sl][i] = P::load_at(Ab + (AKF ? kbA : kqA[i]), voA[i], 0u);
+            if constexpr (PAIR) ra[sl][i] = *(const V*)(Ab + kbA + voA[i]);
+            else ra[sl][i] = P::load_at(Ab + (AKF ? kbA : kqA[i]), voA[i], 0u);
         }
 #pragma unroll
         for (int i = 0; i < SB::PER; ++i) {
+            if (i % parts != part) continue;
             asm("" : "+v"(voB[i]));
-            rb[sl][i] = P::load_at(Bb + (BKF ? kbB : kqB[i]), voB[i], 0u);
+            if constexpr (PAIR) rb[sl][i] = *(const V*)(Bb + kbB + voB[i]);
+            else rb[sl][i] = P::load_at(Bb + (BKF ? kbB : kqB[i]), voB[i], 0u);
         }
     };
     auto stage = [&](auto BUF, auto SLOT, int slab) __attribute__((always_inline)) {
@@ -772,9 +818,23 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
             }
         }
 #pragma unroll
-        for (int i = 0; i < SA::PER; ++i) lds_store<T>(wA[b] + i * dWA, ra[sl][i]);
+        for (int i = 0; i < SA::PER; ++i) {
+            if constexpr (PAIR) {
+                lds_store<T>(wA[b] + i * dWA, ra[sl][i].x);
+                lds_store<T>(wA2[b] + i * dWA, ra[sl][i].y);
+            } else {
+                lds_store<T>(wA[b] + i * dWA, ra[sl][i]);
+            }
+        }
 #pragma unroll
-        for (int i = 0; i < SB::PER; ++i) lds_store<T>(wB[b] + i * dWB, rb[sl][i]);
+        for (int i = 0; i < SB::PER; ++i) {
+            if constexpr (PAIR) {
+                lds_store<T>(wB[b] + i * dWB, rb[sl][i].x);
+                lds_store<T>(wB2[b] + i * dWB, rb[sl][i].y);
+            } else {
+                lds_store<T>(wB[b] + i * dWB, rb[sl][i]);
+            }
+        }
     };
 
     acc_t acc[FM][FN];
@@ -805,11 +865,11 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
     // are clamped: harmless loads that are never staged).
     if (n > 0) {
         k_offsets(kb);
-        gather(std::integral_constant<int, 0>{}, kb);
+        gather(std::integral_constant<int, 0>{}, kb, 0, 1);
         k_offsets(kb + 1);
         stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, kb);
         static_for<0, DEPTH>([&](auto D) __attribute__((always_inline)) {
-            gather(std::integral_constant<int, (1 + decltype(D)::value) % DEPTH>{}, kb + 1 + decltype(D)::value);
+            gather(std::integral_constant<int, (1 + decltype(D)::value) % DEPTH>{}, kb + 1 + decltype(D)::value, 0, 1);
             k_offsets(kb + 2 + decltype(D)::value);
         });
     }
@@ -827,32 +887,54 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
     // iteration i has IDX = i % UNROLL.
     constexpr int UNROLL = NB * DEPTH / (NB % DEPTH == 0 ? DEPTH : DEPTH % NB == 0 ? NB : 1);
     static_assert(UNROLL % NB == 0 && UNROLL % DEPTH == 0, "unroll factor");
-    auto round = [&](int i, auto IDX) __attribute__((always_inline)) {
+    // FULL: the caller guarantees i + 1 < n, and the round has no branch.  (With the loads under
+    // a condition the compiler cannot count how many younger loads are in flight when a slab is
+    // staged, and waits for all of them.)
+    auto round = [&](int i, auto IDX, auto FULL) __attribute__((always_inline)) {
+        constexpr bool full = decltype(FULL)::value;
         using BUF = std::integral_constant<int, decltype(IDX)::value % NB>;
         using NEXT_BUF = std::integral_constant<int, (decltype(IDX)::value + 1) % NB>;
         using NEXT_SLOT = std::integral_constant<int, (decltype(IDX)::value + 1) % DEPTH>;
         // memory phase: no vector-ALU instruction in here
-        if (i + 1 < n) {
-            stage(NEXT_BUF{}, NEXT_SLOT{}, kb + i + 1);
-            gather(NEXT_SLOT{}, kb + i + 1 + DEPTH);
-            k_offsets(kb + i + 2 + DEPTH);
+        if (full || i + 1 < n) {
+            if constexpr (LATE) {
+                k_offsets(kb + i + 1 + DEPTH);           // for the loads of the coming compute phase
+                stage(NEXT_BUF{}, NEXT_SLOT{}, kb + i + 1);
+            } else {
+                stage(NEXT_BUF{}, NEXT_SLOT{}, kb + i + 1);
+                gather(NEXT_SLOT{}, kb + i + 1 + DEPTH, 0, 1);
+                k_offsets(kb + i + 2 + DEPTH);
+            }
         }
-        if (i < n) frag_load(BUF{}, 0, 0);
+        if (full || i < n) frag_load(BUF{}, 0, 0);
         phase_end();
         // compute phase
-        if (i < n) {
+        if (full || i < n) {
 #pragma unroll
             for (int st = 0; st < STEPS; ++st) {
                 if (st + 1 < STEPS) frag_load(BUF{}, st + 1, (st + 1) & 1);
                 mfmas(st & 1);
+                // LATE: the slab's loads go out a few per k-step behind MFMAs that keep the matrix
+                // pipe busy while the address unit takes them
+                if constexpr (LATE) {
+                    // pinned behind this step's MFMAs: hoisted to the start of the phase the loads
+                    // would hold up the first MFMA for as long as the address unit takes them
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (full || i + 1 < n) gather(NEXT_SLOT{}, kb + i + 1 + DEPTH, st, STEPS);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
         phase_end();
     };
     int i = 0;
-    for (; i + UNROLL <= n_all; i += UNROLL) static_for<0, UNROLL>([&](auto IDX) __attribute__((always_inline)) { round(i + decltype(IDX)::value, IDX); });
+    if constexpr (LATE)
+        for (; i + UNROLL < n; i += UNROLL)
+            static_for<0, UNROLL>([&](auto IDX) __attribute__((always_inline)) { round(i + decltype(IDX)::value, IDX, std::true_type{}); });
+    for (; i + UNROLL <= n_all; i += UNROLL)
+        static_for<0, UNROLL>([&](auto IDX) __attribute__((always_inline)) { round(i + decltype(IDX)::value, IDX, std::false_type{}); });
     static_for<0, UNROLL - 1>([&](auto IDX) __attribute__((always_inline)) {
-        if (i + decltype(IDX)::value < n_all) round(i + decltype(IDX)::value, IDX);
+        if (i + decltype(IDX)::value < n_all) round(i + decltype(IDX)::value, IDX, std::false_type{});
     });
     if (!second_group) __builtin_amdgcn_s_barrier();      // pairs with the second group's last barrier
     settle_accumulators();
@@ -1089,7 +1171,15 @@ hipError_t launch_one(const GettArgs& a, int64_t blocks, hipStream_t st) {
             constexpr int threads = NTG * (s.dual ? 2 : 1);
             const int64_t wgs = s.dual ? (blocks + 1) / 2 : blocks;
             const bool ragged = a.sizeK % s.kt != 0;
+            constexpr bool PAIRED = s.dual && std::is_same<typename P::elem, double>::value;      // the shapes that have a paired-load twin
             auto launch = [&](const GettArgs& r, int64_t count) {
+                if constexpr (PAIRED) {
+                    if (r.pair && !ragged) {
+                        gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual, (s.depth < 2 ? 2 : s.depth), false, true, 2>
+                            <<<dim3((unsigned)count), dim3(threads), 0, st>>>(r);
+                        return;
+                    }
+                }
                 if (ragged)
                     gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual, s.depth, true>
                         <<<dim3((unsigned)count), dim3(threads), 0, st>>>(r);

@@ -79,6 +79,8 @@ struct GettArgs {
     int32_t periodicA, periodicB;   // krel is the same in every slab (two-phase kernel, lanes along k)
     int64_t lid_base;      // first tile number of this launch (a product may be launched in rounds)
     int32_t round_size;    // > 0: launch the grid in rounds of this many workgroups (two-phase kernel)
+    int32_t pair;          // two-phase kernel, 8-byte elements: a gather load brings two elements that the host found contiguous and 16-byte aligned
+    int32_t psA, psB;      // ... element x along the lanes' direction is paired with x + ps
     int64_t sizeM, sizeN, sizeK, sizeH;
     int32_t tilesM, tilesN, tilesK;
     int32_t nH;

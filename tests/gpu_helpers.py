@@ -57,6 +57,7 @@ class GpuProduct:
                                    dD.data_ptr() + p.D.base * item, want_status=True)
         self.last_path = T.tcx_status_get(st, T.TCX_KEY_PATH)
         self.last_variant = T.tcx_status_get(st, T.TCX_KEY_VARIANT)
+        self.last_gather_width = T.tcx_status_get(st, T.TCX_KEY_GATHER_WIDTH)
         assert T.tcx_status_get(st, T.TCX_KEY_HIP_ERROR) == 0
         assert T.tcx_destroy_status(st) == 0
 

@@ -233,7 +233,7 @@ def _plan(handle, p):
     out = {k: T.tcx_product_get(prod, getattr(T, "TCX_KEY_" + k)) for k in
            ("PATH", "SIZE_H", "SIZE_M", "SIZE_N", "SIZE_K", "MODES_H", "MODES_M", "MODES_N", "MODES_K",
             "A_K_FASTEST", "B_K_FASTEST", "D_N_FASTEST", "TILE_M", "TILE_N", "TILE_K", "GRID", "BLOCK", "VARIANT",
-            "SPLIT_K", "LAUNCHES")}
+            "SPLIT_K", "LAUNCHES", "GATHER_WIDTH")}
     T.tcx_destroy_product(prod)
     return out
 
@@ -334,6 +334,49 @@ def test_planner_routes_each_configuration(handle):
     assert c1["BLOCK"] == 256 and c1["SPLIT_K"] > 1 and c1["LAUNCHES"] == 2
     c3 = _plan(handle, W.config3())
     assert c3["BLOCK"] == 256                                               # K = (e41, d29): slabs of 16 do not repeat
+
+
+def test_tile_modes_cover_a_cache_line_of_every_tensor(handle):
+    """Order of the modes inside a group: a tile's rows are the first modes of M (columns: of N, slab:
+    of K).  For a tensor network with random mode orders the fastest modes of D *and* of the operand
+    must both come first, or every access to one of them touches a 128-byte line for one element.
+    (Modes are (extent, strideA, strideB, strideD).)"""
+    for seed in range(1000, 1008):
+        p = W.config5(perm_seed=seed)
+        a = _plan(handle, p)
+        line = 16                                             # fp64 elements per 128 bytes
+
+        def line_strides(which):
+            modes = [m for g in ("MODES_M", "MODES_N", "MODES_K") for m in a[g] if m[which] != 0]
+            out, have = [], 1
+            for m in sorted(modes, key=lambda m: abs(m[which])):
+                if have >= line:
+                    break
+                out.append(abs(m[which]))
+                have *= m[0]
+            return out
+
+        def first_modes(group, count):
+            got, have = [], 1
+            for m in a[group]:
+                if have >= count:
+                    break
+                got.append(m)
+                have *= m[0]
+            return got
+
+        tile = {"MODES_M": first_modes("MODES_M", a["TILE_M"]), "MODES_N": first_modes("MODES_N", a["TILE_N"]),
+                "MODES_K": first_modes("MODES_K", a["TILE_K"])}
+        for which, groups in ((1, ("MODES_M", "MODES_K")), (2, ("MODES_N", "MODES_K")), (3, ("MODES_M", "MODES_N"))):
+            inside = [abs(m[which]) for g in groups for m in tile[g]]
+            # the fastest mode always; the rest of the line unless the other tensor's line has
+            # used up the tile (a slab holds only 16 contracted indices)
+            assert line_strides(which)[0] in inside, (seed, which, tile)
+        # ... and then both operands can be gathered two contiguous elements per load
+        assert a["GATHER_WIDTH"] == 2, seed
+    assert _plan(handle, W.config5())["GATHER_WIDTH"] == 2
+    assert _plan(handle, W.config2())["GATHER_WIDTH"] == 1      # the 256 x 128 tile has no paired twin
+    assert _plan(handle, W.config4())["GATHER_WIDTH"] == 1      # 16-byte elements
 
 
 def test_forcing_a_shape_the_plan_cannot_take_is_refused(handle):

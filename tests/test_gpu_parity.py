@@ -192,6 +192,67 @@ def test_two_phase_kernel_batches_and_negative_strides(dtype):
                 assert normalised_error(p, got, truth, S, c) <= TOLERANCE[p.dtype]
 
 
+def _run_on(gp, p, a, b, c, shift_a=0):
+    """Execute plan gp; shift_a: A is stored that many elements into its device buffer (an operand
+    pointer that is not 16-byte aligned)."""
+    import torch
+    dA = torch.empty(a.size + shift_a, dtype=torch.from_numpy(a).dtype, device="cuda:0")
+    dA[shift_a:] = torch.from_numpy(a).cuda()
+    dB, dD = torch.from_numpy(b).cuda(), torch.from_numpy(c.copy()).cuda()
+    gp.execute(dA[shift_a:], dB, dD, dD)
+    torch.cuda.synchronize()
+    return dD.cpu().numpy()
+
+
+def test_two_phase_kernel_paired_loads():
+    """fp64 tiles of one wave group each: with whole tiles and slabs, contiguous neighbours and
+    16-byte alignment a gather load brings two elements (status: gather width 2).  Every operand
+    orientation, K unsplit / in two / in three parts, integer inputs bit for bit; the same plan
+    run on an operand pointer that is only 8-byte aligned takes the one-element kernel; a layout
+    whose contiguous neighbours are four rows apart inside the tile."""
+    from gpu_helpers import GpuProduct, say
+    import paper_2601_07827_amd as T
+    for flags in range(8):
+        akf, bkf, dnf = bool(flags & 4), bool(flags & 2), bool(flags & 1)
+        p = _matrix_product(256, 384, 96, akf, bkf, dnf, "f64")
+        a, b, c = W.make_operands(p, "ints")
+        truth, _ = run_oracle(p, a, b, c, oracle.MODE_TRUTH)
+        for variant in (10, 11):
+            for parts in (None, 2, 3):
+                gp = GpuProduct(p, GETT, variant, parts)
+                try:
+                    assert gp.get(T.TCX_KEY_GATHER_WIDTH) == 2
+                    for shift, width in ((0, 2), (1, 1)):
+                        say("%s shape %d parts %s A shifted by %d" % (p.name, variant, parts, shift))
+                        got = _run_on(gp, p, a, b, c, shift)
+                        assert gp.last_gather_width == width and gp.last_variant == variant
+                        assert np.array_equal(W.strided_view(got, p.D), W.strided_view(truth, p.D))
+                finally:
+                    gp.close()
+    # B[k,x,y,z] stored z-fastest, D[x,m,y,z] stored x-fastest: the tile's columns run (x, z, y), so
+    # B's contiguous neighbours (along z) are four columns apart
+    e = {"m": 128, "k": 48, "x": 4, "y": 8, "z": 4}
+    p = W.Problem("paired_step4", "f64", W.tensor("mk", e), W.tensor("kxyz", e, memory_order="zkxy"),
+                  W.tensor("mxyz", e, memory_order="xmyz"), alpha=2.0, beta=-1.0, seed=W.BASE_SEED + 23)
+    for dist, exact in (("uniform", False), ("ints", True)):
+        a, b, c = W.make_operands(p, dist)
+        truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+        for variant in (10, 11):
+            gp = GpuProduct(p, GETT, variant)
+            try:
+                assert gp.get(T.TCX_KEY_GATHER_WIDTH) == 2
+                assert [m[0] for m in gp.get(T.TCX_KEY_MODES_N)] == [4, 4, 8]
+                say("%s shape %d dist %s" % (p.name, variant, dist))
+                got = _run_on(gp, p, a, b, c)
+                assert gp.last_gather_width == 2
+                if exact:
+                    assert np.array_equal(W.strided_view(got, p.D), W.strided_view(truth, p.D))
+                else:
+                    assert normalised_error(p, got, truth, S, c) <= TOLERANCE[p.dtype]
+            finally:
+                gp.close()
+
+
 @pytest.mark.parametrize("h_slowest", [False, True])
 def test_two_phase_kernel_complex(h_slowest):
     """The two-phase kernel with one 96 x 96 complex tile per wave group: batched conj(A)^T B with
