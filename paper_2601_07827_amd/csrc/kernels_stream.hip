@@ -182,10 +182,13 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs g) {
 // Blocked tiles: thread `tid` owns lane index tid of the tile and a regA x regB block of outputs
 // (free indices of A times free indices of B held in registers): regA + regB operand rows are
 // read from LDS for regA * regB outputs.  No chunk is ragged here (the planner takes divisors).
-template <class T, int KC>
+// PER: staged operand elements per thread and operand the instantiation has registers for (the
+// launcher picks the smallest that holds the plan's item lists: a tile that stages few elements
+// then runs three waves per SIMD instead of two).
+template <class T, int KC, int PER>
 __global__ __launch_bounds__(kStreamThreads) void stream_blocked_kernel(StreamArgs g) {
     using N_ = SNum<T>;
-    constexpr int PER = kStreamPerThread;
+    static_assert(PER <= kStreamPerThread, "the planner's cap");
     constexpr int RB = kStreamRegBlock;
     constexpr unsigned NEVER = 0xffffu;
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -299,10 +302,18 @@ __global__ __launch_bounds__(kStreamThreads) void stream_blocked_kernel(StreamAr
 template <class T>
 hipError_t launch_k(bool blocked, const StreamArgs& a, size_t lds, unsigned blocks, hipStream_t st) {
     if (blocked) {
+        const int need = (std::max(a.nItemsA, a.nItemsB) + kStreamThreads - 1) / kStreamThreads;
+        if (need > kStreamPerThread) return hipErrorInvalidValue;
+        auto go = [&](auto KC_) {
+            constexpr int KC = decltype(KC_)::value;
+            if (need <= 2) stream_blocked_kernel<T, KC, 2><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a);
+            else if (need <= 4) stream_blocked_kernel<T, KC, 4><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a);
+            else stream_blocked_kernel<T, KC, kStreamPerThread><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a);
+        };
         switch (a.K) {
-            case 1: stream_blocked_kernel<T, 1><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
-            case 2: stream_blocked_kernel<T, 2><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
-            case 4: stream_blocked_kernel<T, 4><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
+            case 1: go(std::integral_constant<int, 1>{}); break;
+            case 2: go(std::integral_constant<int, 2>{}); break;
+            case 4: go(std::integral_constant<int, 4>{}); break;
             default: return hipErrorInvalidValue;
         }
         return hipGetLastError();
