@@ -32,8 +32,8 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {
     ("cfg2_f64_ppladder_v192_o64", 1, 0): 110.21e9 + 1.34e9,               # 18 launches (rounds) per step
     ("cfg5_f64_network_e4_k5_f5_p7832", 1, 10): 52.2e6 + 8.39e6,
-    ("cfg5_f64_network_e4_k1_f7_p7832", 2, 1): 35.1e6 + 2147.48e6,         # s1
-    ("cfg5_f64_network_e4_k0_f7_p7832", 2, 1): 5.6e6 + 2147.48e6,          # s2
+    ("cfg5_f64_network_e4_k1_f7_p7832", 2, 1): 31.2e6 + 2147.48e6,         # s1
+    ("cfg5_f64_network_e4_k0_f7_p7832", 2, 1): 5.7e6 + 2147.48e6,          # s2
     ("hadamard_f64_4x128", 2, 0): None,                                     # s3 / s3b differ by beta: see profiles/
 }
 DT = {"f32": 0, "f64": 1, "c128": 3}
