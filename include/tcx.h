@@ -79,7 +79,7 @@ enum {
     TCX_ERR_LAUNCH = 14,             /* the HIP runtime refused a launch or copy; see the status object */
     TCX_ERR_NO_DEVICE = 15,          /* the handle was created without a usable gfx950 GPU (plans only) */
     TCX_ERR_TOO_LARGE = 16,          /* an offset or an index range exceeds what the kernels address */
-    TCX_ERR_BAD_KEY = 17,            /* unknown key in tcx_status_get / tcx_product_get */
+    TCX_ERR_BAD_KEY = 17,            /* unknown key in tcx_status_get / tcx_product_get / tcx_attr_*, or a free-form key that holds no value */
     TCX_ERR_BUFFER_TOO_SMALL = 18    /* *nbytes is smaller than the value; *nbytes is set to the need */
 };
 
@@ -178,6 +178,30 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
 /* ---- status object (Sec. "Status Objects") ------------------------------------------ */
 tcx_error_t tcx_status_get(tcx_status_t status, int32_t key, void* value, size_t* nbytes);
 tcx_error_t tcx_destroy_status(tcx_status_t* status);
+
+/* ---- virtual key-value stores (Sec. "Virtual Key-Value Stores (VKVs)") -----------------
+ * A mapping from integral keys to arbitrary binary values, available on every object of the
+ * library through one interface, and as a bare store of its own.  `object` is any live handle,
+ * executor, tensor info, product, status or bare store (else TCX_ERR_INVALID_HANDLE).
+ *   keys >= TCX_KEY_USER   free-form: the library copies the nbytes bytes at `value` into the
+ *                          object (value may be NULL iff nbytes == 0), returns them unchanged,
+ *                          forgets them on clear and when the object is destroyed;
+ *   keys <  TCX_KEY_USER   the library's own ("virtual": they read and write state kept elsewhere):
+ *                          on a product the TCX_KEY_* of tcx_product_get / tcx_product_set, on a
+ *                          status those of tcx_status_get; clearing TCX_KEY_FORCE_PATH,
+ *                          TCX_KEY_VARIANT or TCX_KEY_SPLIT_K on a product returns the whole plan
+ *                          to the analyser's own choice; on other objects TCX_ERR_BAD_KEY.
+ * get: *nbytes in = capacity of value, out = size of the stored value; value NULL or too small:
+ * TCX_ERR_NULL_ARG / TCX_ERR_BUFFER_TOO_SMALL with *nbytes set to the need.  A key that was never
+ * set (or was cleared): TCX_ERR_BAD_KEY.  The caller keeps ownership of `value` in all calls. */
+#define TCX_KEY_USER 65536
+typedef intptr_t tcx_attr_t;       /* a bare store */
+typedef intptr_t tcx_object_t;     /* any object of the library */
+tcx_error_t tcx_create_attr(tcx_handle_t handle, tcx_attr_t* out);
+tcx_error_t tcx_destroy_attr(tcx_attr_t* attr);
+tcx_error_t tcx_attr_set(tcx_object_t object, int32_t key, const void* value, size_t nbytes);
+tcx_error_t tcx_attr_get(tcx_object_t object, int32_t key, void* value, size_t* nbytes);
+tcx_error_t tcx_attr_clear(tcx_object_t object, int32_t key);
 
 /* ---- error handling (Sec. "Error Handling") ------------------------------------------ */
 int tcx_check_success(tcx_error_t error);                                  /* 1 iff error == TCX_SUCCESS */

@@ -23,7 +23,7 @@ except ImportError:
     pass
 
 if not os.path.exists(LIB_PATH):
-    raise ImportError("libtcx.so is not built: run `python -m paper_2601_07827_amd.build` "
+    raise ImportError("libtcx.so is not built: run `python paper_2601_07827_amd/build.py` "
                       "(hipcc --offload-arch=gfx950); there is no CPU fallback")
 _lib = ctypes.CDLL(LIB_PATH)
 
@@ -42,12 +42,14 @@ TCX_PATH_GENERIC, TCX_PATH_GETT_MFMA, TCX_PATH_BANDWIDTH = 0, 1, 2
  TCX_KEY_MODES_N, TCX_KEY_MODES_K, TCX_KEY_MODES_H, TCX_KEY_FORCE_PATH, TCX_KEY_SPLIT_K, TCX_KEY_LAUNCHES,
  TCX_KEY_GATHER_WIDTH) = range(1, 28)
 TCX_MAX_MODES = 32
+TCX_KEY_USER = 65536
 
 EXPORTS = [
     "tcx_create_handle", "tcx_destroy_handle", "tcx_handle_has_device", "tcx_create_executor", "tcx_destroy_executor",
     "tcx_create_tensor_info", "tcx_destroy_tensor_info", "tcx_tensor_info_get", "tcx_create_product",
     "tcx_destroy_product", "tcx_product_get", "tcx_product_set", "tcx_execute_product", "tcx_status_get",
     "tcx_destroy_status", "tcx_check_success", "tcx_explain_error",
+    "tcx_create_attr", "tcx_destroy_attr", "tcx_attr_set", "tcx_attr_get", "tcx_attr_clear",
 ]
 
 _h = ctypes.c_ssize_t            # intptr_t
@@ -71,6 +73,11 @@ _lib.tcx_product_set.argtypes = [_h, ctypes.c_int32, _vp, ctypes.c_size_t]
 _lib.tcx_execute_product.argtypes = [_h, _h, _hp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.tcx_status_get.argtypes = [_h, ctypes.c_int32, _vp, _szp]
 _lib.tcx_destroy_status.argtypes = [_hp]
+_lib.tcx_create_attr.argtypes = [_h, _hp]
+_lib.tcx_destroy_attr.argtypes = [_hp]
+_lib.tcx_attr_set.argtypes = [_h, ctypes.c_int32, _vp, ctypes.c_size_t]
+_lib.tcx_attr_get.argtypes = [_h, ctypes.c_int32, _vp, _szp]
+_lib.tcx_attr_clear.argtypes = [_h, ctypes.c_int32]
 _lib.tcx_check_success.argtypes = [ctypes.c_int32]
 _lib.tcx_explain_error.argtypes = [ctypes.c_int32, ctypes.c_size_t, ctypes.c_char_p]
 _lib.tcx_explain_error.restype = ctypes.c_size_t
@@ -230,6 +237,48 @@ def tcx_destroy_status(status: int) -> int:
     s = _h(status)
     _check(_lib.tcx_destroy_status(ctypes.byref(s)), "tcx_destroy_status")
     return s.value
+
+
+def tcx_create_attr(handle: int) -> int:
+    a = _h(0)
+    _check(_lib.tcx_create_attr(handle, ctypes.byref(a)), "tcx_create_attr")
+    return a.value
+
+
+def tcx_destroy_attr(attr: int) -> int:
+    a = _h(attr)
+    _check(_lib.tcx_destroy_attr(ctypes.byref(a)), "tcx_destroy_attr")
+    return a.value
+
+
+def tcx_attr_set(obj: int, key: int, value) -> None:
+    """value: bytes for a free-form key (>= TCX_KEY_USER), an int for one of the library's keys."""
+    if key < TCX_KEY_USER:
+        v = ctypes.c_int64(int(value))
+        _check(_lib.tcx_attr_set(obj, key, ctypes.byref(v), 8), "tcx_attr_set")
+        return
+    data = bytes(value)
+    buf = ctypes.create_string_buffer(data, len(data)) if data else None
+    _check(_lib.tcx_attr_set(obj, key, buf, len(data)), "tcx_attr_set")
+
+
+def tcx_attr_get(obj: int, key: int):
+    """bytes for a free-form key; for the library's keys what tcx_product_get / tcx_status_get return."""
+    if key < TCX_KEY_USER:
+        return _get(_lib.tcx_attr_get, obj, key, "tcx_attr_get")
+    n = ctypes.c_size_t(0)
+    err = _lib.tcx_attr_get(obj, key, None, ctypes.byref(n))          # size query
+    if err not in (TCX_SUCCESS, TCX_ERR_NULL_ARG):
+        _check(err, "tcx_attr_get")
+    if n.value == 0:
+        return b""
+    buf = ctypes.create_string_buffer(n.value)
+    _check(_lib.tcx_attr_get(obj, key, buf, ctypes.byref(n)), "tcx_attr_get")
+    return buf.raw[: n.value]
+
+
+def tcx_attr_clear(obj: int, key: int) -> None:
+    _check(_lib.tcx_attr_clear(obj, key), "tcx_attr_clear")
 
 
 def raw():

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <map>
 #include <mutex>
 #include <new>
 #include <unordered_map>
@@ -16,7 +17,7 @@
 namespace tcx {
 namespace {
 
-enum : uint32_t { MAGIC_HANDLE = 0x74637801, MAGIC_EXEC, MAGIC_INFO, MAGIC_PRODUCT, MAGIC_STATUS };
+enum : uint32_t { MAGIC_HANDLE = 0x74637801, MAGIC_EXEC, MAGIC_INFO, MAGIC_PRODUCT, MAGIC_STATUS, MAGIC_ATTR };
 
 struct Handle {
     int device = -1;
@@ -46,6 +47,7 @@ struct Product {
     unsigned char* dev_narrow = nullptr;
     size_t narrow_off[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     int narrow_variant = -1;         // tile shape the narrow tables were built for (-1: none)
+    int analysed_path = TCX_PATH_GENERIC; // the analyser's verdict, before routing and overrides
     bool periodic[2] = {false, false};   // A, B: relative k offsets repeat from slab to slab
     bool pairs = false;                  // both operands can be gathered two neighbouring elements at a time
     int pair_step[2] = {0, 0};           // ... element x along the lanes is paired with x + step
@@ -68,6 +70,9 @@ int64_t round_size_of(const Product& p, const GettVariant& s) {
 
 std::mutex g_mu;
 std::unordered_map<intptr_t, uint32_t> g_live;   // handle value -> object type
+// free-form key-value pairs of every live object (Sec. "Virtual Key-Value Stores")
+std::unordered_map<intptr_t, std::map<int32_t, std::vector<unsigned char>>> g_kv;
+struct Attr {};                                  // a bare store: all it has lives in g_kv
 
 template <class T> intptr_t publish(T* obj, uint32_t magic) {
     std::lock_guard<std::mutex> lk(g_mu);
@@ -89,6 +94,7 @@ template <class T> tcx_error_t retire(intptr_t* h, uint32_t magic) {
         if (*h == 0 || it == g_live.end() || it->second != magic) return TCX_ERR_INVALID_HANDLE;
         obj = (T*)*h;
         g_live.erase(it);
+        g_kv.erase(*h);
     }
     delete obj;
     *h = 0;
@@ -538,6 +544,25 @@ tcx_error_t tcx_tensor_info_get(tcx_tensor_info_t info, tcx_dtype_t* dtype, int3
     return TCX_SUCCESS;
 }
 
+// Routing.  Low arithmetic intensity goes to the streaming path when its tile re-reads little
+// operand data per output; otherwise the tiled MFMA path if the free index space can fill MFMA
+// tiles; otherwise streaming if it applies at all; else generic.
+tcx_error_t route(Product* p) {
+    tcx_error_t err = TCX_SUCCESS;
+    p->an.path = p->analysed_path;
+    const bool low_ai = stream_preferred(p->an, elem_bytes(p->an.dtype));
+    const bool stream_ok = low_ai && build_stream(p) == TCX_SUCCESS;
+    if (stream_ok && (p->stream.staged_per_output <= 0.5 || p->an.path != TCX_PATH_GETT_MFMA)) {
+        p->an.path = TCX_PATH_BANDWIDTH;
+    } else if (p->an.path == TCX_PATH_GETT_MFMA) {
+        choose_plan(p->an, p->handle.num_cu, &p->variant, &p->splitK);
+        err = prepare_tiled(p);
+        if (err == TCX_ERR_UNSUPPORTED_OP) { err = TCX_SUCCESS; p->an.path = TCX_PATH_GENERIC; }
+    }
+    p->an.variant = p->variant;
+    return err;
+}
+
 tcx_error_t tcx_create_product(tcx_handle_t handle, tcx_op_t opA, tcx_tensor_info_t A, const int64_t* labelsA,
                                tcx_op_t opB, tcx_tensor_info_t B, const int64_t* labelsB, tcx_op_t opC,
                                tcx_tensor_info_t C, const int64_t* labelsC, tcx_op_t opD, tcx_tensor_info_t D,
@@ -559,19 +584,8 @@ tcx_error_t tcx_create_product(tcx_handle_t handle, tcx_op_t opA, tcx_tensor_inf
                               (int)opB, (int)opC, (int)opD, (int)precision, &p->an);
     if (err == TCX_SUCCESS) {
         fill_generic(p->an, &p->generic);
-        // Routing.  Low arithmetic intensity goes to the streaming path when its tile re-reads
-        // little operand data per output; otherwise the tiled MFMA path if the free index
-        // space can fill MFMA tiles; otherwise streaming if it applies at all; else generic.
-        const bool low_ai = stream_preferred(p->an, elem_bytes(p->an.dtype));
-        const bool stream_ok = low_ai && build_stream(p) == TCX_SUCCESS;
-        if (stream_ok && (p->stream.staged_per_output <= 0.5 || p->an.path != TCX_PATH_GETT_MFMA)) {
-            p->an.path = TCX_PATH_BANDWIDTH;
-        } else if (p->an.path == TCX_PATH_GETT_MFMA) {
-            choose_plan(p->an, h->num_cu, &p->variant, &p->splitK);
-            err = prepare_tiled(p);
-            if (err == TCX_ERR_UNSUPPORTED_OP) { err = TCX_SUCCESS; p->an.path = TCX_PATH_GENERIC; }
-        }
-        p->an.variant = p->variant;
+        p->analysed_path = p->an.path;
+        err = route(p);
     }
     if (err != TCX_SUCCESS) { delete p; return err; }
     *out = publish(p, MAGIC_PRODUCT);
@@ -811,6 +825,75 @@ tcx_error_t tcx_status_get(tcx_status_t status, int32_t key, void* value, size_t
 }
 
 tcx_error_t tcx_destroy_status(tcx_status_t* status) { return retire<Status>(status, MAGIC_STATUS); }
+
+tcx_error_t tcx_create_attr(tcx_handle_t handle, tcx_attr_t* out) {
+    if (!out) return TCX_ERR_NULL_ARG;
+    if (!lookup<Handle>(handle, MAGIC_HANDLE)) return TCX_ERR_INVALID_HANDLE;
+    Attr* a = new (std::nothrow) Attr;
+    if (!a) return TCX_ERR_ALLOC;
+    *out = publish(a, MAGIC_ATTR);
+    return TCX_SUCCESS;
+}
+
+tcx_error_t tcx_destroy_attr(tcx_attr_t* attr) { return retire<Attr>(attr, MAGIC_ATTR); }
+
+namespace {
+uint32_t type_of(intptr_t object) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    auto it = g_live.find(object);
+    return object != 0 && it != g_live.end() ? it->second : 0u;
+}
+}  // namespace
+
+tcx_error_t tcx_attr_set(tcx_object_t object, int32_t key, const void* value, size_t nbytes) {
+    const uint32_t type = type_of(object);
+    if (!type) return TCX_ERR_INVALID_HANDLE;
+    if (key < TCX_KEY_USER) return type == MAGIC_PRODUCT ? tcx_product_set(object, key, value, nbytes) : TCX_ERR_BAD_KEY;
+    if (!value && nbytes) return TCX_ERR_NULL_ARG;
+    try {
+        std::vector<unsigned char> copy((const unsigned char*)value, (const unsigned char*)value + nbytes);
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (!g_live.count(object)) return TCX_ERR_INVALID_HANDLE;       // destroyed meanwhile
+        g_kv[object][key] = std::move(copy);
+    } catch (const std::bad_alloc&) {
+        return TCX_ERR_ALLOC;
+    }
+    return TCX_SUCCESS;
+}
+
+tcx_error_t tcx_attr_get(tcx_object_t object, int32_t key, void* value, size_t* nbytes) {
+    const uint32_t type = type_of(object);
+    if (!type) return TCX_ERR_INVALID_HANDLE;
+    if (key < TCX_KEY_USER) {
+        if (type == MAGIC_PRODUCT) return tcx_product_get(object, key, value, nbytes);
+        if (type == MAGIC_STATUS) return tcx_status_get(object, key, value, nbytes);
+        return TCX_ERR_BAD_KEY;
+    }
+    if (!nbytes) return TCX_ERR_NULL_ARG;
+    std::lock_guard<std::mutex> lk(g_mu);
+    auto obj = g_kv.find(object);
+    if (obj == g_kv.end()) return TCX_ERR_BAD_KEY;
+    auto it = obj->second.find(key);
+    if (it == obj->second.end()) return TCX_ERR_BAD_KEY;
+    const std::vector<unsigned char>& v = it->second;
+    if (v.empty()) { *nbytes = 0; return TCX_SUCCESS; }
+    return put(v.data(), v.size(), value, nbytes);
+}
+
+tcx_error_t tcx_attr_clear(tcx_object_t object, int32_t key) {
+    const uint32_t type = type_of(object);
+    if (!type) return TCX_ERR_INVALID_HANDLE;
+    if (key < TCX_KEY_USER) {
+        if (type != MAGIC_PRODUCT || (key != TCX_KEY_FORCE_PATH && key != TCX_KEY_VARIANT && key != TCX_KEY_SPLIT_K))
+            return TCX_ERR_BAD_KEY;
+        Product* p = lookup<Product>(object, MAGIC_PRODUCT);
+        return p ? route(p) : TCX_ERR_INVALID_HANDLE;
+    }
+    std::lock_guard<std::mutex> lk(g_mu);
+    auto obj = g_kv.find(object);
+    if (obj == g_kv.end() || !obj->second.erase(key)) return TCX_ERR_BAD_KEY;
+    return TCX_SUCCESS;
+}
 
 int tcx_check_success(tcx_error_t error) { return error == TCX_SUCCESS ? 1 : 0; }
 

@@ -393,3 +393,65 @@ def test_forcing_a_shape_the_plan_cannot_take_is_refused(handle):
     T.tcx_product_set(prod, T.TCX_KEY_VARIANT, 2)                # a classic shape is fine
     assert T.tcx_product_get(prod, T.TCX_KEY_VARIANT) == 2 and T.tcx_product_get(prod, T.TCX_KEY_SPLIT_K) == 1
     T.tcx_destroy_product(prod)
+
+
+def test_key_value_stores_on_every_object(handle):
+    """Sec. "Virtual Key-Value Stores": one set/get/clear interface on every object and on a bare
+    store; free-form keys hold arbitrary binary values; the library's own keys are a layer over
+    state kept elsewhere (the plan, the status)."""
+    p = W.config1()
+    ids = W.label_ids(p)
+    infos = [T.tcx_create_tensor_info(handle, 1, t.extents, t.strides) for t in (p.A, p.B, p.D)]
+    labs = [[ids[l] for l in t.labels] for t in (p.A, p.B, p.D)]
+    prod = T.tcx_create_product(handle, 0, infos[0], labs[0], 0, infos[1], labs[1], 0, infos[2], labs[2], 0, infos[2], labs[2])
+    ex = T.tcx_create_executor(handle, 0)
+    bare = T.tcx_create_attr(handle)
+    U = T.TCX_KEY_USER
+    objects = [handle, ex, infos[0], prod, bare]
+    for n, obj in enumerate(objects):
+        assert _code(T.tcx_attr_get, obj, U + 7) == T.TCX_ERR_BAD_KEY                   # never set
+        blob = bytes(range(n, n + 40)) + b"\x00tail"
+        T.tcx_attr_set(obj, U + 7, blob)
+        T.tcx_attr_set(obj, U + 8, b"")                                                # an empty value is a value
+    for n, obj in enumerate(objects):                                                   # stores are per object
+        assert T.tcx_attr_get(obj, U + 7) == bytes(range(n, n + 40)) + b"\x00tail"
+        assert T.tcx_attr_get(obj, U + 8) == b""
+    T.tcx_attr_set(bare, U + 7, b"replaced")
+    assert T.tcx_attr_get(bare, U + 7) == b"replaced"
+    # the two-call protocol of the C interface: size query, short buffer, exact buffer
+    n = ctypes.c_size_t(0)
+    assert T.raw().tcx_attr_get(bare, U + 7, None, ctypes.byref(n)) == T.TCX_ERR_NULL_ARG and n.value == 8
+    buf = ctypes.create_string_buffer(4)
+    n = ctypes.c_size_t(4)
+    assert T.raw().tcx_attr_get(bare, U + 7, buf, ctypes.byref(n)) == T.TCX_ERR_BUFFER_TOO_SMALL and n.value == 8
+    assert T.raw().tcx_attr_get(bare, U + 7, buf, None) == T.TCX_ERR_NULL_ARG
+    assert T.raw().tcx_attr_set(bare, U + 9, None, 3) == T.TCX_ERR_NULL_ARG
+    T.tcx_attr_clear(bare, U + 7)
+    assert _code(T.tcx_attr_get, bare, U + 7) == T.TCX_ERR_BAD_KEY
+    assert _code(T.tcx_attr_clear, bare, U + 7) == T.TCX_ERR_BAD_KEY
+    assert T.tcx_attr_get(bare, U + 8) == b""                                           # other keys stay
+    # the library's own keys: on a product they are the plan's
+    assert T.tcx_attr_get(prod, T.TCX_KEY_SIZE_K) == 576 == T.tcx_product_get(prod, T.TCX_KEY_SIZE_K)
+    assert T.tcx_attr_get(prod, T.TCX_KEY_MODES_K) == T.tcx_product_get(prod, T.TCX_KEY_MODES_K)
+    planned = {k: T.tcx_product_get(prod, k) for k in (T.TCX_KEY_PATH, T.TCX_KEY_VARIANT, T.TCX_KEY_SPLIT_K)}
+    T.tcx_attr_set(prod, T.TCX_KEY_VARIANT, 2)                                          # a tuning override ...
+    T.tcx_attr_set(prod, T.TCX_KEY_SPLIT_K, 2)
+    assert (T.tcx_product_get(prod, T.TCX_KEY_VARIANT), T.tcx_product_get(prod, T.TCX_KEY_SPLIT_K)) == (2, 2)
+    T.tcx_attr_set(prod, T.TCX_KEY_FORCE_PATH, T.TCX_PATH_GENERIC)
+    assert T.tcx_product_get(prod, T.TCX_KEY_PATH) == T.TCX_PATH_GENERIC
+    T.tcx_attr_clear(prod, T.TCX_KEY_FORCE_PATH)                                        # ... and back to the analyser's choice
+    assert {k: T.tcx_product_get(prod, k) for k in planned} == planned
+    assert _code(T.tcx_attr_clear, prod, T.TCX_KEY_SIZE_K) == T.TCX_ERR_BAD_KEY         # not something that can be cleared
+    assert _code(T.tcx_attr_set, prod, T.TCX_KEY_SIZE_K, 5) == T.TCX_ERR_BAD_KEY
+    assert _code(T.tcx_attr_get, handle, T.TCX_KEY_SIZE_K) == T.TCX_ERR_BAD_KEY         # a handle has no such key
+    assert _code(T.tcx_attr_set, ex, T.TCX_KEY_VARIANT, 1) == T.TCX_ERR_BAD_KEY
+    # destroyed objects: invalid handle, and their values are gone with them
+    assert T.tcx_destroy_attr(bare) == 0
+    assert _code(T.tcx_attr_get, bare, U + 8) == T.TCX_ERR_INVALID_HANDLE
+    assert _code(T.tcx_attr_set, 0, U, b"x") == T.TCX_ERR_INVALID_HANDLE
+    assert _code(T.tcx_destroy_attr, bare) == T.TCX_ERR_INVALID_HANDLE
+    assert _code(T.tcx_destroy_attr, prod) == T.TCX_ERR_INVALID_HANDLE                  # wrong object type
+    T.tcx_destroy_product(prod)
+    T.tcx_destroy_executor(ex)
+    for i in infos:
+        T.tcx_destroy_tensor_info(i)

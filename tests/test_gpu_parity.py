@@ -378,3 +378,40 @@ def test_round_by_round_launch(dist):
     assert res["ok"], res
     if dist == "ints":
         assert res["bit_exact"], res
+
+
+def test_key_value_interface_on_a_status_and_a_replanned_product():
+    """The unified key-value interface on objects that only exist with a device: a status object
+    answers its keys through it and carries free-form values; a product whose tuning overrides were
+    set and then cleared through it computes the same result as before."""
+    import torch
+    import paper_2601_07827_amd as T
+    from gpu_helpers import GpuProduct
+    p = W.config1(16)
+    a, b, c = W.make_operands(p)
+    truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+    gp = GpuProduct(p)
+    try:
+        planned = {k: gp.get(k) for k in (T.TCX_KEY_PATH, T.TCX_KEY_VARIANT, T.TCX_KEY_SPLIT_K)}
+        for step in ("planned", "forced", "cleared"):
+            if step == "forced":
+                T.tcx_attr_set(gp.prod, T.TCX_KEY_FORCE_PATH, GETT)
+                T.tcx_attr_set(gp.prod, T.TCX_KEY_VARIANT, 1)
+                T.tcx_attr_set(gp.prod, T.TCX_KEY_SPLIT_K, 2)
+            if step == "cleared":
+                T.tcx_attr_clear(gp.prod, T.TCX_KEY_VARIANT)
+                assert {k: gp.get(k) for k in planned} == planned
+            dA, dB, dD = torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda(), torch.from_numpy(c.copy()).cuda()
+            st = T.tcx_execute_product(gp.prod, gp.ex, gp.dtype, p.alpha, dA.data_ptr(), dB.data_ptr(), p.beta,
+                                       dD.data_ptr(), dD.data_ptr(), want_status=True)
+            torch.cuda.synchronize()
+            for key in (T.TCX_KEY_PATH, T.TCX_KEY_VARIANT, T.TCX_KEY_GRID, T.TCX_KEY_HIP_ERROR):
+                assert T.tcx_attr_get(st, key) == T.tcx_status_get(st, key)
+            if step == "forced":
+                assert (T.tcx_attr_get(st, T.TCX_KEY_PATH), T.tcx_attr_get(st, T.TCX_KEY_VARIANT)) == (GETT, 1)
+            T.tcx_attr_set(st, T.TCX_KEY_USER + 1, step.encode())
+            assert T.tcx_attr_get(st, T.TCX_KEY_USER + 1) == step.encode()
+            assert T.tcx_destroy_status(st) == 0
+            assert normalised_error(p, dD.cpu().numpy(), truth, S, c) <= TOLERANCE[p.dtype], step
+    finally:
+        gp.close()
