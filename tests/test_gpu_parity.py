@@ -415,3 +415,81 @@ def test_key_value_interface_on_a_status_and_a_replanned_product():
             assert normalised_error(p, dD.cpu().numpy(), truth, S, c) <= TOLERANCE[p.dtype], step
     finally:
         gp.close()
+
+
+def _sub(labels, ext, parent_ext, fixed=None, negative=()):
+    """A sub-tensor: a box of extents `ext` inside a column-major parent with extents `parent_ext`
+    over the same label order plus the labels in `fixed` (parent indices held fixed: a view with
+    fewer modes than its parent); labels in `negative` are walked backwards."""
+    fixed = fixed or {}
+    order = list(labels) + [l for l in fixed if l not in labels]
+    stride, run = {}, 1
+    for l in order:
+        stride[l] = run
+        run *= parent_ext[l]
+    strides = [(-stride[l] if l in negative else stride[l]) for l in labels]
+    e = tuple(ext[l] for l in labels)
+    base, _ = W.span_of(e, strides)
+    return W.TensorSpec(tuple(labels), e, tuple(strides), base + sum(i * stride[l] for l, i in fixed.items()), run)
+
+
+def _paper_list_cases():
+    ext = dict(h=3, m=20, n=17, k=9, l=5, x=4)
+    big = dict(h=5, m=33, n=19, k=12, l=7, x=6)
+    rep, run = [], 1
+    for l in "kmk":                                        # A[k,m,k]: a repeated label, each position its own stride
+        rep.append(run)
+        run *= ext[l]
+    A_rep = W.TensorSpec(("k", "m", "k"), (ext["k"], ext["m"], ext["k"]), tuple(rep), 0, run)
+    t = W.tensor
+    cases = [
+        ("t7_all_contracted", t("kl", ext), t("lk", ext), t("", ext)),
+        ("t8_zero_mode_A", t("", ext), t("nm", ext), t("mn", ext)),
+        ("t8_zero_mode_all", t("", ext), t("", ext), t("", ext)),
+        ("t9_one_mode", t("k", ext), t("k", ext), t("", ext)),
+        ("t9_one_mode_outer", t("m", ext), t("n", ext), t("nm", ext)),
+        ("t10_subtensors_same_modes", _sub("mk", ext, big), _sub("kn", ext, big), _sub("mn", ext, big)),
+        ("t11_subtensors_fewer_modes", _sub("mk", ext, big, fixed={"x": 2}), _sub("kn", ext, big, fixed={"h": 1}),
+         _sub("mn", ext, big, fixed={"l": 3})),
+        ("t13_subtensors_negative", _sub("mk", ext, big, negative="k"), _sub("kn", ext, big, negative="kn"),
+         _sub("mn", ext, big, negative="m")),
+        ("t17_mixed_signs_fewer_modes", _sub("mkl", ext, big, fixed={"x": 1}, negative="l"), _sub("lkn", ext, big, negative="n"),
+         _sub("nm", ext, big, fixed={"h": 2}, negative="n")),
+        ("t21_zero_stride_A", t("mk", ext, strides={"m": 0, "k": 1}), t("kn", ext), t("mn", ext)),
+        ("t21_zero_stride_B_k", t("mk", ext), t("kn", ext, strides={"k": 0, "n": 1}), t("mn", ext)),
+        ("t23_repeated_label", A_rep, t("kn", ext), t("nm", ext)),
+        ("t24_hadamard_free", t("hm", ext), t("nh", ext), t("mhn", ext)),
+        ("t25_hadamard_contracted", t("hkm", ext), t("khl", ext), t("hlm", ext)),
+    ]
+    out = []
+    for name, A, B, D in cases:
+        for dtype in ("f64", "c128"):
+            out.append(W.Problem("%s_%s" % (name, dtype), dtype, A, B, D, alpha=2.0, beta=-1.0,
+                                 opA=int(dtype == "c128"), seed=W.BASE_SEED + 31))
+    return out
+
+
+@pytest.mark.parametrize("p", _paper_list_cases(), ids=lambda p: p.name)
+def test_shapes_of_the_papers_test_list(p):
+    """The shapes of the paper's own test list (Sec. "Testing") that the other tests do not reach:
+    everything contracted, tensors with zero modes and with one mode, sub-tensors with as many and
+    with fewer modes than their parents, with negative and mixed strides, a zero stride in an input,
+    a repeated label, Hadamard labels combined with free and with contracted ones — on every kernel
+    path that accepts the plan, integer inputs bit for bit."""
+    from gpu_helpers import run_gpu, say
+    a, b, c = W.make_operands(p, "ints")
+    truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+    ran = 0
+    for path in (None, GENERIC, GETT, STREAM):
+        say("%s path=%s" % (p.name, path))
+        try:
+            got = run_gpu(p, a, b, c, force_path=path)
+        except Exception as exc:
+            if path in (GETT, STREAM) and getattr(exc, "code", None) == 11:
+                say("  (path declined this plan)")
+                continue
+            raise
+        ran += 1
+        assert gaps_untouched(p, c, got)
+        assert np.array_equal(W.strided_view(got, p.D), W.strided_view(truth, p.D)), path
+    assert ran >= 2
