@@ -235,6 +235,13 @@ __device__ __forceinline__ int64_t xcd_contiguous(int64_t id, int64_t nb) {
     return id < per * 8 ? (id % 8) * per + id / 8 : id;
 }
 
+// Quotient of two non-negative numbers.  A 64-bit division costs a few hundred cycles on this
+// chip (no hardware divider); tile and item numbers nearly always fit 32 bits, where it costs a
+// fraction of that, and a workgroup does several before its first load can go out.
+__device__ __forceinline__ int64_t quotient(int64_t a, int64_t b) {
+    return ((uint64_t)(a | b) >> 32) == 0 ? (int64_t)((uint32_t)a / (uint32_t)b) : a / b;
+}
+
 struct Tile {
     int64_t m0, n0;          // first row / column of the tile in the linearised M, N index
     int64_t hA, hB, hD;      // base offsets from the hyper index
@@ -242,9 +249,10 @@ struct Tile {
 
 // Tile number -> tile coordinates.  Tiles are walked in bands of 8 tile-rows; the hyper index
 // is the slowest (Eq. case2: an independent product per value of H).
+template <bool FAST = false>
 __device__ __forceinline__ Tile locate_tile(int64_t t_all, const GettArgs& g, int mt_m, int mt_n) {
     const int64_t tiles_per_h = (int64_t)g.tilesM * g.tilesN;
-    const int64_t h = t_all / tiles_per_h;
+    const int64_t h = FAST ? quotient(t_all, tiles_per_h) : t_all / tiles_per_h;
     const int t = (int)(t_all - h * tiles_per_h);
     constexpr int BAND = 8;
     const int band = t / (BAND * g.tilesN);
@@ -257,7 +265,7 @@ __device__ __forceinline__ Tile locate_tile(int64_t t_all, const GettArgs& g, in
     r.hA = r.hB = r.hD = 0;
     int64_t rem = h;
     for (int i = 0; i < g.nH; ++i) {
-        const int64_t q = rem / g.hExt[i], idx = rem - q * g.hExt[i];
+        const int64_t q = FAST ? quotient(rem, g.hExt[i]) : rem / g.hExt[i], idx = rem - q * g.hExt[i];
         rem = q;
         r.hA += idx * g.hSA[i];
         r.hB += idx * g.hSB[i];
@@ -269,6 +277,53 @@ __device__ __forceinline__ Tile locate_tile(int64_t t_all, const GettArgs& g, in
 // alpha/beta epilogue of one thread's accumulators: strided scatter through D's offset tables.
 // The reads of C for a whole row of fragments are issued together before any of them is used,
 // so a thread pays the memory latency FM times rather than once per element.
+// Small real tiles read D's offsets before the main loop (registers are plentiful there), so
+// that the epilogue starts with its stores instead of with a table read per row of fragments.
+template <class P, int FM, int FN> struct DOffsets {
+    int64_t off[FM][FN][4];
+    bool ok[FM][FN][4];
+};
+template <class P, int FM, int FN, int WT_M, int WT_N, bool DNF>
+__device__ __forceinline__ void d_offsets(DOffsets<P, FM, FN>& o, const GettArgs& g, const Tile& tile, int wm, int wn, int lane) {
+    using MF = typename P::MF;
+    const int fr = lane & 15;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int rr = MF::row_of(lane, v);
+                const int ml = wm * WT_M + i * 16 + (DNF ? rr : fr);
+                const int nl = wn * WT_N + j * 16 + (DNF ? fr : rr);
+                o.ok[i][j][v] = tile.m0 + ml < g.sizeM && tile.n0 + nl < g.sizeN;
+                o.off[i][j][v] = tile.hD + g.oDM[tile.m0 + ml] + g.oDN[tile.n0 + nl];      // padded tables: always a valid entry
+            }
+}
+template <class P, int FM, int FN>
+__device__ __forceinline__ void scatter_at(const typename P::acc_t (&acc)[FM][FN], const GettArgs& g, const DOffsets<P, FM, FN>& o) {
+    using T = typename P::elem;
+    const T* __restrict__ C = (const T*)g.C;
+    T* __restrict__ D = (T*)g.D;
+    const bool read_c = g.read_c != 0;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        T cval[FN][4];
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                cval[j][v] = P::zero();
+                if (read_c && o.ok[i][j][v]) cval[j][v] = C[o.off[i][j][v]];
+            }
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (o.ok[i][j][v]) D[o.off[i][j][v]] = P::combine(acc[i][j], v, g.s, read_c, cval[j][v], g.opC);
+    }
+}
+
 template <class P, int FM, int FN, int WT_M, int WT_N, bool DNF>
 __device__ __forceinline__ void scatter(const typename P::acc_t (&acc)[FM][FN], const GettArgs& g, const Tile& tile,
                                         int wm, int wn, int lane) {
@@ -678,7 +733,7 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
     const int per_split = (nk + g.splitK - 1) / g.splitK;
     auto slabs_of = [&](int64_t item, int* first) __attribute__((always_inline)) {
         if (item >= items) { *first = 0; return 0; }
-        const int sp = (int)(item % g.splitK);
+        const int sp = DUAL ? (int)(item - quotient(item, g.splitK) * g.splitK) : (int)(item % g.splitK);
         *first = sp * per_split;
         return max(0, min(nk, *first + per_split) - *first);
     };
@@ -686,7 +741,10 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
     const int n = wave_uniform(slabs_of(lid, &kb));
     const int n_all = DUAL ? wave_uniform(max(n, slabs_of(lid ^ 1, &kb_other))) : n;
     kb = wave_uniform(kb);
-    const Tile tile = locate_tile(min(lid, items - 1) / g.splitK, g, MT_M, MT_N);
+    // (the short divisions only in the small-tile instantiations, whose prologue matters; the
+    // large tile's steady state is sensitive to any change of its code and keeps what it had)
+    const Tile tile = DUAL ? locate_tile<true>(quotient(min(lid, items - 1), g.splitK), g, MT_M, MT_N)
+                           : locate_tile(min(lid, items - 1) / g.splitK, g, MT_M, MT_N);
     const int64_t m0 = wave_uniform(tile.m0), n0 = wave_uniform(tile.n0);
     const char* const Ab = (const char*)g.A + wave_uniform(tile.hA * (int64_t)sizeof(T) + scalar_table(g.rbA)[m0 / MT_M]);
     const char* const Bb = (const char*)g.B + wave_uniform(tile.hB * (int64_t)sizeof(T) + scalar_table(g.rbB)[n0 / MT_N]);
@@ -717,6 +775,10 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
         voB[i] = g.rrB[n0 + rowB_of(e)] + (BLANES_K ? g.krB[kinB_of(e)] : 0u);
         kinB[i] = BLANES_K ? 0u : (unsigned)__builtin_amdgcn_readfirstlane(SB::kin(e));
     }
+    // small real tiles: D's offsets too, in the same round trip to the tables
+    constexpr bool D_AHEAD = DUAL && sizeof(T) <= 8 && FM * FN <= 8;
+    DOffsets<P, D_AHEAD ? FM : 1, D_AHEAD ? FN : 1> d_at;
+    if constexpr (D_AHEAD) d_offsets<P, FM, FN, WT_M, WT_N, DNF>(d_at, g, tile, wm, wn, lane);
     // LDS byte addresses, per LDS slab: where this thread writes its first element of A and of
     // B, and where it reads its first fragment of A and of B.  Further elements / fragments are
     // at compile-time offsets from these.
@@ -862,13 +924,20 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
     };
 
     // Prologue: slab kb to LDS, slabs kb+1 .. kb+DEPTH into the ring (slab numbers past the end
-    // are clamped: harmless loads that are never staged).
+    // are clamped: harmless loads that are never staged).  With a ring of two or more the second
+    // slab's loads go out before the wait for the first (its slot is free), so that the first
+    // iteration does not meet a second load latency.
     if (n > 0) {
+        constexpr int EARLY = DEPTH >= 2 ? 1 : 0;
         k_offsets(kb);
         gather(std::integral_constant<int, 0>{}, kb, 0, 1);
         k_offsets(kb + 1);
+        if constexpr (EARLY) {
+            gather(std::integral_constant<int, 1 % DEPTH>{}, kb + 1, 0, 1);
+            k_offsets(kb + 2);
+        }
         stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, kb);
-        static_for<0, DEPTH>([&](auto D) __attribute__((always_inline)) {
+        static_for<EARLY, DEPTH>([&](auto D) __attribute__((always_inline)) {
             gather(std::integral_constant<int, (1 + decltype(D)::value) % DEPTH>{}, kb + 1 + decltype(D)::value, 0, 1);
             k_offsets(kb + 2 + decltype(D)::value);
         });
@@ -951,7 +1020,8 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
         __syncthreads();
         if (!second_group) {
             P::template accumulate<FM, FN>(acc, part + tid, NTG);
-            scatter<P, FM, FN, WT_M, WT_N, DNF>(acc, g, tile, wm, wn, lane);
+            if constexpr (D_AHEAD) scatter_at<P, FM, FN>(acc, g, d_at);
+            else scatter<P, FM, FN, WT_M, WT_N, DNF>(acc, g, tile, wm, wn, lane);
         }
         return;
     }
@@ -960,7 +1030,8 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
         typename P::real* ws = (typename P::real*)g.workspace + (size_t)lid * (NTG * P::template acc_reals<FM, FN>());
         P::template spill<FM, FN>(acc, ws + tid, NTG);
     } else {
-        scatter<P, FM, FN, WT_M, WT_N, DNF>(acc, g, tile, wm, wn, lane);
+        if constexpr (D_AHEAD) scatter_at<P, FM, FN>(acc, g, d_at);
+        else scatter<P, FM, FN, WT_M, WT_N, DNF>(acc, g, tile, wm, wn, lane);
     }
 }
 
