@@ -212,13 +212,13 @@ def test_two_phase_kernel_paired_loads():
     whose contiguous neighbours are four rows apart inside the tile."""
     from gpu_helpers import GpuProduct, say
     import paper_2601_07827_amd as T
-    for flags in range(8):
+    for flags, k in [(f, 96) for f in range(8)] + [(5, 16), (2, 32), (7, 48), (0, 80)]:    # short loops: 1 - 5 slabs
         akf, bkf, dnf = bool(flags & 4), bool(flags & 2), bool(flags & 1)
-        p = _matrix_product(256, 384, 96, akf, bkf, dnf, "f64")
+        p = _matrix_product(256, 384, k, akf, bkf, dnf, "f64")
         a, b, c = W.make_operands(p, "ints")
         truth, _ = run_oracle(p, a, b, c, oracle.MODE_TRUTH)
         for variant in (10, 11):
-            for parts in (None, 2, 3):
+            for parts in (None, 2, 3) if k >= 48 else (None,):
                 gp = GpuProduct(p, GETT, variant, parts)
                 try:
                     assert gp.get(T.TCX_KEY_GATHER_WIDTH) == 2
