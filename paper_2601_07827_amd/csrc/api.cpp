@@ -55,7 +55,7 @@ struct Product {
     // bandwidth path: plan and its device tables (one allocation)
     StreamPlan stream;
     unsigned char* dev_stream = nullptr;
-    size_t stream_off[6] = {0, 0, 0, 0, 0, 0};   // rowAB, dD, itemsA, itemsB, tabLo, tabHi
+    size_t stream_off[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // rowAB, dD, itemsA, itemsB, tabLo, tabHi, laneA, laneB
 };
 struct Status {
     int64_t path = 0, variant = 0, grid = 0, block = 0, tile_m = 0, tile_n = 0, tile_k = 0, hip_error = 0, gather_width = 1;
@@ -402,19 +402,21 @@ tcx_error_t build_stream(Product* p, bool allow_blocked = true) {
     if (!p->stream.ok) return TCX_ERR_UNSUPPORTED_OP;
     if (!p->handle.has_device) return TCX_SUCCESS;
     const StreamPlan& sp = p->stream;
-    const size_t bytes[6] = {sp.rowAB.size() * sizeof(uint32_t), sp.dD.size() * sizeof(int64_t),
+    const size_t bytes[8] = {sp.rowAB.size() * sizeof(uint32_t), sp.dD.size() * sizeof(int64_t),
                              sp.itemsA.size() * sizeof(StreamItem), sp.itemsB.size() * sizeof(StreamItem),
-                             sp.tabLo.size() * sizeof(int64_t), sp.tabHi.size() * sizeof(int64_t)};
-    const void* src[6] = {sp.rowAB.data(), sp.dD.data(), sp.itemsA.data(), sp.itemsB.data(), sp.tabLo.data(), sp.tabHi.data()};
+                             sp.tabLo.size() * sizeof(int64_t), sp.tabHi.size() * sizeof(int64_t),
+                             sp.laneA.size() * sizeof(int64_t), sp.laneB.size() * sizeof(int64_t)};
+    const void* src[8] = {sp.rowAB.data(), sp.dD.data(), sp.itemsA.data(), sp.itemsB.data(), sp.tabLo.data(), sp.tabHi.data(),
+                          sp.laneA.data(), sp.laneB.data()};
     size_t total = 0;
-    for (int i = 0; i < 6; ++i) { p->stream_off[i] = total; total += (bytes[i] + 255) / 256 * 256; }
+    for (int i = 0; i < 8; ++i) { p->stream_off[i] = total; total += (bytes[i] + 255) / 256 * 256; }
     if (hipMalloc((void**)&p->dev_stream, total) != hipSuccess) {
         p->dev_stream = nullptr;
         (void)hipGetLastError();
         return TCX_ERR_ALLOC;
     }
-    for (int i = 0; i < 6; ++i)
-        if (hipMemcpy(p->dev_stream + p->stream_off[i], src[i], bytes[i], hipMemcpyHostToDevice) != hipSuccess) {
+    for (int i = 0; i < 8; ++i)
+        if (bytes[i] && hipMemcpy(p->dev_stream + p->stream_off[i], src[i], bytes[i], hipMemcpyHostToDevice) != hipSuccess) {
             (void)hipGetLastError();
             (void)hipFree(p->dev_stream);
             p->dev_stream = nullptr;
@@ -738,6 +740,9 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
         g.dD = (const int64_t*)(p->dev_stream + p->stream_off[1]);
         g.itemsA = (const StreamItem*)(p->dev_stream + p->stream_off[2]);
         g.itemsB = (const StreamItem*)(p->dev_stream + p->stream_off[3]);
+        g.laneA = (const int64_t*)(p->dev_stream + p->stream_off[6]);
+        g.laneB = (const int64_t*)(p->dev_stream + p->stream_off[7]);
+        for (int i = 0; i < kStreamRegBlock; ++i) { g.aReg[i] = sp.aReg[i]; g.bReg[i] = sp.bReg[i]; g.aK[i] = sp.aK[i]; g.bK[i] = sp.bK[i]; }
         g.nItemsA = (int32_t)sp.itemsA.size(); g.nItemsB = (int32_t)sp.itemsB.size();
         g.tile = sp.tile; g.inner = sp.inner; g.chunk = sp.chunk; g.K = sp.K; g.rowsA = sp.rowsA; g.rowsB = sp.rowsB;
         g.regA = sp.regA; g.regB = sp.regB; g.rowStepA = sp.rowStepA; g.rowStepB = sp.rowStepB;
@@ -748,7 +753,7 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
         g.s = s;
         g.opA = p->an.opA; g.opB = p->an.opB; g.opC = p->an.opC;
         g.read_c = read_c;
-        hip_err = launch_stream(p->an.dtype, sp.blocked, g, sp.lds_bytes, p->handle.num_cu, (void*)e->stream, &grid, &block);
+        hip_err = launch_stream(p->an.dtype, sp.blocked, sp.direct, g, sp.lds_bytes, p->handle.num_cu, (void*)e->stream, &grid, &block);
         st.path = TCX_PATH_BANDWIDTH;
         st.variant = sp.blocked ? 1 : 0;
         st.tile_m = sp.tile; st.tile_n = sp.regA * sp.regB; st.tile_k = sp.K;

@@ -299,8 +299,75 @@ __global__ __launch_bounds__(kStreamThreads) void stream_blocked_kernel(StreamAr
     }
 }
 
+// Blocked tiles whose lanes all run along hyper (batch) modes: no lane shares an operand element
+// with another, so there is nothing to stage.  Every lane reads the regA + regB operand rows of
+// its own batch index straight from memory, contracted index by contracted index, and keeps the
+// regA x regB accumulators in registers; loads and stores coalesce along the batch modes.  No
+// LDS, no barrier; the waves of a CU cover each other's load latency.
+template <class T, int KC>
+__global__ __launch_bounds__(kStreamThreads) void stream_direct_kernel(StreamArgs g) {
+    using N_ = SNum<T>;
+    constexpr int RB = kStreamRegBlock;
+    const int tid = threadIdx.x;
+    if (tid >= g.tile) return;
+    const int64_t offA = g.laneA[tid], offB = g.laneB[tid], offD = g.dD[tid];
+    const int64_t step = gridDim.x;
+    for (int64_t tile = blockIdx.x; tile < g.num_tiles; tile += step) {
+        const int64_t hi = tile / g.outer_lo, lo = tile - hi * g.outer_lo;
+        const int64_t* pl = g.tabLo + lo * 4;
+        const int64_t* ph = g.tabHi + hi * 4;
+        const T* A = (const T*)g.A + pl[0] + ph[0] + offA;
+        const T* B = (const T*)g.B + pl[1] + ph[1] + offB;
+        const T* C = (const T*)g.C + pl[2] + ph[2] + offD;
+        T* D = (T*)g.D + pl[2] + ph[2] + offD;
+        // Straight-line code: register indices beyond the block repeat its last row (a load that
+        // hits the cache, an unused product) instead of branching around the loads, so that the
+        // loads of a tile are issued together and waited for once.
+        T acc[RB][RB];
+#pragma unroll
+        for (int ra = 0; ra < RB; ++ra)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) acc[ra][rb] = N_::zero();
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+            T a[RB], b[RB];
+#pragma unroll
+            for (int r = 0; r < RB; ++r) a[r] = N_::ld(A, g.aReg[min(r, g.regA - 1)] + g.aK[k], g.opA);
+#pragma unroll
+            for (int r = 0; r < RB; ++r) b[r] = N_::ld(B, g.bReg[min(r, g.regB - 1)] + g.bK[k], g.opB);
+#pragma unroll
+            for (int ra = 0; ra < RB; ++ra)
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) acc[ra][rb] = N_::fma(a[ra], b[rb], acc[ra][rb]);
+        }
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const int64_t col = g.dRegB[min(rb, g.regB - 1)];
+            T cv[RB];
+#pragma unroll
+            for (int ra = 0; ra < RB; ++ra) cv[ra] = N_::zero();
+            if (g.read_c) {
+#pragma unroll
+                for (int ra = 0; ra < RB; ++ra) cv[ra] = C[g.dRegA[min(ra, g.regA - 1)] + col];
+            }
+#pragma unroll
+            for (int ra = 0; ra < RB; ++ra)
+                if (ra < g.regA && rb < g.regB) D[g.dRegA[ra] + col] = N_::out(g.s, acc[ra][rb], g.read_c != 0, cv[ra], g.opC);
+        }
+    }
+}
+
 template <class T>
-hipError_t launch_k(bool blocked, const StreamArgs& a, size_t lds, unsigned blocks, hipStream_t st) {
+hipError_t launch_k(bool blocked, bool direct, const StreamArgs& a, size_t lds, unsigned blocks, hipStream_t st) {
+    if (blocked && direct) {
+        switch (a.K) {
+            case 1: stream_direct_kernel<T, 1><<<dim3(blocks), dim3(kStreamThreads), 0, st>>>(a); break;
+            case 2: stream_direct_kernel<T, 2><<<dim3(blocks), dim3(kStreamThreads), 0, st>>>(a); break;
+            case 4: stream_direct_kernel<T, 4><<<dim3(blocks), dim3(kStreamThreads), 0, st>>>(a); break;
+            default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
     if (blocked) {
         const int need = (std::max(a.nItemsA, a.nItemsB) + kStreamThreads - 1) / kStreamThreads;
         if (need > kStreamPerThread) return hipErrorInvalidValue;
@@ -330,7 +397,7 @@ hipError_t launch_k(bool blocked, const StreamArgs& a, size_t lds, unsigned bloc
 
 }  // namespace
 
-int launch_stream(int dtype, bool blocked, const StreamArgs& args, size_t lds_bytes, int num_cu, void* stream,
+int launch_stream(int dtype, bool blocked, bool direct, const StreamArgs& args, size_t lds_bytes, int num_cu, void* stream,
                   int64_t* grid, int* block) {
     // persistent-style grid: enough workgroups to fill every CU several times over, each
     // walking the tile list with a grid stride
@@ -341,9 +408,9 @@ int launch_stream(int dtype, bool blocked, const StreamArgs& args, size_t lds_by
     if (blocks <= 0) return (int)hipErrorInvalidConfiguration;
     hipStream_t st = (hipStream_t)stream;
     switch (dtype) {
-        case TCX_F64: return (int)launch_k<double>(blocked, args, lds_bytes, (unsigned)blocks, st);
-        case TCX_F32: return (int)launch_k<float>(blocked, args, lds_bytes, (unsigned)blocks, st);
-        case TCX_C128: return (int)launch_k<double2>(blocked, args, lds_bytes, (unsigned)blocks, st);
+        case TCX_F64: return (int)launch_k<double>(blocked, direct, args, lds_bytes, (unsigned)blocks, st);
+        case TCX_F32: return (int)launch_k<float>(blocked, direct, args, lds_bytes, (unsigned)blocks, st);
+        case TCX_C128: return (int)launch_k<double2>(blocked, direct, args, lds_bytes, (unsigned)blocks, st);
         default: return (int)hipErrorInvalidValue;
     }
 }

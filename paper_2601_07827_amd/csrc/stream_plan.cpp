@@ -60,16 +60,23 @@ bool build(const std::vector<DMode>& dm, const std::vector<Piece>& pieces, bool 
     const int64_t cap = (int64_t)kStreamThreads * kStreamPerThread;      // what a workgroup's registers hold
     const size_t lds = (size_t)(rowsA + rowsB) * (size_t)K * (size_t)elem_bytes;
     const bool blocked = ra * rb > 1;
-    if (lds > 64 * 1024 || rowsA * K > cap || rowsB * K > cap || rowsA > 65535 || rowsB > 65535) return false;
+    // Lanes that all run along hyper modes share no operand element: staging through LDS would
+    // only add traffic, and every lane reads its own rows straight from memory instead (the
+    // loads coalesce as the stores do when the hyper modes are the operands' fastest too).
+    bool direct = blocked && K <= kStreamRegBlock;
+    for (const Piece& pc : pieces)
+        if (pc.role == LANE && !(dm[(size_t)pc.mode].inA && dm[(size_t)pc.mode].inB)) direct = false;
+    if (!direct && (lds > 64 * 1024 || rowsA * K > cap || rowsB * K > cap || rowsA > 65535 || rowsB > 65535)) return false;
     if (blocked ? lanes > kStreamThreads : lanes > cap) return false;
     if (ra > kStreamRegBlock || rb > kStreamRegBlock) return false;
 
     p.blocked = blocked;
+    p.direct = direct;
     p.tile = (int32_t)lanes;
     p.regA = (int32_t)ra; p.regB = (int32_t)rb;
     p.rowsA = (int32_t)rowsA; p.rowsB = (int32_t)rowsB;
     p.rowStepA = (int32_t)rowsA_lane; p.rowStepB = (int32_t)rowsB_lane;
-    p.lds_bytes = lds;
+    p.lds_bytes = direct ? 0 : lds;
 
     // the ragged piece, if any, is the last LANE piece
     int last_lane = -1;
@@ -85,6 +92,7 @@ bool build(const std::vector<DMode>& dm, const std::vector<Piece>& pieces, bool 
     for (const Piece& pc : pieces) if (pc.role == LANE) lp.push_back(&pc);
     p.rowAB.assign((size_t)lanes, 0);
     p.dD.assign((size_t)lanes, 0);
+    if (direct) { p.laneA.assign((size_t)lanes, 0); p.laneB.assign((size_t)lanes, 0); }
     {
         std::vector<int64_t> idx(lp.size(), 0);
         for (int64_t l = 0; l < lanes; ++l) {
@@ -92,6 +100,10 @@ bool build(const std::vector<DMode>& dm, const std::vector<Piece>& pieces, bool 
             for (size_t i = 0; i < lp.size(); ++i) {
                 const DMode& d = dm[(size_t)lp[i]->mode];
                 offD += idx[i] * lp[i]->mult * d.m.sD;
+                if (direct) {
+                    p.laneA[(size_t)l] += idx[i] * lp[i]->mult * d.m.sA;
+                    p.laneB[(size_t)l] += idx[i] * lp[i]->mult * d.m.sB;
+                }
                 if (d.inA) { rA += idx[i] * wa; wa *= lp[i]->count; }
                 if (d.inB) { rB += idx[i] * wb; wb *= lp[i]->count; }
             }
@@ -104,13 +116,13 @@ bool build(const std::vector<DMode>& dm, const std::vector<Piece>& pieces, bool 
         }
     }
     // register-block offsets in D
-    auto reg_offsets = [&](int role, int64_t n, int64_t* dst) {
+    auto reg_offsets = [&](int role, int64_t n, int64_t* dst, int64_t Mode::*stride) {
         std::vector<const Piece*> rp;
         for (const Piece& pc : pieces) if (pc.role == role) rp.push_back(&pc);
         std::vector<int64_t> idx(rp.size(), 0);
         for (int64_t r = 0; r < n; ++r) {
             int64_t off = 0;
-            for (size_t i = 0; i < rp.size(); ++i) off += idx[i] * rp[i]->mult * dm[(size_t)rp[i]->mode].m.sD;
+            for (size_t i = 0; i < rp.size(); ++i) off += idx[i] * rp[i]->mult * (dm[(size_t)rp[i]->mode].m.*stride);
             dst[r] = off;
             for (size_t i = 0; i < rp.size(); ++i) {
                 if (++idx[i] < rp[i]->count) break;
@@ -118,13 +130,19 @@ bool build(const std::vector<DMode>& dm, const std::vector<Piece>& pieces, bool 
             }
         }
     };
-    for (int i = 0; i < kStreamRegBlock; ++i) p.dRegA[i] = p.dRegB[i] = 0;
-    reg_offsets(REG_A, ra, p.dRegA);
-    reg_offsets(REG_B, rb, p.dRegB);
+    for (int i = 0; i < kStreamRegBlock; ++i) p.dRegA[i] = p.dRegB[i] = p.aReg[i] = p.bReg[i] = p.aK[i] = p.bK[i] = 0;
+    reg_offsets(REG_A, ra, p.dRegA, &Mode::sD);
+    reg_offsets(REG_B, rb, p.dRegB, &Mode::sD);
+    if (direct) {
+        reg_offsets(REG_A, ra, p.aReg, &Mode::sA);
+        reg_offsets(REG_B, rb, p.bReg, &Mode::sB);
+    }
 
     // staging lists.  Rows are numbered over the pieces the operand carries: LANE pieces first
     // (as in the lane tables), then its REG pieces.
     const std::vector<int64_t> kA = offset_table(an.K, 0, 0), kB = offset_table(an.K, 1, 0);
+    if (direct)
+        for (int k = 0; k < K; ++k) { p.aK[k] = kA[(size_t)k]; p.bK[k] = kB[(size_t)k]; }
     auto items = [&](bool forA, int64_t rows, const std::vector<int64_t>& kOff) {
         std::vector<const Piece*> op;
         for (const Piece& pc : pieces)
@@ -153,8 +171,10 @@ bool build(const std::vector<DMode>& dm, const std::vector<Piece>& pieces, bool 
         std::stable_sort(v.begin(), v.end(), [](const StreamItem& a, const StreamItem& b) { return a.src < b.src; });
         return v;
     };
-    p.itemsA = items(true, rowsA, kA);
-    p.itemsB = items(false, rowsB, kB);
+    if (!direct) {
+        p.itemsA = items(true, rowsA, kA);
+        p.itemsB = items(false, rowsB, kB);
+    }
 
     // LDS bank conflicts of a flat tile.  Rows are numbered in D's lane order, so the lanes read
     // consecutive rows; the staging writes go in the operand's own address order, which for a

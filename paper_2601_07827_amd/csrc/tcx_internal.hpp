@@ -147,6 +147,7 @@ struct StreamItem {        // one element to stage: where it comes from and wher
 struct StreamPlan {
     bool ok = false;
     bool blocked = false;      // threads own a regA x regB register block of outputs
+    bool direct = false;       // blocked tile whose lanes all run along hyper modes: every lane has operand rows of its own, read straight from memory
     int32_t tile = 0;          // lane indices per tile (flat: outputs per full tile = inner * chunk)
     int32_t inner = 0;         // flat tiles: product of the tile modes below the split mode
     int32_t chunk = 1;         // flat tiles: indices of the split mode per tile
@@ -159,6 +160,9 @@ struct StreamPlan {
     // host tables
     std::vector<uint32_t> rowAB;     // [tile]: rowA | rowB << 16 of a lane index
     std::vector<int64_t> dD;         // [tile]: D offset of a lane index relative to the tile base
+    std::vector<int64_t> laneA, laneB;   // direct tiles, [tile]: A / B offset of a lane index
+    int64_t aReg[kStreamRegBlock], bReg[kStreamRegBlock];   // direct tiles: A / B offset per register index
+    int64_t aK[kStreamRegBlock], bK[kStreamRegBlock];       // direct tiles: A / B offset per contracted index (K <= 4)
     std::vector<StreamItem> itemsA, itemsB;
     // tile index -> base offsets: tile = lo + outer_lo * hi; rows are (offA, offB, offD, digits)
     int64_t outer_lo = 1;
@@ -176,6 +180,9 @@ struct StreamArgs {
     const int64_t* dD;
     const StreamItem* itemsA;
     const StreamItem* itemsB;
+    const int64_t* laneA;      // direct tiles
+    const int64_t* laneB;
+    int64_t aReg[kStreamRegBlock], bReg[kStreamRegBlock], aK[kStreamRegBlock], bK[kStreamRegBlock];
     int32_t nItemsA, nItemsB;
     int32_t tile, inner, chunk, K, rowsA, rowsB;
     int32_t regA, regB, rowStepA, rowStepB;
@@ -195,7 +202,7 @@ StreamPlan plan_stream(const Analysis& an, int elem_bytes, bool allow_blocked = 
 // Arithmetic intensity test + size limits: should this product take the streaming path?
 bool stream_preferred(const Analysis& an, int elem_bytes);
 
-int launch_stream(int dtype, bool blocked, const StreamArgs& args, size_t lds_bytes, int num_cu, void* stream,
+int launch_stream(int dtype, bool blocked, bool direct, const StreamArgs& args, size_t lds_bytes, int num_cu, void* stream,
                   int64_t* grid, int* block);
 
 }  // namespace tcx

@@ -493,3 +493,48 @@ def test_shapes_of_the_papers_test_list(p):
         assert gaps_untouched(p, c, got)
         assert np.array_equal(W.strided_view(got, p.D), W.strided_view(truth, p.D)), path
     assert ran >= 2
+
+
+def _batch_lane_cases():
+    t = W.tensor
+    out = []
+    for dtype in ("f64", "f32", "c128"):
+        for k in (1, 2, 4):
+            e = {"h": 512, "i": 12, "j": 8, "k": k}
+            out.append(W.Problem("batch_lanes_%s_k%d" % (dtype, k), dtype, t("hki", e), t("hkj", e), t("hij", e),
+                                 alpha=2.0, beta=-1.0, opA=int(dtype == "c128"), opB=int(dtype == "c128" and k == 2),
+                                 seed=W.BASE_SEED + 41))
+        # two batch modes that do not fuse (padded), four contracted terms from two modes, A walked backwards along g
+        e = {"g": 16, "h": 32, "i": 6, "j": 10, "p": 2, "q": 2}
+        A = t("ghpqi", e, strides={"g": -1, "h": 20, "p": 700, "q": 1400, "i": 2800})
+        B = t("ghqpj", e, strides={"g": 1, "h": 16, "q": 512, "p": 1024, "j": 2048})
+        D = t("ghji", e, strides={"g": 1, "h": 17, "j": 600, "i": 6000})
+        out.append(W.Problem("batch_lanes_%s_two_modes" % dtype, dtype, A, B, D, alpha=-1.0, beta=0.0, seed=W.BASE_SEED + 42))
+    return out
+
+
+@pytest.mark.parametrize("p", _batch_lane_cases(), ids=lambda p: p.name)
+def test_streaming_tiles_with_batch_lanes(p):
+    """Low-intensity batched products whose batch modes are the fastest in A, B and D: the streaming
+    tile's lanes all run along batch modes, nothing is staged through LDS and every lane reads its
+    own operand rows (the LDS-free blocked kernel).  The plan must take that tile by itself; every
+    other path must agree; integer inputs bit for bit."""
+    from gpu_helpers import GpuProduct, run_gpu, say
+    import paper_2601_07827_amd as T
+    gp = GpuProduct(p)
+    try:
+        assert gp.get(T.TCX_KEY_PATH) == STREAM and gp.get(T.TCX_KEY_VARIANT) == 1 and gp.get(T.TCX_KEY_TILE_M) == 256
+    finally:
+        gp.close()
+    a, b, c = W.make_operands(p, "ints")
+    truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+    for path, variant in ((None, None), (GENERIC, None), (STREAM, 0), (GETT, None)):
+        say("%s path=%s variant=%s" % (p.name, path, variant))
+        try:
+            got = run_gpu(p, a, b, c, force_path=path, variant=variant, c_null=(p.beta == 0))
+        except Exception as exc:
+            if path == GETT and getattr(exc, "code", None) == 11:
+                continue
+            raise
+        assert gaps_untouched(p, c, got)
+        assert np.array_equal(W.strided_view(got, p.D), W.strided_view(truth, p.D)), (path, variant)
