@@ -259,20 +259,19 @@ __global__ __launch_bounds__(kStreamThreads) void stream_blocked_kernel(StreamAr
             const T* C = (const T*)g.C + cur.d + offL;
             T* D = (T*)g.D + cur.d + offL;
             T a[RB][KC], b[RB][KC];
+            // (register indices beyond the block re-read its last row: no branch around the reads)
 #pragma unroll
-            for (int r = 0; r < RB; ++r)
-                if (r < g.regA) {
-                    const T* row = sA + (size_t)((rab & 0xffffu) + r * g.rowStepA) * KC;
+            for (int r = 0; r < RB; ++r) {
+                const T* row = sA + (size_t)((rab & 0xffffu) + min(r, g.regA - 1) * g.rowStepA) * KC;
 #pragma unroll
-                    for (int k = 0; k < KC; ++k) a[r][k] = row[k];
-                }
+                for (int k = 0; k < KC; ++k) a[r][k] = row[k];
+            }
 #pragma unroll
-            for (int r = 0; r < RB; ++r)
-                if (r < g.regB) {
-                    const T* row = sB + (size_t)((rab >> 16) + r * g.rowStepB) * KC;
+            for (int r = 0; r < RB; ++r) {
+                const T* row = sB + (size_t)((rab >> 16) + min(r, g.regB - 1) * g.rowStepB) * KC;
 #pragma unroll
-                    for (int k = 0; k < KC; ++k) b[r][k] = row[k];
-                }
+                for (int k = 0; k < KC; ++k) b[r][k] = row[k];
+            }
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
                 if (rb < g.regB) {
