@@ -538,3 +538,58 @@ def test_streaming_tiles_with_batch_lanes(p):
             raise
         assert gaps_untouched(p, c, got)
         assert np.array_equal(W.strided_view(got, p.D), W.strided_view(truth, p.D)), (path, variant)
+
+
+def test_small_tiles_on_random_network_layouts():
+    """Seeded random tensor-network-like products (M, N, K each a product of modes with extents
+    2 - 16, every tensor in its own random memory order, sometimes a batch mode) on the small
+    two-phase tiles, unsplit and with K in two: whichever of the one-element and the paired-load
+    kernels the layout admits must reproduce the oracle bit for bit on integer inputs, and paired
+    loads must actually occur."""
+    import torch
+    from gpu_helpers import GpuProduct, say
+    import paper_2601_07827_amd as T
+    rng = np.random.default_rng(20260107)
+    runs = paired = 0
+    for case in range(30):
+        def modes(prefix, target):
+            out, left, i = [], target, 0
+            while left > 1:
+                e = int(rng.choice([x for x in (2, 4, 8, 16) if left % x == 0]))
+                out.append(("%s%d" % (prefix, i), e))
+                left //= e
+                i += 1
+            return out
+        Mm, Nm = modes("m", int(rng.choice([64, 128, 256]))), modes("n", int(rng.choice([64, 128])))
+        Km = modes("k", int(rng.choice([16, 32, 64])))
+        Hm = [("h0", int(rng.choice([2, 3])))] if rng.random() < 0.3 else []
+        ext = dict(Mm + Nm + Km + Hm)
+
+        def layout(labels):
+            labels = list(labels)
+            rng.shuffle(labels)
+            order = list(labels)
+            rng.shuffle(order)
+            return W.tensor(labels, ext, memory_order=order)
+        p = W.Problem("network%d" % case, "f64", layout([l for l, _ in Hm + Mm + Km]), layout([l for l, _ in Hm + Km + Nm]),
+                      layout([l for l, _ in Hm + Mm + Nm]), alpha=2.0, beta=-1.0, seed=W.BASE_SEED + 100 + case)
+        a, b, c = W.make_operands(p, "ints")
+        truth, _ = run_oracle(p, a, b, c, oracle.MODE_TRUTH)
+        for variant in (10, 11):
+            for parts in (None, 2):
+                try:
+                    gp = GpuProduct(p, GETT, variant, parts)
+                except T.TcxError as exc:
+                    assert exc.code == T.TCX_ERR_UNSUPPORTED_OP            # k offsets that do not repeat from slab to slab
+                    continue
+                try:
+                    say("%s shape %d parts %s" % (p.name, variant, parts))
+                    dA, dB, dD = torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda(), torch.from_numpy(c.copy()).cuda()
+                    gp.execute(dA, dB, dD, dD)
+                    torch.cuda.synchronize()
+                    runs += 1
+                    paired += gp.last_gather_width == 2
+                    assert np.array_equal(W.strided_view(dD.cpu().numpy(), p.D), W.strided_view(truth, p.D))
+                finally:
+                    gp.close()
+    assert runs >= 60 and paired >= runs // 3
