@@ -13,10 +13,10 @@
 //     strides of all its occurrences are added.
 //   * Cases 4 and 5 (labels in only one of A, B, or only in D) are not required by
 //     the standard (Note 7) and are rejected by oracle_validate().
-// How it computes it (paper, Sec. "Algorithm Structure", Figs. "implementation" and
-// "helper-functions"): an odometer over the distinct labels of D, first label fastest,
-// an inner odometer over the contracted labels, one offset = sum(index*stride) per
-// tensor per term.  Strides are in ELEMENTS, measured from the element whose indices
+// How it computes it (paper, Sec. "Algorithm Structure"): every index tuple over the
+// distinct labels of D, first label fastest; for each, every tuple over the contracted
+// labels, again first label fastest; per term one displacement sum(index*stride) per
+// tensor.  Strides are in ELEMENTS, measured from the element whose indices
 // are all zero (glossary, "Strided layout"); absent labels get stride 0.
 //
 // Readings where the paper is silent:
@@ -185,18 +185,20 @@ template <class R> inline std::complex<R> mul(std::complex<R> a, std::complex<R>
 
 template <class X> inline bool is_zero(X x) { return x == X(0); }
 
-// Odometer step, first index fastest (Fig. "helper-functions", increment).
-inline void increment(std::vector<int64_t>& idx, const std::vector<int64_t>& shape) {
-    for (size_t k = 0; k < shape.size(); ++k) {
-        idx[k] = (idx[k] + 1) % shape[k];
-        if (idx[k] > 0) return;
-    }
+// Next index tuple in the order "first index fastest" (Sec. "Algorithm Structure": the free and
+// the contracted index spaces are each walked in reverse lexicographical order).  A position
+// that has reached its extent goes back to zero and hands a carry to the next one; the tuple
+// after the last one is all zeros again.
+inline void advance(std::vector<int64_t>& idx, const std::vector<int64_t>& shape) {
+    size_t k = 0;
+    while (k < shape.size() && ++idx[k] == shape[k]) idx[k++] = 0;
 }
-// Fig. "helper-functions", offset (with the return the figure leaves out).
-inline int64_t offset(const std::vector<int64_t>& idx, const std::vector<int64_t>& strides) {
-    int64_t off = 0;
-    for (size_t k = 0; k < strides.size(); ++k) off += idx[k] * strides[k];
-    return off;
+// Position of an index tuple relative to the all-zero element (glossary, "Strided layout":
+// base + sum_k i_k * s_k), in elements.
+inline int64_t displacement(const std::vector<int64_t>& idx, const std::vector<int64_t>& strides) {
+    int64_t d = 0;
+    for (size_t k = 0; k < idx.size(); ++k) d += strides[k] * idx[k];
+    return d;
 }
 
 template <class T, class Acc>
@@ -225,21 +227,24 @@ void contract(int mode, const std::vector<Loop>& free_loops, const std::vector<L
         std::vector<int64_t> I(dshape.size());
         int64_t rem = lin;
         for (size_t k = 0; k < dshape.size(); ++k) { I[k] = rem % dshape[k]; rem /= dshape[k]; }
-        const int64_t off_D = offset(I, dsD);
-        const int64_t baseA = offset(I, dsA);
-        const int64_t baseB = offset(I, dsB);
+        const int64_t off_D = displacement(I, dsD);
+        const int64_t baseA = displacement(I, dsA);
+        const int64_t baseB = displacement(I, dsB);
         std::vector<int64_t> K(pshape.size(), 0);
 
         if (mode == MODE_LITERAL) {
-            // storage-precision read-modify-write, exactly the figure's statements
+            // The order of operations of Fig. "implementation": D starts as beta*C and every
+            // term alpha*a*b is added to it as it comes, all in the storage type.  The running
+            // value is kept in a variable of the storage type and stored once, which rounds
+            // exactly like a read-modify-write of D per term.  C is read even when beta is 0.
             const T al = Narrow<T, Acc>::of(alpha), be = Narrow<T, Acc>::of(beta);
-            D[off_D] = mul(be, apply_op(C[off_D], opC));
-            for (int64_t k = 0; k < size_P; ++k) {
-                const int64_t off_A = baseA + offset(K, psA);
-                const int64_t off_B = baseB + offset(K, psB);
-                D[off_D] = D[off_D] + mul(al, mul(apply_op(A[off_A], opA), apply_op(B[off_B], opB)));
-                increment(K, pshape);
+            T running = mul(be, apply_op(C[off_D], opC));
+            for (int64_t k = 0; k < size_P; ++k, advance(K, pshape)) {
+                const T a = apply_op(A[baseA + displacement(K, psA)], opA);
+                const T b = apply_op(B[baseB + displacement(K, psB)], opB);
+                running = running + mul(al, mul(a, b));
             }
+            D[off_D] = running;
             continue;
         }
 
@@ -247,13 +252,13 @@ void contract(int mode, const std::vector<Loop>& free_loops, const std::vector<L
         long double s = 0.0L;
         if (read_ab) {
             for (int64_t k = 0; k < size_P; ++k) {
-                const int64_t off_A = baseA + offset(K, psA);
-                const int64_t off_B = baseB + offset(K, psB);
+                const int64_t off_A = baseA + displacement(K, psA);
+                const int64_t off_B = baseB + displacement(K, psB);
                 const Acc a = Widen<Acc, T>::of(apply_op(A[off_A], opA));
                 const Acc b = Widen<Acc, T>::of(apply_op(B[off_B], opB));
                 acc = acc + mul(a, b);
                 if (S) s += (long double)modulus(a) * (long double)modulus(b);
-                increment(K, pshape);
+                advance(K, pshape);
             }
         }
         Acc d = mul(alpha, acc);

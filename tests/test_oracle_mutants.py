@@ -17,17 +17,24 @@ SRC = open(os.path.join(os.path.dirname(oracle.__file__), "contraction_oracle.cp
 MUTANTS = [
     ("conj_dropped", "return op == OP_CONJ ? std::conj(x) : x;", "return x;"),
     ("complex_mul_sign", "a.real() * b.real() - a.imag() * b.imag()", "a.real() * b.real() + a.imag() * b.imag()"),
-    ("odometer_never_carries", "if (idx[k] > 0) return;", "return;"),
+    ("odometer_never_carries", "while (k < shape.size() && ++idx[k] == shape[k]) idx[k++] = 0;",
+     "if (!shape.empty() && ++idx[0] == shape[0]) idx[0] = 0;"),
     ("beta_term_dropped", "if (read_c) d = d + mul(beta,", "if (false) d = d + mul(beta,"),
     ("repeated_label_last_stride_only", "if (t.label[i] == lab) s += t.stride[i];", "if (t.label[i] == lab) s = t.stride[i];"),
-    ("B_addressed_with_A_strides", "const int64_t off_B = baseB + offset(K, psB);", "const int64_t off_B = baseB + offset(K, psA);"),
+    ("B_addressed_with_A_strides", "const int64_t off_B = baseB + displacement(K, psB);", "const int64_t off_B = baseB + displacement(K, psA);"),
     ("opC_ignored", "Widen<Acc, T>::of(apply_op(C[off_D], opC))", "Widen<Acc, T>::of(C[off_D])"),
     ("C_read_at_linear_index", "mul(beta, Widen<Acc, T>::of(apply_op(C[off_D], opC)))", "mul(beta, Widen<Acc, T>::of(apply_op(C[lin], opC)))"),
     ("alpha_also_scales_C", "D[off_D] = Narrow<T, Acc>::of(d);", "D[off_D] = Narrow<T, Acc>::of(read_c ? mul(alpha, d) : d);"),
     ("hadamard_label_summed", "if (has_label(tD, lab)) continue;", "if (has_label(tD, lab) && !has_label(tB, lab)) continue;"),
     ("aliasing_check_off", "if (p.first <= span) return V_D_ALIASING;", "if (false) return V_D_ALIASING;"),
     ("isolated_in_B_accepted", "if (!has_label(A, B.label[i]) && !has_label(D, B.label[i])) return V_ISOLATED;", ";"),
-    ("free_stride_of_A_dropped", "const int64_t baseA = offset(I, dsA);", "const int64_t baseA = 0;"),
+    ("free_stride_of_A_dropped", "const int64_t baseA = displacement(I, dsA);", "const int64_t baseA = 0;"),
+    ("complex_modulus_is_squared_norm", "return hypotl(x.real(), x.imag());", "return x.real() * x.real() + x.imag() * x.imag();"),
+    ("complex_modulus_is_taxicab", "return hypotl(x.real(), x.imag());", "return fabsl(x.real()) + fabsl(x.imag());"),
+    ("storage_complex_modulus_is_squared_norm", "return std::hypot(x.real(), x.imag());", "return x.real() * x.real() + x.imag() * x.imag();"),
+    ("real_modulus_keeps_sign", "inline long double modulus(long double x) { return fabsl(x); }", "inline long double modulus(long double x) { return x; }"),
+    ("normaliser_uses_only_A", "s += (long double)modulus(a) * (long double)modulus(b);", "s += (long double)modulus(a);"),
+    ("literal_mode_scales_C_by_alpha", "T running = mul(be, apply_op(C[off_D], opC));", "T running = mul(al, apply_op(C[off_D], opC));"),
     ("last_term_skipped", "for (int64_t k = 0; k < size_P; ++k) {", "for (int64_t k = 1; k < size_P; ++k) {"),
 ]
 
@@ -42,6 +49,9 @@ def _pins_to_run():
             calls.append((pins.test_einsum_random_problems, (dt, seed)))
     for row in pins._paper_examples():
         calls.append((pins.test_paper_label_examples, (row,)))
+    for dt in ("c128", "f64", "f32"):
+        for mode in (pins.oracle.MODE_TRUTH, pins.oracle.MODE_TIMED):
+            calls.append((pins.test_normaliser_on_exact_moduli, (dt, mode)))
     calls += [(pins.test_repeated_label_equals_summed_stride, ()), (pins.test_validation_classes, ()),
               (pins.test_conjugation_symmetry_and_op_equals_preconjugated_copy, ()),
               (pins.test_delta_operand_reproduces_permutation, ("c128",)),

@@ -115,6 +115,52 @@ def test_S_is_sum_of_moduli():
     assert np.array_equal(W.strided_view(S, p.D), W.strided_view(d_abs, p.D))
 
 
+# Gaussian integers whose moduli are integers (Pythagorean triples): |3+4i| = 5, |5+12i| = 13, ...
+_PYTHAGOREAN = [(3, 4, 5), (5, 12, 13), (8, 15, 17), (7, 24, 25), (20, 21, 29), (12, 35, 37), (9, 40, 41)]
+
+
+@pytest.mark.parametrize("mode", [oracle.MODE_TRUTH, oracle.MODE_TIMED], ids=["truth", "timed"])
+@pytest.mark.parametrize("dtype", ["c128", "f64", "f32"])
+def test_normaliser_on_exact_moduli(dtype, mode):
+    """S = sum_P |op(a)||op(b)| with the complex MODULUS (the error measure's denominator).
+    Complex operands are drawn from Gaussian integers with integer moduli, in all sign, swap and
+    conjugation variants, so S is an integer that plain integer arithmetic gives exactly; a
+    squared norm, |re| + |im| or max(|re|, |im|) in place of the modulus gives another integer.
+    Real operands are signed integers (modulus = absolute value)."""
+    rng = np.random.default_rng(17 + len(dtype))
+    ext = dict(h=2, m=3, n=4, k=5, l=3)
+    A = W.tensor("mhkl", ext, memory_order="khlm")
+    B = W.tensor("lnkh", ext)
+    D = W.tensor("nhm", ext, strides=dict(n=2, h=8, m=-16))
+    p = W.Problem("moduli", dtype, A, B, D, alpha=2.0, beta=0.5, opA=1, opB=0, opC=1)
+
+    def draw(spec):
+        """(buffer, integer moduli shaped like the tensor)."""
+        buf = np.zeros(spec.size, dtype=p.np_dtype)
+        mod = np.zeros(spec.extents, dtype=object)
+        v = W.strided_view(buf, spec)
+        for at in itertools.product(*[range(e) for e in spec.extents]):
+            if dtype == "c128":
+                x, y, r = _PYTHAGOREAN[int(rng.integers(len(_PYTHAGOREAN)))]
+                if rng.random() < 0.5:
+                    x, y = y, x
+                v[at] = complex(x * int(rng.choice([-1, 1])), y * int(rng.choice([-1, 1])))
+            else:
+                r = int(rng.integers(0, 9))
+                v[at] = r * int(rng.choice([-1, 1]))
+            mod[at] = r
+        return buf, mod
+
+    a, ma = draw(A)
+    b, mb = draw(B)
+    c = W.fill(D, 3, W.TAG_C, p.np_dtype, "ints")
+    _, S = run_oracle(p, a, b, c, mode, want_S=True)
+    vs = W.strided_view(S, D)
+    for n, h, m in itertools.product(range(4), range(2), range(3)):
+        expect = sum(ma[m, h, k, l] * mb[l, n, k, h] for k in range(5) for l in range(3))
+        assert vs[n, h, m] == float(expect), (dtype, mode, (n, h, m))
+
+
 # ---- P2: numpy.einsum as an independent library evaluation ----------------------------
 def einsum_reference(p: W.Problem, bufA, bufB, bufC):
     letters = {}
