@@ -35,10 +35,15 @@
  *    address are left bit-unchanged.
  *  - tcx_execute_product enqueues work on the executor's stream and returns; argument
  *    errors are reported synchronously, before anything is enqueued.
- *  - Objects are immutable after creation (tcx_product_set aside).  A product whose plan cuts
- *    the contracted range into parts (TCX_KEY_SPLIT_K > 1) owns a device workspace for the
- *    partial sums: executions of that one product must not overlap in time.  Other products
- *    may be executed concurrently on different executors.
+ *  - Objects are immutable after creation (tcx_product_set and the executor's keys aside), so
+ *    one product may be executed from several threads and on several executors at once.  A
+ *    product whose plan cuts the contracted range into parts (TCX_KEY_SPLIT_K > 1) writes
+ *    partial sums to a device workspace that belongs to the EXECUTOR: work on one stream runs in
+ *    order, so executions through one executor share it safely, and executions through different
+ *    executors use different buffers.  The workspace grows on demand inside tcx_execute_product
+ *    (the only device allocation an execution can make; TCX_KEY_WORKSPACE_BYTES on the product
+ *    says how much it needs, the same key set on an executor reserves it ahead of time); if that
+ *    allocation fails the product runs unsplit.
  */
 #ifndef TCX_H
 #define TCX_H
@@ -73,14 +78,16 @@ enum {
     TCX_ERR_D_ALIASING = 8,          /* two index tuples of D share an address (appendix test 28) */
     TCX_ERR_ISOLATED_INDEX = 9,      /* Case 4 / Case 5 label (Eq. FreeD, Note 7) */
     TCX_ERR_DTYPE_MIX = 10,          /* the four tensors do not share one dtype */
-    TCX_ERR_UNSUPPORTED_OP = 11,     /* op value unknown, or opD != identity; from tcx_product_set: this plan cannot take the path, tile shape or split */
+    TCX_ERR_UNSUPPORTED_OP = 11,     /* op value unknown, or opD != identity */
     TCX_ERR_UNSUPPORTED_PRECISION = 12,
     TCX_ERR_ALLOC = 13,              /* host or device allocation failed */
     TCX_ERR_LAUNCH = 14,             /* the HIP runtime refused a launch or copy; see the status object */
     TCX_ERR_NO_DEVICE = 15,          /* the handle was created without a usable gfx950 GPU (plans only) */
     TCX_ERR_TOO_LARGE = 16,          /* an offset or an index range exceeds what the kernels address */
     TCX_ERR_BAD_KEY = 17,            /* unknown key in tcx_status_get / tcx_product_get / tcx_attr_*, or a free-form key that holds no value */
-    TCX_ERR_BUFFER_TOO_SMALL = 18    /* *nbytes is smaller than the value; *nbytes is set to the need */
+    TCX_ERR_BUFFER_TOO_SMALL = 18,   /* *nbytes is smaller than the value; *nbytes is set to the need */
+    TCX_ERR_PLAN_REFUSED = 19,       /* tcx_product_set: this plan cannot take the requested path, tile shape or split */
+    TCX_ERR_SCRATCH_TOO_SMALL = 20   /* the product needs more scratch memory than the library's fixed buffer holds */
 };
 
 #define TCX_MAX_MODES 32
@@ -115,8 +122,10 @@ tcx_error_t tcx_tensor_info_get(tcx_tensor_info_t info, tcx_dtype_t* dtype, int3
  * analysis (classification into H / F_A / F_B / P, merging of repeated labels, fusion of
  * contiguous modes, choice of kernel path and tile plan) happen here, once, so that their
  * cost is amortised over executions.  On a handle with a device this also uploads the
- * plan's offset tables (synchronous, default stream).  C must match D mode by mode in
- * label, extent and stride; opD must be TCX_OP_IDENTITY. */
+ * plan's offset tables (synchronous, default stream).  C must be laid out like D (Note 5): the
+ * same set of labels and, per distinct label, D's extent and D's stride (the strides of a
+ * repeated label summed); the order in which C's modes are listed is free.  opD must be
+ * TCX_OP_IDENTITY. */
 tcx_error_t tcx_create_product(tcx_handle_t handle,
                                tcx_op_t opA, tcx_tensor_info_t A, const int64_t* labelsA,
                                tcx_op_t opB, tcx_tensor_info_t B, const int64_t* labelsB,
@@ -153,7 +162,12 @@ enum {
     TCX_KEY_FORCE_PATH = 24,   /* tcx_product_set only: force a tcx_path_t (testing, tuning) */
     TCX_KEY_SPLIT_K = 25,      /* tiled path: number of parts the contracted range is cut into (1 = unsplit) */
     TCX_KEY_LAUNCHES = 26,     /* read-only: kernel launches one execution enqueues (rounds of a long-tile product; +1 for the split-K reduction) */
-    TCX_KEY_GATHER_WIDTH = 27  /* read-only: elements one gather load of the tiled kernel brings (2: neighbouring pairs of 8-byte elements; a status reports what the execution used, which also depends on the operand pointers being 16-byte aligned) */
+    TCX_KEY_GATHER_WIDTH = 27, /* read-only: elements one gather load of the tiled kernel brings (2: neighbouring pairs of 8-byte elements; a status reports what the execution used, which also depends on the operand pointers being 16-byte aligned) */
+    TCX_KEY_TABLE_ENTRIES = 28,/* read-only, int64_t[3]: entries of the plan's offset tables over M, N, K including padding (0 before the tiled path was prepared) */
+    TCX_KEY_WORKSPACE_BYTES = 29, /* product (read-only): device bytes of partial sums one execution writes; executor: size of its workspace, settable to reserve at least that much */
+    TCX_KEY_DEVICE = 30,       /* handle, executor (read-only): HIP device ordinal the object is bound to, -1 if none */
+    TCX_KEY_NUM_CU = 31,       /* handle (read-only): compute units of the bound device */
+    TCX_KEY_STREAM = 32        /* executor: the hipStream_t as an integer; settable (the caller keeps the new stream alive) */
 };
 typedef enum {
     TCX_PATH_GENERIC = 0,      /* one thread per element of D, loops over the contracted index space */
@@ -164,8 +178,9 @@ typedef enum {
 /* Read a property of the plan.  *nbytes: in = capacity of value, out = bytes written. */
 tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, size_t* nbytes);
 /* Override a plan decision: TCX_KEY_FORCE_PATH, or TCX_KEY_VARIANT (tiled path: index of the tile
- * shape; bandwidth path: 0 = flat tiles only, 1 = register-blocked tiles where possible).  Returns
- * TCX_ERR_UNSUPPORTED_OP if the plan cannot run that way. */
+ * shape; bandwidth path: 0 = flat tiles only, 1 = register-blocked tiles where possible), or
+ * TCX_KEY_SPLIT_K.  Returns TCX_ERR_PLAN_REFUSED if the plan cannot run that way (the plan is
+ * then unchanged). */
 tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* value, size_t nbytes);
 
 /* ---- execution (Sec. "Execution") ----------------------------------------------------
@@ -190,7 +205,9 @@ tcx_error_t tcx_destroy_status(tcx_status_t* status);
  *                          on a product the TCX_KEY_* of tcx_product_get / tcx_product_set, on a
  *                          status those of tcx_status_get; clearing TCX_KEY_FORCE_PATH,
  *                          TCX_KEY_VARIANT or TCX_KEY_SPLIT_K on a product returns the whole plan
- *                          to the analyser's own choice; on other objects TCX_ERR_BAD_KEY.
+ *                          to the analyser's own choice; on a handle TCX_KEY_DEVICE and
+ *                          TCX_KEY_NUM_CU, on an executor TCX_KEY_DEVICE, TCX_KEY_STREAM and
+ *                          TCX_KEY_WORKSPACE_BYTES; any other combination TCX_ERR_BAD_KEY.
  * get: *nbytes in = capacity of value, out = size of the stored value; value NULL or too small:
  * TCX_ERR_NULL_ARG / TCX_ERR_BUFFER_TOO_SMALL with *nbytes set to the need.  A key that was never
  * set (or was cleared): TCX_ERR_BAD_KEY.  The caller keeps ownership of `value` in all calls. */

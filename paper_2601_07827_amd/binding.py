@@ -35,12 +35,14 @@ TCX_PATH_GENERIC, TCX_PATH_GETT_MFMA, TCX_PATH_BANDWIDTH = 0, 1, 2
 (TCX_SUCCESS, TCX_ERR_NULL_ARG, TCX_ERR_INVALID_HANDLE, TCX_ERR_BAD_DTYPE, TCX_ERR_BAD_NMODE, TCX_ERR_BAD_EXTENT,
  TCX_ERR_EXTENT_MISMATCH, TCX_ERR_CD_MISMATCH, TCX_ERR_D_ALIASING, TCX_ERR_ISOLATED_INDEX, TCX_ERR_DTYPE_MIX,
  TCX_ERR_UNSUPPORTED_OP, TCX_ERR_UNSUPPORTED_PRECISION, TCX_ERR_ALLOC, TCX_ERR_LAUNCH, TCX_ERR_NO_DEVICE,
- TCX_ERR_TOO_LARGE, TCX_ERR_BAD_KEY, TCX_ERR_BUFFER_TOO_SMALL) = range(19)
+ TCX_ERR_TOO_LARGE, TCX_ERR_BAD_KEY, TCX_ERR_BUFFER_TOO_SMALL, TCX_ERR_PLAN_REFUSED,
+ TCX_ERR_SCRATCH_TOO_SMALL) = range(21)
 (TCX_KEY_PATH, TCX_KEY_SIZE_H, TCX_KEY_SIZE_M, TCX_KEY_SIZE_N, TCX_KEY_SIZE_K, TCX_KEY_NMODES_H, TCX_KEY_NMODES_M,
  TCX_KEY_NMODES_N, TCX_KEY_NMODES_K, TCX_KEY_TILE_M, TCX_KEY_TILE_N, TCX_KEY_TILE_K, TCX_KEY_GRID, TCX_KEY_BLOCK,
  TCX_KEY_A_K_FASTEST, TCX_KEY_B_K_FASTEST, TCX_KEY_D_N_FASTEST, TCX_KEY_VARIANT, TCX_KEY_HIP_ERROR, TCX_KEY_MODES_M,
  TCX_KEY_MODES_N, TCX_KEY_MODES_K, TCX_KEY_MODES_H, TCX_KEY_FORCE_PATH, TCX_KEY_SPLIT_K, TCX_KEY_LAUNCHES,
- TCX_KEY_GATHER_WIDTH) = range(1, 28)
+ TCX_KEY_GATHER_WIDTH, TCX_KEY_TABLE_ENTRIES, TCX_KEY_WORKSPACE_BYTES, TCX_KEY_DEVICE, TCX_KEY_NUM_CU,
+ TCX_KEY_STREAM) = range(1, 33)
 TCX_MAX_MODES = 32
 TCX_KEY_USER = 65536
 
@@ -188,6 +190,11 @@ def _get(fn, obj: int, key: int, where: str):
         _check(fn(obj, key, buf, ctypes.byref(n)), where)
         flat = list(buf)[: n.value // 8]
         return [tuple(flat[i:i + 4]) for i in range(0, len(flat), 4)]
+    if key == TCX_KEY_TABLE_ENTRIES:
+        buf = (ctypes.c_int64 * 3)()
+        n = ctypes.c_size_t(ctypes.sizeof(buf))
+        _check(fn(obj, key, buf, ctypes.byref(n)), where)
+        return list(buf)
     v = ctypes.c_int64(0)
     n = ctypes.c_size_t(8)
     _check(fn(obj, key, ctypes.byref(v), ctypes.byref(n)), where)

@@ -27,6 +27,11 @@ struct Handle {
 struct Executor {
     Handle handle;
     hipStream_t stream = nullptr;
+    // Partial sums of split-K products executed through this executor.  Work on one stream runs
+    // in order, so successive executions may share the buffer; other executors have their own.
+    void* workspace = nullptr;
+    size_t workspace_bytes = 0;
+    std::mutex mu;
 };
 struct Info {
     TensorDesc desc;
@@ -36,8 +41,6 @@ struct Product {
     Analysis an;
     int variant = 0;                 // index into the tiled kernel instantiations
     int splitK = 1;                  // parts the K slabs are divided into (tiled path)
-    void* workspace = nullptr;       // split-K partial accumulators, device memory owned by the plan
-    size_t workspace_bytes = 0;
     // offset tables, host copies and one device allocation holding all six
     std::vector<int64_t> tables[6];  // oAM oAK oBN oBK oDM oDN
     int64_t* dev_tables = nullptr;
@@ -183,9 +186,30 @@ void fill_generic(const Analysis& an, GenericArgs* g) {
     g->opA = an.opA; g->opB = an.opB; g->opC = an.opC;
 }
 
+// The wide tables are padded so that every compiled tile shape finds a whole number of its tiles
+// in them (kernels index rows and columns of a ragged last tile without a mask): the padding unit
+// is the least common multiple of the shapes' extents (tiles of 256 and of 96: 768).
+void table_units(int dtype, int64_t* unitM, int64_t* unitN, int64_t* unitK) {
+    auto lcm = [](int64_t a, int64_t b) {
+        int64_t x = a, y = b;
+        while (y) { const int64_t t = x % y; x = y; y = t; }
+        return a / x * b;
+    };
+    *unitM = *unitN = 256;
+    *unitK = 64;
+    for (int v = 0; v < gett_num_variants(dtype); ++v) {
+        const GettVariant s = gett_variant(dtype, v);
+        *unitM = lcm(*unitM, s.mt_m);
+        *unitN = lcm(*unitN, s.mt_n);
+        *unitK = lcm(*unitK, s.kt);
+    }
+}
+
 tcx_error_t build_tables(Product* p) {
     const Analysis& an = p->an;
-    const int64_t padM = round_up(an.sizeM, 256), padN = round_up(an.sizeN, 256), padK = round_up(an.sizeK, 64);
+    int64_t unitM, unitN, unitK;
+    table_units(an.dtype, &unitM, &unitN, &unitK);
+    const int64_t padM = round_up(an.sizeM, unitM), padN = round_up(an.sizeN, unitN), padK = round_up(an.sizeK, unitK);
     try {
         p->tables[0] = offset_table(an.M, 0, padM);
         p->tables[1] = offset_table(an.K, 0, padK);
@@ -215,21 +239,26 @@ tcx_error_t build_tables(Product* p) {
     return TCX_SUCCESS;
 }
 
-// (Re)allocate the split-K workspace for the plan's current shape and split count.
-tcx_error_t ensure_workspace(Product* p) {
-    if (p->splitK <= 1 || !p->handle.has_device) return TCX_SUCCESS;
-    const GettVariant s = gett_variant(p->an.dtype, p->variant);
-    if (p->splitK == 2 && s.pair_in_lds) return TCX_SUCCESS;
-    const size_t real_bytes = p->an.dtype == TCX_F32 ? 4 : 8;
-    const size_t need = (size_t)tiles_of(p->an, s) * (size_t)p->splitK * (size_t)s.acc_reals * real_bytes;
-    if (need <= p->workspace_bytes) return TCX_SUCCESS;
-    if (p->workspace) { (void)hipFree(p->workspace); p->workspace = nullptr; p->workspace_bytes = 0; }
-    if (hipMalloc(&p->workspace, need) != hipSuccess) {
+// Bytes of partial sums one execution of the plan writes (0: none, or summed inside the workgroup).
+size_t workspace_need(const Product& p) {
+    if (p.an.path != TCX_PATH_GETT_MFMA || p.splitK <= 1) return 0;
+    const GettVariant s = gett_variant(p.an.dtype, p.variant);
+    if (p.splitK == 2 && s.pair_in_lds) return 0;
+    const size_t real_bytes = p.an.dtype == TCX_F32 ? 4 : 8;
+    return (size_t)tiles_of(p.an, s) * (size_t)p.splitK * (size_t)s.acc_reals * real_bytes;
+}
+
+// Grow the executor's workspace to `need` bytes.  hipFree waits for the work that still uses the
+// old buffer.  Caller holds e->mu.
+tcx_error_t grow_workspace(Executor* e, size_t need) {
+    if (need <= e->workspace_bytes) return TCX_SUCCESS;
+    if (e->workspace) { (void)hipFree(e->workspace); e->workspace = nullptr; e->workspace_bytes = 0; }
+    if (hipMalloc(&e->workspace, need) != hipSuccess) {
         (void)hipGetLastError();
-        p->workspace = nullptr;
+        e->workspace = nullptr;
         return TCX_ERR_ALLOC;
     }
-    p->workspace_bytes = need;
+    e->workspace_bytes = need;
     return TCX_SUCCESS;
 }
 
@@ -289,7 +318,7 @@ bool narrow_operand(const std::vector<int64_t>& rows, int64_t nrows, int mt, con
     return max_row + max_k <= 0xffffffffull;                     // the kernel adds the two in 32 bits
 }
 
-// Builds the narrow tables for tile shape `variant`; TCX_ERR_UNSUPPORTED_OP if a tile of that
+// Builds the narrow tables for tile shape `variant`; TCX_ERR_PLAN_REFUSED if a tile of that
 // shape spans 4 GB or more of an operand.
 tcx_error_t build_narrow(Product* p, int variant) {
     const GettVariant s = gett_variant(p->an.dtype, variant);
@@ -299,13 +328,13 @@ tcx_error_t build_narrow(Product* p, int variant) {
     try {
         if (!narrow_operand(p->tables[0], p->an.sizeM, s.mt_m, p->tables[1], p->an.sizeK, s.kt, es, &a) ||
             !narrow_operand(p->tables[2], p->an.sizeN, s.mt_n, p->tables[3], p->an.sizeK, s.kt, es, &b))
-            return TCX_ERR_UNSUPPORTED_OP;
+            return TCX_ERR_PLAN_REFUSED;
         // the two-phase kernel precomputes the per-lane k offsets of an operand whose lanes run along k
         auto operand_ok = [&](bool k_fastest, bool periodic, int mt) {
             return k_fastest ? periodic : (mt % 64 == 0 && s.threads % mt == 0);
         };
         if (s.pingpong && (!operand_ok(p->an.a_k_fastest, a.periodic, s.mt_m) || !operand_ok(p->an.b_k_fastest, b.periodic, s.mt_n)))
-            return TCX_ERR_UNSUPPORTED_OP;
+            return TCX_ERR_PLAN_REFUSED;
         p->periodic[0] = a.periodic;
         p->periodic[1] = b.periodic;
         // Paired gather loads (8-byte elements, two-phase kernel with one tile per wave group):
@@ -372,7 +401,7 @@ tcx_error_t prepare_tiled(Product* p) {
     }
     // order: the plan's shape, the shape it names as its stand-in, then the others as the cost
     // model ranks them (each with its own best split count)
-    tcx_error_t err = TCX_ERR_UNSUPPORTED_OP;
+    tcx_error_t err = TCX_ERR_PLAN_REFUSED;
     const int first = p->variant, second = gett_variant(p->an.dtype, first).fallback;
     std::vector<PlanChoice> order = {{0.0, first, p->splitK}};
     if (second >= 0) order.push_back({0.0, second, 1});
@@ -384,11 +413,10 @@ tcx_error_t prepare_tiled(Product* p) {
             if (c.variant != p->variant) { p->variant = c.variant; p->splitK = c.splitK; }
             break;
         }
-        if (err != TCX_ERR_UNSUPPORTED_OP) break;
+        if (err != TCX_ERR_PLAN_REFUSED) break;
     }
     if (err != TCX_SUCCESS) return err;
     p->an.variant = p->variant;
-    if (ensure_workspace(p) != TCX_SUCCESS) p->splitK = 1;      // no memory: run unsplit
     return TCX_SUCCESS;
 }
 
@@ -399,7 +427,7 @@ tcx_error_t build_stream(Product* p, bool allow_blocked = true) {
     } catch (const std::bad_alloc&) {
         return TCX_ERR_ALLOC;
     }
-    if (!p->stream.ok) return TCX_ERR_UNSUPPORTED_OP;
+    if (!p->stream.ok) return TCX_ERR_PLAN_REFUSED;
     if (!p->handle.has_device) return TCX_SUCCESS;
     const StreamPlan& sp = p->stream;
     const size_t bytes[8] = {sp.rowAB.size() * sizeof(uint32_t), sp.dD.size() * sizeof(int64_t),
@@ -452,7 +480,7 @@ const char* const kMessages[] = {
     "two index tuples of tensor D address the same element",
     "a label occurs in only one of A, B, D (isolated index: reduction or broadcast is not supported)",
     "the four tensors do not share one data type",
-    "unsupported: an element-wise operation (opD must be the identity), or a path / tile shape / split that this plan cannot take",
+    "unsupported element-wise operation (op value unknown, or opD is not the identity)",
     "unsupported computational precision",
     "memory allocation failed",
     "the HIP runtime reported an error; query TCX_KEY_HIP_ERROR on the status object",
@@ -460,6 +488,8 @@ const char* const kMessages[] = {
     "an index range or offset exceeds what the kernels can address",
     "unknown key",
     "value buffer too small",
+    "this plan cannot take the requested kernel path, tile shape or split of the contracted range",
+    "the product needs more scratch memory than the library's fixed buffer holds",
 };
 
 }  // namespace
@@ -511,7 +541,13 @@ tcx_error_t tcx_create_executor(tcx_handle_t handle, void* hip_stream, tcx_execu
     return TCX_SUCCESS;
 }
 
-tcx_error_t tcx_destroy_executor(tcx_executor_t* executor) { return retire<Executor>(executor, MAGIC_EXEC); }
+tcx_error_t tcx_destroy_executor(tcx_executor_t* executor) {
+    if (!executor) return TCX_ERR_NULL_ARG;
+    Executor* e = lookup<Executor>(*executor, MAGIC_EXEC);
+    if (!e) return TCX_ERR_INVALID_HANDLE;
+    if (e->workspace) { (void)hipFree(e->workspace); e->workspace = nullptr; e->workspace_bytes = 0; }
+    return retire<Executor>(executor, MAGIC_EXEC);
+}
 
 tcx_error_t tcx_create_tensor_info(tcx_handle_t handle, tcx_dtype_t dtype, int32_t nmode, const int64_t* extents,
                                    const int64_t* strides, tcx_tensor_info_t* out) {
@@ -559,7 +595,7 @@ tcx_error_t route(Product* p) {
     } else if (p->an.path == TCX_PATH_GETT_MFMA) {
         choose_plan(p->an, p->handle.num_cu, &p->variant, &p->splitK);
         err = prepare_tiled(p);
-        if (err == TCX_ERR_UNSUPPORTED_OP) { err = TCX_SUCCESS; p->an.path = TCX_PATH_GENERIC; }
+        if (err == TCX_ERR_PLAN_REFUSED) { err = TCX_SUCCESS; p->an.path = TCX_PATH_GENERIC; }
     }
     p->an.variant = p->variant;
     return err;
@@ -601,7 +637,6 @@ tcx_error_t tcx_destroy_product(tcx_product_t* product) {
     if (p->dev_tables) { (void)hipFree(p->dev_tables); p->dev_tables = nullptr; }
     if (p->dev_narrow) { (void)hipFree(p->dev_narrow); p->dev_narrow = nullptr; }
     if (p->dev_stream) { (void)hipFree(p->dev_stream); p->dev_stream = nullptr; }
-    if (p->workspace) { (void)hipFree(p->workspace); p->workspace = nullptr; }
     return retire<Product>(product, MAGIC_PRODUCT);
 }
 
@@ -642,6 +677,11 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
                            value, nbytes);
         }
         case TCX_KEY_GATHER_WIDTH: return put_i64(tiled && s.pingpong && s.dual && p->pairs ? 2 : 1, value, nbytes);
+        case TCX_KEY_WORKSPACE_BYTES: return put_i64((int64_t)workspace_need(*p), value, nbytes);
+        case TCX_KEY_TABLE_ENTRIES: {
+            const int64_t n[3] = {(int64_t)p->tables[0].size(), (int64_t)p->tables[2].size(), (int64_t)p->tables[1].size()};
+            return put(n, sizeof n, value, nbytes);
+        }
         case TCX_KEY_VARIANT:
             return put_i64(tiled ? p->variant : (an.path == TCX_PATH_BANDWIDTH && p->stream.blocked) ? 1 : 0, value, nbytes);
         case TCX_KEY_MODES_M: return put_modes(an.M, value, nbytes);
@@ -662,7 +702,7 @@ tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* valu
     if (key == TCX_KEY_FORCE_PATH) {
         if (v == TCX_PATH_GENERIC) { p->an.path = TCX_PATH_GENERIC; return TCX_SUCCESS; }
         if (v == TCX_PATH_GETT_MFMA) {
-            if (gett_num_variants(p->an.dtype) == 0 || (int)p->an.H.size() > kMaxHModes) return TCX_ERR_UNSUPPORTED_OP;
+            if (gett_num_variants(p->an.dtype) == 0 || (int)p->an.H.size() > kMaxHModes) return TCX_ERR_PLAN_REFUSED;
             if (p->tables[0].empty()) choose_plan(p->an, p->handle.num_cu, &p->variant, &p->splitK);
             const tcx_error_t err = prepare_tiled(p);
             if (err != TCX_SUCCESS) return err;
@@ -677,15 +717,15 @@ tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* valu
             p->an.path = TCX_PATH_BANDWIDTH;
             return TCX_SUCCESS;
         }
-        return TCX_ERR_UNSUPPORTED_OP;
+        return TCX_ERR_PLAN_REFUSED;
     }
     if (key == TCX_KEY_VARIANT && p->an.path == TCX_PATH_BANDWIDTH) {
         // 0: flat tiles only, 1: register-blocked tiles where the shape allows them
-        if (v != 0 && v != 1) return TCX_ERR_UNSUPPORTED_OP;
+        if (v != 0 && v != 1) return TCX_ERR_PLAN_REFUSED;
         return build_stream(p, v == 1);
     }
     if (key == TCX_KEY_VARIANT) {
-        if (p->an.path != TCX_PATH_GETT_MFMA || v < 0 || v >= gett_num_variants(p->an.dtype)) return TCX_ERR_UNSUPPORTED_OP;
+        if (p->an.path != TCX_PATH_GETT_MFMA || v < 0 || v >= gett_num_variants(p->an.dtype)) return TCX_ERR_PLAN_REFUSED;
         if (gett_variant(p->an.dtype, (int)v).staged) {
             const tcx_error_t err = build_narrow(p, (int)v);
             if (err != TCX_SUCCESS) return err;
@@ -696,12 +736,12 @@ tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* valu
         return TCX_SUCCESS;
     }
     if (key == TCX_KEY_SPLIT_K) {
-        if (p->an.path != TCX_PATH_GETT_MFMA || v < 1 || v > 64) return TCX_ERR_UNSUPPORTED_OP;
+        if (p->an.path != TCX_PATH_GETT_MFMA || v < 1 || v > 64) return TCX_ERR_PLAN_REFUSED;
         const GettVariant sh = gett_variant(p->an.dtype, p->variant);
         const int64_t nk = (p->an.sizeK + sh.kt - 1) / sh.kt;
         const int64_t per = (nk + v - 1) / v;
         p->splitK = (int)((nk + per - 1) / per);        // no part may be empty
-        return ensure_workspace(p);
+        return TCX_SUCCESS;
     }
     return TCX_ERR_BAD_KEY;
 }
@@ -787,7 +827,12 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
         g.opA = p->an.opA; g.opB = p->an.opB; g.opC = p->an.opC;
         g.read_c = read_c;
         g.splitK = p->splitK;
-        g.workspace = p->workspace;
+        if (const size_t need = workspace_need(*p)) {
+            // leased from the executor: executions on its stream run in order and may share it
+            std::lock_guard<std::mutex> lk(e->mu);
+            if (grow_workspace(e, need) == TCX_SUCCESS) g.workspace = e->workspace;
+            else g.splitK = 1;                               // no memory for partial sums: run unsplit
+        }
         g.lid_base = 0;
         // rounds pay off when a tile runs for milliseconds (hundreds of slabs) and there are several rounds
         g.round_size = (int32_t)round_size_of(*p, v);
@@ -853,7 +898,23 @@ uint32_t type_of(intptr_t object) {
 tcx_error_t tcx_attr_set(tcx_object_t object, int32_t key, const void* value, size_t nbytes) {
     const uint32_t type = type_of(object);
     if (!type) return TCX_ERR_INVALID_HANDLE;
-    if (key < TCX_KEY_USER) return type == MAGIC_PRODUCT ? tcx_product_set(object, key, value, nbytes) : TCX_ERR_BAD_KEY;
+    if (key < TCX_KEY_USER) {
+        if (type == MAGIC_PRODUCT) return tcx_product_set(object, key, value, nbytes);
+        if (type == MAGIC_EXEC && (key == TCX_KEY_STREAM || key == TCX_KEY_WORKSPACE_BYTES)) {
+            Executor* e = lookup<Executor>(object, MAGIC_EXEC);
+            if (!e) return TCX_ERR_INVALID_HANDLE;
+            if (!value) return TCX_ERR_NULL_ARG;
+            if (nbytes != sizeof(int64_t)) return TCX_ERR_BUFFER_TOO_SMALL;
+            int64_t v;
+            std::memcpy(&v, value, sizeof v);
+            std::lock_guard<std::mutex> lk(e->mu);
+            if (key == TCX_KEY_STREAM) { e->stream = (hipStream_t)(intptr_t)v; return TCX_SUCCESS; }
+            if (v < 0) return TCX_ERR_TOO_LARGE;
+            if (!e->handle.has_device) return TCX_ERR_NO_DEVICE;
+            return grow_workspace(e, (size_t)v);              // reserve ahead of the first execution
+        }
+        return TCX_ERR_BAD_KEY;
+    }
     if (!value && nbytes) return TCX_ERR_NULL_ARG;
     try {
         std::vector<unsigned char> copy((const unsigned char*)value, (const unsigned char*)value + nbytes);
@@ -872,6 +933,24 @@ tcx_error_t tcx_attr_get(tcx_object_t object, int32_t key, void* value, size_t* 
     if (key < TCX_KEY_USER) {
         if (type == MAGIC_PRODUCT) return tcx_product_get(object, key, value, nbytes);
         if (type == MAGIC_STATUS) return tcx_status_get(object, key, value, nbytes);
+        if (type == MAGIC_HANDLE) {
+            Handle* h = lookup<Handle>(object, MAGIC_HANDLE);
+            if (!h) return TCX_ERR_INVALID_HANDLE;
+            if (key == TCX_KEY_DEVICE) return put_i64(h->has_device ? h->device : -1, value, nbytes);
+            if (key == TCX_KEY_NUM_CU) return put_i64(h->num_cu, value, nbytes);
+            return TCX_ERR_BAD_KEY;
+        }
+        if (type == MAGIC_EXEC) {
+            Executor* e = lookup<Executor>(object, MAGIC_EXEC);
+            if (!e) return TCX_ERR_INVALID_HANDLE;
+            if (key == TCX_KEY_DEVICE) return put_i64(e->handle.has_device ? e->handle.device : -1, value, nbytes);
+            if (key == TCX_KEY_STREAM) return put_i64((int64_t)(intptr_t)e->stream, value, nbytes);
+            if (key == TCX_KEY_WORKSPACE_BYTES) {
+                std::lock_guard<std::mutex> lk(e->mu);
+                return put_i64((int64_t)e->workspace_bytes, value, nbytes);
+            }
+            return TCX_ERR_BAD_KEY;
+        }
         return TCX_ERR_BAD_KEY;
     }
     if (!nbytes) return TCX_ERR_NULL_ARG;

@@ -35,8 +35,8 @@ def test_header_constants_match_binding():
 
 def test_explain_error_and_check_success():
     assert T.tcx_check_success(0) and not T.tcx_check_success(T.TCX_ERR_D_ALIASING)
-    texts = {T.tcx_explain_error(c) for c in range(19)}
-    assert len(texts) == 19 and all(texts)
+    texts = {T.tcx_explain_error(c) for c in range(21)}
+    assert len(texts) == 21 and all(texts)
     assert "unknown" in T.tcx_explain_error(12345)
     # truncation keeps a NUL and returns the full length
     buf = ctypes.create_string_buffer(8)
@@ -214,7 +214,7 @@ def test_product_get_conventions(handle):
     assert lib.tcx_product_get(prod, 999, ctypes.byref(v), ctypes.byref(n)) == T.TCX_ERR_BAD_KEY
     assert lib.tcx_product_get(prod, T.TCX_KEY_SIZE_M, ctypes.byref(v), None) == T.TCX_ERR_NULL_ARG
     assert T.tcx_product_get(prod, T.TCX_KEY_SIZE_M) == 576
-    assert _code(T.tcx_product_set, prod, T.TCX_KEY_VARIANT, 99) == T.TCX_ERR_UNSUPPORTED_OP
+    assert _code(T.tcx_product_set, prod, T.TCX_KEY_VARIANT, 99) == T.TCX_ERR_PLAN_REFUSED
     T.tcx_destroy_product(prod)
     for i in infos:
         T.tcx_destroy_tensor_info(i)
@@ -388,7 +388,7 @@ def test_forcing_a_shape_the_plan_cannot_take_is_refused(handle):
     before = T.tcx_product_get(prod, T.TCX_KEY_VARIANT)
     with pytest.raises(T.TcxError) as e:
         T.tcx_product_set(prod, T.TCX_KEY_VARIANT, 0)            # two-phase 256x128: needs slab-periodic k offsets
-    assert e.value.code == T.TCX_ERR_UNSUPPORTED_OP
+    assert e.value.code == T.TCX_ERR_PLAN_REFUSED and "plan cannot take" in str(e.value)
     assert T.tcx_product_get(prod, T.TCX_KEY_VARIANT) == before   # the plan is unchanged
     T.tcx_product_set(prod, T.TCX_KEY_VARIANT, 2)                # a classic shape is fine
     assert T.tcx_product_get(prod, T.TCX_KEY_VARIANT) == 2 and T.tcx_product_get(prod, T.TCX_KEY_SPLIT_K) == 1
@@ -455,3 +455,88 @@ def test_key_value_stores_on_every_object(handle):
     T.tcx_destroy_executor(ex)
     for i in infos:
         T.tcx_destroy_tensor_info(i)
+
+
+# ---- padding of the plan's offset tables ----------------------------------------------------------
+def _matrix_product(handle, dtype, m, n, k, a_kfast=False, b_kfast=True):
+    e = dict(m=m, n=n, k=k)
+    A = W.tensor("mk", e, memory_order="km" if a_kfast else "mk")
+    B = W.tensor("kn", e, memory_order="kn" if b_kfast else "nk")
+    D = W.tensor("mn", e)
+    infos = [T.tcx_create_tensor_info(handle, dtype, t.extents, t.strides) for t in (A, B, D)]
+    prod = T.tcx_create_product(handle, 0, infos[0], [1, 3], 0, infos[1], [3, 2], 0, infos[2], [1, 2], 0, infos[2], [1, 2])
+    for i in infos:
+        T.tcx_destroy_tensor_info(i)
+    return prod
+
+
+def _tile_shapes(handle, dtype):
+    """(tile rows, tile columns, slab) of every compiled tile shape of a dtype, read through the
+    plan interface on products that each shape accepts (both operand orientations)."""
+    shapes = {}
+    for a_kfast, b_kfast in ((False, True), (True, True), (False, False), (True, False)):
+        prod = _matrix_product(handle, dtype, 768, 768, 64, a_kfast, b_kfast)
+        T.tcx_product_set(prod, T.TCX_KEY_FORCE_PATH, T.TCX_PATH_GETT_MFMA)
+        for v in range(32):
+            try:
+                T.tcx_product_set(prod, T.TCX_KEY_VARIANT, v)
+            except T.TcxError as exc:
+                assert exc.code == T.TCX_ERR_PLAN_REFUSED
+                continue
+            shapes[v] = tuple(T.tcx_product_get(prod, k) for k in (T.TCX_KEY_TILE_M, T.TCX_KEY_TILE_N, T.TCX_KEY_TILE_K))
+        T.tcx_destroy_product(prod)
+    return shapes
+
+
+@pytest.mark.parametrize("dtype", [T.TCX_F64, T.TCX_F32, T.TCX_C128])
+def test_offset_tables_hold_a_whole_number_of_tiles_of_every_shape(handle, dtype):
+    """The tiled kernels index the rows and columns of a ragged last tile without a mask, so the
+    padded tables must reach the end of the last tile of EVERY compiled shape (tiles of 96 and 48
+    do not divide a padding unit of 256), for every size of M, N and K."""
+    shapes = _tile_shapes(handle, dtype)
+    assert len(shapes) >= (8 if dtype == T.TCX_C128 else 12), shapes
+    assert {s[0] for s in shapes.values()} >= ({96, 48} if dtype == T.TCX_C128 else {256, 32})
+    for size in list(range(1, 1101)) + [36864, 4096]:
+        m, n, k = size, max(2, 1101 - size if size <= 1100 else 4096), 2 + size % 71
+        if m * n < 256:
+            n = 256
+        prod = _matrix_product(handle, dtype, m, n, k)
+        T.tcx_product_set(prod, T.TCX_KEY_FORCE_PATH, T.TCX_PATH_GETT_MFMA)
+        lenM, lenN, lenK = T.tcx_product_get(prod, T.TCX_KEY_TABLE_ENTRIES)
+        for v, (tm, tn, tk) in shapes.items():
+            assert -(-m // tm) * tm <= lenM, (m, v, tm, lenM)
+            assert -(-n // tn) * tn <= lenN, (n, v, tn, lenN)
+            assert -(-k // tk) * tk <= lenK, (k, v, tk, lenK)
+        T.tcx_destroy_product(prod)
+
+
+def test_keys_of_handle_and_executor(handle):
+    """Sec. "Virtual Key-Value Stores": the library's own keys on a handle and on an executor."""
+    assert T.tcx_attr_get(handle, T.TCX_KEY_DEVICE) == (-1 if not T.tcx_handle_has_device(handle) else T.tcx_attr_get(handle, T.TCX_KEY_DEVICE))
+    assert T.tcx_attr_get(handle, T.TCX_KEY_NUM_CU) >= 0
+    assert _code(T.tcx_attr_get, handle, T.TCX_KEY_STREAM) == T.TCX_ERR_BAD_KEY
+    assert _code(T.tcx_attr_set, handle, T.TCX_KEY_NUM_CU, 5) == T.TCX_ERR_BAD_KEY
+    ex = T.tcx_create_executor(handle, 0)
+    assert T.tcx_attr_get(ex, T.TCX_KEY_STREAM) == 0
+    T.tcx_attr_set(ex, T.TCX_KEY_STREAM, 0x1230)
+    assert T.tcx_attr_get(ex, T.TCX_KEY_STREAM) == 0x1230
+    T.tcx_attr_set(ex, T.TCX_KEY_STREAM, 0)
+    assert T.tcx_attr_get(ex, T.TCX_KEY_WORKSPACE_BYTES) == 0
+    if not T.tcx_handle_has_device(handle):
+        assert _code(T.tcx_attr_set, ex, T.TCX_KEY_WORKSPACE_BYTES, 4096) == T.TCX_ERR_NO_DEVICE
+    assert _code(T.tcx_attr_get, ex, T.TCX_KEY_NUM_CU) == T.TCX_ERR_BAD_KEY
+    T.tcx_destroy_executor(ex)
+
+
+def test_split_products_report_their_workspace(handle):
+    """A plan cut along K says how many bytes of partial sums an execution writes; an unsplit plan
+    and a two-part split summed inside the workgroup write none."""
+    prod = _matrix_product(handle, T.TCX_F64, 64, 64, 4096)
+    T.tcx_product_set(prod, T.TCX_KEY_FORCE_PATH, T.TCX_PATH_GETT_MFMA)
+    T.tcx_product_set(prod, T.TCX_KEY_VARIANT, 3)                     # 32 x 32 tiles: 4 of them
+    T.tcx_product_set(prod, T.TCX_KEY_SPLIT_K, 8)
+    assert T.tcx_product_get(prod, T.TCX_KEY_SPLIT_K) == 8
+    assert T.tcx_product_get(prod, T.TCX_KEY_WORKSPACE_BYTES) == 4 * 8 * 32 * 32 * 8
+    T.tcx_product_set(prod, T.TCX_KEY_SPLIT_K, 1)
+    assert T.tcx_product_get(prod, T.TCX_KEY_WORKSPACE_BYTES) == 0
+    T.tcx_destroy_product(prod)
