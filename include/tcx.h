@@ -190,6 +190,21 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
                                 const void* alpha, const void* A, const void* B,
                                 const void* beta, const void* C, void* D);
 
+/* The same execution for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * tcx_execute_product without the status object; the call allocates nothing, on the device or on
+ * the host.  Where tcx_execute_product would lease the executor's workspace (partial sums of a
+ * plan with TCX_KEY_SPLIT_K > 1, TCX_KEY_WORKSPACE_BYTES of them), this call uses a fixed buffer
+ * of TCX_SCRATCH_BYTES that every GPU running the library holds from load until the process ends.
+ * A product that needs more returns TCX_ERR_SCRATCH_TOO_SMALL and enqueues nothing.  All calls on
+ * one GPU share that buffer: two of them that both need it must not overlap in time (the same
+ * stream, or the caller's own ordering); the buffer keeps the last call's contents and every
+ * call writes all it reads, so nothing has to be cleared. */
+#define TCX_SCRATCH_BYTES (32 * 1024 * 1024)
+tcx_error_t tcx_execute_product_noalloc(tcx_product_t product, tcx_executor_t executor,
+                                        const void* alpha, const void* A, const void* B,
+                                        const void* beta, const void* C, void* D);
+
 /* ---- status object (Sec. "Status Objects") ------------------------------------------ */
 tcx_error_t tcx_status_get(tcx_status_t status, int32_t key, void* value, size_t* nbytes);
 tcx_error_t tcx_destroy_status(tcx_status_t* status);

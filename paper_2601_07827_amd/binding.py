@@ -44,12 +44,14 @@ TCX_PATH_GENERIC, TCX_PATH_GETT_MFMA, TCX_PATH_BANDWIDTH = 0, 1, 2
  TCX_KEY_GATHER_WIDTH, TCX_KEY_TABLE_ENTRIES, TCX_KEY_WORKSPACE_BYTES, TCX_KEY_DEVICE, TCX_KEY_NUM_CU,
  TCX_KEY_STREAM) = range(1, 33)
 TCX_MAX_MODES = 32
+TCX_SCRATCH_BYTES = 32 * 1024 * 1024
 TCX_KEY_USER = 65536
 
 EXPORTS = [
     "tcx_create_handle", "tcx_destroy_handle", "tcx_handle_has_device", "tcx_create_executor", "tcx_destroy_executor",
     "tcx_create_tensor_info", "tcx_destroy_tensor_info", "tcx_tensor_info_get", "tcx_create_product",
-    "tcx_destroy_product", "tcx_product_get", "tcx_product_set", "tcx_execute_product", "tcx_status_get",
+    "tcx_destroy_product", "tcx_product_get", "tcx_product_set", "tcx_execute_product", "tcx_execute_product_noalloc",
+    "tcx_status_get",
     "tcx_destroy_status", "tcx_check_success", "tcx_explain_error",
     "tcx_create_attr", "tcx_destroy_attr", "tcx_attr_set", "tcx_attr_get", "tcx_attr_clear",
 ]
@@ -73,6 +75,7 @@ _lib.tcx_destroy_product.argtypes = [_hp]
 _lib.tcx_product_get.argtypes = [_h, ctypes.c_int32, _vp, _szp]
 _lib.tcx_product_set.argtypes = [_h, ctypes.c_int32, _vp, ctypes.c_size_t]
 _lib.tcx_execute_product.argtypes = [_h, _h, _hp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.tcx_execute_product_noalloc.argtypes = [_h, _h, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.tcx_status_get.argtypes = [_h, ctypes.c_int32, _vp, _szp]
 _lib.tcx_destroy_status.argtypes = [_hp]
 _lib.tcx_create_attr.argtypes = [_h, _hp]
@@ -234,6 +237,14 @@ def tcx_execute_product(product: int, executor: int, dtype: int, alpha, A: int, 
         _lib.tcx_destroy_status(ctypes.byref(s))
     _check(code, "tcx_execute_product")
     return st.value if want_status else None
+
+
+def tcx_execute_product_noalloc(product: int, executor: int, dtype: int, alpha, A: int, B: int, beta, C: int, D: int) -> None:
+    """tcx_execute_product for callers that cannot allocate: no status object, fixed scratch buffer."""
+    al, be = _scalar(dtype, alpha), _scalar(dtype, beta)
+    _check(_lib.tcx_execute_product_noalloc(product, executor, ctypes.cast(ctypes.pointer(al), _vp), _vp(A), _vp(B),
+                                            ctypes.cast(ctypes.pointer(be), _vp), _vp(C), _vp(D)),
+           "tcx_execute_product_noalloc")
 
 
 def tcx_status_get(status: int, key: int):

@@ -14,6 +14,13 @@
 
 #include "tcx_internal.hpp"
 
+// Fixed scratch buffer of tcx_execute_product_noalloc: device memory that exists from the moment
+// the library's code is loaded on a GPU until the process ends, so that an execution which needs
+// room for split-K partial sums does not have to allocate it.  Every GPU holds its own copy at its
+// own address; in host code the array's name only identifies the symbol.  The address on a device
+// is asked for once, with that device current, when a handle is created on it, and kept.
+static __device__ __align__(256) unsigned char scratch[TCX_SCRATCH_BYTES];
+
 namespace tcx {
 namespace {
 
@@ -23,6 +30,7 @@ struct Handle {
     int device = -1;
     bool has_device = false;
     int num_cu = 0;
+    void* scratch = nullptr;   // this device's copy of the fixed scratch buffer (tcx_execute_product_noalloc)
 };
 struct Executor {
     Handle handle;
@@ -69,6 +77,28 @@ struct Status {
 int64_t round_size_of(const Product& p, const GettVariant& s) {
     const int64_t nk = (p.an.sizeK + s.kt - 1) / s.kt;
     return (s.pingpong && nk >= 256) ? (p.handle.num_cu > 0 ? p.handle.num_cu : 256) : 0;   // a plan-only handle assumes 256 CUs
+}
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+bool g_scratch_asked[kMaxDevices] = {};
+
+// Address of `scratch` on `device`, which must be the current device.  nullptr if the runtime
+// cannot tell (the no-alloc entry point then refuses split products).
+void* scratch_on(int device) {
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_asked[device]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            ptr = nullptr;
+        }
+        g_scratch_ptr[device] = ptr;
+        g_scratch_asked[device] = true;
+    }
+    return g_scratch_ptr[device];
 }
 
 std::mutex g_mu;
@@ -512,6 +542,7 @@ tcx_error_t tcx_create_handle(tcx_handle_t* out) {
             h->device = dev;
             h->has_device = true;
             h->num_cu = prop.multiProcessorCount;
+            h->scratch = scratch_on(dev);
         }
     }
     (void)hipGetLastError();
@@ -746,8 +777,13 @@ tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* valu
     return TCX_ERR_BAD_KEY;
 }
 
-tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, tcx_status_t* status, const void* alpha,
-                                const void* A, const void* B, const void* beta, const void* C, void* D) {
+}  // extern "C"
+
+namespace {
+// Body of both execute calls.  fixed_scratch: partial sums go to the library's fixed per-device
+// buffer and nothing is allocated, neither on the device nor (no status object) on the host.
+tcx_error_t run_product(tcx_product_t product, tcx_executor_t executor, tcx_status_t* status, const void* alpha,
+                        const void* A, const void* B, const void* beta, const void* C, void* D, bool fixed_scratch) {
     Product* p = lookup<Product>(product, MAGIC_PRODUCT);
     Executor* e = lookup<Executor>(executor, MAGIC_EXEC);
     if (!p || !e) return TCX_ERR_INVALID_HANDLE;
@@ -828,10 +864,15 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
         g.read_c = read_c;
         g.splitK = p->splitK;
         if (const size_t need = workspace_need(*p)) {
-            // leased from the executor: executions on its stream run in order and may share it
-            std::lock_guard<std::mutex> lk(e->mu);
-            if (grow_workspace(e, need) == TCX_SUCCESS) g.workspace = e->workspace;
-            else g.splitK = 1;                               // no memory for partial sums: run unsplit
+            if (fixed_scratch) {
+                if (need > (size_t)TCX_SCRATCH_BYTES || !e->handle.scratch) return TCX_ERR_SCRATCH_TOO_SMALL;
+                g.workspace = e->handle.scratch;             // fully written by the parts before the reduction reads it
+            } else {
+                // leased from the executor: executions on its stream run in order and may share it
+                std::lock_guard<std::mutex> lk(e->mu);
+                if (grow_workspace(e, need) == TCX_SUCCESS) g.workspace = e->workspace;
+                else g.splitK = 1;                           // no memory for partial sums: run unsplit
+            }
         }
         g.lid_base = 0;
         // rounds pay off when a tile runs for milliseconds (hundreds of slabs) and there are several rounds
@@ -855,6 +896,19 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
         *status = so ? publish(so, MAGIC_STATUS) : 0;
     }
     return hip_err == 0 ? TCX_SUCCESS : TCX_ERR_LAUNCH;
+}
+}  // namespace
+
+extern "C" {
+
+tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, tcx_status_t* status, const void* alpha,
+                                const void* A, const void* B, const void* beta, const void* C, void* D) {
+    return run_product(product, executor, status, alpha, A, B, beta, C, D, false);
+}
+
+tcx_error_t tcx_execute_product_noalloc(tcx_product_t product, tcx_executor_t executor, const void* alpha, const void* A,
+                                        const void* B, const void* beta, const void* C, void* D) {
+    return run_product(product, executor, nullptr, alpha, A, B, beta, C, D, true);
 }
 
 tcx_error_t tcx_status_get(tcx_status_t status, int32_t key, void* value, size_t* nbytes) {

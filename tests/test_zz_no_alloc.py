@@ -1,0 +1,85 @@
+"""tcx_execute_product_noalloc: the execute call for callers that cannot allocate (code under graph
+capture, serving loops).  Its split-K partial sums go to the library's fixed per-device buffer.
+Checked against tcx_execute_product on the same plan and inputs, bit for bit (same kernels, same
+fixed summation order), on two calls in a row, the second with a smaller input, and against the
+oracle; a plan that needs more than the fixed buffer is refused and touches nothing."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from helpers import TOLERANCE, normalised_error, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+GETT, STREAM = 1, 2
+
+
+def _both_entry_points(p, variant, split_k, path=GETT):
+    """(D from tcx_execute_product, D from tcx_execute_product_noalloc, free device bytes before and
+    after the no-alloc call, workspace bytes the plan needs)."""
+    import torch
+    import paper_2601_07827_amd as T
+    from gpu_helpers import GpuProduct, say
+    say("%s variant=%s split_k=%s: both entry points" % (p.name, variant, split_k))
+    a, b, c = W.make_operands(p)
+    gp = GpuProduct(p, path, variant, split_k)
+    try:
+        need = gp.get(T.TCX_KEY_WORKSPACE_BYTES)
+        dA, dB = torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda()
+        d1, d2 = torch.from_numpy(c.copy()).cuda(), torch.from_numpy(c.copy()).cuda()
+        item = d1.element_size()
+        ptr = lambda t, spec: t.data_ptr() + spec.base * item
+        gp.execute(dA, dB, d1, d1)
+        torch.cuda.synchronize()
+        free0 = torch.cuda.mem_get_info()[0]
+        T.tcx_execute_product_noalloc(gp.prod, gp.ex, gp.dtype, p.alpha, ptr(dA, p.A), ptr(dB, p.B), p.beta,
+                                      ptr(d2, p.D), ptr(d2, p.D))
+        torch.cuda.synchronize()
+        free1 = torch.cuda.mem_get_info()[0]
+        return a, b, c, d1.cpu().numpy(), d2.cpu().numpy(), free0, free1, need
+    finally:
+        gp.close()
+
+
+def test_no_alloc_entry_point_two_calls_second_smaller():
+    import paper_2601_07827_amd as T
+    # first call: 576^3 in 81 tiles of 64 x 64, K in 6 parts: 15.9 MB of partial sums
+    # second call: 144^3 in 25 tiles of 32 x 32, K in 3 parts, on the buffer the first call left behind
+    for p, variant, split_k in ((W.config1(), 2, 6), (W.config1(12), 3, 3)):
+        a, b, c, d_ref, d_new, free0, free1, need = _both_entry_points(p, variant, split_k)
+        assert 0 < need <= T.TCX_SCRATCH_BYTES
+        assert np.array_equal(d_ref, d_new), "the two entry points disagree"
+        assert free1 == free0, "device memory changed hands during the call"
+        truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+        assert normalised_error(p, d_new, truth, S, c) <= TOLERANCE[p.dtype]
+
+
+def test_no_alloc_entry_point_without_scratch_use():
+    """Plans that write no partial sums (unsplit tiled, streaming) run through it unchanged."""
+    for p, path, split_k in ((W.config4(h=6, n=20), GETT, 1), (W.config4(h=24, n=20, k=4), STREAM, None)):
+        a, b, c, d_ref, d_new, free0, free1, need = _both_entry_points(p, None, split_k, path)
+        assert need == 0
+        assert np.array_equal(d_ref, d_new)
+        assert free1 == free0
+
+
+def test_no_alloc_entry_point_refuses_what_does_not_fit():
+    import torch
+    import paper_2601_07827_amd as T
+    from gpu_helpers import GpuProduct
+    e = dict(m=2048, n=2048, k=512)
+    p = W.Problem("too_big_for_scratch", "f64", W.tensor("mk", e), W.tensor("kn", e), W.tensor("mn", e), alpha=1.0, beta=0.0)
+    gp = GpuProduct(p, GETT, 3, 8)                      # 4096 tiles of 32 x 32, 8 parts: 268 MB of partial sums
+    try:
+        assert gp.get(T.TCX_KEY_WORKSPACE_BYTES) > T.TCX_SCRATCH_BYTES
+        dA = torch.zeros(p.A.size, dtype=torch.float64, device="cuda:0")
+        dB = torch.zeros(p.B.size, dtype=torch.float64, device="cuda:0")
+        dD = torch.full((p.D.size,), 7.0, dtype=torch.float64, device="cuda:0")
+        with pytest.raises(T.TcxError) as exc:
+            T.tcx_execute_product_noalloc(gp.prod, gp.ex, gp.dtype, 1.0, dA.data_ptr(), dB.data_ptr(), 0.0, 0, dD.data_ptr())
+        assert exc.value.code == T.TCX_ERR_SCRATCH_TOO_SMALL and "scratch" in str(exc.value)
+        torch.cuda.synchronize()
+        assert bool((dD == 7.0).all()), "a refused call must enqueue nothing"
+    finally:
+        gp.close()
