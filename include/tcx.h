@@ -235,6 +235,18 @@ tcx_error_t tcx_attr_set(tcx_object_t object, int32_t key, const void* value, si
 tcx_error_t tcx_attr_get(tcx_object_t object, int32_t key, void* value, size_t* nbytes);
 tcx_error_t tcx_attr_clear(tcx_object_t object, int32_t key);
 
+/* ---- measurement aid (not part of the contraction) -----------------------------------------
+ * Enqueues ONE launch of a kernel that does a single kind of work on the executor's stream, so
+ * that a benchmark can print what the chip sustains beside its specification figures:
+ *   TCX_PROBE_MFMA_F64 / _F32  every wave of every compute unit issues `iters` x 16 independent
+ *                              16x16x4 MFMAs back to back (buffer: at least 16 bytes, not written);
+ *   TCX_PROBE_STORE            fills buffer[0, bytes) with 16-byte stores;
+ *   TCX_PROBE_COPY             copies the first half of buffer[0, bytes) to the second half.
+ * buffer is a device pointer, 16-byte aligned.  *work receives the flop (MFMA probes) or the bytes
+ * read plus written (memory probes) of the launch; the caller times it with events. */
+typedef enum { TCX_PROBE_MFMA_F64 = 0, TCX_PROBE_MFMA_F32 = 1, TCX_PROBE_STORE = 2, TCX_PROBE_COPY = 3 } tcx_probe_t;
+tcx_error_t tcx_probe_launch(tcx_executor_t executor, int32_t kind, void* buffer, size_t bytes, int64_t iters, double* work);
+
 /* ---- error handling (Sec. "Error Handling") ------------------------------------------ */
 int tcx_check_success(tcx_error_t error);                                  /* 1 iff error == TCX_SUCCESS */
 /* strerror analogue: writes at most maxlen bytes (NUL-terminated if maxlen > 0) and

@@ -45,6 +45,7 @@ TCX_PATH_GENERIC, TCX_PATH_GETT_MFMA, TCX_PATH_BANDWIDTH = 0, 1, 2
  TCX_KEY_STREAM) = range(1, 33)
 TCX_MAX_MODES = 32
 TCX_SCRATCH_BYTES = 32 * 1024 * 1024
+TCX_PROBE_MFMA_F64, TCX_PROBE_MFMA_F32, TCX_PROBE_STORE, TCX_PROBE_COPY = 0, 1, 2, 3
 TCX_KEY_USER = 65536
 
 EXPORTS = [
@@ -53,7 +54,7 @@ EXPORTS = [
     "tcx_destroy_product", "tcx_product_get", "tcx_product_set", "tcx_execute_product", "tcx_execute_product_noalloc",
     "tcx_status_get",
     "tcx_destroy_status", "tcx_check_success", "tcx_explain_error",
-    "tcx_create_attr", "tcx_destroy_attr", "tcx_attr_set", "tcx_attr_get", "tcx_attr_clear",
+    "tcx_create_attr", "tcx_destroy_attr", "tcx_attr_set", "tcx_attr_get", "tcx_attr_clear", "tcx_probe_launch",
 ]
 
 _h = ctypes.c_ssize_t            # intptr_t
@@ -83,6 +84,7 @@ _lib.tcx_destroy_attr.argtypes = [_hp]
 _lib.tcx_attr_set.argtypes = [_h, ctypes.c_int32, _vp, ctypes.c_size_t]
 _lib.tcx_attr_get.argtypes = [_h, ctypes.c_int32, _vp, _szp]
 _lib.tcx_attr_clear.argtypes = [_h, ctypes.c_int32]
+_lib.tcx_probe_launch.argtypes = [_h, ctypes.c_int32, _vp, ctypes.c_size_t, ctypes.c_int64, ctypes.POINTER(ctypes.c_double)]
 _lib.tcx_check_success.argtypes = [ctypes.c_int32]
 _lib.tcx_explain_error.argtypes = [ctypes.c_int32, ctypes.c_size_t, ctypes.c_char_p]
 _lib.tcx_explain_error.restype = ctypes.c_size_t
@@ -297,6 +299,13 @@ def tcx_attr_get(obj: int, key: int):
 
 def tcx_attr_clear(obj: int, key: int) -> None:
     _check(_lib.tcx_attr_clear(obj, key), "tcx_attr_clear")
+
+
+def tcx_probe_launch(executor: int, kind: int, buffer: int, nbytes: int, iters: int = 0) -> float:
+    """One launch of a measurement kernel; returns the flop or bytes it performs."""
+    work = ctypes.c_double(0.0)
+    _check(_lib.tcx_probe_launch(executor, kind, _vp(buffer), nbytes, iters, ctypes.byref(work)), "tcx_probe_launch")
+    return work.value
 
 
 def raw():

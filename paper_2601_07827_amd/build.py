@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtcx.so")
 OBJDIR = os.path.join(HERE, "_build")
 
-SOURCES = ["api.cpp", "analyser.cpp", "stream_plan.cpp", "kernels_generic.hip", "kernels_gett.hip", "kernels_stream.hip"]
+SOURCES = ["api.cpp", "analyser.cpp", "stream_plan.cpp", "kernels_generic.hip", "kernels_gett.hip", "kernels_stream.hip", "probes.hip"]
 HEADERS = [os.path.join(CSRC, "tcx_internal.hpp"), os.path.join(ROOT, "include", "tcx.h")]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",

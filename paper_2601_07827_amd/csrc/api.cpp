@@ -911,6 +911,15 @@ tcx_error_t tcx_execute_product_noalloc(tcx_product_t product, tcx_executor_t ex
     return run_product(product, executor, nullptr, alpha, A, B, beta, C, D, true);
 }
 
+tcx_error_t tcx_probe_launch(tcx_executor_t executor, int32_t kind, void* buffer, size_t bytes, int64_t iters, double* work) {
+    Executor* e = lookup<Executor>(executor, MAGIC_EXEC);
+    if (!e) return TCX_ERR_INVALID_HANDLE;
+    if (!buffer || !work) return TCX_ERR_NULL_ARG;
+    if (!e->handle.has_device) return TCX_ERR_NO_DEVICE;
+    if (((uintptr_t)buffer & 15) != 0) return TCX_ERR_TOO_LARGE;
+    return launch_probe(kind, buffer, bytes, iters, e->handle.num_cu, (void*)e->stream, work) == 0 ? TCX_SUCCESS : TCX_ERR_LAUNCH;
+}
+
 tcx_error_t tcx_status_get(tcx_status_t status, int32_t key, void* value, size_t* nbytes) {
     Status* s = lookup<Status>(status, MAGIC_STATUS);
     if (!s) return TCX_ERR_INVALID_HANDLE;

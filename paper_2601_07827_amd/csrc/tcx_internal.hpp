@@ -202,6 +202,9 @@ StreamPlan plan_stream(const Analysis& an, int elem_bytes, bool allow_blocked = 
 // Arithmetic intensity test + size limits: should this product take the streaming path?
 bool stream_preferred(const Analysis& an, int elem_bytes);
 
+// Measurement aid (probes.hip): one launch of a single-purpose kernel; *work = flop or bytes it does.
+int launch_probe(int kind, void* buffer, size_t bytes, int64_t iters, int num_cu, void* stream, double* work);
+
 int launch_stream(int dtype, bool blocked, bool direct, const StreamArgs& args, size_t lds_bytes, int num_cu, void* stream,
                   int64_t* grid, int* block);
 

@@ -63,3 +63,29 @@ def test_config_shapes_match_the_stated_sizes():
     assert W.config4().real_flops() == 3623878656
     assert W.config3().D.size == 2 * 37 * 53 * 61 and W.config3().D.strides == (122, 4514, 2)
     assert W.config3().A.strides == (2173, 80401, 1, 41)
+
+
+def test_config2_samples_reach_every_launch_round_and_xcd_stretch():
+    """The full-size check of configuration 2 compares a grid of rows x columns of D.  The 4608
+    tiles of 256 x 128 are walked in bands of 8 tile rows; a launch round is 256 consecutive tiles
+    of that order (one band), handed to the 8 XCDs in stretches of 32 consecutive tiles.  Every
+    (round, stretch) pair must hold a sample, or a wrong tile in one of them would go unseen."""
+    import bench
+    p = W.config2()
+    _, M, N, _ = p.sizes()
+    tm, tn = 256, 128
+    tiles_m, tiles_n = M // tm, N // tn
+    assert (tiles_m, tiles_n) == (144, 32)
+    m_idx, n_idx = bench.config2_sample_indices(p, tm, tn, np.random.default_rng(p.seed))
+    assert len(m_idx) * len(n_idx) >= 400
+    seen = set()
+    for m in m_idx:
+        for n in n_idx:
+            row, col = int(m) // tm, int(n) // tn
+            band = row // 8
+            position = band * 8 * tiles_n + (row % 8) + 8 * col        # place in the tile order
+            launch_round, in_round = divmod(position, 256)
+            seen.add((launch_round, in_round // 32))
+    assert seen == {(r, x) for r in range(tiles_m * tiles_n // 256) for x in range(8)}
+    # tile-boundary rows and columns are among the samples
+    assert {0, tm - 1, tm, M - 1} <= set(int(v) for v in m_idx) and {0, tn - 1, tn, N - 1} <= set(int(v) for v in n_idx)
