@@ -137,7 +137,16 @@ template <class T> tcx_error_t retire(intptr_t* h, uint32_t magic) {
 int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 int64_t tiles_of(const Analysis& an, const GettVariant& s) {
-    return ((an.sizeM + s.mt_m - 1) / s.mt_m) * ((an.sizeN + s.mt_n - 1) / s.mt_n) * an.sizeH;
+    return ((an.sizeM + s.mt_m - 1) / s.mt_m) * ((an.sizeN + s.mt_n - 1) / s.mt_n) * (an.sizeH / s.hl);
+}
+
+// The batch-lane kernel takes plans whose fastest hyper mode is the fastest mode of A, B and D
+// (stride 1) with an extent it can cut into whole groups of s.hl batches.
+bool batch_lanes_ok(const Analysis& an, const GettVariant& s) {
+    if (s.hl <= 1) return true;
+    if (an.H.empty()) return false;
+    const Mode& h = an.H[0];
+    return h.sA == 1 && h.sB == 1 && h.sD == 1 && h.extent % s.hl == 0;
 }
 
 // Cost model for tile shape and split-K, in microseconds.  A workgroup's time is its slabs at
@@ -163,13 +172,14 @@ std::vector<PlanChoice> rank_plans(const Analysis& an, int num_cu) {
     const double store_us = (double)an.sizeH * an.sizeM * an.sizeN * ebytes / 4e12 * 1e6;
     for (int v = 0; v < n; ++v) {
         const GettVariant s = gett_variant(an.dtype, v);
+        if (!batch_lanes_ok(an, s)) continue;
         double best = -1;
         int bestS = 1;
         const double tiles = (double)tiles_of(an, s);
         const int64_t nk = (an.sizeK + s.kt - 1) / s.kt;
         const double slab_us = flop_per_mac * s.mt_m * s.mt_n * s.kt / (cu_flops * s.efficiency) * 1e6;
         for (int64_t want : {1, 2, 3, 4, 6, 8}) {
-            if (want > nk) break;
+            if (want > nk || (want > 1 && s.hl > 1)) break;
             const int64_t per = (nk + want - 1) / want;
             const int64_t S = (nk + per - 1) / per;
             // small tiles leave room for several workgroups per CU, which then share its matrix
@@ -352,6 +362,7 @@ bool narrow_operand(const std::vector<int64_t>& rows, int64_t nrows, int mt, con
 // shape spans 4 GB or more of an operand.
 tcx_error_t build_narrow(Product* p, int variant) {
     const GettVariant s = gett_variant(p->an.dtype, variant);
+    if (!batch_lanes_ok(p->an, s)) return TCX_ERR_PLAN_REFUSED;
     if (p->narrow_variant == variant) return TCX_SUCCESS;
     const int64_t es = elem_bytes(p->an.dtype);
     NarrowOperand a, b;
@@ -363,8 +374,12 @@ tcx_error_t build_narrow(Product* p, int variant) {
         auto operand_ok = [&](bool k_fastest, bool periodic, int mt) {
             return k_fastest ? periodic : (mt % 64 == 0 && s.threads % mt == 0);
         };
-        if (s.pingpong && (!operand_ok(p->an.a_k_fastest, a.periodic, s.mt_m) || !operand_ok(p->an.b_k_fastest, b.periodic, s.mt_n)))
+        if (s.hl > 1) {
+            // lanes run along the batches: both operands in the slab-periodic form, whole slabs of K
+            if (!a.periodic || !b.periodic || p->an.sizeK % s.kt != 0) return TCX_ERR_PLAN_REFUSED;
+        } else if (s.pingpong && (!operand_ok(p->an.a_k_fastest, a.periodic, s.mt_m) || !operand_ok(p->an.b_k_fastest, b.periodic, s.mt_n))) {
             return TCX_ERR_PLAN_REFUSED;
+        }
         p->periodic[0] = a.periodic;
         p->periodic[1] = b.periodic;
         // Paired gather loads (8-byte elements, two-phase kernel with one tile per wave group):
@@ -393,7 +408,7 @@ tcx_error_t build_narrow(Product* p, int variant) {
         };
         p->pair_step[0] = pair_step(a, p->an.a_k_fastest, p->an.sizeM, s.mt_m, 0);
         p->pair_step[1] = pair_step(b, p->an.b_k_fastest, p->an.sizeN, s.mt_n, 1);
-        p->pairs = s.pingpong && s.dual && es == 8 && p->pair_step[0] > 0 && p->pair_step[1] > 0;
+        p->pairs = s.pingpong && s.dual && s.hl == 1 && es == 8 && p->pair_step[0] > 0 && p->pair_step[1] > 0;
     } catch (const std::bad_alloc&) {
         return TCX_ERR_ALLOC;
     }
@@ -676,7 +691,7 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
     if (!p) return TCX_ERR_INVALID_HANDLE;
     const Analysis& an = p->an;
     const bool tiled = an.path == TCX_PATH_GETT_MFMA;
-    const GettVariant s = tiled ? gett_variant(an.dtype, p->variant) : GettVariant{0, 0, 0, 256, 0.f, 0};
+    const GettVariant s = tiled ? gett_variant(an.dtype, p->variant) : GettVariant{0, 0, 0, 256, 0.f, 0, false, false, -1, false, false, 1};
     switch (key) {
         case TCX_KEY_PATH: return put_i64(an.path, value, nbytes);
         case TCX_KEY_SIZE_H: return put_i64(an.sizeH, value, nbytes);
@@ -769,6 +784,7 @@ tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* valu
     if (key == TCX_KEY_SPLIT_K) {
         if (p->an.path != TCX_PATH_GETT_MFMA || v < 1 || v > 64) return TCX_ERR_PLAN_REFUSED;
         const GettVariant sh = gett_variant(p->an.dtype, p->variant);
+        if (sh.hl > 1 && v > 1) return TCX_ERR_PLAN_REFUSED;          // the batch-lane kernel keeps K whole
         const int64_t nk = (p->an.sizeK + sh.kt - 1) / sh.kt;
         const int64_t per = (nk + v - 1) / v;
         p->splitK = (int)((nk + per - 1) / per);        // no part may be empty
@@ -858,6 +874,11 @@ tcx_error_t run_product(tcx_product_t product, tcx_executor_t executor, tcx_stat
         g.nH = (int32_t)p->an.H.size();
         for (int i = 0; i < g.nH; ++i) {
             g.hExt[i] = p->an.H[i].extent; g.hSA[i] = p->an.H[i].sA; g.hSB[i] = p->an.H[i].sB; g.hSD[i] = p->an.H[i].sD;
+        }
+        if (v.hl > 1) {
+            // a tile holds v.hl consecutive batches of the fastest hyper mode: the kernel decodes groups of them
+            g.sizeH /= v.hl;
+            g.hExt[0] /= v.hl; g.hSA[0] *= v.hl; g.hSB[0] *= v.hl; g.hSD[0] *= v.hl;
         }
         g.s = s;
         g.opA = p->an.opA; g.opB = p->an.opB; g.opC = p->an.opC;

@@ -43,6 +43,11 @@ template <> struct Mfma<double> {
     static __device__ __forceinline__ vec mac(double rowop, double colop, vec c) {
         return __builtin_amdgcn_mfma_f64_16x16x4f64(rowop, colop, c, 0, 0, 0);
     }
+    // The fp64 MFMA reads its last immediate as sign modifiers (bit 0: first source, bit 1: second,
+    // bit 2: accumulator input): c - rowop * colop without a vector-ALU instruction.
+    static __device__ __forceinline__ vec mac_minus(double rowop, double colop, vec c) {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(rowop, colop, c, 0, 0, 1);
+    }
     static __device__ __forceinline__ int row_of(int lane, int v) { return 4 * v + (lane >> 4); }
 };
 template <> struct Mfma<float> {
@@ -87,11 +92,11 @@ template <class R> struct RealPolicy {
         return *(const elem*)(base + byte_off);
     }
     static __device__ __forceinline__ void conj_fix(elem&, unsigned) {}
-    template <bool DNF> static __device__ __forceinline__ void mac(elem a, elem b, acc_t& c) {
+    template <bool DNF, bool MIXED = false> static __device__ __forceinline__ void mac(elem a, elem b, acc_t& c) {
         c.v = DNF ? MF::mac(a, b, c.v)      // rows = m, lanes along n
                   : MF::mac(b, a, c.v);     // rows = n, lanes along m
     }
-    static __device__ __forceinline__ elem combine(const acc_t& c, int v, const Scalars& s, bool read_c, elem cc, int) {
+    static __device__ __forceinline__ elem combine(const acc_t& c, int v, const Scalars& s, bool read_c, elem cc, int, bool = false) {
         R d = (R)s.alpha_re * c.v[v];
         if (read_c) d += (R)s.beta_re * cc;
         return d;
@@ -151,22 +156,26 @@ struct ComplexPolicy {
         unsigned long long bits = __builtin_bit_cast(unsigned long long, v.y) ^ ((unsigned long long)conj_mask_hi << 32);
         v.y = __builtin_bit_cast(double, bits);
     }
-    template <bool DNF> static __device__ __forceinline__ void mac(elem a, elem b, acc_t& c) {
-        const double nai = -a.y;
+    // MIXED = false: the product a * b.  MIXED = true: conj(a) * b, for kernels that leave
+    // conjugation out of their data path: with both operands conjugated they sum a * b, with one
+    // conj(a) * b, and the epilogue conjugates the sum where the conjugated operand was B
+    // (a * conj(b) = conj(conj(a) * b)).  The one minus sign of either form rides on the MFMA.
+    template <bool DNF, bool MIXED = false> static __device__ __forceinline__ void mac(elem a, elem b, acc_t& c) {
         if (DNF) {
             c.re = MF::mac(a.x, b.x, c.re);
-            c.re = MF::mac(nai, b.y, c.re);
+            c.re = MIXED ? MF::mac(a.y, b.y, c.re) : MF::mac_minus(a.y, b.y, c.re);
             c.im = MF::mac(a.x, b.y, c.im);
-            c.im = MF::mac(a.y, b.x, c.im);
+            c.im = MIXED ? MF::mac_minus(a.y, b.x, c.im) : MF::mac(a.y, b.x, c.im);
         } else {
             c.re = MF::mac(b.x, a.x, c.re);
-            c.re = MF::mac(b.y, nai, c.re);
+            c.re = MIXED ? MF::mac(b.y, a.y, c.re) : MF::mac_minus(b.y, a.y, c.re);
             c.im = MF::mac(b.y, a.x, c.im);
-            c.im = MF::mac(b.x, a.y, c.im);
+            c.im = MIXED ? MF::mac_minus(b.x, a.y, c.im) : MF::mac(b.x, a.y, c.im);
         }
     }
-    static __device__ __forceinline__ elem combine(const acc_t& c, int v, const Scalars& s, bool read_c, elem cc, int opC) {
-        const double re = c.re[v], im = c.im[v];
+    static __device__ __forceinline__ elem combine(const acc_t& c, int v, const Scalars& s, bool read_c, elem cc, int opC,
+                                                   bool conj_acc = false) {
+        const double re = c.re[v], im = conj_acc ? -c.im[v] : c.im[v];
         double dr = s.alpha_re * re - s.alpha_im * im;
         double di = s.alpha_re * im + s.alpha_im * re;
         if (read_c) {
@@ -320,7 +329,7 @@ __device__ __forceinline__ void scatter_at(const typename P::acc_t (&acc)[FM][FN
         for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                if (o.ok[i][j][v]) D[o.off[i][j][v]] = P::combine(acc[i][j], v, g.s, read_c, cval[j][v], g.opC);
+                if (o.ok[i][j][v]) D[o.off[i][j][v]] = P::combine(acc[i][j], v, g.s, read_c, cval[j][v], g.opC, g.conj_acc != 0);
     }
 }
 
@@ -360,7 +369,7 @@ __device__ __forceinline__ void scatter(const typename P::acc_t (&acc)[FM][FN], 
         for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                if (ok[j][v]) D[off[j][v]] = P::combine(acc[i][j], v, g.s, read_c, cval[j][v], g.opC);
+                if (ok[j][v]) D[off[j][v]] = P::combine(acc[i][j], v, g.s, read_c, cval[j][v], g.opC, g.conj_acc != 0);
     }
 }
 
@@ -689,7 +698,7 @@ template <int I, int N, class F> __device__ __forceinline__ void static_for(F&& 
 // tiles, whose memory phase is as long as the compute phase, the number of load instructions is
 // what counts.  Both operands take the slab-periodic form of the k offsets (one scalar base per
 // slab), whichever way their lanes run.
-template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF, bool DUAL, int DEPTH, bool RAGGED, bool LATE = false, int VEC = 1>
+template <class P, int MT_M, int MT_N, int KT, int WGM, int WGN, bool AKF, bool BKF, bool DNF, bool DUAL, int DEPTH, bool RAGGED, bool LATE = false, int VEC = 1, bool MIXED = false>
 __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_kernel(GettArgs g) {
     using T = typename P::elem;
     using V = typename staged_item<T, VEC>::type;
@@ -748,8 +757,6 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
     const int64_t m0 = wave_uniform(tile.m0), n0 = wave_uniform(tile.n0);
     const char* const Ab = (const char*)g.A + wave_uniform(tile.hA * (int64_t)sizeof(T) + scalar_table(g.rbA)[m0 / MT_M]);
     const char* const Bb = (const char*)g.B + wave_uniform(tile.hB * (int64_t)sizeof(T) + scalar_table(g.rbB)[n0 / MT_N]);
-    const unsigned conjA = g.opA == TCX_OP_CONJ ? 0x80000000u : 0u;
-    const unsigned conjB = g.opB == TCX_OP_CONJ ? 0x80000000u : 0u;
 
     // ---- everything per-lane, once.  Global byte offsets of this thread's slab elements
     // relative to the slab's scalar base: the row part, plus (lanes along k) the k part, which
@@ -912,15 +919,14 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
 #pragma unroll
         for (int j = 0; j < FN; ++j) fb[set][j] = lds_load<T>(fB[b] + j * dFB_row + step * dFB_step);
     };
+    // Conjugation never touches the data here: with exactly one operand conjugated (MIXED) the
+    // blocks sum conj(a) * b (one sign moves inside the complex product, on the MFMA's own sign
+    // modifier), and the launcher asks the epilogue to conjugate the sum if that operand was B.
     auto mfmas = [&](int set) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < FM; ++i) P::conj_fix(fa[set][i], conjA);
-#pragma unroll
-        for (int j = 0; j < FN; ++j) P::conj_fix(fb[set][j], conjB);
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < FN; ++j) P::template mac<DNF>(fa[set][i], fb[set][j], acc[i][j]);
+            for (int j = 0; j < FN; ++j) P::template mac<DNF, MIXED>(fa[set][i], fb[set][j], acc[i][j]);
     };
 
     // Prologue: slab kb to LDS, slabs kb+1 .. kb+DEPTH into the ring (slab numbers past the end
@@ -1182,6 +1188,244 @@ __global__ __launch_bounds__(256) void gett_direct_kernel(GettArgs g) {
     }
 }
 
+// ---- batch-lane kernel: batched products whose batch mode is the fastest mode of A, B and D ------
+// When consecutive memory holds consecutive BATCHES (D[h, i, j] with h fastest), an operand row of
+// one batch is one element out of every 128-byte line, and a tile of D for one batch writes one
+// element per line.  This kernel turns the tile around: a wave group of four waves owns FOUR
+// consecutive batches x MT_M x MT_N, wave w computing batch w of them.  Global loads run with four
+// neighbouring lanes on the four batches of a row (64 contiguous bytes of 16-byte elements; the
+// other half of the line belongs to the workgroup's other group, one phase later), LDS keeps one
+// region per batch in [row][k] order, and each wave reads its MFMA fragments from its own region:
+// LDS is the transposition between "lanes along the batches" (memory) and "one batch per wave"
+// (MFMA).  The epilogue goes back the same way: accumulators of a 16 x 16 block to LDS per batch,
+// read back with lanes along the batches, so C is read and D written in 64-byte pieces.
+// The schedule is the two-phase one of gett_pingpong_kernel with one tile per group: memory phase
+// (registers -> LDS, next global loads, fragment reads: no vector-ALU instruction) and compute
+// phase (MFMAs only: conjugation rides on the MFMA sign modifier), the groups one phase apart.
+// Preconditions (host): the fastest hyper mode has stride 1 in A, B and D and an extent that is a
+// multiple of 4; |K| is a multiple of KT; the relative k offsets repeat from slab to slab; K unsplit.
+constexpr int kBatchLanes = 4;
+
+template <class P, int MT_M, int MT_N, int KT, bool DNF, int DEPTH, bool MIXED>
+__global__ __launch_bounds__(512) void gett_hlane_kernel(GettArgs g) {
+    using T = typename P::elem;
+    using acc_t = typename P::acc_t;
+    constexpr int HL = kBatchLanes, NTG = 256, NB = 2;
+    constexpr int FM = MT_M / 16, FN = MT_N / 16;
+    constexpr int QT = NTG / HL;                          // threads of a group per batch
+    constexpr int PER_A = MT_M * KT / QT, PER_B = MT_N * KT / QT;
+    constexpr int LD = KT + kPadK;                        // [row][k] pitch
+    constexpr int REGION = (MT_M + MT_N) * LD + 4;        // elements of one batch's slab; + 64 bytes so the four
+                                                          // batches of a row land in different banks
+    constexpr int SLAB = HL * REGION;
+    constexpr unsigned ES = sizeof(T);
+    static_assert(sizeof(T) == 16, "four batches of 16-byte elements make a 64-byte piece");
+    static_assert(KT == 4, "one MFMA k-step per slab");
+    static_assert(MT_M % 16 == 0 && MT_N % 16 == 0 && (MT_M * KT) % QT == 0 && (MT_N * KT) % QT == 0 && QT % KT == 0, "tile shape");
+    static_assert(NB % DEPTH == 0 || DEPTH % NB == 0, "ring and LDS slabs cycle together");
+    constexpr int EPI = HL * (256 + 4);                   // epilogue: a 16 x 16 block per batch, regions 64 bytes apart in the banks
+    static_assert(2 * EPI <= NB * SLAB, "the epilogue's exchange buffers live in the slabs");
+
+    __shared__ __attribute__((aligned(16))) T lds[2 * NB * SLAB];
+    static_assert(sizeof(T) * 2 * NB * SLAB <= 160 * 1024, "LDS budget of a CU");
+
+    const int wave_all = wave_uniform((int)threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const bool second_group = wave_all >= 4;
+    const int tid = (int)threadIdx.x % NTG;
+    const int wave = wave_all % 4;                        // = the batch of the group's four this wave computes
+    const int hl = tid % HL, q = tid / HL;                // staging: batch and slot of this thread
+
+    // ---- which item: (group of four batches, tile of M x N).  A group past the end repeats the last
+    // item and stores nothing, so that every wave runs the same barriers.
+    const int64_t items = (int64_t)g.tilesM * g.tilesN * g.sizeH;          // sizeH: groups of four batches
+    const int64_t wg = g.lid_base + xcd_contiguous(blockIdx.x, gridDim.x);
+    const int64_t lid = 2 * wg + (second_group ? 1 : 0);
+    const bool active = lid < items;
+    const Tile tile = locate_tile<true>(min(lid, items - 1), g, MT_M, MT_N);
+    const int64_t m0 = wave_uniform(tile.m0), n0 = wave_uniform(tile.n0);
+    const char* const Ab = (const char*)g.A + wave_uniform(tile.hA * (int64_t)ES + scalar_table(g.rbA)[m0 / MT_M]);
+    const char* const Bb = (const char*)g.B + wave_uniform(tile.hB * (int64_t)ES + scalar_table(g.rbB)[n0 / MT_N]);
+    const int nk = g.tilesK;
+
+    // ---- per lane, once: global byte offsets of this thread's slab elements relative to the slab's
+    // scalar base (row part + slab-periodic k part + batch), LDS write and fragment-read addresses.
+    // Item e of the batch's QT-thread slice is (row e / KT, k e % KT); a thread's items are QT apart.
+    uint32_t voA[PER_A], voB[PER_B];
+#pragma unroll
+    for (int i = 0; i < PER_A; ++i) voA[i] = g.rrA[m0 + (q + i * QT) / KT] + g.krA[q % KT] + (uint32_t)hl * ES;
+#pragma unroll
+    for (int i = 0; i < PER_B; ++i) voB[i] = g.rrB[n0 + (q + i * QT) / KT] + g.krB[q % KT] + (uint32_t)hl * ES;
+    const int fr = lane & 15, fq = lane >> 4;
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) T*)lds + (second_group ? ES * NB * SLAB : 0u);
+    unsigned wA[NB], wB[NB], fA[NB], fB[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        wA[b] = lds0 + ES * (unsigned)(b * SLAB + hl * REGION + (q / KT) * LD + q % KT);
+        wB[b] = wA[b] + ES * (unsigned)(MT_M * LD);
+        fA[b] = lds0 + ES * (unsigned)(b * SLAB + wave * REGION + fr * LD + fq);
+        fB[b] = fA[b] + ES * (unsigned)(MT_M * LD);
+        asm volatile("" : "+v"(wA[b]), "+v"(wB[b]), "+v"(fA[b]), "+v"(fB[b]));     // kept, not recomputed in the loop
+    }
+    constexpr unsigned dW = ES * (QT / KT) * LD;          // a thread's next item: QT / KT rows further
+    constexpr unsigned dF = ES * 16 * LD;                 // next block of 16 rows
+
+    int64_t kbA = 0, kbB = 0;                             // per slab, scalar: the base of each load
+    auto k_offsets = [&](int slab) __attribute__((always_inline)) {
+        const int kc = min(slab, nk - 1);                 // slabs past the end repeat the last: loads that nothing uses
+        kbA = scalar_table(g.kbA)[kc];
+        kbB = scalar_table(g.kbB)[kc];
+    };
+    T ra[DEPTH][PER_A], rb[DEPTH][PER_B];                 // slab j waits in ring slot j % DEPTH
+    auto gather = [&](auto SLOT) __attribute__((always_inline)) {
+        constexpr int sl = decltype(SLOT)::value;
+#pragma unroll
+        for (int i = 0; i < PER_A; ++i) {
+            asm("" : "+v"(voA[i]));                       // "scalar base + 32-bit lane offset" stays that way
+            ra[sl][i] = P::load_at(Ab + kbA, voA[i], 0u);
+        }
+#pragma unroll
+        for (int i = 0; i < PER_B; ++i) {
+            asm("" : "+v"(voB[i]));
+            rb[sl][i] = P::load_at(Bb + kbB, voB[i], 0u);
+        }
+    };
+    auto stage = [&](auto BUF, auto SLOT) __attribute__((always_inline)) {
+        constexpr int b = decltype(BUF)::value, sl = decltype(SLOT)::value;
+#pragma unroll
+        for (int i = 0; i < PER_A; ++i) lds_store<T>(wA[b] + i * dW, ra[sl][i]);
+#pragma unroll
+        for (int i = 0; i < PER_B; ++i) lds_store<T>(wB[b] + i * dW, rb[sl][i]);
+    };
+    acc_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) P::clear(acc[i][j]);
+    T fa[FM], fb[FN];
+    auto frag_load = [&](auto BUF) __attribute__((always_inline)) {
+        constexpr int b = decltype(BUF)::value;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) fa[i] = lds_load<T>(fA[b] + i * dF);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) fb[j] = lds_load<T>(fB[b] + j * dF);
+    };
+    auto mfmas = [&]() __attribute__((always_inline)) {       // MIXED: see ComplexPolicy::mac
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) P::template mac<DNF, MIXED>(fa[i], fb[j], acc[i][j]);
+    };
+
+    // Prologue: slab 0 to LDS, slabs 1 .. DEPTH into the ring.
+    k_offsets(0);
+    gather(std::integral_constant<int, 0>{});
+    k_offsets(1);
+    if constexpr (DEPTH >= 2) {
+        gather(std::integral_constant<int, 1>{});
+        k_offsets(2);
+    }
+    stage(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    gather(std::integral_constant<int, DEPTH % DEPTH>{});               // slab DEPTH into the slot slab 0 has left
+    k_offsets(DEPTH + 1);
+    __syncthreads();
+    if (second_group) __builtin_amdgcn_s_barrier();       // one phase behind the first group
+
+    auto phase_end = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // Round i works on slab i (LDS buffer i % NB); its memory phase stages slab i + 1 from ring slot
+    // (i + 1) % DEPTH and refills that slot with slab i + 1 + DEPTH.  No branch inside: slabs past the
+    // end are clamped loads and LDS writes that nothing reads.
+    constexpr int UNROLL = NB > DEPTH ? NB : DEPTH;
+    auto round = [&](int i, auto IDX) __attribute__((always_inline)) {
+        using BUF = std::integral_constant<int, decltype(IDX)::value % NB>;
+        using NEXT_BUF = std::integral_constant<int, (decltype(IDX)::value + 1) % NB>;
+        using NEXT_SLOT = std::integral_constant<int, (decltype(IDX)::value + 1) % DEPTH>;
+        stage(NEXT_BUF{}, NEXT_SLOT{});
+        gather(NEXT_SLOT{});
+        k_offsets(i + 2 + DEPTH);
+        frag_load(BUF{});
+        phase_end();
+        mfmas();
+        phase_end();
+    };
+    int i = 0;
+    for (; i + UNROLL <= nk; i += UNROLL)
+        static_for<0, UNROLL>([&](auto IDX) __attribute__((always_inline)) { round(i + decltype(IDX)::value, IDX); });
+    static_for<0, UNROLL - 1>([&](auto IDX) __attribute__((always_inline)) {
+        if (i + decltype(IDX)::value < nk) round(i + decltype(IDX)::value, IDX);
+    });
+    if (!second_group) __builtin_amdgcn_s_barrier();      // pairs with the second group's last barrier
+    settle_accumulators();
+
+    // ---- epilogue: block by block through LDS.  Wave w writes the 16 x 16 block of its batch in
+    // register order (element 64 v + lane, consecutive lanes on consecutive 16 bytes); after a barrier
+    // thread (batch hl, slot q) reads elements q, q + 64, .. of batch hl, so four neighbouring lanes
+    // hold one element of the four batches: 64 contiguous bytes of C and of D.  Two exchange buffers
+    // alternate, so one barrier per block is enough.
+    const T* __restrict__ C = (const T*)g.C + tile.hD + hl;
+    T* __restrict__ D = (T*)g.D + tile.hD + hl;
+    const bool read_c = g.read_c != 0;
+    const bool conj_acc = g.conj_acc != 0;
+    // element e = 64 r + q of a block is (row 4 r + q / 16 of the MFMA result, lane column q % 16):
+    // rows run along n and columns along m, or the other way round (DNF)
+    int64_t off_col[DNF ? FN : FM], off_row[DNF ? FM : FN][4];
+    bool ok_col[DNF ? FN : FM], ok_row[DNF ? FM : FN][4];
+    {
+        const int col = q % 16, row = q / 16;
+#pragma unroll
+        for (int b = 0; b < (DNF ? FN : FM); ++b) {
+            const int64_t x = (DNF ? n0 : m0) + b * 16 + col;
+            ok_col[b] = x < (DNF ? g.sizeN : g.sizeM);
+            off_col[b] = (DNF ? g.oDN : g.oDM)[x];                     // padded tables: always a valid entry
+        }
+#pragma unroll
+        for (int b = 0; b < (DNF ? FM : FN); ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int64_t x = (DNF ? m0 : n0) + b * 16 + 4 * r + row;
+                ok_row[b][r] = x < (DNF ? g.sizeM : g.sizeN);
+                off_row[b][r] = (DNF ? g.oDM : g.oDN)[x];
+            }
+    }
+    const unsigned ew = lds0 + ES * (unsigned)(wave * (256 + 4) + lane);       // where this lane writes element 64 v + lane
+    const unsigned er = lds0 + ES * (unsigned)(hl * (256 + 4) + q);            // where this thread reads element 64 r + q
+    T cval[2][4];
+    auto c_loads = [&](int blk, int slot) __attribute__((always_inline)) {
+        const int bi = blk % FM, bj = blk / FM;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int bc = DNF ? bj : bi, br = DNF ? bi : bj;
+            cval[slot][r] = P::zero();
+            if (read_c && active && ok_col[bc] && ok_row[br][r]) cval[slot][r] = C[off_col[bc] + off_row[br][r]];
+        }
+    };
+    __syncthreads();                                      // every wave has left the main loop: the slabs are free
+    c_loads(0, 0);
+#pragma unroll
+    for (int blk = 0; blk < FM * FN; ++blk) {
+        const int bi = blk % FM, bj = blk / FM;
+        const unsigned buf = (blk & 1) * ES * EPI;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) lds_store<T>(ew + buf + ES * 64 * v, T{acc[bi][bj].re[v], acc[bi][bj].im[v]});
+        if (blk + 1 < FM * FN) c_loads(blk + 1, (blk + 1) & 1);
+        __syncthreads();
+        const int bc = DNF ? bj : bi, br = DNF ? bi : bj;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const T sum = lds_load<T>(er + buf + ES * 64 * r);
+            typename P::acc_t one;
+            one.re[0] = sum.x;
+            one.im[0] = sum.y;
+            if (active && ok_col[bc] && ok_row[br][r])
+                D[off_col[bc] + off_row[br][r]] = P::combine(one, 0, g.s, read_c, cval[blk & 1][r], g.opC, conj_acc);
+        }
+    }
+}
+
 // ---- instantiation tables -------------------------------------------------------------------
 struct Shape {
     int mt_m, mt_n, kt, wgm, wgn;
@@ -1192,6 +1436,7 @@ struct Shape {
     bool pingpong = false; // two-phase kernel (needs |K| % kt == 0 and slab-periodic k offsets)
     int fallback = -1;     // shape to use instead when this one's preconditions fail (-1: any)
     bool dual = false;     // two-phase kernel: one tile per wave group (two per workgroup)
+    int hl = 0;            // batch-lane kernel: batches per tile (0: the tile belongs to one batch)
 };
 // `efficiency`: measured fraction of a CU's matrix peak that the shape's main loop sustains on
 // MI355X with the CU saturated (256x128: config 2; the others: a 1024^3 product, 576^3, 96^3 x 512).
@@ -1218,6 +1463,7 @@ constexpr Shape kComplexShapes[] = {
     {96, 48, 8, 2, 1, 0.45f, 0, 2, true},
     {48, 96, 8, 1, 2, 0.45f, 0, 2, true},
     {96, 96, 8, 2, 2, 0.85f, 0, 1, true, true, 5, true},
+    {48, 48, 4, 2, 2, 0.90f, 0, 2, true, true, 7, true, kBatchLanes},
 };
 constexpr int kNumRealShapes = sizeof(kRealShapes) / sizeof(Shape);
 constexpr int kNumComplexShapes = sizeof(kComplexShapes) / sizeof(Shape);
@@ -1227,14 +1473,44 @@ constexpr Shape shape_at(bool complex_table, int i) {
 }
 
 template <class P, int S, bool AKF, bool BKF, bool DNF>
-hipError_t launch_one(const GettArgs& a, int64_t blocks, hipStream_t st) {
+hipError_t launch_one(const GettArgs& a_in, int64_t blocks, hipStream_t st) {
     constexpr Shape s = shape_at(std::is_same<P, ComplexPolicy>::value, S);
-    if constexpr (s.ch > 0) {
+    GettArgs a = a_in;
+    // the two-phase and batch-lane kernels sum conj(A) * B or A * B and leave the rest of the
+    // conjugation to the epilogue (ComplexPolicy::mac); the others conjugate as they gather
+    a.conj_acc = (s.ch == 0 && s.pingpong && a.opB == TCX_OP_CONJ) ? 1 : 0;
+    if constexpr (s.hl > 0) {
+        // lanes run along the batches whatever the operands' orientation: one instantiation per DNF
+        if constexpr (!AKF && !BKF && std::is_same<P, ComplexPolicy>::value) {
+            if (!a.periodicA || !a.periodicB || a.sizeK % s.kt != 0 || a.splitK != 1) return hipErrorInvalidValue;
+            const int64_t wgs = (blocks + 1) / 2;
+            auto launch = [&](const GettArgs& r, int64_t count) {
+                if (r.opA != r.opB)
+                    gett_hlane_kernel<P, s.mt_m, s.mt_n, s.kt, DNF, s.depth, true><<<dim3((unsigned)count), dim3(512), 0, st>>>(r);
+                else
+                    gett_hlane_kernel<P, s.mt_m, s.mt_n, s.kt, DNF, s.depth, false><<<dim3((unsigned)count), dim3(512), 0, st>>>(r);
+            };
+            if (a.round_size > 0 && wgs > a.round_size) {
+                GettArgs r = a;
+                for (int64_t at = 0; at < wgs; at += a.round_size) {
+                    r.lid_base = at;
+                    launch(r, std::min<int64_t>(a.round_size, wgs - at));
+                }
+            } else {
+                launch(a, wgs);
+            }
+            return hipGetLastError();
+        } else if constexpr (std::is_same<P, ComplexPolicy>::value) {
+            return launch_one<P, S, false, false, DNF>(a_in, blocks, st);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    } else if constexpr (s.ch > 0) {
         // the direct kernel gathers per lane; the operands' orientation does not enter
         if constexpr (!AKF && !BKF)
             gett_direct_kernel<P, s.mt_m / 32, s.mt_n / 32, s.ch, DNF><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(a);
         else
-            return launch_one<P, S, false, false, DNF>(a, blocks, st);
+            return launch_one<P, S, false, false, DNF>(a_in, blocks, st);
     } else if constexpr (s.pingpong) {
         constexpr int NTG = s.wgm * s.wgn * 64;
         if constexpr (pingpong_operand_ok<s.mt_m, NTG, AKF>() && pingpong_operand_ok<s.mt_n, NTG, BKF>()) {
@@ -1248,6 +1524,17 @@ hipError_t launch_one(const GettArgs& a, int64_t blocks, hipStream_t st) {
                     if (r.pair && !ragged) {
                         gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual, (s.depth < 2 ? 2 : s.depth), false, true, 2>
                             <<<dim3((unsigned)count), dim3(threads), 0, st>>>(r);
+                        return;
+                    }
+                }
+                if constexpr (std::is_same<P, ComplexPolicy>::value) {
+                    if (r.opA != r.opB) {             // exactly one operand conjugated
+                        if (ragged)
+                            gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual, s.depth, true, false, 1, true>
+                                <<<dim3((unsigned)count), dim3(threads), 0, st>>>(r);
+                        else
+                            gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual, s.depth, false, false, 1, true>
+                                <<<dim3((unsigned)count), dim3(threads), 0, st>>>(r);
                         return;
                     }
                 }
@@ -1335,6 +1622,7 @@ hipError_t launch_complex_shape(int variant, bool akf, bool bkf, bool dnf, const
         case 5: return launch_flags<ComplexPolicy, 5>(akf, bkf, dnf, a, blocks, st);
         case 6: return launch_flags<ComplexPolicy, 6>(akf, bkf, dnf, a, blocks, st);
         case 7: return launch_flags<ComplexPolicy, 7>(akf, bkf, dnf, a, blocks, st);
+        case 8: return launch_flags<ComplexPolicy, 8>(akf, bkf, dnf, a, blocks, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1360,7 +1648,8 @@ GettVariant gett_variant(int dtype, int variant) {
     const Shape s = t[variant];
     const int planes = dtype == TCX_C128 ? 2 : 1;
     return {s.mt_m, s.mt_n, s.kt, s.wgm * s.wgn * 64, s.efficiency, s.mt_m * s.mt_n * planes, s.ch == 0 && s.narrow, s.pingpong, s.fallback, s.dual,
-            s.dual && pair_fits_lds(dtype == TCX_F32 ? 4 : dtype == TCX_F64 ? 8 : 16, dtype == TCX_F32 ? 4 : 8, planes, s.mt_m, s.mt_n, s.kt)};
+            s.hl == 0 && s.dual && pair_fits_lds(dtype == TCX_F32 ? 4 : dtype == TCX_F64 ? 8 : 16, dtype == TCX_F32 ? 4 : 8, planes, s.mt_m, s.mt_n, s.kt),
+            s.hl > 0 ? s.hl : 1};
 }
 
 int launch_gett(int dtype, int variant, bool a_kf, bool b_kf, bool d_nf, const GettArgs& args, void* stream,
@@ -1369,7 +1658,7 @@ int launch_gett(int dtype, int variant, bool a_kf, bool b_kf, bool d_nf, const G
     if (args.splitK < 1) return (int)hipErrorInvalidValue;
     if (args.splitK > 1 && !args.workspace && !(args.splitK == 2 && gett_variant(dtype, variant).pair_in_lds))
         return (int)hipErrorInvalidValue;
-    const int64_t blocks = (int64_t)args.tilesM * args.tilesN * args.sizeH * args.splitK;
+    const int64_t blocks = (int64_t)args.tilesM * args.tilesN * args.sizeH * args.splitK;      // sizeH: in units of the shape's batches per tile
     const GettVariant gv = gett_variant(dtype, variant);
     *grid = gv.dual ? (blocks + 1) / 2 : blocks;
     *block = gv.threads * (gv.dual ? 2 : 1);

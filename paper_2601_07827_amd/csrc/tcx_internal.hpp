@@ -88,6 +88,7 @@ struct GettArgs {
     Scalars s;
     int32_t opA, opB, opC;
     int32_t read_c;      // beta != 0
+    int32_t conj_acc;    // set by the launcher: the kernel sums the conjugate of the wanted product (complex two-phase kernels)
     int32_t splitK;      // >= 1: number of parts the K slabs are divided into
     void* workspace;     // splitK > 1: [tiles * splitK][accumulator reals of a tile], owned by the plan
 };
@@ -101,6 +102,7 @@ struct GettVariant {
     int fallback;        // shape to try first when this one cannot serve the plan (-1: none)
     bool dual;           // two-phase kernel with one tile per wave group: a workgroup takes two items
     bool pair_in_lds;    // ... and reduces a two-part split of K inside the workgroup (no workspace, no second kernel)
+    int hl;              // batches per tile (> 1: batch-lane kernel; the fastest hyper mode is cut into groups of hl; K unsplit)
 };
 
 // Generic fallback: every mode of D (H, M, N together, D-fastest first) and every K mode.

@@ -327,8 +327,12 @@ def test_planner_routes_each_configuration(handle):
     # 256 tiles of 64x64, K in two halves = 512 items, two per workgroup, summed inside it: one launch
     assert (c5["TILE_M"], c5["TILE_N"], c5["BLOCK"], c5["GRID"], c5["SPLIT_K"], c5["LAUNCHES"]) == (64, 64, 512, 256, 2, 1)
     c4 = _plan(handle, W.config4())
-    # 512 batches, one 96x96 complex tile each, two per workgroup
-    assert (c4["TILE_M"], c4["TILE_N"], c4["TILE_K"], c4["BLOCK"], c4["GRID"], c4["LAUNCHES"]) == (96, 96, 8, 512, 256, 1)
+    # batches fastest in memory: tiles of four consecutive batches x 48 x 48 (128 groups of batches x 4 tiles),
+    # two per workgroup, K whole
+    assert (c4["TILE_M"], c4["TILE_N"], c4["TILE_K"], c4["BLOCK"], c4["GRID"], c4["SPLIT_K"], c4["LAUNCHES"]) == (48, 48, 4, 512, 256, 1, 1)
+    c4s = _plan(handle, W.config4(h_slowest=True))
+    # batches slowest: 512 contiguous matrices, one 96x96 complex tile each, two per workgroup
+    assert (c4s["TILE_M"], c4s["TILE_N"], c4s["TILE_K"], c4s["BLOCK"], c4s["GRID"], c4s["LAUNCHES"]) == (96, 96, 8, 512, 256, 1)
     c1 = _plan(handle, W.config1())
     # B's lanes run along k = (c, d) with extent 24: slabs of 16 do not repeat -> classic kernel, split K + reduction
     assert c1["BLOCK"] == 256 and c1["SPLIT_K"] > 1 and c1["LAUNCHES"] == 2
@@ -494,7 +498,7 @@ def test_offset_tables_hold_a_whole_number_of_tiles_of_every_shape(handle, dtype
     padded tables must reach the end of the last tile of EVERY compiled shape (tiles of 96 and 48
     do not divide a padding unit of 256), for every size of M, N and K."""
     shapes = _tile_shapes(handle, dtype)
-    assert len(shapes) >= (8 if dtype == T.TCX_C128 else 12), shapes
+    assert len(shapes) >= (8 if dtype == T.TCX_C128 else 12), shapes      # (the batch-lane shape needs a batch mode)
     assert {s[0] for s in shapes.values()} >= ({96, 48} if dtype == T.TCX_C128 else {256, 32})
     for size in list(range(1, 1101)) + [36864, 4096]:
         m, n, k = size, max(2, 1101 - size if size <= 1100 else 4096), 2 + size % 71

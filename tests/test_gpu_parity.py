@@ -16,13 +16,14 @@ GENERIC, GETT, STREAM = 0, 1, 2
 REFUSED = 19                                        # TCX_ERR_PLAN_REFUSED
 
 
-TWO_PHASE = {False: (0, 10, 11), True: (7,)}      # tile shapes served by the two-phase kernel (real, complex)
+TWO_PHASE = {False: (0, 10, 11), True: (7, 8)}    # tile shapes served by the two-phase kernels (real, complex); 8: batch lanes
+NUM_SHAPES = {False: 12, True: 9}
 
 
 def _paths_for(p):
     from gpu_helpers import DT  # noqa: F401
     paths = [(GENERIC, None)]
-    paths += [(GETT, v) for v in range(8 if p.dtype == "c128" else 12)]
+    paths += [(GETT, v) for v in range(NUM_SHAPES[p.dtype == "c128"])]
     if p.sizes()[3] <= 64:
         paths.append((STREAM, None))
     return paths
@@ -307,7 +308,79 @@ def test_ragged_last_tiles_of_every_shape(dtype):
         _check(p, a, b, c, path, variant, truth=truth, S=S)
         if path == GETT:
             _check(p, a, b, c, path, variant, truth=truth, S=S, split_k=2)
-    assert _TALLY["declined"] <= 1                    # at most the streaming path (operand rows beyond its LDS budget)
+    # at most the streaming path (operand rows beyond its LDS budget) and, unsplit and split, the
+    # batch-lane shape (this product has no batch mode)
+    assert _TALLY["declined"] <= (3 if dtype == "c128" else 1)
+
+
+def _batched_complex(h, m, n, k, a_order, b_order, d_order, ops, beta=0.5, name="bl"):
+    """D[h,i,j] = sum_k op(A[h,k,i]) op(B[h,k,j]) + beta op(C[h,i,j]) with the given memory orders."""
+    e = dict(h=h, i=m, j=n, k=k)
+    return W.Problem("%s_h%d_%dx%dx%d_%s_%s_%s_ops%d%d%d" % ((name, h, m, n, k, a_order, b_order, d_order) + tuple(ops)), "c128",
+                     W.tensor("hki", e, memory_order=a_order), W.tensor("hkj", e, memory_order=b_order),
+                     W.tensor("hij", e, memory_order=d_order), alpha=0.75 - 0.5j, beta=beta,
+                     opA=ops[0], opB=ops[1], opC=ops[2], seed=W.BASE_SEED + 61)
+
+
+def test_batch_lane_kernel():
+    """The batch-lane kernel (complex tile shape 8): batches fastest in A, B and D, four batches per
+    wave group.  Every combination of conjugations (the kernel sums conj(A) B or A B and conjugates
+    the sum where needed), both orientations of A, B and D behind the batch mode, batch counts that
+    leave the last workgroup's second group without a tile, ragged tiles of M and N, one and many
+    slabs of K, beta = 0 with C absent, integer inputs bit for bit.  Layouts it cannot take (batch
+    mode not fastest, batch count not a multiple of four, |K| not in whole slabs) are refused."""
+    from gpu_helpers import GpuProduct, run_gpu, say
+    import paper_2601_07827_amd as T
+    cases = []
+    for ops in ((0, 0, 0), (1, 0, 0), (0, 1, 1), (1, 1, 0)):
+        cases.append(_batched_complex(8, 48, 48, 8, "hki", "hkj", "hij", ops))
+    cases += [_batched_complex(12, 40, 100, 4, "hki", "hkj", "hij", (1, 0, 1)),        # odd number of groups, ragged tiles, one slab
+              _batched_complex(4, 96, 50, 36, "hik", "hjk", "hji", (0, 1, 0)),          # rows before k in A and B, j before i in D
+              _batched_complex(20, 17, 33, 12, "hki", "hjk", "hij", (1, 1, 1), beta=0.0),
+              _batched_complex(16, 96, 96, 96, "hki", "hkj", "hij", (1, 0, 0))]         # configuration 4's shape, fewer batches
+    for p in cases:
+        for dist, exact in (("uniform", False), ("ints", True)):
+            a, b, c = W.make_operands(p, dist)
+            p2 = p if not exact else W.Problem(p.name + "_ints", p.dtype, p.A, p.B, p.D, alpha=2.0 - 1.0j, beta=(0.5 if p.beta != 0 else 0.0),
+                                               opA=p.opA, opB=p.opB, opC=p.opC, seed=p.seed)
+            truth, S = run_oracle(p2, a, b, c, oracle.MODE_TRUTH, want_S=True)
+            say("%s dist=%s" % (p2.name, dist))
+            got = run_gpu(p2, a, b, c, force_path=GETT, variant=8, c_null=(p2.beta == 0))      # must not be declined
+            assert gaps_untouched(p2, c, got)
+            if exact:
+                assert np.array_equal(W.strided_view(got, p2.D), W.strided_view(truth, p2.D))
+            else:
+                assert normalised_error(p2, got, truth, S, c) <= TOLERANCE[p2.dtype]
+    for bad in (_batched_complex(8, 48, 48, 8, "kih", "kjh", "ijh", (0, 0, 0)),            # batches slowest
+                _batched_complex(6, 48, 48, 8, "hki", "hkj", "hij", (0, 0, 0)),            # 6 batches
+                _batched_complex(8, 48, 48, 6, "hki", "hkj", "hij", (0, 0, 0))):           # |K| = 6
+        with pytest.raises(T.TcxError) as exc:
+            GpuProduct(bad, GETT, 8)
+        assert exc.value.code == T.TCX_ERR_PLAN_REFUSED
+    # K may not be split on it
+    gp = GpuProduct(cases[0], GETT, 8)
+    try:
+        with pytest.raises(T.TcxError) as exc:
+            T.tcx_product_set(gp.prod, T.TCX_KEY_SPLIT_K, 2)
+        assert exc.value.code == T.TCX_ERR_PLAN_REFUSED
+    finally:
+        gp.close()
+
+
+def test_conjugation_combinations_on_the_complex_two_phase_tile():
+    """The 96 x 96 complex two-phase tile keeps conjugation out of its data path (sign modifier of
+    the MFMA, conjugated sum): all eight combinations of opA, opB, opC, unsplit, K in two (summed in
+    the second kernel) and with a ragged last slab."""
+    from gpu_helpers import run_gpu, say
+    for ops in [(a, b, c) for a in (0, 1) for b in (0, 1) for c in (0, 1)]:
+        for k in (24, 21):
+            p = _batched_complex(3, 100, 50, k, "kih", "kjh", "ijh", ops, name="conj")
+            a, b, c = W.make_operands(p)
+            truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+            for split in (None, 2):
+                say("%s split=%s" % (p.name, split))
+                got = run_gpu(p, a, b, c, force_path=GETT, variant=7, split_k=split)
+                assert normalised_error(p, got, truth, S, c) <= TOLERANCE[p.dtype]
 
 
 LOW_AI_LARGE = [W.config5(extent=4, nshared=1, nfree=7), W.config4(h=512, n=96, k=4),
