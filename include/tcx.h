@@ -28,7 +28,7 @@
  *    whose indices are all zero.  Zero strides are legal in A and B (broadcast), not in D.
  *  - Data pointers passed to tcx_execute_product are DEVICE pointers on the handle's GPU.
  *    alpha and beta are HOST pointers to one element of D's dtype (two doubles for
- *    TCX_C128) and are read before the call returns.
+ *    TCX_C128, two floats for TCX_C64) and are read before the call returns.
  *  - beta == 0: C is never read and may be NULL; D is overwritten.  alpha == 0: A and B
  *    are never read.  C may be the same pointer as D (in place); any other overlap of
  *    D with A, B or C is undefined.  Buffer elements of D that (extents, strides) do not
@@ -62,9 +62,16 @@ typedef intptr_t tcx_tensor_info_t;
 typedef intptr_t tcx_product_t;
 typedef intptr_t tcx_status_t;
 
-typedef enum { TCX_F32 = 0, TCX_F64 = 1, TCX_C128 = 3 } tcx_dtype_t;     /* 2 is reserved for complex64 */
+/* Element types (Sec. "The Reference Implementation": real and complex, 64 and 32 bit; the four
+ * tensors of a product share one).  Complex elements are (re, im) pairs of their real type. */
+typedef enum { TCX_F32 = 0, TCX_F64 = 1, TCX_C64 = 2, TCX_C128 = 3 } tcx_dtype_t;
 typedef enum { TCX_OP_IDENTITY = 0, TCX_OP_CONJ = 1 } tcx_op_t;          /* conj of a real type is the identity */
-typedef enum { TCX_PREC_DEFAULT = 0 } tcx_prec_t;                        /* accumulate in the dtype's own real type */
+/* The plan's "desired computational precision" (Sec. "Tensor Operation Descriptors").
+ *   TCX_PREC_DEFAULT  products and sums in the dtype's own real type (fp32 means fp32 MFMA);
+ *   TCX_PREC_F64      products and sums in 64-bit reals whatever the storage type: 32-bit elements
+ *                     are widened as they are read, alpha, beta and C are applied in 64 bits and D
+ *                     is rounded once, on the store.  The same as the default for 64-bit dtypes. */
+typedef enum { TCX_PREC_DEFAULT = 0, TCX_PREC_F64 = 1 } tcx_prec_t;
 
 enum {
     TCX_SUCCESS = 0,
@@ -167,7 +174,8 @@ enum {
     TCX_KEY_WORKSPACE_BYTES = 29, /* product (read-only): device bytes of partial sums one execution writes; executor: size of its workspace, settable to reserve at least that much */
     TCX_KEY_DEVICE = 30,       /* handle, executor (read-only): HIP device ordinal the object is bound to, -1 if none */
     TCX_KEY_NUM_CU = 31,       /* handle (read-only): compute units of the bound device */
-    TCX_KEY_STREAM = 32        /* executor: the hipStream_t as an integer; settable (the caller keeps the new stream alive) */
+    TCX_KEY_STREAM = 32,       /* executor: the hipStream_t as an integer; settable (the caller keeps the new stream alive) */
+    TCX_KEY_PRECISION = 33     /* product (read-only): the tcx_prec_t the plan computes in */
 };
 typedef enum {
     TCX_PATH_GENERIC = 0,      /* one thread per element of D, loops over the contracted index space */

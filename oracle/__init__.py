@@ -22,14 +22,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "contraction_oracle.cpp")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
-DT_F32, DT_F64, DT_C128 = 0, 1, 3
+DT_F32, DT_F64, DT_C64, DT_C128 = 0, 1, 2, 3
 MODE_TRUTH, MODE_TIMED, MODE_LITERAL = 0, 1, 2
 OP_IDENTITY, OP_CONJ = 0, 1
 
 V_OK, V_EXTENT_MISMATCH, V_CD_MISMATCH, V_D_ALIASING, V_ISOLATED, V_BAD_ARG = range(6)
 V_NAMES = ["ok", "extent_mismatch", "cd_mismatch", "d_aliasing", "isolated_index", "bad_arg"]
 
-_NP_DTYPE = {DT_F32: np.float32, DT_F64: np.float64, DT_C128: np.complex128}
+_NP_DTYPE = {DT_F32: np.float32, DT_F64: np.float64, DT_C64: np.complex64, DT_C128: np.complex128}
 _DT_OF_NP = {np.dtype(v): k for k, v in _NP_DTYPE.items()}
 
 
@@ -85,7 +85,7 @@ def contract(A, B, C, D, ops: Sequence[int], alpha, beta,
              base=(0, 0, 0, 0), mode: int = MODE_TRUTH, want_S: bool = False):
     """Run the loop nest.  A, B, C, D are (extents, strides, labels); ops = (opA, opB, opC).
 
-    bufX are 1-D numpy arrays of one dtype (float32, float64 or complex128); bufD is
+    bufX are 1-D numpy arrays of one dtype (float32, float64, complex64 or complex128); bufD is
     written in place (bufC may be bufD, or None when beta == 0).  base[i] is the element
     offset inside the buffer of the element with all indices zero.  Returns (status, S)
     where S is None or a float64 array shaped like bufD holding sum|a||b| per D element.

@@ -49,7 +49,7 @@
 
 namespace {
 
-enum { DT_F32 = 0, DT_F64 = 1, DT_C128 = 3 };
+enum { DT_F32 = 0, DT_F64 = 1, DT_C64 = 2, DT_C128 = 3 };
 enum { MODE_TRUTH = 0, MODE_TIMED = 1, MODE_LITERAL = 2 };
 enum { OP_IDENTITY = 0, OP_CONJ = 1 };
 
@@ -176,6 +176,7 @@ inline long double modulus(std::complex<long double> x) { return hypotl(x.real()
 inline double modulus(double x) { return std::fabs(x); }
 inline float modulus(float x) { return std::fabs(x); }
 inline double modulus(std::complex<double> x) { return std::hypot(x.real(), x.imag()); }
+inline float modulus(std::complex<float> x) { return std::hypot(x.real(), x.imag()); }
 
 // Complex multiply written out (no library special-casing of inf/nan).
 template <class R> inline R mul(R a, R b) { return a * b; }
@@ -317,6 +318,7 @@ int oracle_contract(int dtype, int mode,
 
     using cld = std::complex<long double>;
     using cd = std::complex<double>;
+    using cf = std::complex<float>;
     if (dtype == DT_F64) {
         if (mode == MODE_TRUTH)
             contract<double, long double>(mode, free_loops, sum_loops, opA, opB, opC, alpha[0], beta[0],
@@ -338,6 +340,13 @@ int oracle_contract(int dtype, int mode,
         else
             contract<cd, cd>(mode, free_loops, sum_loops, opA, opB, opC, cd(alpha[0], alpha[1]), cd(beta[0], beta[1]),
                              (const cd*)A, (const cd*)B, (const cd*)C, (cd*)D, S);
+    } else if (dtype == DT_C64) {
+        if (mode == MODE_TRUTH)
+            contract<cf, cld>(mode, free_loops, sum_loops, opA, opB, opC, cld(alpha[0], alpha[1]), cld(beta[0], beta[1]),
+                              (const cf*)A, (const cf*)B, (const cf*)C, (cf*)D, S);
+        else
+            contract<cf, cf>(mode, free_loops, sum_loops, opA, opB, opC, cf((float)alpha[0], (float)alpha[1]),
+                             cf((float)beta[0], (float)beta[1]), (const cf*)A, (const cf*)B, (const cf*)C, (cf*)D, S);
     } else {
         return V_BAD_ARG;
     }

@@ -28,9 +28,9 @@ if not os.path.exists(LIB_PATH):
 _lib = ctypes.CDLL(LIB_PATH)
 
 # ---- constants of include/tcx.h ------------------------------------------------------------
-TCX_F32, TCX_F64, TCX_C128 = 0, 1, 3
+TCX_F32, TCX_F64, TCX_C64, TCX_C128 = 0, 1, 2, 3
 TCX_OP_IDENTITY, TCX_OP_CONJ = 0, 1
-TCX_PREC_DEFAULT = 0
+TCX_PREC_DEFAULT, TCX_PREC_F64 = 0, 1
 TCX_PATH_GENERIC, TCX_PATH_GETT_MFMA, TCX_PATH_BANDWIDTH = 0, 1, 2
 (TCX_SUCCESS, TCX_ERR_NULL_ARG, TCX_ERR_INVALID_HANDLE, TCX_ERR_BAD_DTYPE, TCX_ERR_BAD_NMODE, TCX_ERR_BAD_EXTENT,
  TCX_ERR_EXTENT_MISMATCH, TCX_ERR_CD_MISMATCH, TCX_ERR_D_ALIASING, TCX_ERR_ISOLATED_INDEX, TCX_ERR_DTYPE_MIX,
@@ -42,7 +42,7 @@ TCX_PATH_GENERIC, TCX_PATH_GETT_MFMA, TCX_PATH_BANDWIDTH = 0, 1, 2
  TCX_KEY_A_K_FASTEST, TCX_KEY_B_K_FASTEST, TCX_KEY_D_N_FASTEST, TCX_KEY_VARIANT, TCX_KEY_HIP_ERROR, TCX_KEY_MODES_M,
  TCX_KEY_MODES_N, TCX_KEY_MODES_K, TCX_KEY_MODES_H, TCX_KEY_FORCE_PATH, TCX_KEY_SPLIT_K, TCX_KEY_LAUNCHES,
  TCX_KEY_GATHER_WIDTH, TCX_KEY_TABLE_ENTRIES, TCX_KEY_WORKSPACE_BYTES, TCX_KEY_DEVICE, TCX_KEY_NUM_CU,
- TCX_KEY_STREAM) = range(1, 33)
+ TCX_KEY_STREAM, TCX_KEY_PRECISION) = range(1, 34)
 TCX_MAX_MODES = 32
 TCX_SCRATCH_BYTES = 32 * 1024 * 1024
 TCX_PROBE_MFMA_F64, TCX_PROBE_MFMA_F32, TCX_PROBE_STORE, TCX_PROBE_COPY = 0, 1, 2, 3
@@ -221,6 +221,8 @@ def _scalar(dtype: int, x):
     if dtype == TCX_F64:
         return ctypes.c_double(float(x))
     z = complex(x)
+    if dtype == TCX_C64:
+        return (ctypes.c_float * 2)(z.real, z.imag)
     return (ctypes.c_double * 2)(z.real, z.imag)
 
 

@@ -89,7 +89,8 @@ tcx_error_t analyse(const TensorDesc& A, const int64_t* labA, const TensorDesc& 
     for (int op : {opA, opB, opC, opD})
         if (op != TCX_OP_IDENTITY && op != TCX_OP_CONJ) return TCX_ERR_UNSUPPORTED_OP;
     if (opD != TCX_OP_IDENTITY) return TCX_ERR_UNSUPPORTED_OP;
-    if (precision != TCX_PREC_DEFAULT) return TCX_ERR_UNSUPPORTED_PRECISION;
+    if (!valid_dtype(A.dtype)) return TCX_ERR_BAD_DTYPE;
+    if (precision != TCX_PREC_DEFAULT && precision != TCX_PREC_F64) return TCX_ERR_UNSUPPORTED_PRECISION;
 
     LabelMap a, b, c, d;
     if (!merge_labels(A, labA, &a) || !merge_labels(B, labB, &b) || !merge_labels(C, labC, &c) ||
@@ -134,8 +135,9 @@ tcx_error_t analyse(const TensorDesc& A, const int64_t* labA, const TensorDesc& 
     // ---- a1: classification by set membership ----------------------------------------------
     Analysis r;
     r.dtype = D.dtype;
+    r.precision = precision;
     r.opA = opA; r.opB = opB; r.opC = opC;
-    if (r.dtype != TCX_C128) r.opA = r.opB = r.opC = TCX_OP_IDENTITY;   // conj of a real number
+    if (!is_complex(r.dtype)) r.opA = r.opB = r.opC = TCX_OP_IDENTITY;   // conj of a real number
     auto stride_in = [](const LabelMap& m, int64_t lab) {
         auto it = m.find(lab);
         return it == m.end() ? (int64_t)0 : it->second.stride;
@@ -172,7 +174,7 @@ tcx_error_t analyse(const TensorDesc& A, const int64_t* labA, const TensorDesc& 
     // rest by the stride of the tensor whose fastest mode the group holds (D if D's fastest mode
     // is an M mode, else A).  N likewise with B.  K: the line modes of whichever input is
     // K-fastest (both: the larger operand first), then the rest by that input's stride.
-    const int64_t line = 128 / (r.dtype == TCX_F32 ? 4 : r.dtype == TCX_F64 ? 8 : 16);
+    const int64_t line = 128 / elem_bytes_of(r.dtype);
     auto line_strides = [&](int which) {
         // strides (in tensor `which`) of its fastest modes, up to a line's worth of elements
         std::vector<std::pair<int64_t, int64_t>> se;

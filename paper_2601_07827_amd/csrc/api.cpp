@@ -166,13 +166,13 @@ std::vector<PlanChoice> rank_plans(const Analysis& an, int num_cu) {
     std::vector<PlanChoice> ranked;
     const int n = gett_num_variants(an.dtype);
     const double cus = num_cu > 0 ? num_cu : 256;
-    const double cu_flops = (an.dtype == TCX_F32 ? 157.3e12 : 78.6e12) / 256.0;
-    const double flop_per_mac = an.dtype == TCX_C128 ? 8.0 : 2.0;
-    const int ebytes = an.dtype == TCX_F32 ? 4 : an.dtype == TCX_F64 ? 8 : 16;
+    const double cu_flops = (compute_real_bytes(an.dtype, an.precision) == 4 ? 157.3e12 : 78.6e12) / 256.0;
+    const double flop_per_mac = is_complex(an.dtype) ? 8.0 : 2.0;
+    const int ebytes = elem_bytes_of(an.dtype);
     const double store_us = (double)an.sizeH * an.sizeM * an.sizeN * ebytes / 4e12 * 1e6;
     for (int v = 0; v < n; ++v) {
         const GettVariant s = gett_variant(an.dtype, v);
-        if (!batch_lanes_ok(an, s)) continue;
+        if (!gett_available(an.dtype, an.precision, v) || !batch_lanes_ok(an, s)) continue;
         double best = -1;
         int bestS = 1;
         const double tiles = (double)tiles_of(an, s);
@@ -284,7 +284,7 @@ size_t workspace_need(const Product& p) {
     if (p.an.path != TCX_PATH_GETT_MFMA || p.splitK <= 1) return 0;
     const GettVariant s = gett_variant(p.an.dtype, p.variant);
     if (p.splitK == 2 && s.pair_in_lds) return 0;
-    const size_t real_bytes = p.an.dtype == TCX_F32 ? 4 : 8;
+    const size_t real_bytes = (size_t)compute_real_bytes(p.an.dtype, p.an.precision);
     return (size_t)tiles_of(p.an, s) * (size_t)p.splitK * (size_t)s.acc_reals * real_bytes;
 }
 
@@ -302,7 +302,7 @@ tcx_error_t grow_workspace(Executor* e, size_t need) {
     return TCX_SUCCESS;
 }
 
-int elem_bytes(int dtype) { return dtype == TCX_F32 ? 4 : dtype == TCX_F64 ? 8 : 16; }
+int elem_bytes(int dtype) { return elem_bytes_of(dtype); }
 
 // Gather tables of the LDS-staged tiled kernels.  An operand element's address is split as
 //   base(workgroup) + rowbase[tile] + { kofs[k]  |  kbase[slab] + krel[k] } + rowrel[row],
@@ -362,7 +362,7 @@ bool narrow_operand(const std::vector<int64_t>& rows, int64_t nrows, int mt, con
 // shape spans 4 GB or more of an operand.
 tcx_error_t build_narrow(Product* p, int variant) {
     const GettVariant s = gett_variant(p->an.dtype, variant);
-    if (!batch_lanes_ok(p->an, s)) return TCX_ERR_PLAN_REFUSED;
+    if (!gett_available(p->an.dtype, p->an.precision, variant) || !batch_lanes_ok(p->an, s)) return TCX_ERR_PLAN_REFUSED;
     if (p->narrow_variant == variant) return TCX_SUCCESS;
     const int64_t es = elem_bytes(p->an.dtype);
     NarrowOperand a, b;
@@ -453,7 +453,9 @@ tcx_error_t prepare_tiled(Product* p) {
     for (const PlanChoice& c : rank_plans(p->an, p->handle.num_cu))
         if (c.variant != first && c.variant != second) order.push_back(c);
     for (const PlanChoice& c : order) {
-        err = gett_variant(p->an.dtype, c.variant).staged ? build_narrow(p, c.variant) : TCX_SUCCESS;
+        err = !gett_available(p->an.dtype, p->an.precision, c.variant) ? TCX_ERR_PLAN_REFUSED
+              : gett_variant(p->an.dtype, c.variant).staged                ? build_narrow(p, c.variant)
+                                                                           : TCX_SUCCESS;
         if (err == TCX_SUCCESS) {
             if (c.variant != p->variant) { p->variant = c.variant; p->splitK = c.splitK; }
             break;
@@ -599,7 +601,7 @@ tcx_error_t tcx_create_tensor_info(tcx_handle_t handle, tcx_dtype_t dtype, int32
                                    const int64_t* strides, tcx_tensor_info_t* out) {
     if (!out) return TCX_ERR_NULL_ARG;
     if (!lookup<Handle>(handle, MAGIC_HANDLE)) return TCX_ERR_INVALID_HANDLE;
-    if (dtype != TCX_F32 && dtype != TCX_F64 && dtype != TCX_C128) return TCX_ERR_BAD_DTYPE;
+    if (!valid_dtype((int)dtype)) return TCX_ERR_BAD_DTYPE;
     if (nmode < 0 || nmode > TCX_MAX_MODES) return TCX_ERR_BAD_NMODE;
     if (nmode > 0 && (!extents || !strides)) return TCX_ERR_NULL_ARG;
     for (int i = 0; i < nmode; ++i)
@@ -724,6 +726,7 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
         }
         case TCX_KEY_GATHER_WIDTH: return put_i64(tiled && s.pingpong && s.dual && p->pairs ? 2 : 1, value, nbytes);
         case TCX_KEY_WORKSPACE_BYTES: return put_i64((int64_t)workspace_need(*p), value, nbytes);
+        case TCX_KEY_PRECISION: return put_i64(an.precision, value, nbytes);
         case TCX_KEY_TABLE_ENTRIES: {
             const int64_t n[3] = {(int64_t)p->tables[0].size(), (int64_t)p->tables[2].size(), (int64_t)p->tables[1].size()};
             return put(n, sizeof n, value, nbytes);
@@ -772,6 +775,7 @@ tcx_error_t tcx_product_set(tcx_product_t product, int32_t key, const void* valu
     }
     if (key == TCX_KEY_VARIANT) {
         if (p->an.path != TCX_PATH_GETT_MFMA || v < 0 || v >= gett_num_variants(p->an.dtype)) return TCX_ERR_PLAN_REFUSED;
+        if (!gett_available(p->an.dtype, p->an.precision, (int)v)) return TCX_ERR_PLAN_REFUSED;
         if (gett_variant(p->an.dtype, (int)v).staged) {
             const tcx_error_t err = build_narrow(p, (int)v);
             if (err != TCX_SUCCESS) return err;
@@ -808,6 +812,10 @@ tcx_error_t run_product(tcx_product_t product, tcx_executor_t executor, tcx_stat
     switch (p->an.dtype) {
         case TCX_F32: s.alpha_re = *(const float*)alpha; s.beta_re = *(const float*)beta; break;
         case TCX_F64: s.alpha_re = *(const double*)alpha; s.beta_re = *(const double*)beta; break;
+        case TCX_C64:
+            s.alpha_re = ((const float*)alpha)[0]; s.alpha_im = ((const float*)alpha)[1];
+            s.beta_re = ((const float*)beta)[0]; s.beta_im = ((const float*)beta)[1];
+            break;
         default:
             s.alpha_re = ((const double*)alpha)[0]; s.alpha_im = ((const double*)alpha)[1];
             s.beta_re = ((const double*)beta)[0]; s.beta_im = ((const double*)beta)[1];
@@ -898,7 +906,7 @@ tcx_error_t run_product(tcx_product_t product, tcx_executor_t executor, tcx_stat
         g.lid_base = 0;
         // rounds pay off when a tile runs for milliseconds (hundreds of slabs) and there are several rounds
         g.round_size = (int32_t)round_size_of(*p, v);
-        hip_err = launch_gett(p->an.dtype, p->variant, p->an.a_k_fastest, p->an.b_k_fastest, p->an.d_n_fastest, g,
+        hip_err = launch_gett(p->an.dtype, p->an.precision, p->variant, p->an.a_k_fastest, p->an.b_k_fastest, p->an.d_n_fastest, g,
                               (void*)e->stream, &grid, &block);
         st.path = TCX_PATH_GETT_MFMA; st.variant = p->variant;
         st.gather_width = g.pair && v.pingpong && v.dual && g.sizeK % v.kt == 0 ? 2 : 1;
@@ -908,7 +916,7 @@ tcx_error_t run_product(tcx_product_t product, tcx_executor_t executor, tcx_stat
         g.A = A; g.B = B; g.C = C; g.D = D;
         g.s = s;
         g.read_c = read_c; g.read_ab = read_ab;
-        hip_err = launch_generic(p->an.dtype, g, (void*)e->stream, &grid, &block);
+        hip_err = launch_generic(p->an.dtype, p->an.precision, g, (void*)e->stream, &grid, &block);
         st.path = TCX_PATH_GENERIC;
     }
     st.grid = grid; st.block = block; st.hip_error = hip_err;

@@ -11,56 +11,56 @@
 namespace tcx {
 namespace {
 
-struct cplx {
-    double re, im;
+// Arithmetic policies: `stor` is what memory holds, `acc_t` what products and sums are formed in
+// (the storage type itself, or its 64-bit widening when the plan asks for TCX_PREC_F64).
+template <class R> struct cplx_of {
+    R re, im;
 };
 
-template <class T> struct Num;
-template <> struct Num<double> {
-    using acc_t = double;
-    static __device__ __forceinline__ double load(const double* p, int64_t off, int) { return p[off]; }
-    static __device__ __forceinline__ double zero() { return 0.0; }
-    static __device__ __forceinline__ double fma(double a, double b, double c) { return __builtin_fma(a, b, c); }
-    static __device__ __forceinline__ double scale(const Scalars& s, bool alpha, double x) {
-        return (alpha ? s.alpha_re : s.beta_re) * x;
+template <class S, class R> struct RealNum {
+    using stor = S;
+    using acc_t = R;
+    static __device__ __forceinline__ R load(const S* p, int64_t off, int) { return (R)p[off]; }
+    static __device__ __forceinline__ R zero() { return (R)0; }
+    static __device__ __forceinline__ R fma(R a, R b, R c) {
+        if constexpr (sizeof(R) == 4) return __builtin_fmaf(a, b, c);
+        else return __builtin_fma(a, b, c);
     }
-    static __device__ __forceinline__ double add(double a, double b) { return a + b; }
+    static __device__ __forceinline__ R scale(const Scalars& s, bool alpha, R x) { return (R)(alpha ? s.alpha_re : s.beta_re) * x; }
+    static __device__ __forceinline__ R add(R a, R b) { return a + b; }
+    static __device__ __forceinline__ S narrow(R x) { return (S)x; }
 };
-template <> struct Num<float> {
-    using acc_t = float;
-    static __device__ __forceinline__ float load(const float* p, int64_t off, int) { return p[off]; }
-    static __device__ __forceinline__ float zero() { return 0.0f; }
-    static __device__ __forceinline__ float fma(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
-    static __device__ __forceinline__ float scale(const Scalars& s, bool alpha, float x) {
-        return (float)(alpha ? s.alpha_re : s.beta_re) * x;
+
+template <class S, class R> struct ComplexNum {
+    using stor = cplx_of<S>;
+    using acc_t = cplx_of<R>;
+    static __device__ __forceinline__ acc_t load(const stor* p, int64_t off, int op) {
+        const stor v = p[off];
+        return {(R)v.re, op == TCX_OP_CONJ ? -(R)v.im : (R)v.im};
     }
-    static __device__ __forceinline__ float add(float a, float b) { return a + b; }
-};
-template <> struct Num<cplx> {
-    using acc_t = cplx;
-    static __device__ __forceinline__ cplx load(const cplx* p, int64_t off, int op) {
-        cplx v = p[off];
-        if (op == TCX_OP_CONJ) v.im = -v.im;
-        return v;
+    static __device__ __forceinline__ acc_t zero() { return {(R)0, (R)0}; }
+    static __device__ __forceinline__ R f(R a, R b, R c) {
+        if constexpr (sizeof(R) == 4) return __builtin_fmaf(a, b, c);
+        else return __builtin_fma(a, b, c);
     }
-    static __device__ __forceinline__ cplx zero() { return {0.0, 0.0}; }
-    static __device__ __forceinline__ cplx fma(cplx a, cplx b, cplx c) {
-        c.re = __builtin_fma(a.re, b.re, c.re);
-        c.re = __builtin_fma(-a.im, b.im, c.re);
-        c.im = __builtin_fma(a.re, b.im, c.im);
-        c.im = __builtin_fma(a.im, b.re, c.im);
+    static __device__ __forceinline__ acc_t fma(acc_t a, acc_t b, acc_t c) {
+        c.re = f(a.re, b.re, c.re);
+        c.re = f(-a.im, b.im, c.re);
+        c.im = f(a.re, b.im, c.im);
+        c.im = f(a.im, b.re, c.im);
         return c;
     }
-    static __device__ __forceinline__ cplx scale(const Scalars& s, bool alpha, cplx x) {
-        const double sr = alpha ? s.alpha_re : s.beta_re, si = alpha ? s.alpha_im : s.beta_im;
+    static __device__ __forceinline__ acc_t scale(const Scalars& s, bool alpha, acc_t x) {
+        const R sr = (R)(alpha ? s.alpha_re : s.beta_re), si = (R)(alpha ? s.alpha_im : s.beta_im);
         return {sr * x.re - si * x.im, sr * x.im + si * x.re};
     }
-    static __device__ __forceinline__ cplx add(cplx a, cplx b) { return {a.re + b.re, a.im + b.im}; }
+    static __device__ __forceinline__ acc_t add(acc_t a, acc_t b) { return {a.re + b.re, a.im + b.im}; }
+    static __device__ __forceinline__ stor narrow(acc_t x) { return {(S)x.re, (S)x.im}; }
 };
 
-template <class T>
+template <class N_>
 __global__ __launch_bounds__(256) void generic_contract(GenericArgs g) {
-    using N_ = Num<T>;
+    using T = typename N_::stor;
     const int64_t lin = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (lin >= g.sizeD) return;
     // decode the D index, D-fastest mode first
@@ -91,23 +91,32 @@ __global__ __launch_bounds__(256) void generic_contract(GenericArgs g) {
             }
         }
     }
-    T d = N_::scale(g.s, true, acc);
+    typename N_::acc_t d = N_::scale(g.s, true, acc);
     if (g.read_c) d = N_::add(d, N_::scale(g.s, false, N_::load((const T*)g.C, offD, g.opC)));
-    ((T*)g.D)[offD] = d;
+    ((T*)g.D)[offD] = N_::narrow(d);
 }
 
 }  // namespace
 
-int launch_generic(int dtype, const GenericArgs& args, void* stream, int64_t* grid, int* block) {
+int launch_generic(int dtype, int precision, const GenericArgs& args, void* stream, int64_t* grid, int* block) {
     const int64_t blocks = (args.sizeD + 255) / 256;
     *grid = blocks;
     *block = 256;
     if (blocks > 0x7fffffff) return (int)hipErrorInvalidConfiguration;
     hipStream_t st = (hipStream_t)stream;
+    const dim3 gr((unsigned)blocks), bl(256);
+    const bool wide = is_widened(dtype, precision);
     switch (dtype) {
-        case TCX_F64: generic_contract<double><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(args); break;
-        case TCX_F32: generic_contract<float><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(args); break;
-        case TCX_C128: generic_contract<cplx><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(args); break;
+        case TCX_F64: generic_contract<RealNum<double, double>><<<gr, bl, 0, st>>>(args); break;
+        case TCX_F32:
+            if (wide) generic_contract<RealNum<float, double>><<<gr, bl, 0, st>>>(args);
+            else generic_contract<RealNum<float, float>><<<gr, bl, 0, st>>>(args);
+            break;
+        case TCX_C128: generic_contract<ComplexNum<double, double>><<<gr, bl, 0, st>>>(args); break;
+        case TCX_C64:
+            if (wide) generic_contract<ComplexNum<float, double>><<<gr, bl, 0, st>>>(args);
+            else generic_contract<ComplexNum<float, float>><<<gr, bl, 0, st>>>(args);
+            break;
         default: return (int)hipErrorInvalidValue;
     }
     return (int)hipGetLastError();

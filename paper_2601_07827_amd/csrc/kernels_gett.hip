@@ -55,14 +55,24 @@ template <> struct Mfma<float> {
     static __device__ __forceinline__ vec mac(float rowop, float colop, vec c) {
         return __builtin_amdgcn_mfma_f32_16x16x4f32(rowop, colop, c, 0, 0, 0);
     }
+    // (the fp32 MFMA has no sign modifiers: the operand is negated on the vector ALU)
+    static __device__ __forceinline__ vec mac_minus(float rowop, float colop, vec c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(-rowop, colop, c, 0, 0, 0);
+    }
     static __device__ __forceinline__ int row_of(int lane, int v) { return 4 * (lane >> 4) + v; }
 };
 
 // ---- arithmetic policies: what an element is, how a 16x16x4 block is accumulated, and how
 // the epilogue combines alpha, beta, the accumulator and op(C) --------------------------------
-template <class R> struct RealPolicy {
+// `elem` is what the kernels compute on and keep in LDS, `stor` what memory holds: the same type,
+// or its 32-bit form when a plan widens 32-bit tensors to 64-bit arithmetic (elements are widened
+// as they are gathered, D is rounded once on the store).
+template <class R, class S = R> struct RealPolicy {
     using elem = R;
+    using stor = S;
     using real = R;
+    static constexpr bool is_complex = false;
+    static constexpr bool two_phase = std::is_same<R, S>::value;       // the two-phase kernels move raw storage
     template <int FM, int FN> static constexpr int acc_reals() { return FM * FN * 4; }
     template <int FM, int FN, class A> static __device__ __forceinline__ void spill(const A (&acc)[FM][FN], R* dst, int pitch) {
 #pragma unroll
@@ -87,31 +97,35 @@ template <class R> struct RealPolicy {
     };
     static __device__ __forceinline__ void clear(acc_t& c) { c.v = vec{0, 0, 0, 0}; }
     static __device__ __forceinline__ elem zero() { return R(0); }
-    static __device__ __forceinline__ elem load(const elem* p, int64_t off, unsigned) { return p[off]; }
+    static __device__ __forceinline__ elem load(const stor* p, int64_t off, unsigned) { return (R)p[off]; }
     static __device__ __forceinline__ elem load_at(const char* base, uint32_t byte_off, unsigned) {
-        return *(const elem*)(base + byte_off);
+        return (R) * (const stor*)(base + byte_off);
     }
-    static __device__ __forceinline__ void conj_fix(elem&, unsigned) {}
     template <bool DNF, bool MIXED = false> static __device__ __forceinline__ void mac(elem a, elem b, acc_t& c) {
         c.v = DNF ? MF::mac(a, b, c.v)      // rows = m, lanes along n
                   : MF::mac(b, a, c.v);     // rows = n, lanes along m
     }
-    static __device__ __forceinline__ elem combine(const acc_t& c, int v, const Scalars& s, bool read_c, elem cc, int, bool = false) {
+    static __device__ __forceinline__ stor combine(const acc_t& c, int v, const Scalars& s, bool read_c, stor cc, int, bool = false) {
         R d = (R)s.alpha_re * c.v[v];
-        if (read_c) d += (R)s.beta_re * cc;
-        return d;
+        if (read_c) d += (R)s.beta_re * (R)cc;
+        return (S)d;
     }
 };
 
-// complex128 as pairs of reals: four real MFMAs per complex 16x16x4 block,
+// Complex numbers as pairs of reals: four real MFMAs per complex 16x16x4 block,
 //   re += ar*br - ai*bi,  im += ar*bi + ai*br.
-// Conjugation is applied once, as the element is gathered (the sign bit of the imaginary part
-// is flipped), so the main loop does not depend on the ops.
-struct ComplexPolicy {
-    using elem = double2;
-    using real = double;
+template <class R> struct pair_of;
+template <> struct pair_of<double> { using type = double2; };
+template <> struct pair_of<float> { using type = float2; };
+
+template <class R, class S = R> struct ComplexPolicyT {
+    using elem = typename pair_of<R>::type;
+    using stor = typename pair_of<S>::type;
+    using real = R;
+    static constexpr bool is_complex = true;
+    static constexpr bool two_phase = std::is_same<R, double>::value && std::is_same<S, double>::value;
     template <int FM, int FN> static constexpr int acc_reals() { return FM * FN * 8; }
-    template <int FM, int FN, class A> static __device__ __forceinline__ void spill(const A (&acc)[FM][FN], double* dst, int pitch) {
+    template <int FM, int FN, class A> static __device__ __forceinline__ void spill(const A (&acc)[FM][FN], R* dst, int pitch) {
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -122,7 +136,7 @@ struct ComplexPolicy {
                     dst[(size_t)((i * FN + j) * 8 + 4 + v) * pitch] = acc[i][j].im[v];
                 }
     }
-    template <int FM, int FN, class A> static __device__ __forceinline__ void accumulate(A (&acc)[FM][FN], const double* src, int pitch) {
+    template <int FM, int FN, class A> static __device__ __forceinline__ void accumulate(A (&acc)[FM][FN], const R* src, int pitch) {
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -133,33 +147,33 @@ struct ComplexPolicy {
                     acc[i][j].im[v] += src[(size_t)((i * FN + j) * 8 + 4 + v) * pitch];
                 }
     }
-    using MF = Mfma<double>;
-    using vec = double4_t;
+    using MF = Mfma<R>;
+    using vec = typename MF::vec;
     struct acc_t {
         vec re, im;
     };
     static __device__ __forceinline__ void clear(acc_t& c) { c.re = vec{0, 0, 0, 0}; c.im = vec{0, 0, 0, 0}; }
-    static __device__ __forceinline__ elem zero() { return double2{0.0, 0.0}; }
-    static __device__ __forceinline__ elem load(const elem* p, int64_t off, unsigned conj_mask_hi) {
-        elem v = p[off];
-        unsigned long long bits = __builtin_bit_cast(unsigned long long, v.y) ^ ((unsigned long long)conj_mask_hi << 32);
-        v.y = __builtin_bit_cast(double, bits);
-        return v;
+    static __device__ __forceinline__ elem zero() { return elem{R(0), R(0)}; }
+    // Kernels that conjugate as they gather pass the sign bit to flip (0 or 0x80000000).
+    static __device__ __forceinline__ elem widen(stor v, unsigned conj_mask_hi) {
+        elem e{(R)v.x, (R)v.y};
+        if constexpr (sizeof(R) == 8) {
+            const unsigned long long bits = __builtin_bit_cast(unsigned long long, e.y) ^ ((unsigned long long)conj_mask_hi << 32);
+            e.y = __builtin_bit_cast(double, bits);
+        } else {
+            e.y = __builtin_bit_cast(float, __builtin_bit_cast(unsigned, e.y) ^ conj_mask_hi);
+        }
+        return e;
     }
+    static __device__ __forceinline__ elem load(const stor* p, int64_t off, unsigned conj_mask_hi) { return widen(p[off], conj_mask_hi); }
     static __device__ __forceinline__ elem load_at(const char* base, uint32_t byte_off, unsigned conj_mask_hi) {
-        elem v = *(const elem*)(base + byte_off);
-        unsigned long long bits = __builtin_bit_cast(unsigned long long, v.y) ^ ((unsigned long long)conj_mask_hi << 32);
-        v.y = __builtin_bit_cast(double, bits);
-        return v;
-    }
-    static __device__ __forceinline__ void conj_fix(elem& v, unsigned conj_mask_hi) {
-        unsigned long long bits = __builtin_bit_cast(unsigned long long, v.y) ^ ((unsigned long long)conj_mask_hi << 32);
-        v.y = __builtin_bit_cast(double, bits);
+        return widen(*(const stor*)(base + byte_off), conj_mask_hi);
     }
     // MIXED = false: the product a * b.  MIXED = true: conj(a) * b, for kernels that leave
     // conjugation out of their data path: with both operands conjugated they sum a * b, with one
     // conj(a) * b, and the epilogue conjugates the sum where the conjugated operand was B
-    // (a * conj(b) = conj(conj(a) * b)).  The one minus sign of either form rides on the MFMA.
+    // (a * conj(b) = conj(conj(a) * b)).  The one minus sign of either form rides on the MFMA
+    // (fp64: its sign modifier).
     template <bool DNF, bool MIXED = false> static __device__ __forceinline__ void mac(elem a, elem b, acc_t& c) {
         if (DNF) {
             c.re = MF::mac(a.x, b.x, c.re);
@@ -173,19 +187,22 @@ struct ComplexPolicy {
             c.im = MIXED ? MF::mac_minus(b.x, a.y, c.im) : MF::mac(b.x, a.y, c.im);
         }
     }
-    static __device__ __forceinline__ elem combine(const acc_t& c, int v, const Scalars& s, bool read_c, elem cc, int opC,
+    static __device__ __forceinline__ stor combine(const acc_t& c, int v, const Scalars& s, bool read_c, stor cs, int opC,
                                                    bool conj_acc = false) {
-        const double re = c.re[v], im = conj_acc ? -c.im[v] : c.im[v];
-        double dr = s.alpha_re * re - s.alpha_im * im;
-        double di = s.alpha_re * im + s.alpha_im * re;
+        const R re = c.re[v], im = conj_acc ? -c.im[v] : c.im[v];
+        const R ar = (R)s.alpha_re, ai = (R)s.alpha_im;
+        R dr = ar * re - ai * im;
+        R di = ar * im + ai * re;
         if (read_c) {
-            if (opC == TCX_OP_CONJ) cc.y = -cc.y;
-            dr += s.beta_re * cc.x - s.beta_im * cc.y;
-            di += s.beta_re * cc.y + s.beta_im * cc.x;
+            const R br = (R)s.beta_re, bi = (R)s.beta_im;
+            const R cx = (R)cs.x, cy = opC == TCX_OP_CONJ ? -(R)cs.y : (R)cs.y;
+            dr += br * cx - bi * cy;
+            di += br * cy + bi * cx;
         }
-        return double2{dr, di};
+        return stor{(S)dr, (S)di};
     }
 };
+using ComplexPolicy = ComplexPolicyT<double>;
 
 constexpr int kPadMN = 16;   // [k][mn] rows: the four k-rows of a fragment land on distinct banks
 constexpr int kPadK = 1;     // [mn][k] rows: odd row pitch spreads the 16 rows of a fragment
@@ -311,7 +328,7 @@ __device__ __forceinline__ void d_offsets(DOffsets<P, FM, FN>& o, const GettArgs
 }
 template <class P, int FM, int FN>
 __device__ __forceinline__ void scatter_at(const typename P::acc_t (&acc)[FM][FN], const GettArgs& g, const DOffsets<P, FM, FN>& o) {
-    using T = typename P::elem;
+    using T = typename P::stor;
     const T* __restrict__ C = (const T*)g.C;
     T* __restrict__ D = (T*)g.D;
     const bool read_c = g.read_c != 0;
@@ -322,7 +339,7 @@ __device__ __forceinline__ void scatter_at(const typename P::acc_t (&acc)[FM][FN
         for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                cval[j][v] = P::zero();
+                cval[j][v] = T{};
                 if (read_c && o.ok[i][j][v]) cval[j][v] = C[o.off[i][j][v]];
             }
 #pragma unroll
@@ -336,7 +353,7 @@ __device__ __forceinline__ void scatter_at(const typename P::acc_t (&acc)[FM][FN
 template <class P, int FM, int FN, int WT_M, int WT_N, bool DNF>
 __device__ __forceinline__ void scatter(const typename P::acc_t (&acc)[FM][FN], const GettArgs& g, const Tile& tile,
                                         int wm, int wn, int lane) {
-    using T = typename P::elem;
+    using T = typename P::stor;
     using MF = typename P::MF;
     const T* __restrict__ C = (const T*)g.C + tile.hD;
     T* __restrict__ D = (T*)g.D + tile.hD;
@@ -356,7 +373,7 @@ __device__ __forceinline__ void scatter(const typename P::acc_t (&acc)[FM][FN], 
                 const int nl = wn * WT_N + j * 16 + (DNF ? fr : rr);
                 ok[j][v] = tile.m0 + ml < g.sizeM && tile.n0 + nl < g.sizeN;
                 off[j][v] = g.oDM[tile.m0 + ml] + g.oDN[tile.n0 + nl];      // padded tables: always a valid entry
-                cval[j][v] = P::zero();
+                cval[j][v] = T{};
             }
         if (read_c) {
 #pragma unroll
@@ -405,8 +422,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gett_kernel(GettArgs g) {
     // ---- gather addressing.  An element's address is a wave-uniform 64-bit base plus a 32-bit
     // per-lane byte offset (the plan's tile-relative tables), which the hardware adds itself: no
     // 64-bit vector arithmetic in the loop and one register per offset.
-    const char* const Ab = (const char*)g.A + wave_uniform(tile.hA * (int64_t)sizeof(T) + scalar_table(g.rbA)[m0 / MT_M]);
-    const char* const Bb = (const char*)g.B + wave_uniform(tile.hB * (int64_t)sizeof(T) + scalar_table(g.rbB)[n0 / MT_N]);
+    const char* const Ab = (const char*)g.A + wave_uniform(tile.hA * (int64_t)sizeof(typename P::stor) + scalar_table(g.rbA)[m0 / MT_M]);
+    const char* const Bb = (const char*)g.B + wave_uniform(tile.hB * (int64_t)sizeof(typename P::stor) + scalar_table(g.rbB)[n0 / MT_N]);
     // Row offsets are loop-invariant.  Rows past the end of M or N repeat a valid row of the
     // tile; what they accumulate is never stored.
     uint32_t rrA[SA::PER], rrB[SB::PER];
@@ -705,6 +722,7 @@ __global__ __launch_bounds__(WGM* WGN * 64 * (DUAL ? 2 : 1)) void gett_pingpong_
     using acc_t = typename P::acc_t;
     constexpr bool PAIR = VEC > 1;
     constexpr bool ALANES_K = AKF || PAIR, BLANES_K = BKF || PAIR;      // per-lane k offsets, one scalar base per slab
+    static_assert(P::two_phase, "this kernel moves raw storage and (complex) uses the fp64 MFMA's sign modifier");
     static_assert(!(PAIR && RAGGED), "paired loads need whole slabs");
     static_assert(!LATE || DEPTH >= 2, "loads issued in a compute phase need a phase more to arrive");
     constexpr int NTG = WGM * WGN * 64;                   // threads that work on one tile
@@ -1094,8 +1112,8 @@ __global__ __launch_bounds__(256) void gett_direct_kernel(GettArgs g) {
     const int64_t lid = g.lid_base + xcd_contiguous(blockIdx.x, gridDim.x);
     const int split = (int)(lid % g.splitK);
     const Tile tile = locate_tile(lid / g.splitK, g, MT_M, MT_N);
-    const T* __restrict__ A = (const T*)g.A + tile.hA;
-    const T* __restrict__ B = (const T*)g.B + tile.hB;
+    const typename P::stor* __restrict__ A = (const typename P::stor*)g.A + tile.hA;
+    const typename P::stor* __restrict__ B = (const typename P::stor*)g.B + tile.hB;
     const unsigned conjA = g.opA == TCX_OP_CONJ ? 0x80000000u : 0u;
     const unsigned conjB = g.opB == TCX_OP_CONJ ? 0x80000000u : 0u;
 
@@ -1219,7 +1237,7 @@ __global__ __launch_bounds__(512) void gett_hlane_kernel(GettArgs g) {
                                                           // batches of a row land in different banks
     constexpr int SLAB = HL * REGION;
     constexpr unsigned ES = sizeof(T);
-    static_assert(sizeof(T) == 16, "four batches of 16-byte elements make a 64-byte piece");
+    static_assert(sizeof(T) == 16 && P::two_phase, "four batches of 16-byte elements make a 64-byte piece");
     static_assert(KT == 4, "one MFMA k-step per slab");
     static_assert(MT_M % 16 == 0 && MT_N % 16 == 0 && (MT_M * KT) % QT == 0 && (MT_N * KT) % QT == 0 && QT % KT == 0, "tile shape");
     static_assert(NB % DEPTH == 0 || DEPTH % NB == 0, "ring and LDS slabs cycle together");
@@ -1474,14 +1492,14 @@ constexpr Shape shape_at(bool complex_table, int i) {
 
 template <class P, int S, bool AKF, bool BKF, bool DNF>
 hipError_t launch_one(const GettArgs& a_in, int64_t blocks, hipStream_t st) {
-    constexpr Shape s = shape_at(std::is_same<P, ComplexPolicy>::value, S);
+    constexpr Shape s = shape_at(P::is_complex, S);
     GettArgs a = a_in;
     // the two-phase and batch-lane kernels sum conj(A) * B or A * B and leave the rest of the
     // conjugation to the epilogue (ComplexPolicy::mac); the others conjugate as they gather
     a.conj_acc = (s.ch == 0 && s.pingpong && a.opB == TCX_OP_CONJ) ? 1 : 0;
     if constexpr (s.hl > 0) {
         // lanes run along the batches whatever the operands' orientation: one instantiation per DNF
-        if constexpr (!AKF && !BKF && std::is_same<P, ComplexPolicy>::value) {
+        if constexpr (!AKF && !BKF && P::is_complex && P::two_phase) {
             if (!a.periodicA || !a.periodicB || a.sizeK % s.kt != 0 || a.splitK != 1) return hipErrorInvalidValue;
             const int64_t wgs = (blocks + 1) / 2;
             auto launch = [&](const GettArgs& r, int64_t count) {
@@ -1500,7 +1518,7 @@ hipError_t launch_one(const GettArgs& a_in, int64_t blocks, hipStream_t st) {
                 launch(a, wgs);
             }
             return hipGetLastError();
-        } else if constexpr (std::is_same<P, ComplexPolicy>::value) {
+        } else if constexpr (P::is_complex && P::two_phase) {
             return launch_one<P, S, false, false, DNF>(a_in, blocks, st);
         } else {
             return hipErrorInvalidValue;
@@ -1513,7 +1531,9 @@ hipError_t launch_one(const GettArgs& a_in, int64_t blocks, hipStream_t st) {
             return launch_one<P, S, false, false, DNF>(a_in, blocks, st);
     } else if constexpr (s.pingpong) {
         constexpr int NTG = s.wgm * s.wgn * 64;
-        if constexpr (pingpong_operand_ok<s.mt_m, NTG, AKF>() && pingpong_operand_ok<s.mt_n, NTG, BKF>()) {
+        if constexpr (!P::two_phase) {
+            return hipErrorInvalidValue;      // not built for this element type / precision: the plan must not choose it
+        } else if constexpr (pingpong_operand_ok<s.mt_m, NTG, AKF>() && pingpong_operand_ok<s.mt_n, NTG, BKF>()) {
             if ((AKF && !a.periodicA) || (BKF && !a.periodicB)) return hipErrorInvalidValue;
             constexpr int threads = NTG * (s.dual ? 2 : 1);
             const int64_t wgs = s.dual ? (blocks + 1) / 2 : blocks;
@@ -1527,7 +1547,7 @@ hipError_t launch_one(const GettArgs& a_in, int64_t blocks, hipStream_t st) {
                         return;
                     }
                 }
-                if constexpr (std::is_same<P, ComplexPolicy>::value) {
+                if constexpr (P::is_complex) {
                     if (r.opA != r.opB) {             // exactly one operand conjugated
                         if (ragged)
                             gett_pingpong_kernel<P, s.mt_m, s.mt_n, s.kt, s.wgm, s.wgn, AKF, BKF, DNF, s.dual, s.depth, true, false, 1, true>
@@ -1612,23 +1632,39 @@ hipError_t launch_real_shape(int variant, bool akf, bool bkf, bool dnf, const Ge
     }
 }
 
+template <class P>
 hipError_t launch_complex_shape(int variant, bool akf, bool bkf, bool dnf, const GettArgs& a, int64_t blocks, hipStream_t st) {
     switch (variant) {
-        case 0: return launch_flags<ComplexPolicy, 0>(akf, bkf, dnf, a, blocks, st);
-        case 1: return launch_flags<ComplexPolicy, 1>(akf, bkf, dnf, a, blocks, st);
-        case 2: return launch_flags<ComplexPolicy, 2>(akf, bkf, dnf, a, blocks, st);
-        case 3: return launch_flags<ComplexPolicy, 3>(akf, bkf, dnf, a, blocks, st);
-        case 4: return launch_flags<ComplexPolicy, 4>(akf, bkf, dnf, a, blocks, st);
-        case 5: return launch_flags<ComplexPolicy, 5>(akf, bkf, dnf, a, blocks, st);
-        case 6: return launch_flags<ComplexPolicy, 6>(akf, bkf, dnf, a, blocks, st);
-        case 7: return launch_flags<ComplexPolicy, 7>(akf, bkf, dnf, a, blocks, st);
-        case 8: return launch_flags<ComplexPolicy, 8>(akf, bkf, dnf, a, blocks, st);
-        default: return hipErrorInvalidValue;
+        case 0: return launch_flags<P, 0>(akf, bkf, dnf, a, blocks, st);
+        case 1: return launch_flags<P, 1>(akf, bkf, dnf, a, blocks, st);
+        case 2: return launch_flags<P, 2>(akf, bkf, dnf, a, blocks, st);
+        case 3: return launch_flags<P, 3>(akf, bkf, dnf, a, blocks, st);
+        case 4: return launch_flags<P, 4>(akf, bkf, dnf, a, blocks, st);
+        case 5: return launch_flags<P, 5>(akf, bkf, dnf, a, blocks, st);
+        case 6: return launch_flags<P, 6>(akf, bkf, dnf, a, blocks, st);
+        default: break;
     }
+    if constexpr (P::two_phase) {
+        if (variant == 7) return launch_flags<P, 7>(akf, bkf, dnf, a, blocks, st);
+        if (variant == 8) return launch_flags<P, 8>(akf, bkf, dnf, a, blocks, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+// 32-bit tensors computed in 64-bit arithmetic: two staged shapes each (64 x 64 and 32 x 32)
+constexpr int kWideRealShapes[] = {2, 3};
+constexpr int kWideComplexShapes[] = {1, 2};
+template <class P>
+hipError_t launch_wide_shape(int variant, bool akf, bool bkf, bool dnf, const GettArgs& a, int64_t blocks, hipStream_t st) {
+    constexpr int v0 = P::is_complex ? kWideComplexShapes[0] : kWideRealShapes[0];
+    constexpr int v1 = P::is_complex ? kWideComplexShapes[1] : kWideRealShapes[1];
+    if (variant == v0) return launch_flags<P, v0>(akf, bkf, dnf, a, blocks, st);
+    if (variant == v1) return launch_flags<P, v1>(akf, bkf, dnf, a, blocks, st);
+    return hipErrorInvalidValue;
 }
 
 const Shape* shapes_of(int dtype, int* n) {
-    if (dtype == TCX_C128) { *n = kNumComplexShapes; return kComplexShapes; }
+    if (dtype == TCX_C128 || dtype == TCX_C64) { *n = kNumComplexShapes; return kComplexShapes; }
     if (dtype == TCX_F64 || dtype == TCX_F32) { *n = kNumRealShapes; return kRealShapes; }
     *n = 0;
     return nullptr;
@@ -1646,15 +1682,25 @@ GettVariant gett_variant(int dtype, int variant) {
     int n = 0;
     const Shape* t = shapes_of(dtype, &n);
     const Shape s = t[variant];
-    const int planes = dtype == TCX_C128 ? 2 : 1;
+    const int planes = is_complex(dtype) ? 2 : 1;
     return {s.mt_m, s.mt_n, s.kt, s.wgm * s.wgn * 64, s.efficiency, s.mt_m * s.mt_n * planes, s.ch == 0 && s.narrow, s.pingpong, s.fallback, s.dual,
-            s.hl == 0 && s.dual && pair_fits_lds(dtype == TCX_F32 ? 4 : dtype == TCX_F64 ? 8 : 16, dtype == TCX_F32 ? 4 : 8, planes, s.mt_m, s.mt_n, s.kt),
+            s.hl == 0 && s.dual && pair_fits_lds(elem_bytes_of(dtype), real_bytes_of(dtype), planes, s.mt_m, s.mt_n, s.kt),
             s.hl > 0 ? s.hl : 1};
 }
 
-int launch_gett(int dtype, int variant, bool a_kf, bool b_kf, bool d_nf, const GettArgs& args, void* stream,
+bool gett_available(int dtype, int precision, int variant) {
+    if (variant < 0 || variant >= gett_num_variants(dtype)) return false;
+    if (is_widened(dtype, precision)) {
+        const int* ok = is_complex(dtype) ? kWideComplexShapes : kWideRealShapes;
+        return variant == ok[0] || variant == ok[1];
+    }
+    if (dtype == TCX_C64) return !gett_variant(dtype, variant).pingpong;      // the two-phase complex kernels are fp64 only
+    return true;
+}
+
+int launch_gett(int dtype, int precision, int variant, bool a_kf, bool b_kf, bool d_nf, const GettArgs& args, void* stream,
                 int64_t* grid, int* block) {
-    if (variant < 0 || variant >= gett_num_variants(dtype)) return (int)hipErrorInvalidValue;
+    if (!gett_available(dtype, precision, variant)) return (int)hipErrorInvalidValue;
     if (args.splitK < 1) return (int)hipErrorInvalidValue;
     if (args.splitK > 1 && !args.workspace && !(args.splitK == 2 && gett_variant(dtype, variant).pair_in_lds))
         return (int)hipErrorInvalidValue;
@@ -1664,10 +1710,18 @@ int launch_gett(int dtype, int variant, bool a_kf, bool b_kf, bool d_nf, const G
     *block = gv.threads * (gv.dual ? 2 : 1);
     if (blocks <= 0 || blocks > 0x7fffffff) return (int)hipErrorInvalidConfiguration;
     hipStream_t st = (hipStream_t)stream;
-    if (dtype == TCX_F64) return (int)launch_real_shape<RealPolicy<double>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
-    if (dtype == TCX_F32) return (int)launch_real_shape<RealPolicy<float>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
-    if (dtype == TCX_C128) return (int)launch_complex_shape(variant, a_kf, b_kf, d_nf, args, blocks, st);
-    return (int)hipErrorInvalidValue;
+    const bool wide = is_widened(dtype, precision);
+    switch (dtype) {
+        case TCX_F64: return (int)launch_real_shape<RealPolicy<double>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
+        case TCX_F32:
+            if (wide) return (int)launch_wide_shape<RealPolicy<double, float>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
+            return (int)launch_real_shape<RealPolicy<float>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
+        case TCX_C128: return (int)launch_complex_shape<ComplexPolicyT<double>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
+        case TCX_C64:
+            if (wide) return (int)launch_wide_shape<ComplexPolicyT<double, float>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
+            return (int)launch_complex_shape<ComplexPolicyT<float>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
+        default: return (int)hipErrorInvalidValue;
+    }
 }
 
 }  // namespace tcx

@@ -63,6 +63,32 @@ template <> struct SNum<double2> {
     }
 };
 
+template <> struct SNum<float2> {
+    static __device__ __forceinline__ float2 ld(const float2* p, int64_t o, int op) {
+        float2 v = p[o];
+        if (op == TCX_OP_CONJ) v.y = -v.y;
+        return v;
+    }
+    static __device__ __forceinline__ float2 zero() { return float2{0.0f, 0.0f}; }
+    static __device__ __forceinline__ float2 fma(float2 a, float2 b, float2 c) {
+        c.x = __builtin_fmaf(a.x, b.x, c.x);
+        c.x = __builtin_fmaf(-a.y, b.y, c.x);
+        c.y = __builtin_fmaf(a.x, b.y, c.y);
+        c.y = __builtin_fmaf(a.y, b.x, c.y);
+        return c;
+    }
+    static __device__ __forceinline__ float2 out(const Scalars& s, float2 acc, bool rc, float2 c, int opC) {
+        const float ar = (float)s.alpha_re, ai = (float)s.alpha_im, br = (float)s.beta_re, bi = (float)s.beta_im;
+        float2 d{ar * acc.x - ai * acc.y, ar * acc.y + ai * acc.x};
+        if (rc) {
+            if (opC == TCX_OP_CONJ) c.y = -c.y;
+            d.x += br * c.x - bi * c.y;
+            d.y += br * c.y + bi * c.x;
+        }
+        return d;
+    }
+};
+
 // KC > 0: the number of contracted terms is the compile-time constant KC (inner loop unrolled);
 // KC == 0: any K.
 //
@@ -410,6 +436,7 @@ int launch_stream(int dtype, bool blocked, bool direct, const StreamArgs& args, 
         case TCX_F64: return (int)launch_k<double>(blocked, direct, args, lds_bytes, (unsigned)blocks, st);
         case TCX_F32: return (int)launch_k<float>(blocked, direct, args, lds_bytes, (unsigned)blocks, st);
         case TCX_C128: return (int)launch_k<double2>(blocked, direct, args, lds_bytes, (unsigned)blocks, st);
+        case TCX_C64: return (int)launch_k<float2>(blocked, direct, args, lds_bytes, (unsigned)blocks, st);
         default: return (int)hipErrorInvalidValue;
     }
 }

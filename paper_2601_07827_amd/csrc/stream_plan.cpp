@@ -294,16 +294,17 @@ bool build(const std::vector<DMode>& dm, const std::vector<Piece>& pieces, bool 
 
 bool stream_preferred(const Analysis& an, int elem_bytes) {
     // Flop per byte if every operand moved exactly once (beta taken as 0: an upper bound).
-    const double flop = (an.dtype == TCX_C128 ? 8.0 : 2.0) * (double)an.sizeH * an.sizeM * an.sizeN * an.sizeK;
+    if (is_widened(an.dtype, an.precision)) return false;       // the streaming kernels compute in the storage type
+    const double flop = (is_complex(an.dtype) ? 8.0 : 2.0) * (double)an.sizeH * an.sizeM * an.sizeN * an.sizeK;
     const double bytes = (double)elem_bytes * ((double)an.sizeH * an.sizeM * an.sizeK + (double)an.sizeH * an.sizeN * an.sizeK +
                                                (double)an.sizeH * an.sizeM * an.sizeN);
-    const double ridge = an.dtype == TCX_F32 ? 19.7 : 9.8;     // peak matrix flop/s over peak HBM byte/s
+    const double ridge = real_bytes_of(an.dtype) == 4 ? 19.7 : 9.8;     // peak matrix flop/s over peak HBM byte/s
     return an.sizeK <= 32 && flop / bytes < ridge;
 }
 
 StreamPlan plan_stream(const Analysis& an, int elem_bytes, bool allow_blocked) {
     StreamPlan p;
-    if (an.sizeK > 64) return p;
+    if (an.sizeK > 64 || is_widened(an.dtype, an.precision)) return p;
     // every mode that indexes D, D-fastest first
     std::vector<DMode> dm;
     for (const Mode& m : an.H) dm.push_back({m, true, true});

@@ -16,6 +16,15 @@ struct Mode {
     int64_t sA, sB, sD;
 };
 
+// ---- element types --------------------------------------------------------------------
+inline int elem_bytes_of(int dtype) { return dtype == TCX_F32 ? 4 : dtype == TCX_C128 ? 16 : 8; }
+inline int real_bytes_of(int dtype) { return dtype == TCX_F32 || dtype == TCX_C64 ? 4 : 8; }
+inline bool is_complex(int dtype) { return dtype == TCX_C64 || dtype == TCX_C128; }
+inline bool valid_dtype(int dtype) { return dtype == TCX_F32 || dtype == TCX_F64 || dtype == TCX_C64 || dtype == TCX_C128; }
+// 32-bit storage with products and sums in 64-bit reals (TCX_PREC_F64)
+inline bool is_widened(int dtype, int precision) { return precision == TCX_PREC_F64 && real_bytes_of(dtype) == 4; }
+inline int compute_real_bytes(int dtype, int precision) { return is_widened(dtype, precision) ? 8 : real_bytes_of(dtype); }
+
 struct TensorDesc {
     int32_t dtype = 0;
     std::vector<int64_t> extent, stride;
@@ -24,6 +33,7 @@ struct TensorDesc {
 // Result of validation + classification + merging + fusion + sorting.
 struct Analysis {
     int32_t dtype = 0;
+    int32_t precision = 0;                  // tcx_prec_t
     int32_t opA = 0, opB = 0, opC = 0;
     std::vector<Mode> H, M, N, K;           // fastest mode first
     int64_t sizeH = 1, sizeM = 1, sizeN = 1, sizeK = 1;
@@ -121,11 +131,14 @@ struct GenericArgs {
 };
 
 // Launchers (defined in the .hip files).  `stream` is a hipStream_t.  Return a hipError_t.
-int launch_generic(int dtype, const GenericArgs& args, void* stream, int64_t* grid, int* block);
+int launch_generic(int dtype, int precision, const GenericArgs& args, void* stream, int64_t* grid, int* block);
 
 int gett_num_variants(int dtype);
 GettVariant gett_variant(int dtype, int variant);
-int launch_gett(int dtype, int variant, bool a_kf, bool b_kf, bool d_nf, const GettArgs& args, void* stream,
+// Is tile shape `variant` built for this element type and precision?  (The two-phase kernels exist
+// for fp32, fp64 and complex128 in their own precision; widened 32-bit types have two shapes each.)
+bool gett_available(int dtype, int precision, int variant);
+int launch_gett(int dtype, int precision, int variant, bool a_kf, bool b_kf, bool d_nf, const GettArgs& args, void* stream,
                 int64_t* grid, int* block);
 
 }  // namespace tcx

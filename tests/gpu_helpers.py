@@ -8,7 +8,7 @@ import numpy as np
 
 import workloads as W
 
-DT = {"f32": 0, "f64": 1, "c128": 3}
+DT = {"f32": 0, "f64": 1, "c64": 2, "c128": 3}
 
 
 def say(msg: str):
@@ -19,7 +19,7 @@ def say(msg: str):
 class GpuProduct:
     """Plan for one Problem: tensor infos + product + executor on torch's current stream."""
 
-    def __init__(self, p: W.Problem, force_path=None, variant=None, split_k=None):
+    def __init__(self, p: W.Problem, force_path=None, variant=None, split_k=None, precision=0):
         import torch
         import paper_2601_07827_amd as T
         self.T, self.p = T, p
@@ -32,7 +32,7 @@ class GpuProduct:
         ib = T.tcx_create_tensor_info(self.h, self.dtype, p.B.extents, p.B.strides)
         idd = T.tcx_create_tensor_info(self.h, self.dtype, p.D.extents, p.D.strides)
         la, lb, ld = ([ids[l] for l in t.labels] for t in (p.A, p.B, p.D))
-        self.prod = T.tcx_create_product(self.h, p.opA, ia, la, p.opB, ib, lb, p.opC, idd, ld, 0, idd, ld)
+        self.prod = T.tcx_create_product(self.h, p.opA, ia, la, p.opB, ib, lb, p.opC, idd, ld, 0, idd, ld, precision)
         for i in (ia, ib, idd):
             T.tcx_destroy_tensor_info(i)       # the plan keeps its own copy
         if force_path is not None:
@@ -68,10 +68,10 @@ class GpuProduct:
 
 
 def run_gpu(p: W.Problem, bufA, bufB, bufC, force_path=None, variant=None, alpha=None, beta=None, c_null=False,
-            split_k=None):
+            split_k=None, precision=0):
     """D buffer (numpy) after D := alpha op(A) op(B) + beta op(C), computed in place over a copy of bufC."""
     import torch
-    gp = GpuProduct(p, force_path, variant, split_k)
+    gp = GpuProduct(p, force_path, variant, split_k, precision)
     try:
         dA, dB = torch.from_numpy(bufA).cuda(), torch.from_numpy(bufB).cuda()
         dD = torch.from_numpy(bufC.copy()).cuda()

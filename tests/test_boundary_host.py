@@ -77,7 +77,8 @@ def test_handle_lifecycle_and_null_conventions(handle):
 
 def test_tensor_info_errors_and_roundtrip(handle):
     assert _code(T.tcx_create_tensor_info, handle, 7, [2], [1]) == T.TCX_ERR_BAD_DTYPE
-    assert _code(T.tcx_create_tensor_info, handle, 2, [2], [1]) == T.TCX_ERR_BAD_DTYPE      # complex64 reserved
+    assert _code(T.tcx_create_tensor_info, handle, 4, [2], [1]) == T.TCX_ERR_BAD_DTYPE
+    assert _code(T.tcx_create_tensor_info, handle, -1, [2], [1]) == T.TCX_ERR_BAD_DTYPE
     assert _code(T.tcx_create_tensor_info, handle, T.TCX_F64, [1] * 33, [1] * 33) == T.TCX_ERR_BAD_NMODE
     assert _code(T.tcx_create_tensor_info, handle, T.TCX_F64, [3, 0], [1, 3]) == T.TCX_ERR_BAD_EXTENT
     assert _code(T.tcx_create_tensor_info, handle, T.TCX_F64, [3, -2], [1, 3]) == T.TCX_ERR_BAD_EXTENT
@@ -492,14 +493,15 @@ def _tile_shapes(handle, dtype):
     return shapes
 
 
-@pytest.mark.parametrize("dtype", [T.TCX_F64, T.TCX_F32, T.TCX_C128])
+@pytest.mark.parametrize("dtype", [T.TCX_F64, T.TCX_F32, T.TCX_C128, T.TCX_C64])
 def test_offset_tables_hold_a_whole_number_of_tiles_of_every_shape(handle, dtype):
     """The tiled kernels index the rows and columns of a ragged last tile without a mask, so the
     padded tables must reach the end of the last tile of EVERY compiled shape (tiles of 96 and 48
     do not divide a padding unit of 256), for every size of M, N and K."""
     shapes = _tile_shapes(handle, dtype)
-    assert len(shapes) >= (8 if dtype == T.TCX_C128 else 12), shapes      # (the batch-lane shape needs a batch mode)
-    assert {s[0] for s in shapes.values()} >= ({96, 48} if dtype == T.TCX_C128 else {256, 32})
+    # (the batch-lane shape needs a batch mode; complex64 has no two-phase shapes)
+    assert len(shapes) >= {T.TCX_C128: 8, T.TCX_C64: 7}.get(dtype, 12), shapes
+    assert {s[0] for s in shapes.values()} >= ({96, 48} if dtype in (T.TCX_C128, T.TCX_C64) else {256, 32})
     for size in list(range(1, 1101)) + [36864, 4096]:
         m, n, k = size, max(2, 1101 - size if size <= 1100 else 4096), 2 + size % 71
         if m * n < 256:
@@ -544,3 +546,28 @@ def test_split_products_report_their_workspace(handle):
     T.tcx_product_set(prod, T.TCX_KEY_SPLIT_K, 1)
     assert T.tcx_product_get(prod, T.TCX_KEY_WORKSPACE_BYTES) == 0
     T.tcx_destroy_product(prod)
+
+
+def test_plan_precision(handle):
+    """Sec. "Tensor Operation Descriptors": the plan carries a desired computational precision.
+    TCX_PREC_F64 widens 32-bit tensors to 64-bit arithmetic: such plans take the generic kernel or
+    one of the two widened tile shapes, never the streaming path; on 64-bit dtypes it changes nothing."""
+    e = dict(m=300, n=200, k=64)
+    A, B, D = W.tensor("mk", e), W.tensor("kn", e), W.tensor("mn", e)
+    for dtype in (T.TCX_F32, T.TCX_C64, T.TCX_F64):
+        infos = [T.tcx_create_tensor_info(handle, dtype, t.extents, t.strides) for t in (A, B, D)]
+        args = (handle, 0, infos[0], [1, 3], 0, infos[1], [3, 2], 0, infos[2], [1, 2], 0, infos[2], [1, 2])
+        assert _code(T.tcx_create_product, *args, 7) == T.TCX_ERR_UNSUPPORTED_PRECISION
+        plain, wide = T.tcx_create_product(*args), T.tcx_create_product(*args, T.TCX_PREC_F64)
+        assert T.tcx_product_get(plain, T.TCX_KEY_PRECISION) == 0 and T.tcx_product_get(wide, T.TCX_KEY_PRECISION) == 1
+        assert T.tcx_product_get(wide, T.TCX_KEY_PATH) == T.TCX_PATH_GETT_MFMA
+        if dtype == T.TCX_F64:
+            assert T.tcx_product_get(wide, T.TCX_KEY_VARIANT) == T.tcx_product_get(plain, T.TCX_KEY_VARIANT)
+        else:
+            assert T.tcx_product_get(wide, T.TCX_KEY_VARIANT) in ((2, 3) if dtype == T.TCX_F32 else (1, 2))
+            assert _code(T.tcx_product_set, wide, T.TCX_KEY_VARIANT, 0) == T.TCX_ERR_PLAN_REFUSED
+            assert _code(T.tcx_product_set, wide, T.TCX_KEY_FORCE_PATH, T.TCX_PATH_BANDWIDTH) == T.TCX_ERR_PLAN_REFUSED
+        for prod in (plain, wide):
+            T.tcx_destroy_product(prod)
+        for i in infos:
+            T.tcx_destroy_tensor_info(i)

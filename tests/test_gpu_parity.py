@@ -8,7 +8,7 @@ import pytest
 
 import oracle
 import workloads as W
-from helpers import TOLERANCE, gaps_untouched, normalised_error, random_problem, run_oracle
+from helpers import TOLERANCE, TOLERANCE_WIDENED, gaps_untouched, normalised_error, random_problem, run_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -18,12 +18,13 @@ REFUSED = 19                                        # TCX_ERR_PLAN_REFUSED
 
 TWO_PHASE = {False: (0, 10, 11), True: (7, 8)}    # tile shapes served by the two-phase kernels (real, complex); 8: batch lanes
 NUM_SHAPES = {False: 12, True: 9}
+COMPLEX = ("c128", "c64")
 
 
 def _paths_for(p):
     from gpu_helpers import DT  # noqa: F401
     paths = [(GENERIC, None)]
-    paths += [(GETT, v) for v in range(NUM_SHAPES[p.dtype == "c128"])]
+    paths += [(GETT, v) for v in range(7 if p.dtype == "c64" else NUM_SHAPES[p.dtype in COMPLEX])]      # complex64: no two-phase shapes
     if p.sizes()[3] <= 64:
         paths.append((STREAM, None))
     return paths
@@ -55,7 +56,7 @@ def _check(p, a, b, c, path, variant, exact=False, truth=None, S=None, split_k=N
             say("  (streaming path declined: |K| = %d)" % p.sizes()[3])
             _TALLY["declined"] += p.sizes()[3] <= 64           # beyond 64 contracted terms it always declines: not counted
             return
-        if path == GETT and variant in TWO_PHASE[p.dtype == "c128"] and getattr(exc, "code", None) == REFUSED:
+        if path == GETT and variant in TWO_PHASE[p.dtype in COMPLEX] and getattr(exc, "code", None) == REFUSED:
             # the two-phase kernel needs |K| in whole slabs and slab-periodic k offsets
             say("  (two-phase kernel declined this plan)")
             _TALLY["declined"] += 1
@@ -94,20 +95,20 @@ def test_reduced_configs_integer_inputs_bit_exact(p):
             _check(p2, a, b, c, path, variant, exact=True, truth=truth, S=S, split_k=3)
 
 
-@pytest.mark.parametrize("dtype", ["f64", "f32", "c128"])
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64"])
 def test_random_problems(dtype):
     rng = np.random.default_rng(31337)
     for i in range(40):
         p = random_problem(rng, dtype, max_group=3, max_extent=6, allow_neg=(i % 3 == 0), name="rand%d_%s" % (i, dtype))
         a, b, c = W.make_operands(p)
         truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
-        paths = [(GENERIC, None), (GETT, (1 + i % 6) if dtype == "c128" else (2 + i % 7)), (STREAM, None)]
+        paths = [(GENERIC, None), (GETT, (1 + i % 6) if dtype in COMPLEX else (2 + i % 7)), (STREAM, None)]
         for path, variant in paths:
             _check(p, a, b, c, path, variant, truth=truth, S=S)
         _check(p, a, b, c, GETT, paths[1][1], truth=truth, S=S, split_k=2 + i % 3)
 
 
-@pytest.mark.parametrize("dtype", ["f64", "f32", "c128"])
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64"])
 def test_one_hot_operand_is_a_bit_exact_permutation(dtype):
     ext = dict(m0=7, m1=9, k0=11, k1=5, n0=11, n1=5)
     A = W.tensor(["m0", "k1", "m1", "k0"], ext, memory_order=["k0", "m1", "m0", "k1"])
@@ -292,16 +293,16 @@ def test_two_phase_kernel_complex(h_slowest):
                     assert normalised_error(p, got, truth, S, c) <= TOLERANCE[p.dtype]
 
 
-@pytest.mark.parametrize("dtype", ["c128", "f64", "f32"])
+@pytest.mark.parametrize("dtype", ["c128", "c64", "f64", "f32"])
 def test_ragged_last_tiles_of_every_shape(dtype):
     """M = 200 and N = 250 end inside the last tile of every compiled shape (tiles of 32 to 256,
     and of 96 and 48 for complex128, which do not divide the tables' former padding unit): every
     shape, unsplit and split, against the oracle; every forced shape must run."""
     e = dict(m=200, n=250, k=40)
     # (the complex two-phase tile takes operands whose fastest mode is contracted)
-    p = W.Problem("ragged_tiles_" + dtype, dtype, W.tensor("mk", e, memory_order="km" if dtype == "c128" else "mk"),
+    p = W.Problem("ragged_tiles_" + dtype, dtype, W.tensor("mk", e, memory_order="km" if dtype in COMPLEX else "mk"),
                   W.tensor("kn", e), W.tensor("mn", e),
-                  alpha=1.5, beta=-0.5, opA=int(dtype == "c128"), seed=W.BASE_SEED + 51)
+                  alpha=1.5, beta=-0.5, opA=int(dtype in COMPLEX), seed=W.BASE_SEED + 51)
     a, b, c = W.make_operands(p)
     truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
     for path, variant in _paths_for(p):
@@ -381,6 +382,64 @@ def test_conjugation_combinations_on_the_complex_two_phase_tile():
                 say("%s split=%s" % (p.name, split))
                 got = run_gpu(p, a, b, c, force_path=GETT, variant=7, split_k=split)
                 assert normalised_error(p, got, truth, S, c) <= TOLERANCE[p.dtype]
+
+
+def _c64(p):
+    return W.Problem(p.name.replace("c128", "c64"), "c64", p.A, p.B, p.D, alpha=p.alpha, beta=p.beta, opA=p.opA, opB=p.opB,
+                     opC=p.opC, seed=p.seed)
+
+
+@pytest.mark.parametrize("p", [_c64(W.config4(h=6, n=20)), _c64(W.config4(h=5, n=18, h_slowest=True)), _c64(W.config4(h=24, n=20, k=4)),
+                               _c64(W.hadamard(2, 9, dtype="c128", permuted=True)), _c64(W.config4(h=3, n=96, k=40))],
+                         ids=lambda p: p.name)
+def test_complex64(p):
+    """complex64 (Sec. "The Reference Implementation": complex numbers in 32-bit precision): the
+    batched conjugated product of configuration 4 in both layouts, a low-intensity and a Hadamard
+    shape, on every path and tile shape built for the type, K unsplit and split; integer inputs
+    bit for bit; the error gate is the fp32 one."""
+    for dist, exact in (("uniform", False), ("ints", True)):
+        a, b, c = W.make_operands(p, dist)
+        q = p if not exact else W.Problem(p.name + "_ints", p.dtype, p.A, p.B, p.D, alpha=2.0 - 1.0j, beta=(0.5 if p.beta != 0 else 0.0),
+                                          opA=p.opA, opB=p.opB, opC=p.opC, seed=p.seed)
+        truth, S = run_oracle(q, a, b, c, oracle.MODE_TRUTH, want_S=True)
+        for path, variant in _paths_for(q) + [(None, None)]:
+            _check(q, a, b, c, path, variant, exact=exact, truth=truth, S=S)
+            if path == GETT and q.sizes()[3] >= 16:
+                _check(q, a, b, c, path, variant, exact=exact, truth=truth, S=S, split_k=2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "c64"])
+def test_precision_f64_on_32_bit_tensors(dtype):
+    """TCX_PREC_F64 (Sec. "Tensor Operation Descriptors": the plan's computational precision):
+    32-bit tensors, products and sums in 64-bit arithmetic, one rounding on the store.  With 8192
+    contracted terms the result sits within one storage rounding of the truth (gate 2^-23 of the
+    normaliser, against 1e-5 for 32-bit arithmetic), on the generic kernel and on both widened tile
+    shapes, K unsplit and split; the same plan in default precision is measurably further away;
+    integer inputs bit for bit."""
+    from gpu_helpers import run_gpu, say
+    import paper_2601_07827_amd as T
+    e = dict(m=150, n=70, k=8192)
+    cplx = dtype == "c64"
+    p = W.Problem("wide_" + dtype, dtype, W.tensor("km", e), W.tensor("kn", e), W.tensor("mn", e),
+                  alpha=(0.5 - 0.25j) if cplx else 0.5, beta=-2.0, opA=int(cplx), seed=W.BASE_SEED + 71)
+    a, b, c = W.make_operands(p)
+    truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+    shapes = (1, 2) if cplx else (2, 3)
+    worst_wide = 0.0
+    for path, variant, split in [(GENERIC, None, None)] + [(GETT, v, sp) for v in shapes for sp in (None, 4)] + [(None, None, None)]:
+        say("%s path=%s shape=%s split=%s TCX_PREC_F64" % (p.name, path, variant, split))
+        got = run_gpu(p, a, b, c, force_path=path, variant=variant, split_k=split, precision=T.TCX_PREC_F64)
+        err = normalised_error(p, got, truth, S, c)
+        assert err <= TOLERANCE_WIDENED, (path, variant, split, err)
+        worst_wide = max(worst_wide, err)
+    plain = normalised_error(p, run_gpu(p, a, b, c, force_path=GETT, variant=shapes[0]), truth, S, c)
+    assert plain <= TOLERANCE[dtype] and plain > 2 * worst_wide, (plain, worst_wide)
+    a, b, c = W.make_operands(p, "ints")
+    q = W.Problem(p.name + "_ints", dtype, p.A, p.B, p.D, alpha=2.0, beta=-1.0, opA=p.opA, seed=p.seed)
+    truth, _ = run_oracle(q, a, b, c, oracle.MODE_TRUTH)
+    for path, variant in ((GENERIC, None), (GETT, shapes[0]), (GETT, shapes[1])):
+        got = run_gpu(q, a, b, c, force_path=path, variant=variant, precision=T.TCX_PREC_F64)
+        assert np.array_equal(W.strided_view(got, q.D), W.strided_view(truth, q.D))
 
 
 LOW_AI_LARGE = [W.config5(extent=4, nshared=1, nfree=7), W.config4(h=512, n=96, k=4),
@@ -573,9 +632,9 @@ def _paper_list_cases():
     ]
     out = []
     for name, A, B, D in cases:
-        for dtype in ("f64", "c128"):
+        for dtype in ("f64", "c128", "c64"):
             out.append(W.Problem("%s_%s" % (name, dtype), dtype, A, B, D, alpha=2.0, beta=-1.0,
-                                 opA=int(dtype == "c128"), seed=W.BASE_SEED + 31))
+                                 opA=int(dtype in COMPLEX), seed=W.BASE_SEED + 31))
     return out
 
 

@@ -32,6 +32,8 @@ MUTANTS = [
     ("complex_modulus_is_squared_norm", "return hypotl(x.real(), x.imag());", "return x.real() * x.real() + x.imag() * x.imag();"),
     ("complex_modulus_is_taxicab", "return hypotl(x.real(), x.imag());", "return fabsl(x.real()) + fabsl(x.imag());"),
     ("storage_complex_modulus_is_squared_norm", "return std::hypot(x.real(), x.imag());", "return x.real() * x.real() + x.imag() * x.imag();"),
+    ("single_complex_modulus_is_squared_norm", "inline float modulus(std::complex<float> x) { return std::hypot(x.real(), x.imag()); }",
+     "inline float modulus(std::complex<float> x) { return x.real() * x.real() + x.imag() * x.imag(); }"),
     ("real_modulus_keeps_sign", "inline long double modulus(long double x) { return fabsl(x); }", "inline long double modulus(long double x) { return x; }"),
     ("normaliser_uses_only_A", "s += (long double)modulus(a) * (long double)modulus(b);", "s += (long double)modulus(a);"),
     ("literal_mode_scales_C_by_alpha", "T running = mul(be, apply_op(C[off_D], opC));", "T running = mul(al, apply_op(C[off_D], opC));"),
@@ -49,7 +51,7 @@ def _pins_to_run():
             calls.append((pins.test_einsum_random_problems, (dt, seed)))
     for row in pins._paper_examples():
         calls.append((pins.test_paper_label_examples, (row,)))
-    for dt in ("c128", "f64", "f32"):
+    for dt in ("c128", "c64", "f64", "f32"):
         for mode in (pins.oracle.MODE_TRUTH, pins.oracle.MODE_TIMED):
             calls.append((pins.test_normaliser_on_exact_moduli, (dt, mode)))
     calls += [(pins.test_repeated_label_equals_summed_stride, ()), (pins.test_validation_classes, ()),

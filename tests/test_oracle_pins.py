@@ -68,7 +68,7 @@ def _as_complex(x):
 
 
 # ---- P1: brute force on tiny tensors --------------------------------------------------
-@pytest.mark.parametrize("dtype", ["f64", "f32", "c128"])
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64"])
 @pytest.mark.parametrize("seed", range(12))
 def test_brute_force_integer_inputs_exact(dtype, seed):
     """Integer-valued inputs: every partial sum is exactly representable, so the oracle (all
@@ -120,7 +120,7 @@ _PYTHAGOREAN = [(3, 4, 5), (5, 12, 13), (8, 15, 17), (7, 24, 25), (20, 21, 29), 
 
 
 @pytest.mark.parametrize("mode", [oracle.MODE_TRUTH, oracle.MODE_TIMED], ids=["truth", "timed"])
-@pytest.mark.parametrize("dtype", ["c128", "f64", "f32"])
+@pytest.mark.parametrize("dtype", ["c128", "c64", "f64", "f32"])
 def test_normaliser_on_exact_moduli(dtype, mode):
     """S = sum_P |op(a)||op(b)| with the complex MODULUS (the error measure's denominator).
     Complex operands are drawn from Gaussian integers with integer moduli, in all sign, swap and
@@ -140,7 +140,7 @@ def test_normaliser_on_exact_moduli(dtype, mode):
         mod = np.zeros(spec.extents, dtype=object)
         v = W.strided_view(buf, spec)
         for at in itertools.product(*[range(e) for e in spec.extents]):
-            if dtype == "c128":
+            if dtype in ("c128", "c64"):
                 x, y, r = _PYTHAGOREAN[int(rng.integers(len(_PYTHAGOREAN)))]
                 if rng.random() < 0.5:
                     x, y = y, x
@@ -168,7 +168,7 @@ def einsum_reference(p: W.Problem, bufA, bufB, bufC):
         for l in t.labels:
             letters.setdefault(l, "abcdefghijklmnopqrstuvwxyzABCDEFGHIJKLMNOPQRSTUVWXYZ"[len(letters)])
     sub = lambda t: "".join(letters[l] for l in t.labels)
-    hi = np.complex128 if p.dtype == "c128" else np.float64
+    hi = np.complex128 if p.dtype in ("c128", "c64") else np.float64
     vA = W.strided_view(bufA, p.A).astype(hi)
     vB = W.strided_view(bufB, p.B).astype(hi)
     vC = W.strided_view(bufC, p.D).astype(hi)
@@ -184,7 +184,7 @@ def einsum_reference(p: W.Problem, bufA, bufB, bufC):
     return out
 
 
-@pytest.mark.parametrize("dtype", ["f64", "f32", "c128"])
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64"])
 @pytest.mark.parametrize("seed", range(10))
 def test_einsum_random_problems(dtype, seed):
     rng = np.random.default_rng(3000 + seed)
@@ -330,7 +330,7 @@ def test_all_ones_config1_value():
 
 
 # ---- P4: one-hot operand => pure gather / permutation, bit exact -----------------------
-@pytest.mark.parametrize("dtype", ["f64", "f32", "c128"])
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64"])
 def test_delta_operand_reproduces_permutation(dtype):
     """B[k..., n...] = prod delta(k_i, n_i)  =>  D[m..., n...] = A[m..., k... = n...]: each
     sum has exactly one non-zero term, so D is a bit-exact re-layout of A."""
@@ -398,17 +398,17 @@ def test_permuting_D_labels_with_memory_order_gives_permuted_values():
     assert not np.array_equal(d0, d1)
 
 
-@pytest.mark.parametrize("dtype", ["f64", "c128"])
+@pytest.mark.parametrize("dtype", ["f64", "c128", "c64"])
 def test_linearity_in_alpha_and_beta(dtype):
     rng = np.random.default_rng(77)
     p = random_problem(rng, dtype, max_group=2, max_extent=4, min_k=1)
     a, b, c = W.make_operands(p)
-    al, be = (0.75 - 0.5j, -1.25 + 2j) if dtype == "c128" else (0.75, -1.25)
+    al, be = (0.75 - 0.5j, -1.25 + 2j) if dtype != "f64" else (0.75, -1.25)
     d, S = run_oracle(p, a, b, c, want_S=True, alpha=al, beta=be)
     d10, _ = run_oracle(p, a, b, c, alpha=1.0, beta=0.0)
     d01, _ = run_oracle(p, a, b, c, alpha=0.0, beta=1.0)
     combo = (al * d10 + be * d01).astype(p.np_dtype)
-    assert normalised_error(p, combo, d, S, c, alpha=al, beta=be) <= 8 * 2.0 ** -53
+    assert normalised_error(p, combo, d, S, c, alpha=al, beta=be) <= 8 * UNIT_ROUNDOFF[dtype]
     # alpha = 0, beta = 1 returns op(C) exactly
     vc = W.strided_view(c, p.D)
     assert np.array_equal(W.strided_view(d01, p.D), np.conj(vc) if p.opC else vc)

@@ -63,11 +63,12 @@ def mix64(seed: int, tag: int, idx: np.ndarray) -> np.ndarray:
 def uniform_pm1(seed: int, tag: int, idx: np.ndarray, dtype) -> np.ndarray:
     """Uniform on [-1, 1): 53 random bits for float64, 24 for float32 (both exact)."""
     dtype = np.dtype(dtype)
-    if dtype == np.complex128:
-        out = np.empty(np.shape(idx), dtype=np.complex128)
+    if dtype in (np.complex128, np.complex64):
+        real = np.float64 if dtype == np.complex128 else np.float32
+        out = np.empty(np.shape(idx), dtype=dtype)
         two = np.asarray(idx).astype(np.uint64) * np.uint64(2)
-        out.real = uniform_pm1(seed, tag, two, np.float64)
-        out.imag = uniform_pm1(seed, tag, two + np.uint64(1), np.float64)
+        out.real = uniform_pm1(seed, tag, two, real)
+        out.imag = uniform_pm1(seed, tag, two + np.uint64(1), real)
         return out
     if dtype == np.float64:
         return _hashed(seed, tag, idx, np.float64,
@@ -81,10 +82,10 @@ def uniform_pm1(seed: int, tag: int, idx: np.ndarray, dtype) -> np.ndarray:
 def normal01(seed: int, tag: int, idx: np.ndarray, dtype) -> np.ndarray:
     """Standard normal by Box-Muller on two hashed uniforms (host only)."""
     dtype = np.dtype(dtype)
-    if dtype == np.complex128:
+    if dtype in (np.complex128, np.complex64):
         re = normal01(seed, tag, idx.astype(np.uint64) * np.uint64(2), np.float64)
         im = normal01(seed, tag, idx.astype(np.uint64) * np.uint64(2) + np.uint64(1), np.float64)
-        return re + 1j * im
+        return (re + 1j * im).astype(dtype)
     h1 = mix64(seed, tag, idx)
     h2 = mix64(seed, tag + 101, idx)
     u1 = ((h1 >> np.uint64(11)).astype(np.float64) + 1.0) * 2.0 ** -53      # (0, 1]
@@ -96,10 +97,10 @@ def small_ints(seed: int, tag: int, idx: np.ndarray, dtype, lo: int = -4, hi: in
     """Integer-valued entries in [lo, hi]: every partial sum of products is exact."""
     dtype = np.dtype(dtype)
     span = np.uint64(hi - lo + 1)
-    if dtype == np.complex128:
+    if dtype in (np.complex128, np.complex64):
         re = small_ints(seed, tag, idx.astype(np.uint64) * np.uint64(2), np.float64, lo, hi)
         im = small_ints(seed, tag, idx.astype(np.uint64) * np.uint64(2) + np.uint64(1), np.float64, lo, hi)
-        return re + 1j * im
+        return (re + 1j * im).astype(dtype)
     h = mix64(seed, tag, idx) >> np.uint64(33)
     return ((h % span).astype(np.int64) + lo).astype(dtype)
 
@@ -161,7 +162,7 @@ def tensor(labels: Sequence[str], extent_of: Dict[str, int], memory_order: Optio
 @dataclass(frozen=True)
 class Problem:
     name: str
-    dtype: str                        # "f32" | "f64" | "c128"
+    dtype: str                        # "f32" | "f64" | "c64" | "c128"
     A: TensorSpec
     B: TensorSpec
     D: TensorSpec                     # C shares D's description
@@ -176,7 +177,7 @@ class Problem:
 
     @property
     def np_dtype(self):
-        return {"f32": np.float32, "f64": np.float64, "c128": np.complex128}[self.dtype]
+        return {"f32": np.float32, "f64": np.float64, "c64": np.complex64, "c128": np.complex128}[self.dtype]
 
     def extent_of(self) -> Dict[str, int]:
         out: Dict[str, int] = {}
@@ -210,7 +211,7 @@ class Problem:
 
     def real_flops(self) -> int:
         h, m, n, k = self.sizes()
-        return (8 if self.dtype == "c128" else 2) * h * m * n * k
+        return (8 if self.dtype in ("c128", "c64") else 2) * h * m * n * k
 
     def algorithmic_bytes(self) -> int:
         item = np.dtype(self.np_dtype).itemsize
