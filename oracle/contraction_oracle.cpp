@@ -11,8 +11,12 @@
 //   * Case 2 / Eq. (case2): labels present in A, B and D (H) are element-wise.
 //   * Case 3 + Note 6: a label repeated inside one tensor addresses a diagonal; the
 //     strides of all its occurrences are added.
-//   * Cases 4 and 5 (labels in only one of A, B, or only in D) are not required by
-//     the standard (Note 7) and are rejected by oracle_validate().
+//   * Case 4 / its equation: a label in A only (I_A) or in B only (I_B) is summed inside
+//     that tensor before the product:  sum_P (sum_{I_A} A) (sum_{I_B} B).
+//   * Case 5 / its equation: a label in D (and C) only (I_C) broadcasts the product: the
+//     same alpha * sum is written for every value of the label, plus beta * C at that place.
+//     (The standard does not require Cases 4 and 5 (Note 7); their definitions are still the
+//     paper's, so the oracle states them.)
 // How it computes it (paper, Sec. "Algorithm Structure"): every index tuple over the
 // distinct labels of D, first label fastest; for each, every tuple over the contracted
 // labels, again first label fastest; per term one displacement sum(index*stride) per
@@ -59,7 +63,7 @@ enum {
     V_EXTENT_MISMATCH = 1,   // same label, different extent (Preliminaries: Id(i)=Id(j) only if d_i=d_j)
     V_CD_MISMATCH = 2,       // C is not laid out exactly as D (Note 5)
     V_D_ALIASING = 3,        // two index tuples of D address the same element
-    V_ISOLATED = 4,          // Case 4 or Case 5 label
+    V_ISOLATED = 4,          // (no longer produced: Cases 4 and 5 are defined and evaluated)
     V_BAD_ARG = 5            // non-positive extent, bad rank
 };
 
@@ -75,7 +79,6 @@ struct Loop {
     int64_t label;
     int64_t extent;
     int64_t sA, sB, sD;   // summed strides (Note 6); 0 where the label is absent
-    bool inA, inB, inD;
 };
 
 bool has_label(const Tensor& t, int64_t lab) {
@@ -125,13 +128,6 @@ int validate(const Tensor& A, const Tensor& B, const Tensor& C, const Tensor& D)
             if (ed > 1 && summed_stride(C, lab) != summed_stride(D, lab)) return V_CD_MISMATCH;
         }
     }
-    // Eq. (FreeD): every label of D is in A or B.  Note 7: no label lives in A only or B only.
-    for (int i = 0; i < D.n; ++i)
-        if (!has_label(A, D.label[i]) && !has_label(B, D.label[i])) return V_ISOLATED;
-    for (int i = 0; i < A.n; ++i)
-        if (!has_label(B, A.label[i]) && !has_label(D, A.label[i])) return V_ISOLATED;
-    for (int i = 0; i < B.n; ++i)
-        if (!has_label(A, B.label[i]) && !has_label(D, B.label[i])) return V_ISOLATED;
     // Aliasing inside D.  Work on distinct labels with summed strides, drop extent 1,
     // sort by |stride| and require each stride to clear the span of the smaller ones.
     // Sufficient for "no two tuples collide"; conservative for exotic layouts.
@@ -202,11 +198,36 @@ inline int64_t displacement(const std::vector<int64_t>& idx, const std::vector<i
     return d;
 }
 
+// The sum over one tensor's isolated labels (Case 4: a reduction inside the tensor) of the
+// elements at base + displacement, each passed through op.  With no isolated label it is the one
+// element at base.  *mod receives the sum of the moduli (for the normaliser).
+template <class Acc, class T>
+Acc reduced(const T* X, int64_t base, const std::vector<int64_t>& shape, const std::vector<int64_t>& strides, int op,
+            long double* mod) {
+    if (shape.empty()) {                       // nothing to sum over: the element itself
+        const Acc x = Widen<Acc, T>::of(apply_op(X[base], op));
+        *mod = (long double)modulus(x);
+        return x;
+    }
+    int64_t count = 1;
+    for (int64_t e : shape) count *= e;
+    std::vector<int64_t> I(shape.size(), 0);
+    Acc sum = Acc(0);
+    *mod = 0.0L;
+    for (int64_t n = 0; n < count; ++n, advance(I, shape)) {
+        const Acc x = Widen<Acc, T>::of(apply_op(X[base + displacement(I, strides)], op));
+        sum = sum + x;
+        *mod += (long double)modulus(x);
+    }
+    return sum;
+}
+
 template <class T, class Acc>
 void contract(int mode, const std::vector<Loop>& free_loops, const std::vector<Loop>& sum_loops,
+              const std::vector<Loop>& only_A, const std::vector<Loop>& only_B,
               int opA, int opB, int opC, Acc alpha, Acc beta,
               const T* A, const T* B, const T* C, T* D, double* S) {
-    std::vector<int64_t> dshape, dsA, dsB, dsD, pshape, psA, psB;
+    std::vector<int64_t> dshape, dsA, dsB, dsD, pshape, psA, psB, iashape, iasA, ibshape, ibsB;
     int64_t size_D = 1, size_P = 1;
     for (const Loop& l : free_loops) {
         dshape.push_back(l.extent); dsA.push_back(l.sA); dsB.push_back(l.sB); dsD.push_back(l.sD);
@@ -216,6 +237,8 @@ void contract(int mode, const std::vector<Loop>& free_loops, const std::vector<L
         pshape.push_back(l.extent); psA.push_back(l.sA); psB.push_back(l.sB);
         size_P *= l.extent;
     }
+    for (const Loop& l : only_A) { iashape.push_back(l.extent); iasA.push_back(l.sA); }
+    for (const Loop& l : only_B) { ibshape.push_back(l.extent); ibsB.push_back(l.sB); }
     const bool read_ab = !is_zero(alpha);
     const bool read_c = !is_zero(beta);
 
@@ -240,9 +263,10 @@ void contract(int mode, const std::vector<Loop>& free_loops, const std::vector<L
             // exactly like a read-modify-write of D per term.  C is read even when beta is 0.
             const T al = Narrow<T, Acc>::of(alpha), be = Narrow<T, Acc>::of(beta);
             T running = mul(be, apply_op(C[off_D], opC));
+            long double unused;
             for (int64_t k = 0; k < size_P; ++k, advance(K, pshape)) {
-                const T a = apply_op(A[baseA + displacement(K, psA)], opA);
-                const T b = apply_op(B[baseB + displacement(K, psB)], opB);
+                const T a = reduced<T, T>(A, baseA + displacement(K, psA), iashape, iasA, opA, &unused);
+                const T b = reduced<T, T>(B, baseB + displacement(K, psB), ibshape, ibsB, opB, &unused);
                 running = running + mul(al, mul(a, b));
             }
             D[off_D] = running;
@@ -255,10 +279,11 @@ void contract(int mode, const std::vector<Loop>& free_loops, const std::vector<L
             for (int64_t k = 0; k < size_P; ++k) {
                 const int64_t off_A = baseA + displacement(K, psA);
                 const int64_t off_B = baseB + displacement(K, psB);
-                const Acc a = Widen<Acc, T>::of(apply_op(A[off_A], opA));
-                const Acc b = Widen<Acc, T>::of(apply_op(B[off_B], opB));
+                long double ma, mb;
+                const Acc a = reduced<Acc, T>(A, off_A, iashape, iasA, opA, &ma);      // Case 4: sum over I_A
+                const Acc b = reduced<Acc, T>(B, off_B, ibshape, ibsB, opB, &mb);      // Case 4: sum over I_B
                 acc = acc + mul(a, b);
-                if (S) s += (long double)modulus(a) * (long double)modulus(b);
+                if (S) s += ma * mb;
                 advance(K, pshape);
             }
         }
@@ -307,13 +332,23 @@ int oracle_contract(int dtype, int mode,
         l.sA = summed_stride(tA, lab); l.sB = summed_stride(tB, lab); l.sD = summed_stride(tD, lab);
         free_loops.push_back(l);
     }
+    std::vector<Loop> only_A, only_B;
     for (int64_t lab : distinct_labels(tA)) {
         if (has_label(tD, lab)) continue;
         Loop l{};
         l.label = lab;
         for (int i = 0; i < nA; ++i) if (labA[i] == lab) l.extent = extA[i];
         l.sA = summed_stride(tA, lab); l.sB = summed_stride(tB, lab); l.sD = 0;
-        sum_loops.push_back(l);
+        if (has_label(tB, lab)) sum_loops.push_back(l);       // P
+        else only_A.push_back(l);                             // I_A
+    }
+    for (int64_t lab : distinct_labels(tB)) {
+        if (has_label(tD, lab) || has_label(tA, lab)) continue;
+        Loop l{};
+        l.label = lab;
+        for (int i = 0; i < nB; ++i) if (labB[i] == lab) l.extent = extB[i];
+        l.sA = 0; l.sB = summed_stride(tB, lab); l.sD = 0;
+        only_B.push_back(l);                                  // I_B
     }
 
     using cld = std::complex<long double>;
@@ -321,31 +356,31 @@ int oracle_contract(int dtype, int mode,
     using cf = std::complex<float>;
     if (dtype == DT_F64) {
         if (mode == MODE_TRUTH)
-            contract<double, long double>(mode, free_loops, sum_loops, opA, opB, opC, alpha[0], beta[0],
+            contract<double, long double>(mode, free_loops, sum_loops, only_A, only_B, opA, opB, opC, alpha[0], beta[0],
                                           (const double*)A, (const double*)B, (const double*)C, (double*)D, S);
         else
-            contract<double, double>(mode, free_loops, sum_loops, opA, opB, opC, alpha[0], beta[0],
+            contract<double, double>(mode, free_loops, sum_loops, only_A, only_B, opA, opB, opC, alpha[0], beta[0],
                                      (const double*)A, (const double*)B, (const double*)C, (double*)D, S);
     } else if (dtype == DT_F32) {
         if (mode == MODE_TRUTH)
-            contract<float, long double>(mode, free_loops, sum_loops, opA, opB, opC, alpha[0], beta[0],
+            contract<float, long double>(mode, free_loops, sum_loops, only_A, only_B, opA, opB, opC, alpha[0], beta[0],
                                          (const float*)A, (const float*)B, (const float*)C, (float*)D, S);
         else
-            contract<float, float>(mode, free_loops, sum_loops, opA, opB, opC, (float)alpha[0], (float)beta[0],
+            contract<float, float>(mode, free_loops, sum_loops, only_A, only_B, opA, opB, opC, (float)alpha[0], (float)beta[0],
                                    (const float*)A, (const float*)B, (const float*)C, (float*)D, S);
     } else if (dtype == DT_C128) {
         if (mode == MODE_TRUTH)
-            contract<cd, cld>(mode, free_loops, sum_loops, opA, opB, opC, cld(alpha[0], alpha[1]), cld(beta[0], beta[1]),
+            contract<cd, cld>(mode, free_loops, sum_loops, only_A, only_B, opA, opB, opC, cld(alpha[0], alpha[1]), cld(beta[0], beta[1]),
                               (const cd*)A, (const cd*)B, (const cd*)C, (cd*)D, S);
         else
-            contract<cd, cd>(mode, free_loops, sum_loops, opA, opB, opC, cd(alpha[0], alpha[1]), cd(beta[0], beta[1]),
+            contract<cd, cd>(mode, free_loops, sum_loops, only_A, only_B, opA, opB, opC, cd(alpha[0], alpha[1]), cd(beta[0], beta[1]),
                              (const cd*)A, (const cd*)B, (const cd*)C, (cd*)D, S);
     } else if (dtype == DT_C64) {
         if (mode == MODE_TRUTH)
-            contract<cf, cld>(mode, free_loops, sum_loops, opA, opB, opC, cld(alpha[0], alpha[1]), cld(beta[0], beta[1]),
+            contract<cf, cld>(mode, free_loops, sum_loops, only_A, only_B, opA, opB, opC, cld(alpha[0], alpha[1]), cld(beta[0], beta[1]),
                               (const cf*)A, (const cf*)B, (const cf*)C, (cf*)D, S);
         else
-            contract<cf, cf>(mode, free_loops, sum_loops, opA, opB, opC, cf((float)alpha[0], (float)alpha[1]),
+            contract<cf, cf>(mode, free_loops, sum_loops, only_A, only_B, opA, opB, opC, cf((float)alpha[0], (float)alpha[1]),
                              cf((float)beta[0], (float)beta[1]), (const cf*)A, (const cf*)B, (const cf*)C, (cf*)D, S);
     } else {
         return V_BAD_ARG;

@@ -57,9 +57,10 @@ def gaps_untouched(p: W.Problem, before, after) -> bool:
 
 
 def random_problem(rng: np.random.Generator, dtype="f64", max_group=2, max_extent=4, allow_neg=False,
-                   pad=True, min_k=0, name="rand") -> W.Problem:
+                   pad=True, min_k=0, name="rand", isolated=False) -> W.Problem:
     """A random valid Case-1/2 problem: random numbers of H, M, N, K labels, random extents,
-    random label order per tensor, random memory order, optional padding / negative strides."""
+    random label order per tensor, random memory order, optional padding / negative strides.
+    isolated: also labels that live in A only, in B only (Case 4) and in D only (Case 5)."""
     while True:
         nh, nm, nn = (int(rng.integers(0, max_group + 1)) for _ in range(3))
         nk = int(rng.integers(min_k, max_group + 1))
@@ -69,7 +70,10 @@ def random_problem(rng: np.random.Generator, dtype="f64", max_group=2, max_exten
     M = ["m%d" % i for i in range(nm)]
     N = ["n%d" % i for i in range(nn)]
     K = ["k%d" % i for i in range(nk)]
-    ext = {l: int(rng.integers(1, max_extent + 1)) for l in H + M + N + K}
+    IA = ["x%d" % i for i in range(int(rng.integers(0, 3)))] if isolated else []
+    IB = ["y%d" % i for i in range(int(rng.integers(0, 3)))] if isolated else []
+    IC = ["z%d" % i for i in range(int(rng.integers(0, 2)))] if isolated else []
+    ext = {l: int(rng.integers(1, max_extent + 1)) for l in H + M + N + K + IA + IB + IC}
 
     def layout(labels):
         labels = list(labels)
@@ -88,7 +92,7 @@ def random_problem(rng: np.random.Generator, dtype="f64", max_group=2, max_exten
                     strides[l] = -strides[l]
         return W.tensor(labels, ext, strides=strides)
 
-    A, B, D = layout(H + M + K), layout(H + N + K), layout(H + M + N)
+    A, B, D = layout(H + M + K + IA), layout(H + N + K + IB), layout(H + M + N + IC)
     cplx = dtype in ("c128", "c64")
     alpha = complex(rng.integers(-2, 3), rng.integers(-2, 3) if cplx else 0) or 1.0
     beta = complex(rng.integers(-2, 3), rng.integers(-2, 3) if cplx else 0)

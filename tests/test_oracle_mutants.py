@@ -27,7 +27,9 @@ MUTANTS = [
     ("alpha_also_scales_C", "D[off_D] = Narrow<T, Acc>::of(d);", "D[off_D] = Narrow<T, Acc>::of(read_c ? mul(alpha, d) : d);"),
     ("hadamard_label_summed", "if (has_label(tD, lab)) continue;", "if (has_label(tD, lab) && !has_label(tB, lab)) continue;"),
     ("aliasing_check_off", "if (p.first <= span) return V_D_ALIASING;", "if (false) return V_D_ALIASING;"),
-    ("isolated_in_B_accepted", "if (!has_label(A, B.label[i]) && !has_label(D, B.label[i])) return V_ISOLATED;", ";"),
+    ("label_only_in_B_left_out", "only_B.push_back(l);", ";"),
+    ("reduction_in_B_never_moves", "l.sA = 0; l.sB = summed_stride(tB, lab); l.sD = 0;", "l.sA = 0; l.sB = 0; l.sD = 0;"),
+    ("reduction_keeps_last_element", "sum = sum + x;", "sum = x;"),
     ("free_stride_of_A_dropped", "const int64_t baseA = displacement(I, dsA);", "const int64_t baseA = 0;"),
     ("complex_modulus_is_squared_norm", "return hypotl(x.real(), x.imag());", "return x.real() * x.real() + x.imag() * x.imag();"),
     ("complex_modulus_is_taxicab", "return hypotl(x.real(), x.imag());", "return fabsl(x.real()) + fabsl(x.imag());"),
@@ -54,6 +56,9 @@ def _pins_to_run():
     for dt in ("c128", "c64", "f64", "f32"):
         for mode in (pins.oracle.MODE_TRUTH, pins.oracle.MODE_TIMED):
             calls.append((pins.test_normaliser_on_exact_moduli, (dt, mode)))
+    for seed in range(10):
+        calls.append((pins.test_isolated_labels_brute_force, ("f64", seed)))
+    calls += [(pins.test_case4_example_is_a_reduction_then_a_contraction, ()), (pins.test_case5_broadcasts_the_product, ())]
     calls += [(pins.test_repeated_label_equals_summed_stride, ()), (pins.test_validation_classes, ()),
               (pins.test_conjugation_symmetry_and_op_equals_preconjugated_copy, ()),
               (pins.test_delta_operand_reproduces_permutation, ("c128",)),

@@ -256,10 +256,7 @@ def test_paper_label_examples(row):
     p = W.Problem(case, "f64", _rep_tensor(la, ext), _rep_tensor(lb, ext), _rep_tensor(ld, ext), alpha=2.0, beta=-1.0)
     ids = W.label_ids(p)
     st = oracle.validate(desc(p.A, ids), desc(p.B, ids), desc(p.D, ids), desc(p.D, ids))
-    if not supported:
-        assert st == oracle.V_ISOLATED
-        return
-    assert st == oracle.V_OK
+    assert st == oracle.V_OK              # also the cases the standard does not require (Note 7): their equations define the result
     a, b, c = W.make_operands(p, "ints")
     exact = brute_exact(p, a, b, c)
     d, _ = run_oracle(p, a, b, c)
@@ -506,8 +503,8 @@ def test_validation_classes():
     assert oracle.validate(A, B, t("mn", strides=dict(m=1, n=4)), D) == oracle.V_CD_MISMATCH
     assert oracle.validate(A, B, t("mn", strides=dict(m=1, n=2)), t("mn", strides=dict(m=1, n=2))) == oracle.V_D_ALIASING
     assert oracle.validate(A, B, t("mn", strides=dict(m=0, n=1)), t("mn", strides=dict(m=0, n=1))) == oracle.V_D_ALIASING
-    assert oracle.validate(t("mkx"), B, D, D) == oracle.V_ISOLATED      # Case 4
-    assert oracle.validate(A, B, t("mnx"), t("mnx")) == oracle.V_ISOLATED  # Case 5
+    assert oracle.validate(t("mkx"), B, D, D) == oracle.V_OK            # Case 4: x is summed inside A
+    assert oracle.validate(A, B, t("mnx"), t("mnx")) == oracle.V_OK        # Case 5: x broadcasts
     assert oracle.validate(([0, 5], [1, 1], [1, 3]), B, D, D) == oracle.V_BAD_ARG
 
 
@@ -523,3 +520,50 @@ def test_config3_literal_stride_reading_aliases():
     assert oracle.validate(A, B, D, D) == oracle.V_D_ALIASING
     Dok = desc(p.D, lab)
     assert oracle.validate(A, B, Dok, Dok) == oracle.V_OK
+
+
+# ---- Cases 4 and 5: reductions inside A, B and broadcast into D ------------------------------
+@pytest.mark.parametrize("dtype", ["f64", "c128", "f32"])
+@pytest.mark.parametrize("seed", range(10))
+def test_isolated_labels_brute_force(dtype, seed):
+    """Labels in A only or in B only are summed inside that tensor before the product, labels in D
+    only repeat the product (Secs. "Case 4", "Case 5").  The rational evaluator sums A * B over
+    every assignment of ALL labels and scatters to D's entry, which equals the sum of products of
+    the reduced operands by distributivity: an independent form of the same definition.  Integer
+    inputs, exact in all three evaluation orders."""
+    rng = np.random.default_rng(7000 + seed)
+    p = random_problem(rng, dtype, allow_neg=(seed % 2 == 1), isolated=True)
+    a, b, c = W.make_operands(p, "ints")
+    exact = brute_exact(p, a, b, c)
+    for mode in (oracle.MODE_TRUTH, oracle.MODE_TIMED, oracle.MODE_LITERAL):
+        d, _ = run_oracle(p, a, b, c, mode)
+        v = W.strided_view(d, p.D)
+        for key, val in exact.items():
+            assert complex(v[key]) == _as_complex(val), (p, key, mode)
+
+
+def test_case4_example_is_a_reduction_then_a_contraction():
+    """The paper's Case 4 example D[d,a] = A[b,a,b] B[b,g,d,g,a] + C[d,a]: summing B's diagonal over
+    g first and contracting the result is the same computation; einsum agrees."""
+    ext = dict(a=3, b=4, g=2, d=5)
+    A, B, D = _rep_tensor("bab", ext), _rep_tensor("bgdga", ext), _rep_tensor("da", ext)
+    p = W.Problem("case4", "f64", A, B, D, alpha=2.0, beta=-1.0)
+    a, b, c = W.make_operands(p, "ints")
+    d, S = run_oracle(p, a, b, c, want_S=True)
+    va, vb = W.strided_view(a, A), W.strided_view(b, B)
+    ref = 2.0 * np.einsum("bab,bgdga->da", va, vb) - c.reshape((5, 3), order="F")
+    assert np.array_equal(d.reshape((5, 3), order="F"), ref)
+    # the normaliser: sum over b of (|A[b,a,b]|) (sum over g |B[b,g,d,g,a]|)
+    refS = np.einsum("bab,bgdga->da", np.abs(va), np.abs(vb))
+    assert np.array_equal(S.reshape((5, 3), order="F"), refS)
+
+
+def test_case5_broadcasts_the_product():
+    ext = dict(m=3, n=4, k=5, x=6)
+    p = W.Problem("case5", "f64", W.tensor("mk", ext), W.tensor("kn", ext), W.tensor("mxn", ext), alpha=1.0, beta=0.5)
+    a, b, c = W.make_operands(p, "ints")
+    d, _ = run_oracle(p, a, b, c)
+    prod = a.reshape((3, 5), order="F") @ b.reshape((5, 4), order="F")
+    D3, C3 = d.reshape((3, 6, 4), order="F"), c.reshape((3, 6, 4), order="F")
+    for x in range(6):
+        assert np.array_equal(D3[:, x, :], prod + 0.5 * C3[:, x, :])
