@@ -7,9 +7,11 @@
  * occurs in A and B only is contracted (summed, set P); in A and D only, or in B and D
  * only, it is free (F_A, F_B); in A, B and D it is a Hadamard / batch label (H)
  * (Secs. "Case 1", "Case 2", Eqs. case1, case2).  A label repeated inside one tensor
- * addresses a diagonal (Sec. "Case 3", Note 6).  Labels that occur in only one of A, B
- * or only in D (Cases 4 and 5) are not required by the standard (Note 7) and are
- * rejected with TCX_ERR_ISOLATED_INDEX.
+ * addresses a diagonal (Sec. "Case 3", Note 6).  A label that occurs in A only, or in B
+ * only, is summed inside that tensor before the product (Sec. "Case 4": the operand is
+ * reduced by a kernel of its own into workspace memory, TCX_KEY_WORKSPACE_BYTES); a label
+ * that occurs in D (and C) only repeats the product for each of its values (Sec. "Case 5").
+ * The standard does not require the last two (Note 7); this library computes them.
  *
  * Object model (Sec. "Interface Components"): a library handle, an executor (a HIP
  * stream), tensor descriptors ("tensor info": rank, extents, strides, dtype -- no data
@@ -83,7 +85,7 @@ enum {
     TCX_ERR_EXTENT_MISMATCH = 6,     /* one label, two extents (Sec. Preliminaries; appendix test 26) */
     TCX_ERR_CD_MISMATCH = 7,         /* C is not described exactly like D (Note 5; appendix test 27) */
     TCX_ERR_D_ALIASING = 8,          /* two index tuples of D share an address (appendix test 28) */
-    TCX_ERR_ISOLATED_INDEX = 9,      /* Case 4 / Case 5 label (Eq. FreeD, Note 7) */
+    TCX_ERR_ISOLATED_INDEX = 9,      /* (not returned: labels in one tensor only are reduced or broadcast, Secs. "Case 4", "Case 5") */
     TCX_ERR_DTYPE_MIX = 10,          /* the four tensors do not share one dtype */
     TCX_ERR_UNSUPPORTED_OP = 11,     /* op value unknown, or opD != identity */
     TCX_ERR_UNSUPPORTED_PRECISION = 12,
@@ -168,10 +170,10 @@ enum {
     TCX_KEY_MODES_H = 23,
     TCX_KEY_FORCE_PATH = 24,   /* tcx_product_set only: force a tcx_path_t (testing, tuning) */
     TCX_KEY_SPLIT_K = 25,      /* tiled path: number of parts the contracted range is cut into (1 = unsplit) */
-    TCX_KEY_LAUNCHES = 26,     /* read-only: kernel launches one execution enqueues (rounds of a long-tile product; +1 for the split-K reduction) */
+    TCX_KEY_LAUNCHES = 26,     /* read-only: kernel launches one execution enqueues (rounds of a long-tile product; +1 for the split-K reduction; +1 per operand reduced over isolated labels) */
     TCX_KEY_GATHER_WIDTH = 27, /* read-only: elements one gather load of the tiled kernel brings (2: neighbouring pairs of 8-byte elements; a status reports what the execution used, which also depends on the operand pointers being 16-byte aligned) */
     TCX_KEY_TABLE_ENTRIES = 28,/* read-only, int64_t[3]: entries of the plan's offset tables over M, N, K including padding (0 before the tiled path was prepared) */
-    TCX_KEY_WORKSPACE_BYTES = 29, /* product (read-only): device bytes of partial sums one execution writes; executor: size of its workspace, settable to reserve at least that much */
+    TCX_KEY_WORKSPACE_BYTES = 29, /* product (read-only): device bytes of workspace one execution uses (split-K partial sums, operands reduced over isolated labels); executor: size of its workspace, settable to reserve at least that much */
     TCX_KEY_DEVICE = 30,       /* handle, executor (read-only): HIP device ordinal the object is bound to, -1 if none */
     TCX_KEY_NUM_CU = 31,       /* handle (read-only): compute units of the bound device */
     TCX_KEY_STREAM = 32,       /* executor: the hipStream_t as an integer; settable (the caller keeps the new stream alive) */

@@ -110,13 +110,6 @@ tcx_error_t analyse(const TensorDesc& A, const int64_t* labA, const TensorDesc& 
         if (it == c.end() || it->second.extent != kv.second.extent) return TCX_ERR_CD_MISMATCH;
         if (kv.second.extent > 1 && it->second.stride != kv.second.stride) return TCX_ERR_CD_MISMATCH;
     }
-    // Eq. (FreeD) and Note 7: no label may live in exactly one of A, B, D
-    for (const auto& kv : d)
-        if (!a.count(kv.first) && !b.count(kv.first)) return TCX_ERR_ISOLATED_INDEX;
-    for (const auto& kv : a)
-        if (!b.count(kv.first) && !d.count(kv.first)) return TCX_ERR_ISOLATED_INDEX;
-    for (const auto& kv : b)
-        if (!a.count(kv.first) && !d.count(kv.first)) return TCX_ERR_ISOLATED_INDEX;
     // no two index tuples of D may share an address: with modes sorted by |stride| each
     // stride has to clear everything the smaller ones can reach
     {
@@ -144,6 +137,8 @@ tcx_error_t analyse(const TensorDesc& A, const int64_t* labA, const TensorDesc& 
     };
     LabelMap all = a;
     all.insert(b.begin(), b.end());
+    all.insert(d.begin(), d.end());
+    std::vector<Mode> onlyA, onlyB;
     for (const auto& kv : all) {
         const int64_t lab = kv.first;
         const bool inA = a.count(lab), inB = b.count(lab), inD = d.count(lab);
@@ -151,9 +146,40 @@ tcx_error_t analyse(const TensorDesc& A, const int64_t* labA, const TensorDesc& 
         if (m.extent == 1) continue;                       // a2: extent-1 modes address nothing
         if (inA && inB && inD) r.H.push_back(m);
         else if (inA && inB) r.K.push_back(m);
-        else if (inA) r.M.push_back(m);
-        else if (inB) r.N.push_back(m);
+        else if (inA && inD) r.M.push_back(m);
+        else if (inB && inD) r.N.push_back(m);
+        else if (inA) onlyA.push_back(m);                  // Sec. "Case 4": summed inside A
+        else if (inB) onlyB.push_back(m);                  // ... inside B
+        else r.M.push_back(m);                             // Sec. "Case 5": in D (and C) only -- a free mode that neither
+                                                           // operand moves along (strides 0): the product is repeated
     }
+    // Case 4: the operand is reduced over its isolated labels first (one pass over it, into
+    // workspace memory); from here on sA / sB of the other modes address that dense result.
+    auto pre_reduce = [&](const std::vector<Mode>& only, int which, Reduction* red) {
+        if (only.empty()) return;
+        red->active = true;
+        for (const Mode& m : only) { red->sumExt.push_back(m.extent); red->sumSrc.push_back(m.*kStride[which]); }
+        std::vector<Mode*> kept;
+        for (std::vector<Mode>* g : {&r.H, &r.M, &r.N, &r.K})
+            for (Mode& m : *g)
+                if (m.*kStride[which] != 0) kept.push_back(&m);
+        std::stable_sort(kept.begin(), kept.end(), [which](const Mode* x, const Mode* y) {
+            return iabs(x->*kStride[which]) < iabs(y->*kStride[which]);
+        });
+        int64_t run = 1;
+        for (Mode* m : kept) {
+            red->keepExt.push_back(m->extent);
+            red->keepSrc.push_back(m->*kStride[which]);
+            m->*kStride[which] = run;
+            run *= m->extent;
+        }
+        red->count = run;
+    };
+    pre_reduce(onlyA, 0, &r.redA);
+    pre_reduce(onlyB, 1, &r.redB);
+    if ((int)(r.redA.keepExt.size()) > kMaxGenericModes || (int)r.redA.sumExt.size() > kMaxGenericModes ||
+        (int)(r.redB.keepExt.size()) > kMaxGenericModes || (int)r.redB.sumExt.size() > kMaxGenericModes)
+        return TCX_ERR_TOO_LARGE;
 
     // ---- a2: fuse, then order each group -----------------------------------------------------
     fuse(&r.H); fuse(&r.M); fuse(&r.N); fuse(&r.K);

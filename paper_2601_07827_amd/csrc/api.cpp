@@ -280,12 +280,21 @@ tcx_error_t build_tables(Product* p) {
 }
 
 // Bytes of partial sums one execution of the plan writes (0: none, or summed inside the workgroup).
-size_t workspace_need(const Product& p) {
+size_t partials_need(const Product& p) {
     if (p.an.path != TCX_PATH_GETT_MFMA || p.splitK <= 1) return 0;
     const GettVariant s = gett_variant(p.an.dtype, p.variant);
     if (p.splitK == 2 && s.pair_in_lds) return 0;
     const size_t real_bytes = (size_t)compute_real_bytes(p.an.dtype, p.an.precision);
     return (size_t)tiles_of(p.an, s) * (size_t)p.splitK * (size_t)s.acc_reals * real_bytes;
+}
+size_t align256(size_t n) { return (n + 255) / 256 * 256; }
+// Bytes of a pre-reduced operand (Sec. "Case 4"), 0 if the operand is read as it is.
+size_t reduced_bytes(const Product& p, const Reduction& r) {
+    return r.active ? align256((size_t)r.count * (size_t)elem_bytes_of(p.an.dtype)) : 0;
+}
+// Workspace of one execution: [partial sums][reduced A][reduced B], each part 256-byte aligned.
+size_t workspace_need(const Product& p) {
+    return align256(partials_need(p)) + reduced_bytes(p, p.an.redA) + reduced_bytes(p, p.an.redB);
 }
 
 // Grow the executor's workspace to `need` bytes.  hipFree waits for the work that still uses the
@@ -716,12 +725,13 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
         case TCX_KEY_D_N_FASTEST: return put_i64(an.d_n_fastest, value, nbytes);
         case TCX_KEY_SPLIT_K: return put_i64(tiled ? p->splitK : 1, value, nbytes);
         case TCX_KEY_LAUNCHES: {
-            if (!tiled) return put_i64(1, value, nbytes);
+            const int64_t reductions = (an.redA.active ? 1 : 0) + (an.redB.active ? 1 : 0);      // Case 4 pre-reductions
+            if (!tiled) return put_i64(1 + reductions, value, nbytes);
             const int64_t items = tiles_of(an, s) * p->splitK;
             const int64_t blocks = s.dual ? (items + 1) / 2 : items;
             const int64_t round = round_size_of(*p, s);
             const bool second_kernel = p->splitK > 1 && !(p->splitK == 2 && s.pair_in_lds);
-            return put_i64((round > 0 && p->splitK == 1 && blocks > round ? (blocks + round - 1) / round : 1) + (second_kernel ? 1 : 0),
+            return put_i64((round > 0 && p->splitK == 1 && blocks > round ? (blocks + round - 1) / round : 1) + (second_kernel ? 1 : 0) + reductions,
                            value, nbytes);
         }
         case TCX_KEY_GATHER_WIDTH: return put_i64(tiled && s.pingpong && s.dual && p->pairs ? 2 : 1, value, nbytes);
@@ -829,6 +839,47 @@ tcx_error_t run_product(tcx_product_t product, tcx_executor_t executor, tcx_stat
     int hip_err = 0;
     int64_t grid = 0;
     int block = 0;
+    // Workspace of this execution: leased from the executor (executions on its stream run in order
+    // and may share it) or, for the call that may not allocate, the library's fixed buffer.
+    char* ws = nullptr;
+    bool split_ok = true;
+    const size_t need_partials = align256(partials_need(*p));
+    const size_t need_red = read_ab ? reduced_bytes(*p, p->an.redA) + reduced_bytes(*p, p->an.redB) : 0;
+    if (need_partials + need_red > 0) {
+        if (fixed_scratch) {
+            if (need_partials + need_red > (size_t)TCX_SCRATCH_BYTES || !e->handle.scratch) return TCX_ERR_SCRATCH_TOO_SMALL;
+            ws = (char*)e->handle.scratch;                   // every byte read is written first by this execution
+        } else {
+            std::lock_guard<std::mutex> lk(e->mu);
+            if (grow_workspace(e, need_partials + need_red) == TCX_SUCCESS) ws = (char*)e->workspace;
+            else if (need_red > 0) return TCX_ERR_ALLOC;     // a reduced operand has to live somewhere
+            else split_ok = false;                           // no memory for partial sums: run unsplit
+        }
+    }
+    // Sec. "Case 4": operands with isolated labels are summed over them first; the contraction
+    // reads the dense result.
+    if (read_ab && ws) {
+        char* at = ws + need_partials;
+        for (int which = 0; which < 2; ++which) {
+            const Reduction& r = which == 0 ? p->an.redA : p->an.redB;
+            if (!r.active) continue;
+            ReduceArgs ra{};
+            ra.src = which == 0 ? A : B;
+            ra.dst = at;
+            ra.nKeep = (int32_t)r.keepExt.size(); ra.nSum = (int32_t)r.sumExt.size();
+            ra.count = r.count; ra.sumCount = 1;
+            for (int i = 0; i < ra.nKeep; ++i) { ra.keepExt[i] = r.keepExt[i]; ra.keepSrc[i] = r.keepSrc[i]; }
+            for (int i = 0; i < ra.nSum; ++i) { ra.sumExt[i] = r.sumExt[i]; ra.sumSrc[i] = r.sumSrc[i]; ra.sumCount *= r.sumExt[i]; }
+            const int err = launch_reduce(p->an.dtype, p->an.precision, ra, (void*)e->stream);
+            if (err != 0) {
+                st.hip_error = err;
+                if (status) { Status* so = new (std::nothrow) Status(st); *status = so ? publish(so, MAGIC_STATUS) : 0; }
+                return TCX_ERR_LAUNCH;
+            }
+            (which == 0 ? A : B) = at;
+            at += reduced_bytes(*p, r);
+        }
+    }
     const bool tiled = p->an.path == TCX_PATH_GETT_MFMA && read_ab && p->dev_tables &&
                        (!gett_variant(p->an.dtype, p->variant).staged || (p->dev_narrow && p->narrow_variant == p->variant));
     const bool streamed = p->an.path == TCX_PATH_BANDWIDTH && read_ab && p->dev_stream;
@@ -892,16 +943,9 @@ tcx_error_t run_product(tcx_product_t product, tcx_executor_t executor, tcx_stat
         g.opA = p->an.opA; g.opB = p->an.opB; g.opC = p->an.opC;
         g.read_c = read_c;
         g.splitK = p->splitK;
-        if (const size_t need = workspace_need(*p)) {
-            if (fixed_scratch) {
-                if (need > (size_t)TCX_SCRATCH_BYTES || !e->handle.scratch) return TCX_ERR_SCRATCH_TOO_SMALL;
-                g.workspace = e->handle.scratch;             // fully written by the parts before the reduction reads it
-            } else {
-                // leased from the executor: executions on its stream run in order and may share it
-                std::lock_guard<std::mutex> lk(e->mu);
-                if (grow_workspace(e, need) == TCX_SUCCESS) g.workspace = e->workspace;
-                else g.splitK = 1;                           // no memory for partial sums: run unsplit
-            }
+        if (need_partials > 0) {
+            if (split_ok) g.workspace = ws;                  // fully written by the parts before the reduction kernel reads it
+            else g.splitK = 1;
         }
         g.lid_base = 0;
         // rounds pay off when a tile runs for milliseconds (hundreds of slabs) and there are several rounds

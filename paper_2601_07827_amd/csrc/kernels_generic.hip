@@ -96,7 +96,59 @@ __global__ __launch_bounds__(256) void generic_contract(GenericArgs g) {
     ((T*)g.D)[offD] = N_::narrow(d);
 }
 
+// Pre-reduction of an operand over its isolated labels (paper, Sec. "Case 4"): one thread per
+// element of the reduced operand, which is dense (the linear index is the offset), a loop over
+// the summed index space.  Sums are formed in the plan's arithmetic, stored in the storage type.
+template <class N_>
+__global__ __launch_bounds__(256) void reduce_operand(ReduceArgs g) {
+    using T = typename N_::stor;
+    const int64_t lin = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (lin >= g.count) return;
+    int64_t rem = lin, off = 0;
+    for (int i = 0; i < g.nKeep; ++i) {
+        const int64_t e = g.keepExt[i];
+        const int64_t q = rem / e;
+        off += (rem - q * e) * g.keepSrc[i];
+        rem = q;
+    }
+    const T* src = (const T*)g.src;
+    typename N_::acc_t acc = N_::zero();
+    int64_t idx[kMaxGenericModes];
+    for (int i = 0; i < g.nSum; ++i) idx[i] = 0;
+    for (int64_t k = 0; k < g.sumCount; ++k) {
+        acc = N_::add(acc, N_::load(src, off, TCX_OP_IDENTITY));
+        for (int i = 0; i < g.nSum; ++i) {
+            if (++idx[i] < g.sumExt[i]) { off += g.sumSrc[i]; break; }
+            off -= g.sumSrc[i] * (g.sumExt[i] - 1);
+            idx[i] = 0;
+        }
+    }
+    ((T*)g.dst)[lin] = N_::narrow(acc);
+}
+
 }  // namespace
+
+int launch_reduce(int dtype, int precision, const ReduceArgs& args, void* stream) {
+    const int64_t blocks = (args.count + 255) / 256;
+    if (blocks <= 0 || blocks > 0x7fffffff) return (int)hipErrorInvalidConfiguration;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 gr((unsigned)blocks), bl(256);
+    const bool wide = is_widened(dtype, precision);
+    switch (dtype) {
+        case TCX_F64: reduce_operand<RealNum<double, double>><<<gr, bl, 0, st>>>(args); break;
+        case TCX_F32:
+            if (wide) reduce_operand<RealNum<float, double>><<<gr, bl, 0, st>>>(args);
+            else reduce_operand<RealNum<float, float>><<<gr, bl, 0, st>>>(args);
+            break;
+        case TCX_C128: reduce_operand<ComplexNum<double, double>><<<gr, bl, 0, st>>>(args); break;
+        case TCX_C64:
+            if (wide) reduce_operand<ComplexNum<float, double>><<<gr, bl, 0, st>>>(args);
+            else reduce_operand<ComplexNum<float, float>><<<gr, bl, 0, st>>>(args);
+            break;
+        default: return (int)hipErrorInvalidValue;
+    }
+    return (int)hipGetLastError();
+}
 
 int launch_generic(int dtype, int precision, const GenericArgs& args, void* stream, int64_t* grid, int* block) {
     const int64_t blocks = (args.sizeD + 255) / 256;

@@ -30,6 +30,17 @@ struct TensorDesc {
     std::vector<int64_t> extent, stride;
 };
 
+// Sum over an operand's isolated labels (paper, Sec. "Case 4": labels in A only, or in B only,
+// are reduced inside that tensor before the product).  The reduced operand is written densely,
+// column-major over the kept modes in `keep` order, into workspace memory; the contraction then
+// reads it in place of the tensor.
+struct Reduction {
+    bool active = false;
+    std::vector<int64_t> keepExt, keepSrc;     // kept modes, fastest of the reduced operand first: extent, stride in the tensor
+    std::vector<int64_t> sumExt, sumSrc;       // summed modes: extent, stride in the tensor
+    int64_t count = 1;                         // elements of the reduced operand
+};
+
 // Result of validation + classification + merging + fusion + sorting.
 struct Analysis {
     int32_t dtype = 0;
@@ -42,6 +53,7 @@ struct Analysis {
     bool d_n_fastest = false;               // D's smallest |stride| over M and N modes is an N mode
     int32_t path = TCX_PATH_GENERIC;
     int32_t variant = 0;
+    Reduction redA, redB;                   // Case 4: the strides sA / sB above then address the reduced operand
 };
 
 // Host part of the planner (analyser.cpp).  Pure host code: no HIP calls.
@@ -130,7 +142,18 @@ struct GenericArgs {
     int32_t read_c, read_ab;
 };
 
+// Pre-reduction of an operand (Sec. "Case 4"): dst[lin] = sum over the summed modes of src.
+struct ReduceArgs {
+    const void* src;
+    void* dst;
+    int32_t nKeep, nSum;
+    int64_t keepExt[kMaxGenericModes], keepSrc[kMaxGenericModes];
+    int64_t sumExt[kMaxGenericModes], sumSrc[kMaxGenericModes];
+    int64_t count, sumCount;
+};
+
 // Launchers (defined in the .hip files).  `stream` is a hipStream_t.  Return a hipError_t.
+int launch_reduce(int dtype, int precision, const ReduceArgs& args, void* stream);
 int launch_generic(int dtype, int precision, const GenericArgs& args, void* stream, int64_t* grid, int* block);
 
 int gett_num_variants(int dtype);

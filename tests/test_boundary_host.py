@@ -119,8 +119,8 @@ def test_product_validation_errors(handle):
     assert _product_code(handle, A, B, al, al) == T.TCX_ERR_D_ALIASING                                # appendix test 28
     z = t("mn", strides=dict(m=0, n=1))
     assert _product_code(handle, A, B, z, z) == T.TCX_ERR_D_ALIASING
-    assert _product_code(handle, t("mkx"), B, D, D) == T.TCX_ERR_ISOLATED_INDEX                       # Case 4
-    assert _product_code(handle, A, B, t("mnx"), t("mnx")) == T.TCX_ERR_ISOLATED_INDEX                # Case 5
+    assert _product_code(handle, t("mkx"), B, D, D) == 0                                              # Case 4: x summed inside A
+    assert _product_code(handle, A, B, t("mnx"), t("mnx")) == 0                                       # Case 5: x broadcasts
     assert _product_code(handle, A, B, D, D, dtypes=(1, 0, 1, 1)) == T.TCX_ERR_DTYPE_MIX
     assert _product_code(handle, A, B, D, D, ops=(0, 0, 0, 1)) == T.TCX_ERR_UNSUPPORTED_OP            # opD must be identity
     assert _product_code(handle, A, B, D, D, ops=(5, 0, 0, 0)) == T.TCX_ERR_UNSUPPORTED_OP
@@ -140,8 +140,7 @@ def test_config3_literal_stride_reading_is_rejected_as_aliasing(handle):
 
 
 ORACLE_TO_TCX = {oracle.V_OK: 0, oracle.V_EXTENT_MISMATCH: T.TCX_ERR_EXTENT_MISMATCH,
-                 oracle.V_CD_MISMATCH: T.TCX_ERR_CD_MISMATCH, oracle.V_D_ALIASING: T.TCX_ERR_D_ALIASING,
-                 oracle.V_ISOLATED: T.TCX_ERR_ISOLATED_INDEX}
+                 oracle.V_CD_MISMATCH: T.TCX_ERR_CD_MISMATCH, oracle.V_D_ALIASING: T.TCX_ERR_D_ALIASING}
 
 
 def test_library_and_oracle_agree_on_validity(handle):
@@ -164,10 +163,10 @@ def test_library_and_oracle_agree_on_validity(handle):
             D[1][0] = D[1][1]
             C[1][0] = C[1][1]                                            # two modes of D share a stride
         elif kind == 4:
-            A[0].append(2); A[1].append(1000); A[2].append(999)          # label only in A
+            A[0].append(2); A[1].append(1000); A[2].append(999)          # label only in A: a reduction (Case 4), valid
         elif kind == 5:
             for t_ in (C, D):
-                t_[0].append(2); t_[1].append(5000); t_[2].append(998)   # label only in D
+                t_[0].append(2); t_[1].append(5000); t_[2].append(998)   # label only in D: a broadcast (Case 5), valid
         v = oracle.validate(tuple(A), tuple(B), tuple(C), tuple(D))
         code = _product_code(handle, A, B, C, D)
         assert code == ORACLE_TO_TCX[v], (i, kind, A, B, C, D, oracle.V_NAMES[v], code)
@@ -571,3 +570,27 @@ def test_plan_precision(handle):
             T.tcx_destroy_product(prod)
         for i in infos:
             T.tcx_destroy_tensor_info(i)
+
+
+def test_isolated_labels_are_planned_as_reductions_and_broadcasts(handle):
+    """Sec. "Case 4": a label in A only is summed inside A by a launch of its own into workspace
+    memory, and the plan then sees the dense reduced operand; Sec. "Case 5": a label in D only is a
+    free mode that neither operand moves along."""
+    ext = dict(m=30, n=20, k=16, x=5, y=3, z=4)
+    ids = dict(m=1, n=2, k=3, x=4, y=5, z=6)
+    t = lambda labels, **kw: W.tensor(labels, ext, **kw)
+    A, B, D = t("xmky"), t("kn"), t("mzn")
+    infos = [T.tcx_create_tensor_info(handle, T.TCX_F64, s.extents, s.strides) for s in (A, B, D)]
+    labs = [[ids[l] for l in s.labels] for s in (A, B, D)]
+    prod = T.tcx_create_product(handle, 0, infos[0], labs[0], 0, infos[1], labs[1], 0, infos[2], labs[2], 0, infos[2], labs[2])
+    assert T.tcx_product_get(prod, T.TCX_KEY_SIZE_K) == 16 and T.tcx_product_get(prod, T.TCX_KEY_SIZE_M) == 30 * 4
+    # A reduced over x and y is a dense 30 x 16 matrix: m keeps the smaller stride
+    assert sorted(T.tcx_product_get(prod, T.TCX_KEY_MODES_M)) == [(4, 0, 0, 30), (30, 1, 0, 1)]
+    assert T.tcx_product_get(prod, T.TCX_KEY_MODES_K) == [(16, 30, 1, 0)]
+    assert T.tcx_product_get(prod, T.TCX_KEY_WORKSPACE_BYTES) >= 30 * 16 * 8
+    launches = T.tcx_product_get(prod, T.TCX_KEY_LAUNCHES)
+    T.tcx_product_set(prod, T.TCX_KEY_FORCE_PATH, T.TCX_PATH_GENERIC)
+    assert T.tcx_product_get(prod, T.TCX_KEY_LAUNCHES) == 2 and launches >= 2
+    T.tcx_destroy_product(prod)
+    for i in infos:
+        T.tcx_destroy_tensor_info(i)

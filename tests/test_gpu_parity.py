@@ -442,6 +442,50 @@ def test_precision_f64_on_32_bit_tensors(dtype):
         assert np.array_equal(W.strided_view(got, q.D), W.strided_view(truth, q.D))
 
 
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64"])
+def test_isolated_labels(dtype):
+    """Secs. "Case 4" and "Case 5": labels in A only or in B only are summed inside that tensor by a
+    kernel of their own before the product, labels in D only repeat it.  Random label patterns with
+    such labels on every path, uniform inputs within tolerance and integer inputs bit for bit; the
+    paper's two examples (repeated labels on top)."""
+    from gpu_helpers import run_gpu, say
+    rng = np.random.default_rng(4242)
+    for i in range(24):
+        p = random_problem(rng, dtype, max_group=2, max_extent=5, allow_neg=(i % 3 == 0), name="iso%d_%s" % (i, dtype), isolated=True)
+        for dist, exact in (("uniform", False), ("ints", True)):
+            a, b, c = W.make_operands(p, dist)
+            truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+            for path, variant in ((GENERIC, None), (GETT, 2 if dtype not in COMPLEX else 1), (STREAM, None), (None, None)):
+                _check(p, a, b, c, path, variant, exact=exact, truth=truth, S=S)
+    ext = dict(a=13, b=24, g=7, d=35, e=3)
+    rep = lambda labels: _rep(labels, ext)
+    for name, la, lb, ld in (("case4", "bab", "bgdga", "da"), ("case5", "bab", "bgdga", "dae")):
+        p = W.Problem("%s_%s" % (name, dtype), dtype, rep(la), rep(lb), rep(ld), alpha=2.0, beta=-1.0, opA=int(dtype in COMPLEX),
+                      seed=W.BASE_SEED + 81)
+        a, b, c = W.make_operands(p, "ints")
+        truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+        for path in (None, GENERIC, GETT, STREAM):
+            say("%s path=%s" % (p.name, path))
+            try:
+                got = run_gpu(p, a, b, c, force_path=path)
+            except Exception as exc:
+                if path in (GETT, STREAM) and getattr(exc, "code", None) == REFUSED:
+                    continue
+                raise
+            assert np.array_equal(W.strided_view(got, p.D), W.strided_view(truth, p.D)), path
+
+
+def _rep(labels, ext):
+    """Column-major tensor whose label string may repeat a label (each position its own stride)."""
+    strides, run = [], 1
+    for l in labels:
+        strides.append(run)
+        run *= ext[l]
+    e = tuple(ext[l] for l in labels)
+    base, size = W.span_of(e, strides)
+    return W.TensorSpec(tuple(labels), e, tuple(strides), base, size)
+
+
 LOW_AI_LARGE = [W.config5(extent=4, nshared=1, nfree=7), W.config4(h=512, n=96, k=4),
                 W.hadamard(4, 64, permuted=True, beta=0.5), W.config5(extent=4, nshared=0, nfree=6)]
 

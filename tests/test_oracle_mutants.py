@@ -37,7 +37,7 @@ MUTANTS = [
     ("single_complex_modulus_is_squared_norm", "inline float modulus(std::complex<float> x) { return std::hypot(x.real(), x.imag()); }",
      "inline float modulus(std::complex<float> x) { return x.real() * x.real() + x.imag() * x.imag(); }"),
     ("real_modulus_keeps_sign", "inline long double modulus(long double x) { return fabsl(x); }", "inline long double modulus(long double x) { return x; }"),
-    ("normaliser_uses_only_A", "s += (long double)modulus(a) * (long double)modulus(b);", "s += (long double)modulus(a);"),
+    ("normaliser_uses_only_A", "if (S) s += ma * mb;", "if (S) s += ma;"),
     ("literal_mode_scales_C_by_alpha", "T running = mul(be, apply_op(C[off_D], opC));", "T running = mul(al, apply_op(C[off_D], opC));"),
     ("last_term_skipped", "for (int64_t k = 0; k < size_P; ++k) {", "for (int64_t k = 1; k < size_P; ++k) {"),
 ]
