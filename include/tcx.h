@@ -85,7 +85,7 @@ enum {
     TCX_ERR_EXTENT_MISMATCH = 6,     /* one label, two extents (Sec. Preliminaries; appendix test 26) */
     TCX_ERR_CD_MISMATCH = 7,         /* C is not described exactly like D (Note 5; appendix test 27) */
     TCX_ERR_D_ALIASING = 8,          /* two index tuples of D share an address (appendix test 28) */
-    TCX_ERR_ISOLATED_INDEX = 9,      /* (not returned: labels in one tensor only are reduced or broadcast, Secs. "Case 4", "Case 5") */
+    TCX_ERR_ISOLATED_INDEX = 9,      /* tcx_create_unary: A and B do not carry the same set of labels (contractions reduce or broadcast such labels, Secs. "Case 4", "Case 5") */
     TCX_ERR_DTYPE_MIX = 10,          /* the four tensors do not share one dtype */
     TCX_ERR_UNSUPPORTED_OP = 11,     /* op value unknown, or opD != identity */
     TCX_ERR_UNSUPPORTED_PRECISION = 12,
@@ -214,6 +214,30 @@ tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, 
 tcx_error_t tcx_execute_product_noalloc(tcx_product_t product, tcx_executor_t executor,
                                         const void* alpha, const void* A, const void* B,
                                         const void* beta, const void* C, void* D);
+
+/* ---- unary and binary operations (Sec. "Unary and Binary Operations") ----------------------
+ * C := alpha * opA(A) + beta * opB(B).  B and C carry the same labels and C is laid out like B
+ * (as C and D of a contraction: else TCX_ERR_CD_MISMATCH); opC must be the identity.  Labels of A
+ * that C lacks are summed inside A, labels of C that A lacks broadcast A's element (the paper's
+ * I_A and I_B of this operation).  The plan is a tcx_product_t (same keys, tcx_destroy_product)
+ * that only tcx_execute_binary accepts.  B may be the same pointer as C; beta == 0: B is never
+ * read and may be NULL.
+ * B := alpha * opA(A): the unary operation (scaling, copying between layouts, diagonals through
+ * repeated labels).  A and B carry the same set of labels (else TCX_ERR_ISOLATED_INDEX); opB must
+ * be the identity. */
+tcx_error_t tcx_create_binary(tcx_handle_t handle,
+                              tcx_op_t opA, tcx_tensor_info_t A, const int64_t* labelsA,
+                              tcx_op_t opB, tcx_tensor_info_t B, const int64_t* labelsB,
+                              tcx_op_t opC, tcx_tensor_info_t C, const int64_t* labelsC,
+                              tcx_prec_t precision, tcx_product_t* out);
+tcx_error_t tcx_execute_binary(tcx_product_t plan, tcx_executor_t executor, tcx_status_t* status,
+                               const void* alpha, const void* A, const void* beta, const void* B, void* C);
+tcx_error_t tcx_create_unary(tcx_handle_t handle,
+                             tcx_op_t opA, tcx_tensor_info_t A, const int64_t* labelsA,
+                             tcx_op_t opB, tcx_tensor_info_t B, const int64_t* labelsB,
+                             tcx_prec_t precision, tcx_product_t* out);
+tcx_error_t tcx_execute_unary(tcx_product_t plan, tcx_executor_t executor, tcx_status_t* status,
+                              const void* alpha, const void* A, void* B);
 
 /* ---- status object (Sec. "Status Objects") ------------------------------------------ */
 tcx_error_t tcx_status_get(tcx_status_t status, int32_t key, void* value, size_t* nbytes);

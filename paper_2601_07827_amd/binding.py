@@ -55,6 +55,7 @@ EXPORTS = [
     "tcx_status_get",
     "tcx_destroy_status", "tcx_check_success", "tcx_explain_error",
     "tcx_create_attr", "tcx_destroy_attr", "tcx_attr_set", "tcx_attr_get", "tcx_attr_clear", "tcx_probe_launch",
+    "tcx_create_binary", "tcx_execute_binary", "tcx_create_unary", "tcx_execute_unary",
 ]
 
 _h = ctypes.c_ssize_t            # intptr_t
@@ -77,6 +78,10 @@ _lib.tcx_product_get.argtypes = [_h, ctypes.c_int32, _vp, _szp]
 _lib.tcx_product_set.argtypes = [_h, ctypes.c_int32, _vp, ctypes.c_size_t]
 _lib.tcx_execute_product.argtypes = [_h, _h, _hp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.tcx_execute_product_noalloc.argtypes = [_h, _h, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.tcx_create_binary.argtypes = [_h] + [ctypes.c_int, _h, _i64p] * 3 + [ctypes.c_int, _hp]
+_lib.tcx_execute_binary.argtypes = [_h, _h, _hp, _vp, _vp, _vp, _vp, _vp]
+_lib.tcx_create_unary.argtypes = [_h] + [ctypes.c_int, _h, _i64p] * 2 + [ctypes.c_int, _hp]
+_lib.tcx_execute_unary.argtypes = [_h, _h, _hp, _vp, _vp, _vp]
 _lib.tcx_status_get.argtypes = [_h, ctypes.c_int32, _vp, _szp]
 _lib.tcx_destroy_status.argtypes = [_hp]
 _lib.tcx_create_attr.argtypes = [_h, _hp]
@@ -249,6 +254,34 @@ def tcx_execute_product_noalloc(product: int, executor: int, dtype: int, alpha, 
     _check(_lib.tcx_execute_product_noalloc(product, executor, ctypes.cast(ctypes.pointer(al), _vp), _vp(A), _vp(B),
                                             ctypes.cast(ctypes.pointer(be), _vp), _vp(C), _vp(D)),
            "tcx_execute_product_noalloc")
+
+
+def tcx_create_binary(handle: int, opA: int, A: int, labelsA, opB: int, B: int, labelsB, opC: int, C: int, labelsC,
+                      precision: int = TCX_PREC_DEFAULT) -> int:
+    """Plan of C := alpha opA(A) + beta opB(B)."""
+    p = _h(0)
+    _check(_lib.tcx_create_binary(handle, opA, A, _arr(labelsA), opB, B, _arr(labelsB), opC, C, _arr(labelsC), precision,
+                                  ctypes.byref(p)), "tcx_create_binary")
+    return p.value
+
+
+def tcx_execute_binary(plan: int, executor: int, dtype: int, alpha, A: int, beta, B: int, C: int) -> None:
+    al, be = _scalar(dtype, alpha), _scalar(dtype, beta)
+    _check(_lib.tcx_execute_binary(plan, executor, None, ctypes.cast(ctypes.pointer(al), _vp), _vp(A),
+                                   ctypes.cast(ctypes.pointer(be), _vp), _vp(B), _vp(C)), "tcx_execute_binary")
+
+
+def tcx_create_unary(handle: int, opA: int, A: int, labelsA, opB: int, B: int, labelsB, precision: int = TCX_PREC_DEFAULT) -> int:
+    """Plan of B := alpha opA(A)."""
+    p = _h(0)
+    _check(_lib.tcx_create_unary(handle, opA, A, _arr(labelsA), opB, B, _arr(labelsB), precision, ctypes.byref(p)),
+           "tcx_create_unary")
+    return p.value
+
+
+def tcx_execute_unary(plan: int, executor: int, dtype: int, alpha, A: int, B: int) -> None:
+    al = _scalar(dtype, alpha)
+    _check(_lib.tcx_execute_unary(plan, executor, None, ctypes.cast(ctypes.pointer(al), _vp), _vp(A), _vp(B)), "tcx_execute_unary")
 
 
 def tcx_status_get(status: int, key: int):

@@ -21,6 +21,11 @@
 // is asked for once, with that device current, when a handle is created on it, and kept.
 static __device__ __align__(256) unsigned char scratch[TCX_SCRATCH_BYTES];
 
+// The number one in 64-bit and in 32-bit (complex: 1 + 0i): the second operand of the contraction
+// that a unary or binary operation is planned as (C := alpha A + beta B  is  alpha A * 1 + beta B).
+static __device__ __align__(16) double one_in_64_bits[2] = {1.0, 0.0};
+static __device__ __align__(16) float one_in_32_bits[2] = {1.0f, 0.0f};
+
 namespace tcx {
 namespace {
 
@@ -31,6 +36,8 @@ struct Handle {
     bool has_device = false;
     int num_cu = 0;
     void* scratch = nullptr;   // this device's copy of the fixed scratch buffer (tcx_execute_product_noalloc)
+    const void* one64 = nullptr;   // ... of the constants 1 (unary and binary operations)
+    const void* one32 = nullptr;
 };
 struct Executor {
     Handle handle;
@@ -44,8 +51,10 @@ struct Executor {
 struct Info {
     TensorDesc desc;
 };
+enum { KIND_CONTRACTION = 0, KIND_BINARY = 1, KIND_UNARY = 2 };
 struct Product {
     Handle handle;
+    int kind = KIND_CONTRACTION;     // which execute call the plan belongs to
     Analysis an;
     int variant = 0;                 // index into the tiled kernel instantiations
     int splitK = 1;                  // parts the K slabs are divided into (tiled path)
@@ -82,6 +91,8 @@ int64_t round_size_of(const Product& p, const GettVariant& s) {
 constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mu;
 void* g_scratch_ptr[kMaxDevices] = {};
+void* g_one64_ptr[kMaxDevices] = {};
+void* g_one32_ptr[kMaxDevices] = {};
 bool g_scratch_asked[kMaxDevices] = {};
 
 // Address of `scratch` on `device`, which must be the current device.  nullptr if the runtime
@@ -96,6 +107,8 @@ void* scratch_on(int device) {
             ptr = nullptr;
         }
         g_scratch_ptr[device] = ptr;
+        if (hipGetSymbolAddress(&g_one64_ptr[device], HIP_SYMBOL(one_in_64_bits)) != hipSuccess) { (void)hipGetLastError(); g_one64_ptr[device] = nullptr; }
+        if (hipGetSymbolAddress(&g_one32_ptr[device], HIP_SYMBOL(one_in_32_bits)) != hipSuccess) { (void)hipGetLastError(); g_one32_ptr[device] = nullptr; }
         g_scratch_asked[device] = true;
     }
     return g_scratch_ptr[device];
@@ -569,6 +582,8 @@ tcx_error_t tcx_create_handle(tcx_handle_t* out) {
             h->has_device = true;
             h->num_cu = prop.multiProcessorCount;
             h->scratch = scratch_on(dev);
+            h->one64 = g_one64_ptr[dev];
+            h->one32 = g_one32_ptr[dev];
         }
     }
     (void)hipGetLastError();
@@ -685,6 +700,56 @@ tcx_error_t tcx_create_product(tcx_handle_t handle, tcx_op_t opA, tcx_tensor_inf
     if (err != TCX_SUCCESS) { delete p; return err; }
     *out = publish(p, MAGIC_PRODUCT);
     return TCX_SUCCESS;
+}
+
+// Sec. "Unary and Binary Operations": C := alpha opA(A) + beta opB(B) read as the contraction
+// alpha A * 1 + beta B with a rank-0 second operand, so labels of A that C lacks are summed
+// (Case 4) and labels of C that A lacks broadcast (Case 5) through the same analysis and kernels.
+tcx_error_t tcx_create_binary(tcx_handle_t handle, tcx_op_t opA, tcx_tensor_info_t A, const int64_t* labelsA, tcx_op_t opB,
+                              tcx_tensor_info_t B, const int64_t* labelsB, tcx_op_t opC, tcx_tensor_info_t C,
+                              const int64_t* labelsC, tcx_prec_t precision, tcx_product_t* out) {
+    if (!out) return TCX_ERR_NULL_ARG;
+    Handle* h = lookup<Handle>(handle, MAGIC_HANDLE);
+    Info* a = lookup<Info>(A, MAGIC_INFO);
+    Info* b = lookup<Info>(B, MAGIC_INFO);
+    Info* c = lookup<Info>(C, MAGIC_INFO);
+    if (!h || !a || !b || !c) return TCX_ERR_INVALID_HANDLE;
+    if ((!labelsA && !a->desc.extent.empty()) || (!labelsB && !b->desc.extent.empty()) || (!labelsC && !c->desc.extent.empty()))
+        return TCX_ERR_NULL_ARG;
+    Product* p = new (std::nothrow) Product;
+    if (!p) return TCX_ERR_ALLOC;
+    p->handle = *h;
+    p->kind = KIND_BINARY;
+    TensorDesc one;
+    one.dtype = a->desc.dtype;
+    tcx_error_t err = analyse(a->desc, labelsA, one, nullptr, b->desc, labelsB, c->desc, labelsC, (int)opA, TCX_OP_IDENTITY,
+                              (int)opB, (int)opC, (int)precision, &p->an);
+    if (err == TCX_SUCCESS) {
+        fill_generic(p->an, &p->generic);
+        p->analysed_path = p->an.path;
+        err = route(p);
+    }
+    if (err != TCX_SUCCESS) { delete p; return err; }
+    *out = publish(p, MAGIC_PRODUCT);
+    return TCX_SUCCESS;
+}
+
+// B := alpha opA(A): the binary operation with beta = 0; a unary operation has no distinct label
+// subsets (A and B carry the same set of labels; repeated labels address diagonals).
+tcx_error_t tcx_create_unary(tcx_handle_t handle, tcx_op_t opA, tcx_tensor_info_t A, const int64_t* labelsA, tcx_op_t opB,
+                             tcx_tensor_info_t B, const int64_t* labelsB, tcx_prec_t precision, tcx_product_t* out) {
+    if (!out) return TCX_ERR_NULL_ARG;
+    Info* a = lookup<Info>(A, MAGIC_INFO);
+    Info* b = lookup<Info>(B, MAGIC_INFO);
+    if (!a || !b) return TCX_ERR_INVALID_HANDLE;
+    if ((!labelsA && !a->desc.extent.empty()) || (!labelsB && !b->desc.extent.empty())) return TCX_ERR_NULL_ARG;
+    for (size_t i = 0; i < a->desc.extent.size(); ++i)
+        if (std::find(labelsB, labelsB + b->desc.extent.size(), labelsA[i]) == labelsB + b->desc.extent.size()) return TCX_ERR_ISOLATED_INDEX;
+    for (size_t i = 0; i < b->desc.extent.size(); ++i)
+        if (std::find(labelsA, labelsA + a->desc.extent.size(), labelsB[i]) == labelsA + a->desc.extent.size()) return TCX_ERR_ISOLATED_INDEX;
+    const tcx_error_t err = tcx_create_binary(handle, opA, A, labelsA, TCX_OP_IDENTITY, B, labelsB, opB, B, labelsB, precision, out);
+    if (err == TCX_SUCCESS) ((Product*)*out)->kind = KIND_UNARY;
+    return err;
 }
 
 tcx_error_t tcx_destroy_product(tcx_product_t* product) {
@@ -813,11 +878,13 @@ namespace {
 // Body of both execute calls.  fixed_scratch: partial sums go to the library's fixed per-device
 // buffer and nothing is allocated, neither on the device nor (no status object) on the host.
 tcx_error_t run_product(tcx_product_t product, tcx_executor_t executor, tcx_status_t* status, const void* alpha,
-                        const void* A, const void* B, const void* beta, const void* C, void* D, bool fixed_scratch) {
+                        const void* A, const void* B, const void* beta, const void* C, void* D, bool fixed_scratch,
+                        int kind = KIND_CONTRACTION) {
     Product* p = lookup<Product>(product, MAGIC_PRODUCT);
     Executor* e = lookup<Executor>(executor, MAGIC_EXEC);
-    if (!p || !e) return TCX_ERR_INVALID_HANDLE;
+    if (!p || !e || p->kind != kind) return TCX_ERR_INVALID_HANDLE;
     if (!alpha || !beta || !D) return TCX_ERR_NULL_ARG;
+    if (kind != KIND_CONTRACTION) B = real_bytes_of(p->an.dtype) == 4 ? e->handle.one32 : e->handle.one64;
     Scalars s{0, 0, 0, 0};
     switch (p->an.dtype) {
         case TCX_F32: s.alpha_re = *(const float*)alpha; s.beta_re = *(const float*)beta; break;
@@ -832,8 +899,9 @@ tcx_error_t run_product(tcx_product_t product, tcx_executor_t executor, tcx_stat
     }
     const bool read_ab = s.alpha_re != 0 || s.alpha_im != 0;
     const bool read_c = s.beta_re != 0 || s.beta_im != 0;
-    if ((read_ab && (!A || !B)) || (read_c && !C)) return TCX_ERR_NULL_ARG;
+    if ((read_ab && (!A || (!B && kind == KIND_CONTRACTION))) || (read_c && !C)) return TCX_ERR_NULL_ARG;
     if (!p->handle.has_device || !e->handle.has_device) return TCX_ERR_NO_DEVICE;
+    if (read_ab && !B) return TCX_ERR_LAUNCH;                 // the device constant 1 could not be located when the handle was made
 
     Status st;
     int hip_err = 0;
@@ -977,6 +1045,17 @@ extern "C" {
 tcx_error_t tcx_execute_product(tcx_product_t product, tcx_executor_t executor, tcx_status_t* status, const void* alpha,
                                 const void* A, const void* B, const void* beta, const void* C, void* D) {
     return run_product(product, executor, status, alpha, A, B, beta, C, D, false);
+}
+
+tcx_error_t tcx_execute_binary(tcx_product_t plan, tcx_executor_t executor, tcx_status_t* status, const void* alpha, const void* A,
+                               const void* beta, const void* B, void* C) {
+    return run_product(plan, executor, status, alpha, A, nullptr, beta, B, C, false, KIND_BINARY);
+}
+
+tcx_error_t tcx_execute_unary(tcx_product_t plan, tcx_executor_t executor, tcx_status_t* status, const void* alpha, const void* A,
+                              void* B) {
+    const double zero[2] = {0.0, 0.0};                       // beta = 0 in every dtype: B is never read
+    return run_product(plan, executor, status, alpha, A, nullptr, zero, nullptr, B, false, KIND_UNARY);
 }
 
 tcx_error_t tcx_execute_product_noalloc(tcx_product_t product, tcx_executor_t executor, const void* alpha, const void* A,

@@ -594,3 +594,43 @@ def test_isolated_labels_are_planned_as_reductions_and_broadcasts(handle):
     T.tcx_destroy_product(prod)
     for i in infos:
         T.tcx_destroy_tensor_info(i)
+
+
+def test_unary_and_binary_plans(handle):
+    """Sec. "Unary and Binary Operations": C := alpha A + beta B is planned as the contraction
+    alpha A * 1 + beta B (labels of A that C lacks are summed, labels of C that A lacks broadcast);
+    B := alpha A needs the same label set on both sides.  Each plan answers only to its own execute call."""
+    ext = dict(h=6, x=4, y=5)
+    ids = dict(h=1, x=2, y=3)
+    t = lambda labels, **kw: W.tensor(labels, ext, **kw)
+    info = lambda spec: T.tcx_create_tensor_info(handle, T.TCX_F64, spec.extents, spec.strides)
+    lab = lambda spec: [ids[l] for l in spec.labels]
+    A, B = t("hx"), t("yh")
+    ia, ib = info(A), info(B)
+    plan = T.tcx_create_binary(handle, 0, ia, lab(A), 0, ib, lab(B), 0, ib, lab(B))
+    assert T.tcx_product_get(plan, T.TCX_KEY_SIZE_K) == 1 and T.tcx_product_get(plan, T.TCX_KEY_SIZE_H) == 1
+    assert T.tcx_product_get(plan, T.TCX_KEY_SIZE_M) == 30              # h (carried by A) and y (broadcast)
+    assert T.tcx_product_get(plan, T.TCX_KEY_WORKSPACE_BYTES) >= 6 * 8   # A summed over x
+    ex = T.tcx_create_executor(handle, 0)
+    lib = T.raw()
+    one = ctypes.c_double(1.0)
+    args = (ctypes.byref(one), ctypes.c_void_p(16), ctypes.c_void_p(16), ctypes.byref(one), ctypes.c_void_p(16), ctypes.c_void_p(16))
+    assert lib.tcx_execute_product(plan, ex, None, *args) == T.TCX_ERR_INVALID_HANDLE      # a binary plan is not a contraction
+    assert lib.tcx_execute_unary(plan, ex, None, ctypes.byref(one), ctypes.c_void_p(16), ctypes.c_void_p(16)) == T.TCX_ERR_INVALID_HANDLE
+    # C laid out differently from B
+    ic = info(t("yh", memory_order="hy"))
+    assert _code(T.tcx_create_binary, handle, 0, ia, lab(A), 0, ib, lab(B), 0, ic, lab(B)) == T.TCX_ERR_CD_MISMATCH
+    assert _code(T.tcx_create_binary, handle, 0, ia, lab(A), 0, ib, lab(B), 1, ib, lab(B)) == T.TCX_ERR_UNSUPPORTED_OP
+    # unary: same label set on both sides
+    assert _code(T.tcx_create_unary, handle, 0, ia, lab(A), 0, ib, lab(B)) == T.TCX_ERR_ISOLATED_INDEX
+    it = info(t("xh"))
+    un = T.tcx_create_unary(handle, 0, ia, lab(A), 0, it, lab(t("xh")))
+    assert lib.tcx_execute_binary(un, ex, None, ctypes.byref(one), ctypes.c_void_p(16), ctypes.byref(one), ctypes.c_void_p(16),
+                                  ctypes.c_void_p(16)) == T.TCX_ERR_INVALID_HANDLE
+    if not T.tcx_handle_has_device(handle):
+        assert lib.tcx_execute_unary(un, ex, None, ctypes.byref(one), ctypes.c_void_p(16), ctypes.c_void_p(16)) == T.TCX_ERR_NO_DEVICE
+    for prod in (plan, un):
+        T.tcx_destroy_product(prod)
+    T.tcx_destroy_executor(ex)
+    for i in (ia, ib, ic, it):
+        T.tcx_destroy_tensor_info(i)

@@ -486,6 +486,83 @@ def _rep(labels, ext):
     return W.TensorSpec(tuple(labels), e, tuple(strides), base, size)
 
 
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64"])
+def test_unary_and_binary_operations(dtype):
+    """Sec. "Unary and Binary Operations": C := alpha op(A) + beta op(B) with a label of A that C
+    lacks (summed) and a label of C that A lacks (broadcast), in place and into a separate C, against
+    numpy's plain evaluation and against the oracle's contraction alpha A * 1 + beta B; B := alpha
+    op(A) as a scaled transposition between two layouts and as the diagonal of a repeated label.
+    Integer inputs: bit for bit."""
+    import torch
+    import paper_2601_07827_amd as T
+    from gpu_helpers import DT, say
+    ext = dict(h=37, g=11, x=6, y=9)
+    ids = dict(h=1, g=2, x=3, y=4)
+    cplx = dtype in COMPLEX
+    npdt = W.Problem("t", dtype, W.tensor("", ext), W.tensor("", ext), W.tensor("", ext)).np_dtype
+    A = W.tensor("xhg", ext, memory_order="gxh")
+    B = W.tensor("gyh", ext, strides=dict(g=2, y=25, h=-230))
+    a = W.fill(A, 5, W.TAG_A, npdt, "ints")
+    b = W.fill(B, 5, W.TAG_B, npdt, "ints")
+    alpha, beta = ((2.0 - 1.0j), -0.5) if cplx else (2.0, -0.5)
+    opA, opB = int(cplx), int(cplx)
+    va, vb = W.strided_view(a, A), W.strided_view(b, B)
+    fa = np.conj(va) if opA else va
+    fb = np.conj(vb) if opB else vb
+    expect = (alpha * fa.sum(axis=0).T[:, None, :] + beta * fb).astype(npdt)          # [g, y, h]: sum over x, broadcast over y
+    # the same through the oracle: contraction with a rank-0 second operand holding one
+    one = W.tensor("", ext)
+    p = W.Problem("binary_as_contraction", dtype, A, one, B, alpha=alpha, beta=beta, opA=opA, opC=opB)
+    truth, _ = run_oracle(p, a, np.ones(1, dtype=npdt), b, oracle.MODE_TRUTH)
+    assert np.array_equal(W.strided_view(truth, B), expect)
+    h = T.tcx_create_handle()
+    ex = T.tcx_create_executor(h, torch.cuda.current_stream().cuda_stream)
+    info = lambda spec: T.tcx_create_tensor_info(h, DT[dtype], spec.extents, spec.strides)
+    lab = lambda spec: [ids[l] for l in spec.labels]
+    ia, ib = info(A), info(B)
+    plan = T.tcx_create_binary(h, opA, ia, lab(A), opB, ib, lab(B), 0, ib, lab(B))
+    item = np.dtype(npdt).itemsize
+    dA, dB = torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda()
+    for in_place in (False, True):
+        say("binary %s in_place=%s" % (dtype, in_place))
+        dC = dB.clone() if in_place else torch.full_like(dB, -777.0)
+        src = dC if in_place else dB
+        T.tcx_execute_binary(plan, ex, DT[dtype], alpha, dA.data_ptr() + A.base * item, beta, src.data_ptr() + B.base * item,
+                             dC.data_ptr() + B.base * item)
+        torch.cuda.synchronize()
+        got = dC.cpu().numpy()
+        assert np.array_equal(W.strided_view(got, B), expect)
+        keep = b if in_place else np.full_like(b, -777.0)
+        mask = np.zeros(b.shape[0], dtype=bool)
+        W.strided_view(mask, B)[...] = True
+        assert np.array_equal(got[~mask], keep[~mask])                      # gaps of C untouched
+    T.tcx_destroy_product(plan)
+    # unary: B[h,g,x] := alpha op(A[x,h,g]) into another layout
+    Bt = W.tensor("hgx", ext, memory_order="xgh")
+    it = info(Bt)
+    un = T.tcx_create_unary(h, opA, ia, lab(A), 0, it, lab(Bt))
+    dT = torch.full((Bt.size,), -777.0, dtype=dA.dtype, device="cuda:0")
+    T.tcx_execute_unary(un, ex, DT[dtype], alpha, dA.data_ptr() + A.base * item, dT.data_ptr())
+    torch.cuda.synchronize()
+    assert np.array_equal(W.strided_view(dT.cpu().numpy(), Bt), (alpha * fa.transpose(1, 2, 0)).astype(npdt))
+    T.tcx_destroy_product(un)
+    # unary with a repeated label: the diagonal of a square matrix
+    sq = W.TensorSpec(("g", "g"), (11, 11), (1, 11), 0, 121)
+    vec = W.tensor("g", ext)
+    m = W.fill(sq, 6, W.TAG_A, npdt, "ints")
+    isq, iv = info(sq), info(vec)
+    un = T.tcx_create_unary(h, 0, isq, [2, 2], 0, iv, [2])
+    dM, dV = torch.from_numpy(m).cuda(), torch.zeros(11, dtype=dA.dtype, device="cuda:0")
+    T.tcx_execute_unary(un, ex, DT[dtype], 3.0, dM.data_ptr(), dV.data_ptr())
+    torch.cuda.synchronize()
+    assert np.array_equal(dV.cpu().numpy(), (3.0 * np.diagonal(m.reshape(11, 11))).astype(npdt))
+    T.tcx_destroy_product(un)
+    for i in (ia, ib, it, isq, iv):
+        T.tcx_destroy_tensor_info(i)
+    T.tcx_destroy_executor(ex)
+    T.tcx_destroy_handle(h)
+
+
 LOW_AI_LARGE = [W.config5(extent=4, nshared=1, nfree=7), W.config4(h=512, n=96, k=4),
                 W.hadamard(4, 64, permuted=True, beta=0.5), W.config5(extent=4, nshared=0, nfree=6)]
 
