@@ -331,20 +331,26 @@ def cpu_baseline(p: W.Problem):
             "sample": sample, "seconds": dt}
 
 
-def config2_sample_indices(p: W.Problem, tile_m: int, tile_n: int, rng):
-    """Rows and columns whose grid of samples reaches every launch round and, inside a round, the
-    stretch of tiles of every XCD: tiles are walked in bands of 8 tile rows (one round of 256
-    workgroups is one band of 8 x 32 tiles), and an XCD's stretch is 4 tile columns of a band.  One
-    row in every band and one column in every group of 4 tile columns, at seeded random positions,
-    plus tile-boundary rows and columns (+-1), first and last."""
+def config2_sample_indices(p: W.Problem, tile_m: int, tile_n: int, rng, rows=384, cols=192):
+    """Rows and columns whose grid of samples (rows x cols of them, 73 728 by default) reaches every
+    launch round and, inside a round, the stretch of tiles of every XCD: tiles are walked in bands
+    of 8 tile rows (one round of 256 workgroups is one band of 8 x 32 tiles), and an XCD's stretch is
+    4 tile columns of a band.  The last row / column of every tile and the first of the next (every
+    tile boundary), the first and last two of the tensor, one seeded random row in every band and
+    column in every group of 4 tile columns, and seeded random ones up to the requested count."""
     _, M, N, _ = p.sizes()
     band, group = 8 * tile_m, 4 * tile_n
-    m_idx = [int(lo + rng.integers(0, min(band, M - lo))) for lo in range(0, M, band)]
-    n_idx = [int(lo + rng.integers(0, min(group, N - lo))) for lo in range(0, N, group)]
-    m_idx += [0, 1, tile_m - 1, tile_m, tile_m + 1, M - tile_m - 1, M - tile_m, M - 1] + list(rng.integers(0, M, 6))
-    n_idx += [0, 1, tile_n - 1, tile_n, tile_n + 1, N - tile_n - 1, N - tile_n, N - 1]
-    keep = lambda v, hi: np.unique(np.clip(np.asarray(v, dtype=np.int64), 0, hi - 1))
-    return keep(m_idx, M), keep(n_idx, N)
+
+    def pick(extent, tile, stretch, want):
+        idx = [0, 1, extent - 2, extent - 1]
+        for edge in range(tile, extent, tile):
+            idx += [edge - 1, edge]
+        idx += [int(lo + rng.integers(0, min(stretch, extent - lo))) for lo in range(0, extent, stretch)]
+        idx = np.unique(np.clip(np.asarray(idx, dtype=np.int64), 0, extent - 1))
+        if len(idx) < want:
+            idx = np.unique(np.concatenate([idx, rng.integers(0, extent, want - len(idx))]))
+        return idx
+    return pick(M, tile_m, band, rows), pick(N, tile_n, group, cols)
 
 
 def parity_after_run(p: W.Problem, dD, steps_done: int, torch, dist: str = "uniform", tile=(256, 128)):

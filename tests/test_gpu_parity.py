@@ -611,9 +611,10 @@ def test_split_k_is_deterministic():
 @pytest.mark.parametrize("dist", ["uniform", "ints"])
 def test_config2_full_size_sampled(dist):
     """Configuration 2 at its full size (10.9 GB V, generated on the device by the torch twin of
-    the counter-based generator), in the launch configuration bench.py times.  512 sampled
-    outputs -- tile-boundary rows and columns plus random ones -- each a full 36864-term sum
-    evaluated by the oracle.  Integer-valued inputs must match bit for bit."""
+    the counter-based generator), in the launch configuration bench.py times.  More than 65 536
+    sampled outputs -- both sides of every tile boundary, every launch round and XCD stretch, plus
+    random ones -- each a full 36864-term sum evaluated by the oracle.  Integer-valued inputs must
+    match bit for bit."""
     import torch
     import bench
     from gpu_helpers import GpuProduct, say
@@ -638,10 +639,71 @@ def test_config2_full_size_sampled(dist):
         res = bench.parity_after_run(p, dD, 1, torch, dist)
     finally:
         gp.close()
-    assert res["samples"] >= 400
+    assert res["samples"] >= 65536
     assert res["ok"], res
     if dist == "ints":
         assert res["bit_exact"], res
+
+
+def test_config2_full_size_freivalds_probes():
+    """Every element of configuration 2's 1.5e8 outputs at once: for eight seeded random vector
+    pairs (x over the rows, y over the columns of D as a 36864 x 4096 matrix)
+        x^T D y  =  alpha sum_k (x^T V)_k (T y)_k  +  beta x^T D0 y,
+    the right-hand side evaluated by the oracle (long-double sums; V, T and D0 come from the
+    counter-based generator's device twin, copied to the host slab by slab).  A single element that
+    is off by its own magnitude moves the left-hand side by more than the gate, 1e-12 of
+    sum_k |(x^T V)_k| |(T y)_k| + |x|^T |D0 y| (a lower bound of the error measure's normaliser)."""
+    import torch
+    import bench
+    from gpu_helpers import GpuProduct, say
+    p = W.config2()
+    _, M, N, K = p.sizes()
+    P = 8
+    say("%s full size, %d Freivalds probes" % (p.name, P))
+    dA, dB, dD, _ = bench.device_operands(p, torch)
+    X = W.uniform_pm1(p.seed, 40, np.arange(P * M, dtype=np.uint64), np.float64)         # [p, m], p fastest
+    Y = W.uniform_pm1(p.seed, 41, np.arange(N * P, dtype=np.uint64), np.float64)         # [n, p], n fastest
+    e = dict(p=P, m=M, n=N, k=K)
+
+    def times_Y(buf):
+        """[M or K, N] (first index fastest) times Y: rows x P."""
+        rows = buf.shape[0] // N
+        ee = dict(r=rows, n=N, p=P)
+        q = W.Problem("timesY", "f64", W.tensor("rn", ee), W.tensor("np", ee), W.tensor("rp", ee), alpha=1.0, beta=0.0)
+        out, _ = run_oracle(q, buf, Y, np.zeros(rows * P))
+        return out.reshape((rows, P), order="F")
+
+    d0 = dD.cpu().numpy()
+    Z0 = times_Y(d0)                                                   # D0 y
+    del d0
+    Wm = times_Y(dB.cpu().numpy())                                     # T y: [k, p]
+    U = np.empty((P, K))                                               # x^T V: [p, k]
+    kc = 2048
+    for k0 in range(0, K, kc):
+        slab = dA[k0 * M:(k0 + kc) * M].cpu().numpy()                  # V[:, k0 : k0 + kc], rows fastest
+        ee = dict(p=P, m=M, k=kc)
+        q = W.Problem("xV", "f64", W.tensor("pm", ee), W.tensor("mk", ee), W.tensor("pk", ee), alpha=1.0, beta=0.0)
+        out, _ = run_oracle(q, X, slab, np.zeros(P * kc))
+        U[:, k0:k0 + kc] = out.reshape((P, kc), order="F")
+        say("  x^T V: slab %d of %d" % (k0 // kc + 1, K // kc))
+    gp = GpuProduct(p)
+    try:
+        gp.execute(dA, dB, dD, dD)
+        torch.cuda.synchronize()
+    finally:
+        gp.close()
+    Z1 = times_Y(dD.cpu().numpy())                                     # D y
+    ld = np.longdouble
+    Xm = X.reshape((P, M), order="F").astype(ld)
+    for j in range(P):
+        lhs = np.sum(Xm[j] * Z1[:, j].astype(ld))
+        ab = np.sum(U[j].astype(ld) * Wm[:, j].astype(ld))
+        c0 = np.sum(Xm[j] * Z0[:, j].astype(ld))
+        rhs = ld(p.alpha) * ab + ld(p.beta) * c0
+        gate = 1e-12 * float(np.sum(np.abs(U[j]) * np.abs(Wm[:, j])) + np.sum(np.abs(Xm[j]) * np.abs(Z0[:, j])))
+        say("  probe %d: lhs %.6e rhs %.6e |diff| %.3e gate %.3e" % (j, float(lhs), float(rhs), abs(float(lhs - rhs)), gate))
+        assert abs(float(lhs - rhs)) <= gate
+        assert gate < 1.0                                              # a single element off by its own size (tens) would show
 
 
 @pytest.mark.parametrize("dist", ["uniform", "ints"])

@@ -77,7 +77,10 @@ def test_config2_samples_reach_every_launch_round_and_xcd_stretch():
     tiles_m, tiles_n = M // tm, N // tn
     assert (tiles_m, tiles_n) == (144, 32)
     m_idx, n_idx = bench.config2_sample_indices(p, tm, tn, np.random.default_rng(p.seed))
-    assert len(m_idx) * len(n_idx) >= 400
+    assert len(m_idx) * len(n_idx) >= 65536
+    # both sides of every tile boundary
+    assert all({e - 1, e} <= set(int(v) for v in m_idx) for e in range(tm, M, tm))
+    assert all({e - 1, e} <= set(int(v) for v in n_idx) for e in range(tn, N, tn))
     seen = set()
     for m in m_idx:
         for n in n_idx:
