@@ -57,7 +57,9 @@ def make_problem(name: str) -> W.Problem:
              # supplementary HBM-bound shapes
              "s1": lambda: W.config5(extent=4, nshared=1, nfree=7), "s2": lambda: W.config5(extent=4, nshared=0, nfree=7),
              "s3": lambda: W.hadamard(4, 128), "s3p": lambda: W.hadamard(4, 128, permuted=True),
-             "s3b": lambda: W.hadamard(4, 128, beta=0.5), "s4": lambda: W.config4(h=512, n=96, k=4)}
+             "s3b": lambda: W.hadamard(4, 128, beta=0.5), "s4": lambda: W.config4(h=512, n=96, k=4),
+             # s3p with 128 bytes added to every tensor's slowest stride (diagnostic: not all strides powers of two)
+             "s3pp": lambda: W.hadamard(4, 128, permuted=True, pad_slowest=16)}
     return table[name]()
 
 
@@ -228,7 +230,7 @@ def measured_traffic(desc):
         table = json.load(open(TRAFFIC_FILE))
     except (OSError, ValueError):
         return None
-    row = table.get(desc["workload"])
+    row = table.get(desc.get("alias", desc["workload"]))
     if not row or [row.get("path"), row.get("variant"), row.get("split_k")] != [desc["path"], desc["variant"], desc["split_k"]]:
         return None
     return row["fetch_bytes_per_step"] + row["write_bytes_per_step"]
@@ -405,7 +407,7 @@ def measure(name, T, h, ex, torch, stream, want_baseline=True, path=None, varian
     p = make_problem(name)
     ops = Operands(p, torch)
     plan = Plan(T, h, ex, p, path, variant, split_k)
-    desc = plan.describe()
+    desc = dict(plan.describe(), alias=name)
     warm_ptrs = ops.pointers()
     plan.run(warm_ptrs)
     torch.cuda.synchronize()
@@ -419,6 +421,9 @@ def measure(name, T, h, ex, torch, stream, want_baseline=True, path=None, varian
     est_ms = max(e0.elapsed_time(e1) / 3, 1e-3)
     launches = int(min(400, max(10, 20.0 / est_ms)))
     warm_us, warm_min = region_us(torch, stream, lambda: plan.run(warm_ptrs), launches)
+    # the same steps with an event between every two: nothing of one step's launch overlaps the
+    # end of the step before it, so this is the time of a step issued alone
+    _, apart, _ = timed_region(torch, stream, lambda: plan.run(warm_ptrs), min(launches, 100))
     torch.cuda.synchronize()
     # parity of the buffer the timed steps wrote
     if ops.host is not None:
@@ -450,7 +455,8 @@ def measure(name, T, h, ex, torch, stream, want_baseline=True, path=None, varian
     roof = roofline_of(p, warm_us * 1e-6)
     roof["frac_cold"] = roofline_of(p, cold_us * 1e-6)["frac"]
     roof["traffic"] = measured_traffic(desc)
-    out = {"workload": name, "dtype": p.dtype, "config": desc, "warm_us": warm_us, "warm_us_min": warm_min, "cold_us": cold_us,
+    out = {"workload": name, "dtype": p.dtype, "config": desc, "warm_us": warm_us, "warm_us_min": warm_min,
+           "warm_us_apart": float(np.median(apart)) * 1e3, "cold_us": cold_us,
            "launches_per_region": launches, "buffers_cold": cold_note, "roofline": roof, "parity_of_timed_output": parity}
     if base is not None:
         out["cpu_baseline"] = base
@@ -489,11 +495,11 @@ def pmc_summary(args):
         table = json.load(open(TRAFFIC_FILE))
     except (OSError, ValueError):
         table = {}
-    table[desc["workload"]] = row
+    table[desc.get("alias", desc["workload"])] = row
     with open(TRAFFIC_FILE, "w") as f:
         json.dump(table, f, indent=1, sort_keys=True)
         f.write("\n")
-    print(json.dumps({desc["workload"]: row}))
+    print(json.dumps({desc.get("alias", desc["workload"]): row}))
 
 
 def main():
@@ -574,7 +580,7 @@ def main():
     flops = p.real_flops()
     value = flops / (ms_per_step * 1e-3) / 1e9
 
-    cfg = plan.describe()
+    cfg = dict(plan.describe(), alias=head)
     roofline = roofline_of(p, region_ms / args.steps * 1e-3)
     # A step may be several launches of the dominant kernel (a long-tile product is enqueued round
     # by round); the per-launch figures are the step's divided by that count.

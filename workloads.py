@@ -342,16 +342,27 @@ def config5(extent: int = 4, nshared: int = 5, nfree: int = 5, perm_seed: Option
                    alpha=1.0, beta=0.0, seed=seed, dist="normal")
 
 
-def hadamard(nmodes: int = 4, extent: int = 128, permuted: bool = False, dtype: str = "f64", beta: float = 0.0) -> Problem:
+def hadamard(nmodes: int = 4, extent: int = 128, permuted: bool = False, dtype: str = "f64", beta: float = 0.0,
+             pad_slowest: int = 0) -> Problem:
     """Pure Hadamard product D[h..] = A[h..] * B[h..] (+ beta C): every label in all three tensors.
-    `permuted`: A, B and D each store the modes in a different order."""
+    `permuted`: A, B and D each store the modes in a different order.  `pad_slowest`: elements added
+    to the stride of each tensor's slowest mode (a layout whose strides are not all powers of two
+    when the extent is one)."""
     labs = ["h%d" % i for i in range(nmodes)]
     e = dict.fromkeys(labs, extent)
+
+    def laid_out(order):
+        st, run = {}, 1
+        for i, l in enumerate(order):
+            st[l] = run + (pad_slowest if i == nmodes - 1 and nmodes > 1 else 0)
+            run *= extent
+        return tensor(labs, e, strides=st)
     if permuted:
-        A, B, D = tensor(labs, e, memory_order=labs[1:] + labs[:1]), tensor(labs, e, memory_order=labs[::-1]), tensor(labs, e)
+        A, B, D = laid_out(labs[1:] + labs[:1]), laid_out(labs[::-1]), laid_out(labs)
     else:
-        A, B, D = tensor(labs, e), tensor(labs, e), tensor(labs, e)
-    return Problem("hadamard_%s_%dx%d%s" % (dtype, nmodes, extent, "_perm" if permuted else ""), dtype, A, B, D,
+        A, B, D = laid_out(labs), laid_out(labs), laid_out(labs)
+    return Problem("hadamard_%s_%dx%d%s%s" % (dtype, nmodes, extent, "_perm" if permuted else "",
+                                              "_pad%d" % pad_slowest if pad_slowest else ""), dtype, A, B, D,
                    alpha=1.0, beta=beta, seed=BASE_SEED + 13)
 
 
