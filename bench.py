@@ -322,7 +322,7 @@ def sampled_parity_and_baseline(p: W.Problem, ops: Operands, torch, nsamples: in
 def cpu_baseline(p: W.Problem):
     """Configuration 2: the oracle's storage-precision loop nest on a bounded slab."""
     oracle, run_oracle, _ = _oracle()
-    sm, sn = 4096, 192
+    sm, sn = 1024, 192           # about 20 s of the oracle on 16 host threads
     sub, a, b, c = W.config2_sample(p, np.arange(sm), np.arange(sn))
     sample = "rows m<%d of V, columns n<%d of T, all %d contracted terms (%.2e of %.2e flop)" % (
         sm, sn, p.sizes()[3], sub.real_flops(), p.real_flops())

@@ -608,6 +608,38 @@ def test_split_k_is_deterministic():
     assert np.array_equal(r1, r2)
 
 
+def test_one_split_k_product_on_two_executors_at_once():
+    """The partial sums of a split-K plan live in the executor's workspace, not in the plan: one
+    product is executed on two executors (two streams of default priority) whose launches
+    interleave, each into its own D, many times over; both results carry the oracle's bits
+    (integer inputs), also in the iterations where the two streams ran side by side."""
+    import torch
+    import paper_2601_07827_amd as T
+    from gpu_helpers import GpuProduct, say
+    p = W.config1()
+    a, b, c = W.make_operands(p, "ints")
+    truth, _ = run_oracle(p, a, b, c, oracle.MODE_TRUTH)
+    gp = GpuProduct(p, force_path=GETT, variant=3, split_k=6)
+    assert gp.get(T.TCX_KEY_WORKSPACE_BYTES) > 0
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    exs = [T.tcx_create_executor(gp.h, s.cuda_stream) for s in streams]
+    item = a.itemsize
+    dA, dB, dC = (torch.from_numpy(x).cuda() for x in (a, b, c))
+    dD = [torch.zeros_like(dC), torch.zeros_like(dC)]
+    torch.cuda.synchronize()
+    say("%s on two executors, 40 interleaved executions each" % p.name)
+    for it in range(40):
+        for ex, d in zip(exs, dD):
+            T.tcx_execute_product(gp.prod, ex, gp.dtype, p.alpha, dA.data_ptr() + p.A.base * item, dB.data_ptr() + p.B.base * item,
+                                  p.beta, dC.data_ptr() + p.D.base * item, d.data_ptr() + p.D.base * item)
+    torch.cuda.synchronize()
+    for d in dD:
+        assert np.array_equal(W.strided_view(d.cpu().numpy(), p.D), W.strided_view(truth, p.D))
+    for ex in exs:
+        T.tcx_destroy_executor(ex)
+    gp.close()
+
+
 @pytest.mark.parametrize("dist", ["uniform", "ints"])
 def test_config2_full_size_sampled(dist):
     """Configuration 2 at its full size (10.9 GB V, generated on the device by the torch twin of
