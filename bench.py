@@ -612,7 +612,7 @@ def main():
             qptr = qo.pointers()
             for _ in range(3):
                 qp.run(qptr)
-            times.append(region_us(torch, stream, lambda: qp.run(qptr), 50)[0])
+            times.append(region_us(torch, stream, lambda: qp.run(qptr), 400)[0])      # as many steps per region as `configs` uses
             qp.close()
         cfg["perm_seed_us"] = {"min": float(np.min(times)), "median": float(np.median(times)), "max": float(np.max(times)),
                                "n": len(times)}

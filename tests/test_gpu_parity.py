@@ -616,7 +616,8 @@ def test_one_split_k_product_on_two_executors_at_once():
     import torch
     import paper_2601_07827_amd as T
     from gpu_helpers import GpuProduct, say
-    p = W.config1()
+    import dataclasses
+    p = dataclasses.replace(W.config1(), alpha=2.0, beta=-1.0)          # integer scalars: every order of the sums gives the same bits
     a, b, c = W.make_operands(p, "ints")
     truth, _ = run_oracle(p, a, b, c, oracle.MODE_TRUTH)
     gp = GpuProduct(p, force_path=GETT, variant=3, split_k=6)
