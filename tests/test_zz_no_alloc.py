@@ -1,5 +1,6 @@
 """tcx_execute_product_noalloc: the execute call for callers that cannot allocate (code under graph
-capture, serving loops).  Its split-K partial sums go to the library's fixed per-device buffer.
+capture, serving loops).  Its split-K partial sums, and operands reduced over labels of their own, go
+to the library's fixed per-device buffer.
 Checked against tcx_execute_product on the same plan and inputs, bit for bit (same kernels, same
 fixed summation order), on two calls in a row, the second with a smaller input, and against the
 oracle; a plan that needs more than the fixed buffer is refused and touches nothing."""
@@ -62,6 +63,23 @@ def test_no_alloc_entry_point_without_scratch_use():
         assert need == 0
         assert np.array_equal(d_ref, d_new)
         assert free1 == free0
+
+
+def test_no_alloc_entry_point_with_an_operand_reduced_over_its_own_label():
+    """A label that only A carries (Sec. "Case 4") is summed by a kernel of its own into scratch
+    memory ahead of the contraction: the fixed buffer holds that reduced operand, next to the
+    partial sums of a split K."""
+    import paper_2601_07827_amd as T
+    e = dict(m=70, n=50, k=96, x=5)
+    p = W.Problem("isolated_in_A_noalloc", "f64", W.tensor("mxk", e), W.tensor("kn", e), W.tensor("mn", e),
+                  alpha=0.75, beta=-0.5, seed=W.BASE_SEED + 91)
+    for variant, split_k in ((3, 1), (3, 3)):
+        a, b, c, d_ref, d_new, free0, free1, need = _both_entry_points(p, variant, split_k)
+        assert need >= 70 * 96 * 8 and need <= T.TCX_SCRATCH_BYTES
+        assert np.array_equal(d_ref, d_new)
+        assert free1 == free0
+        truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+        assert normalised_error(p, d_new, truth, S, c) <= TOLERANCE[p.dtype]
 
 
 def test_no_alloc_entry_point_refuses_what_does_not_fit():
