@@ -177,7 +177,8 @@ enum {
     TCX_KEY_DEVICE = 30,       /* handle, executor (read-only): HIP device ordinal the object is bound to, -1 if none */
     TCX_KEY_NUM_CU = 31,       /* handle (read-only): compute units of the bound device */
     TCX_KEY_STREAM = 32,       /* executor: the hipStream_t as an integer; settable (the caller keeps the new stream alive) */
-    TCX_KEY_PRECISION = 33     /* product (read-only): the tcx_prec_t the plan computes in */
+    TCX_KEY_PRECISION = 33,    /* product (read-only): the tcx_prec_t the plan computes in */
+    TCX_KEY_PACED_LOADS = 34   /* product (read-only): 1 if the streaming plan issues a tile's loads a few at a time because the cache lines a tile reads from an operand agree in the address bits that select the L2 channel and set (all strides inside the tile multiples of 128 KB) */
 };
 typedef enum {
     TCX_PATH_GENERIC = 0,      /* one thread per element of D, loops over the contracted index space */

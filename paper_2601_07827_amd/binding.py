@@ -42,7 +42,7 @@ TCX_PATH_GENERIC, TCX_PATH_GETT_MFMA, TCX_PATH_BANDWIDTH = 0, 1, 2
  TCX_KEY_A_K_FASTEST, TCX_KEY_B_K_FASTEST, TCX_KEY_D_N_FASTEST, TCX_KEY_VARIANT, TCX_KEY_HIP_ERROR, TCX_KEY_MODES_M,
  TCX_KEY_MODES_N, TCX_KEY_MODES_K, TCX_KEY_MODES_H, TCX_KEY_FORCE_PATH, TCX_KEY_SPLIT_K, TCX_KEY_LAUNCHES,
  TCX_KEY_GATHER_WIDTH, TCX_KEY_TABLE_ENTRIES, TCX_KEY_WORKSPACE_BYTES, TCX_KEY_DEVICE, TCX_KEY_NUM_CU,
- TCX_KEY_STREAM, TCX_KEY_PRECISION) = range(1, 34)
+ TCX_KEY_STREAM, TCX_KEY_PRECISION, TCX_KEY_PACED_LOADS) = range(1, 35)
 TCX_MAX_MODES = 32
 TCX_SCRATCH_BYTES = 32 * 1024 * 1024
 TCX_PROBE_MFMA_F64, TCX_PROBE_MFMA_F32, TCX_PROBE_STORE, TCX_PROBE_COPY = 0, 1, 2, 3

@@ -791,6 +791,7 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
         case TCX_KEY_B_K_FASTEST: return put_i64(an.b_k_fastest, value, nbytes);
         case TCX_KEY_D_N_FASTEST: return put_i64(an.d_n_fastest, value, nbytes);
         case TCX_KEY_SPLIT_K: return put_i64(tiled ? p->splitK : 1, value, nbytes);
+        case TCX_KEY_PACED_LOADS: return put_i64(an.path == TCX_PATH_BANDWIDTH && p->stream.paced ? 1 : 0, value, nbytes);
         case TCX_KEY_LAUNCHES: {
             const int64_t reductions = (an.redA.active ? 1 : 0) + (an.redB.active ? 1 : 0);      // Case 4 pre-reductions
             if (!tiled) return put_i64(1 + reductions, value, nbytes);
@@ -969,6 +970,7 @@ tcx_error_t run_product(tcx_product_t product, tcx_executor_t executor, tcx_stat
         g.regA = sp.regA; g.regB = sp.regB; g.rowStepA = sp.rowStepA; g.rowStepB = sp.rowStepB;
         for (int i = 0; i < kStreamRegBlock; ++i) { g.dRegA[i] = sp.dRegA[i]; g.dRegB[i] = sp.dRegB[i]; }
         g.split_extent = sp.split_extent; g.num_tiles = sp.num_tiles; g.outer_lo = sp.outer_lo;
+        g.paced = sp.paced ? 1 : 0;
         g.tabLo = (const int64_t*)(p->dev_stream + p->stream_off[4]);
         g.tabHi = (const int64_t*)(p->dev_stream + p->stream_off[5]);
         g.s = s;

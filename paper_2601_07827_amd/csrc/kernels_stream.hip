@@ -95,7 +95,11 @@ template <> struct SNum<float2> {
 // Every tile has the same shape, so a thread's share of the lookup tables (which elements it
 // stages, which outputs it forms) is the same for every tile: it is read once into registers
 // before the tile loop.  Inside the loop a thread issues all its global loads back to back.
-template <class T, int KC>
+//
+// PACED: a plan whose operand lines collide in the L2 (stream_plan.cpp) issues a tile's loads in
+// pairs (one of A, one of B) and lets at most one older pair stay in flight behind each new one,
+// instead of sending all of a tile's misses to one L2 set at once.
+template <class T, int KC, bool PACED>
 __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs g) {
     using N_ = SNum<T>;
     constexpr int PER = kStreamPerThread;
@@ -135,12 +139,23 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs g) {
     auto fetch = [&](const Where& w) {       // global loads of a tile's operands (and its C), all in flight together
         const T* A = (const T*)g.A + w.a;
         const T* B = (const T*)g.B + w.b;
+        if constexpr (PACED) {
 #pragma unroll
-        for (int i = 0; i < PER; ++i)
-            if ((packA[i] >> 16) < w.digits) va[i] = N_::ld(A, srcA[i], g.opA);
+            for (int i = 0; i < PER; ++i) {
+                if ((packA[i] >> 16) < w.digits) va[i] = N_::ld(A, srcA[i], g.opA);
+                if ((packB[i] >> 16) < w.digits) vb[i] = N_::ld(B, srcB[i], g.opB);
+                // in-order return: "at most two outstanding" = the pair before this one has arrived
+                // (earlier stores of D count too, which only makes the wait longer)
+                asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+            }
+        } else {
 #pragma unroll
-        for (int i = 0; i < PER; ++i)
-            if ((packB[i] >> 16) < w.digits) vb[i] = N_::ld(B, srcB[i], g.opB);
+            for (int i = 0; i < PER; ++i)
+                if ((packA[i] >> 16) < w.digits) va[i] = N_::ld(A, srcA[i], g.opA);
+#pragma unroll
+            for (int i = 0; i < PER; ++i)
+                if ((packB[i] >> 16) < w.digits) vb[i] = N_::ld(B, srcB[i], g.opB);
+        }
         if (g.read_c) {
             const T* C = (const T*)g.C + w.d;
             const int valid = g.inner * (int)w.digits;
@@ -410,13 +425,18 @@ hipError_t launch_k(bool blocked, bool direct, const StreamArgs& a, size_t lds, 
         }
         return hipGetLastError();
     }
-    switch (a.K) {
-        case 1: stream_kernel<T, 1><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
-        case 2: stream_kernel<T, 2><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
-        case 4: stream_kernel<T, 4><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
-        case 8: stream_kernel<T, 8><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
-        default: stream_kernel<T, 0><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
-    }
+    auto flat = [&](auto PACED_) {
+        constexpr bool PACED = decltype(PACED_)::value;
+        switch (a.K) {
+            case 1: stream_kernel<T, 1, PACED><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
+            case 2: stream_kernel<T, 2, PACED><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
+            case 4: stream_kernel<T, 4, PACED><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
+            case 8: stream_kernel<T, 8, PACED><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
+            default: stream_kernel<T, 0, PACED><<<dim3(blocks), dim3(kStreamThreads), lds, st>>>(a); break;
+        }
+    };
+    if (a.paced) flat(std::true_type{});
+    else flat(std::false_type{});
     return hipGetLastError();
 }
 

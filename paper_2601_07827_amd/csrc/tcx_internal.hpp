@@ -186,6 +186,7 @@ struct StreamPlan {
     bool ok = false;
     bool blocked = false;      // threads own a regA x regB register block of outputs
     bool direct = false;       // blocked tile whose lanes all run along hyper modes: every lane has operand rows of its own, read straight from memory
+    bool paced = false;        // flat tile whose operand lines collide in the L2 (see stream_plan.cpp): loads go out a few at a time
     int32_t tile = 0;          // lane indices per tile (flat: outputs per full tile = inner * chunk)
     int32_t inner = 0;         // flat tiles: product of the tile modes below the split mode
     int32_t chunk = 1;         // flat tiles: indices of the split mode per tile
@@ -233,6 +234,7 @@ struct StreamArgs {
     Scalars s;
     int32_t opA, opB, opC;
     int32_t read_c;
+    int32_t paced;
 };
 
 // Host: lay out the streaming plan for an analysed product (stream_plan.cpp).

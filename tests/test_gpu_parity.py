@@ -563,6 +563,43 @@ def test_unary_and_binary_operations(dtype):
     T.tcx_destroy_handle(h)
 
 
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64"])
+def test_streaming_tiles_whose_lines_collide(dtype):
+    """A three-way transposition whose strides inside a tile are all multiples of 128 KB: the plan
+    marks its loads as paced (TCX_KEY_PACED_LOADS) and runs the paced instantiation of the flat
+    streaming kernel.  Whole tiles, ragged last chunks, with and without the C read, conjugations;
+    integer inputs bit for bit."""
+    import paper_2601_07827_amd as T
+    from gpu_helpers import GpuProduct, run_gpu, say
+    labs = ["h0", "h1", "h2", "h3"]
+    cplx = dtype in ("c128", "c64")
+    unit = 128 * 1024 // {"f32": 4, "f64": 8, "c64": 8, "c128": 16}[dtype]        # elements in 128 KB
+    for ext, beta in ((dict(h0=16, h1=16, h2=3, h3=16), 0.0), (dict(h0=24, h1=32, h2=2, h3=16), 0.5),
+                      (dict(h0=8, h1=16, h2=5, h3=40), -1.0)):
+        A = W.tensor(labs, ext, strides=dict(h1=1, h2=128, h3=unit, h0=32 * unit))
+        B = W.tensor(labs, ext, strides=dict(h3=1, h2=128, h1=unit, h0=32 * unit))
+        D = W.tensor(labs, ext, strides=dict(h0=1, h1=128, h2=unit, h3=32 * unit))
+        for dist in ("uniform", "ints"):
+            alpha = 2.0 if dist == "ints" else ((1.5 - 0.5j) if cplx else 1.5)
+            p = W.Problem("colliding_lines_%s" % dtype, dtype, A, B, D, alpha=alpha, beta=beta if dist == "uniform" else float(int(beta * 2)),
+                          opA=int(cplx), opC=int(cplx), seed=W.BASE_SEED + 97)
+            gp = GpuProduct(p, force_path=STREAM)
+            paced = gp.get(T.TCX_KEY_PACED_LOADS)
+            gp.close()
+            assert paced == 1, "the plan did not see the collision"
+            say("%s extents %s beta %s %s" % (p.name, ext, p.beta, dist))
+            a, b, c = W.make_operands(p, dist)
+            truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
+            got = run_gpu(p, a, b, c, force_path=STREAM)
+            if dist == "ints":
+                assert np.array_equal(W.strided_view(got, p.D), W.strided_view(truth, p.D))
+            else:
+                assert normalised_error(p, got, truth, S, c) <= TOLERANCE[dtype]
+            mask = np.zeros(c.shape[0], dtype=bool)
+            W.strided_view(mask, p.D)[...] = True
+            assert np.array_equal(got[~mask], c[~mask])              # gaps of D untouched
+
+
 LOW_AI_LARGE = [W.config5(extent=4, nshared=1, nfree=7), W.config4(h=512, n=96, k=4),
                 W.hadamard(4, 64, permuted=True, beta=0.5), W.config5(extent=4, nshared=0, nfree=6)]
 
