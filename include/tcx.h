@@ -41,7 +41,8 @@
  *    one product may be executed from several threads and on several executors at once.  A
  *    product whose plan cuts the contracted range into parts (TCX_KEY_SPLIT_K > 1) writes
  *    partial sums to a device workspace that belongs to the EXECUTOR: work on one stream runs in
- *    order, so executions through one executor share it safely, and executions through different
+ *    order, so executions through one executor share it safely (calls from several host threads
+ *    through one executor are enqueued one after the other), and executions through different
  *    executors use different buffers.  The workspace grows on demand inside tcx_execute_product
  *    (the only device allocation an execution can make; TCX_KEY_WORKSPACE_BYTES on the product
  *    says how much it needs, the same key set on an executor reserves it ahead of time); if that

@@ -914,6 +914,7 @@ tcx_error_t run_product(tcx_product_t product, tcx_executor_t executor, tcx_stat
     // and may share it) or, for the call that may not allocate, the library's fixed buffer.
     char* ws = nullptr;
     bool split_ok = true;
+    std::unique_lock<std::mutex> lease;      // held until every launch that uses the workspace is enqueued
     const size_t need_partials = align256(partials_need(*p));
     const size_t need_red = read_ab ? reduced_bytes(*p, p->an.redA) + reduced_bytes(*p, p->an.redB) : 0;
     if (need_partials + need_red > 0) {
@@ -921,7 +922,11 @@ tcx_error_t run_product(tcx_product_t product, tcx_executor_t executor, tcx_stat
             if (need_partials + need_red > (size_t)TCX_SCRATCH_BYTES || !e->handle.scratch) return TCX_ERR_SCRATCH_TOO_SMALL;
             ws = (char*)e->handle.scratch;                   // every byte read is written first by this execution
         } else {
-            std::lock_guard<std::mutex> lk(e->mu);
+            // Two host threads may execute through one executor: the one that grows the workspace
+            // frees the old buffer (hipFree waits for the work already enqueued), so the other must
+            // not be between taking the pointer and enqueuing its kernels.  The lock also makes the
+            // order of enqueuing the order in which executions pass the buffer on.
+            lease = std::unique_lock<std::mutex>(e->mu);
             if (grow_workspace(e, need_partials + need_red) == TCX_SUCCESS) ws = (char*)e->workspace;
             else if (need_red > 0) return TCX_ERR_ALLOC;     // a reduced operand has to live somewhere
             else split_ok = false;                           // no memory for partial sums: run unsplit
