@@ -22,14 +22,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "contraction_oracle.cpp")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
-DT_F32, DT_F64, DT_C64, DT_C128 = 0, 1, 2, 3
+DT_F32, DT_F64, DT_C64, DT_C128, DT_F16 = 0, 1, 2, 3, 4
 MODE_TRUTH, MODE_TIMED, MODE_LITERAL = 0, 1, 2
 OP_IDENTITY, OP_CONJ = 0, 1
 
 V_OK, V_EXTENT_MISMATCH, V_CD_MISMATCH, V_D_ALIASING, V_ISOLATED, V_BAD_ARG = range(6)
 V_NAMES = ["ok", "extent_mismatch", "cd_mismatch", "d_aliasing", "isolated_index", "bad_arg"]
 
-_NP_DTYPE = {DT_F32: np.float32, DT_F64: np.float64, DT_C64: np.complex64, DT_C128: np.complex128}
+_NP_DTYPE = {DT_F32: np.float32, DT_F64: np.float64, DT_C64: np.complex64, DT_C128: np.complex128, DT_F16: np.float16}
 _DT_OF_NP = {np.dtype(v): k for k, v in _NP_DTYPE.items()}
 
 
@@ -52,11 +52,24 @@ def _load():
         _lib.oracle_validate.restype = ctypes.c_int
         _lib.oracle_contract.restype = ctypes.c_int
         _lib.oracle_max_threads.restype = ctypes.c_int
+        _lib.oracle_half_from_double.restype = ctypes.c_uint16
+        _lib.oracle_half_from_double.argtypes = [ctypes.c_double]
+        _lib.oracle_half_to_double.restype = ctypes.c_double
+        _lib.oracle_half_to_double.argtypes = [ctypes.c_uint16]
     return _lib
 
 
 def max_threads() -> int:
     return int(_load().oracle_max_threads())
+
+
+def half_from_double(x: float) -> int:
+    """Bits of the 16-bit value nearest to x (ties to even): the oracle's own conversion."""
+    return int(_load().oracle_half_from_double(float(x)))
+
+
+def half_to_double(bits: int) -> float:
+    return float(_load().oracle_half_to_double(int(bits)))
 
 
 def _i64(seq):

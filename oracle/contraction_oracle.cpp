@@ -53,7 +53,7 @@
 
 namespace {
 
-enum { DT_F32 = 0, DT_F64 = 1, DT_C64 = 2, DT_C128 = 3 };
+enum { DT_F32 = 0, DT_F64 = 1, DT_C64 = 2, DT_C128 = 3, DT_F16 = 4 };
 enum { MODE_TRUTH = 0, MODE_TIMED = 1, MODE_LITERAL = 2 };
 enum { OP_IDENTITY = 0, OP_CONJ = 1 };
 
@@ -148,6 +148,52 @@ int validate(const Tensor& A, const Tensor& B, const Tensor& C, const Tensor& D)
     return V_OK;
 }
 
+// ---- 16-bit storage (Sec. "The Reference Implementation": real types of 64, 32 and 16 bit) ----
+// IEEE 754 binary16: 1 sign bit, 5 exponent bits (bias 15), 10 fraction bits; exponent field 0
+// holds zero and the subnormals (multiples of 2^-24), 31 holds infinities and NaNs.  The host
+// compiler has no such type, so the two conversions are written out: to a wider type exactly, from
+// a wider type with ONE rounding to nearest, ties to even.
+struct half16 {
+    uint16_t bits;
+    half16() : bits(0) {}
+    // One rounding from the exact value of x.  float and double arguments promote exactly.
+    half16(long double x) {
+        const uint16_t sign = std::signbit(x) ? 0x8000u : 0u;
+        long double a = fabsl(x);
+        if (std::isnan(x)) { bits = sign | 0x7e00u; return; }
+        if (a == 0.0L) { bits = sign; return; }
+        if (std::isinf(x)) { bits = sign | 0x7c00u; return; }
+        // the grid the result lies on: 2^(e-10) for a leading exponent e, never finer than 2^-24
+        int e = ilogbl(a);
+        if (e < -14) e = -14;
+        const long double quantum = ldexpl(1.0L, e - 10);
+        const long double n = nearbyintl(a / quantum);          // exact division; rounds to nearest, ties to even
+        a = n * quantum;                                         // may have moved up to the next power of two
+        if (a >= 65536.0L) { bits = sign | 0x7c00u; return; }    // beyond the largest finite value 65504 after rounding
+        if (a == 0.0L) { bits = sign; return; }
+        const int e2 = ilogbl(a);
+        if (e2 < -14) bits = sign | (uint16_t)(a / ldexpl(1.0L, -24));
+        else bits = sign | (uint16_t)((e2 + 15) << 10) | (uint16_t)((long long)(a / ldexpl(1.0L, e2 - 10)) - 1024);
+    }
+    half16(double x) : half16((long double)x) {}
+    half16(float x) : half16((long double)x) {}
+    half16(int x) : half16((long double)x) {}
+    // exact
+    operator long double() const {
+        const int ef = (bits >> 10) & 31, frac = bits & 1023;
+        long double a;
+        if (ef == 31) a = frac ? (long double)NAN : (long double)INFINITY;
+        else if (ef == 0) a = ldexpl((long double)frac, -24);
+        else a = ldexpl((long double)(1024 + frac), ef - 25);
+        return (bits & 0x8000u) ? -a : a;
+    }
+};
+// Arithmetic "in the storage type" (the figure-literal mode): the exact result of one operation
+// on two 16-bit values fits a long double, and is rounded once.
+inline half16 operator*(half16 a, half16 b) { return half16((long double)a * (long double)b); }
+inline half16 operator+(half16 a, half16 b) { return half16((long double)a + (long double)b); }
+inline bool operator==(half16 a, half16 b) { return (long double)a == (long double)b; }
+
 // ---- element access helpers -------------------------------------------------------
 template <class T> struct Real { using type = T; };
 template <class R> struct Real<std::complex<R>> { using type = R; };
@@ -170,6 +216,7 @@ template <class R, class RA> struct Narrow<std::complex<R>, std::complex<RA>> {
 inline long double modulus(long double x) { return fabsl(x); }
 inline long double modulus(std::complex<long double> x) { return hypotl(x.real(), x.imag()); }
 inline double modulus(double x) { return std::fabs(x); }
+inline long double modulus(half16 x) { return fabsl((long double)x); }
 inline float modulus(float x) { return std::fabs(x); }
 inline double modulus(std::complex<double> x) { return std::hypot(x.real(), x.imag()); }
 inline float modulus(std::complex<float> x) { return std::hypot(x.real(), x.imag()); }
@@ -382,11 +429,24 @@ int oracle_contract(int dtype, int mode,
         else
             contract<cf, cf>(mode, free_loops, sum_loops, only_A, only_B, opA, opB, opC, cf((float)alpha[0], (float)alpha[1]),
                              cf((float)beta[0], (float)beta[1]), (const cf*)A, (const cf*)B, (const cf*)C, (cf*)D, S);
+    } else if (dtype == DT_F16) {
+        // truth: long-double sums, one rounding to 16 bits; timed: products and sums in float (what a
+        // plain CPU code does with 16-bit data), one rounding; literal: every operation rounded to 16 bits
+        if (mode == MODE_TRUTH)
+            contract<half16, long double>(mode, free_loops, sum_loops, only_A, only_B, opA, opB, opC, alpha[0], beta[0],
+                                          (const half16*)A, (const half16*)B, (const half16*)C, (half16*)D, S);
+        else
+            contract<half16, float>(mode, free_loops, sum_loops, only_A, only_B, opA, opB, opC, (float)alpha[0], (float)beta[0],
+                                    (const half16*)A, (const half16*)B, (const half16*)C, (half16*)D, S);
     } else {
         return V_BAD_ARG;
     }
     return V_OK;
 }
+
+// The two 16-bit conversions on their own, for the tests that pin them.
+uint16_t oracle_half_from_double(double x) { return half16(x).bits; }
+double oracle_half_to_double(uint16_t bits) { half16 h; h.bits = bits; return (double)(long double)h; }
 
 int oracle_max_threads(void);
 }

@@ -40,6 +40,11 @@ MUTANTS = [
     ("normaliser_uses_only_A", "if (S) s += ma * mb;", "if (S) s += ma;"),
     ("literal_mode_scales_C_by_alpha", "T running = mul(be, apply_op(C[off_D], opC));", "T running = mul(al, apply_op(C[off_D], opC));"),
     ("last_term_skipped", "for (int64_t k = 0; k < size_P; ++k) {", "for (int64_t k = 1; k < size_P; ++k) {"),
+    ("half_rounding_truncates", "const long double n = nearbyintl(a / quantum);", "const long double n = floorl(a / quantum);"),
+    ("half_ties_away_from_zero", "const long double n = nearbyintl(a / quantum);", "const long double n = roundl(a / quantum);"),
+    ("half_subnormal_grid_too_fine", "if (e < -14) e = -14;", "if (e < -15) e = -15;"),
+    ("half_exponent_bias_off_by_one", "else a = ldexpl((long double)(1024 + frac), ef - 25);", "else a = ldexpl((long double)(1024 + frac), ef - 24);"),
+    ("half_overflow_limit_too_high", "if (a >= 65536.0L) { bits = sign | 0x7c00u; return; }", "if (a >= 131072.0L) { bits = sign | 0x7c00u; return; }"),
 ]
 
 
@@ -58,6 +63,8 @@ def _pins_to_run():
             calls.append((pins.test_normaliser_on_exact_moduli, (dt, mode)))
     for seed in range(10):
         calls.append((pins.test_isolated_labels_brute_force, ("f64", seed)))
+    calls.append((pins.test_half_from_double_rounds_to_nearest_even, ()))
+    calls.append((pins.test_half_to_double_on_every_bit_pattern, ()))
     calls += [(pins.test_case4_example_is_a_reduction_then_a_contraction, ()), (pins.test_case5_broadcasts_the_product, ())]
     calls += [(pins.test_repeated_label_equals_summed_stride, ()), (pins.test_validation_classes, ()),
               (pins.test_conjugation_symmetry_and_op_equals_preconjugated_copy, ()),
@@ -83,6 +90,10 @@ def test_a_pin_catches_the_planted_mistake(mutant, monkeypatch):
         bad.oracle_validate.restype = ctypes.c_int
         bad.oracle_contract.restype = ctypes.c_int
         bad.oracle_max_threads.restype = ctypes.c_int
+        bad.oracle_half_from_double.restype = ctypes.c_uint16
+        bad.oracle_half_from_double.argtypes = [ctypes.c_double]
+        bad.oracle_half_to_double.restype = ctypes.c_double
+        bad.oracle_half_to_double.argtypes = [ctypes.c_uint16]
         oracle._load()
         monkeypatch.setattr(oracle, "_lib", bad)
         caught = 0

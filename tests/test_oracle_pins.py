@@ -5,6 +5,7 @@ so the pins are: exact rational brute force on tiny tensors, numpy.einsum as an
 independent library evaluation, closed forms (all-ones, one-hot), invariants of the
 definition, and agreement of the three evaluation orders within the rounding bound.
 """
+import dataclasses
 import itertools
 import os
 from fractions import Fraction
@@ -68,7 +69,7 @@ def _as_complex(x):
 
 
 # ---- P1: brute force on tiny tensors --------------------------------------------------
-@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64"])
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64", "f16"])
 @pytest.mark.parametrize("seed", range(12))
 def test_brute_force_integer_inputs_exact(dtype, seed):
     """Integer-valued inputs: every partial sum is exactly representable, so the oracle (all
@@ -104,6 +105,56 @@ def test_brute_force_uniform_inputs_one_rounding(dtype, seed):
         assert abs(complex(v[key]) - ref) <= 2.0 ** -52 * abs(ref) + 2.0 ** -58 * scale + 1e-300
 
 
+# ---- 16-bit storage: the oracle's own conversions, pinned to numpy's float16 ----------------
+def test_half_to_double_on_every_bit_pattern():
+    """All 65 536 patterns: zeros, subnormals, normals, infinities, NaNs."""
+    bits = np.arange(65536, dtype=np.uint16)
+    ref = bits.view(np.float16).astype(np.float64)
+    for b in range(65536):
+        got = oracle.half_to_double(b)
+        if np.isnan(ref[b]):
+            assert np.isnan(got)
+        else:
+            assert got == ref[b] and np.signbit(got) == np.signbit(ref[b]), hex(b)
+
+
+def test_half_from_double_rounds_to_nearest_even():
+    """numpy converts float64 to float16 with one correct rounding: random doubles over the whole
+    range (normal, subnormal, overflowing), every midpoint between neighbouring 16-bit values
+    (ties go to the even neighbour), and the values just beside those midpoints."""
+    rng = np.random.default_rng(16)
+    xs = [0.0, -0.0, 65504.0, 65519.999, 65520.0, 65536.0, 1e6, 2.0 ** -24, 2.0 ** -25, 2.0 ** -25 * (1 + 2.0 ** -40), 3 * 2.0 ** -25,
+          2.0 ** -14, 2.0 ** -14 - 2.0 ** -25, 1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11, 1 + 2.0 ** -11 + 2.0 ** -40, float("inf")]
+    xs += list(rng.uniform(-1, 1, 2000) * 10.0 ** rng.integers(-9, 6, 2000))
+    pos = np.arange(0, 0x7c00, dtype=np.uint16).view(np.float16).astype(np.float64)      # every finite non-negative value
+    mid = (pos[:-1] + pos[1:]) / 2                                                       # exact in float64
+    xs += list(mid[::7]) + list(np.nextafter(mid[::11], np.inf)) + list(np.nextafter(mid[::13], -np.inf))
+    with np.errstate(over="ignore"):
+        for x in xs:
+            for v in (x, -x):
+                want = int(np.array([v], dtype=np.float64).astype(np.float16).view(np.uint16)[0])
+                assert oracle.half_from_double(v) == want, (v, hex(want))
+
+
+def test_f16_uniform_inputs_round_once():
+    """float16 tensors with uniform entries (multiples of 2^-10) and a handful of terms: every
+    product and sum is exact in any wider type, so the truth is the exact rational result rounded
+    ONCE to 16 bits, and the storage-type evaluation orders differ from it by their own roundings
+    only (timed: float sums, exact here as well)."""
+    for seed in range(8):
+        rng = np.random.default_rng(2600 + seed)
+        p = random_problem(rng, "f16", max_extent=3)
+        p = dataclasses.replace(p, alpha=0.5, beta=-2.0)
+        a, b, c = W.make_operands(p, "uniform")
+        exact = brute_exact(p, a, b, c)
+        for mode in (oracle.MODE_TRUTH, oracle.MODE_TIMED):
+            d, _ = run_oracle(p, a, b, c, mode)
+            v = W.strided_view(d, p.D)
+            for key, val in exact.items():
+                want = np.float16(float(val[0]))          # float(Fraction) is exact here (few terms of 20-bit products)
+                assert v[key] == want, (p, key, mode, v[key], want)
+
+
 def test_S_is_sum_of_moduli():
     """The normaliser returned by the truth mode is sum |a||b| (checked exactly on integers)."""
     rng = np.random.default_rng(5)
@@ -120,7 +171,7 @@ _PYTHAGOREAN = [(3, 4, 5), (5, 12, 13), (8, 15, 17), (7, 24, 25), (20, 21, 29), 
 
 
 @pytest.mark.parametrize("mode", [oracle.MODE_TRUTH, oracle.MODE_TIMED], ids=["truth", "timed"])
-@pytest.mark.parametrize("dtype", ["c128", "c64", "f64", "f32"])
+@pytest.mark.parametrize("dtype", ["c128", "c64", "f64", "f32", "f16"])
 def test_normaliser_on_exact_moduli(dtype, mode):
     """S = sum_P |op(a)||op(b)| with the complex MODULUS (the error measure's denominator).
     Complex operands are drawn from Gaussian integers with integer moduli, in all sign, swap and
@@ -184,7 +235,7 @@ def einsum_reference(p: W.Problem, bufA, bufB, bufC):
     return out
 
 
-@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64"])
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64", "f16"])
 @pytest.mark.parametrize("seed", range(10))
 def test_einsum_random_problems(dtype, seed):
     rng = np.random.default_rng(3000 + seed)
@@ -327,7 +378,7 @@ def test_all_ones_config1_value():
 
 
 # ---- P4: one-hot operand => pure gather / permutation, bit exact -----------------------
-@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64"])
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64", "f16"])
 def test_delta_operand_reproduces_permutation(dtype):
     """B[k..., n...] = prod delta(k_i, n_i)  =>  D[m..., n...] = A[m..., k... = n...]: each
     sum has exactly one non-zero term, so D is a bit-exact re-layout of A."""

@@ -61,7 +61,7 @@ def mix64(seed: int, tag: int, idx: np.ndarray) -> np.ndarray:
 
 
 def uniform_pm1(seed: int, tag: int, idx: np.ndarray, dtype) -> np.ndarray:
-    """Uniform on [-1, 1): 53 random bits for float64, 24 for float32 (both exact)."""
+    """Uniform on [-1, 1): 53 random bits for float64, 24 for float32, 11 for float16 (all exact)."""
     dtype = np.dtype(dtype)
     if dtype in (np.complex128, np.complex64):
         real = np.float64 if dtype == np.complex128 else np.float32
@@ -76,6 +76,9 @@ def uniform_pm1(seed: int, tag: int, idx: np.ndarray, dtype) -> np.ndarray:
     if dtype == np.float32:
         return _hashed(seed, tag, idx, np.float32,
                        lambda h: (h >> np.uint64(40)).astype(np.float32) * np.float32(2.0 ** -23) - np.float32(1.0))
+    if dtype == np.float16:      # 11 random bits: multiples of 2^-10, all of them 16-bit values
+        return _hashed(seed, tag, idx, np.float16,
+                       lambda h: ((h >> np.uint64(53)).astype(np.float32) * np.float32(2.0 ** -10) - np.float32(1.0)).astype(np.float16))
     raise ValueError(dtype)
 
 
@@ -162,7 +165,7 @@ def tensor(labels: Sequence[str], extent_of: Dict[str, int], memory_order: Optio
 @dataclass(frozen=True)
 class Problem:
     name: str
-    dtype: str                        # "f32" | "f64" | "c64" | "c128"
+    dtype: str                        # "f32" | "f64" | "c64" | "c128" | "f16"
     A: TensorSpec
     B: TensorSpec
     D: TensorSpec                     # C shares D's description
@@ -177,7 +180,7 @@ class Problem:
 
     @property
     def np_dtype(self):
-        return {"f32": np.float32, "f64": np.float64, "c64": np.complex64, "c128": np.complex128}[self.dtype]
+        return {"f32": np.float32, "f64": np.float64, "c64": np.complex64, "c128": np.complex128, "f16": np.float16}[self.dtype]
 
     def extent_of(self) -> Dict[str, int]:
         out: Dict[str, int] = {}
