@@ -32,7 +32,7 @@ PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3, "c128": 78.6, "c64": 157.3}     # MI35
 PEAK_HBM_GBS = 8000.0
 CACHE_BYTES = 256e6                                       # memory-side cache: cold runs rotate over more than twice this
 TOLERANCE = {"f32": 1e-5, "f64": 1e-12, "c128": 1e-12, "c64": 1e-5}
-DT = {"f32": 0, "f64": 1, "c64": 2, "c128": 3}
+DT = {"f32": 0, "f64": 1, "c64": 2, "c128": 3, "f16": 4}
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 
 # workloads of the default run besides the headline, in the order they are reported

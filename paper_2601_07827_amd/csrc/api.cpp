@@ -25,6 +25,7 @@ static __device__ __align__(256) unsigned char scratch[TCX_SCRATCH_BYTES];
 // that a unary or binary operation is planned as (C := alpha A + beta B  is  alpha A * 1 + beta B).
 static __device__ __align__(16) double one_in_64_bits[2] = {1.0, 0.0};
 static __device__ __align__(16) float one_in_32_bits[2] = {1.0f, 0.0f};
+static __device__ __align__(16) unsigned short one_in_16_bits[2] = {0x3c00u, 0u};      // IEEE binary16 1.0
 
 namespace tcx {
 namespace {
@@ -38,6 +39,7 @@ struct Handle {
     void* scratch = nullptr;   // this device's copy of the fixed scratch buffer (tcx_execute_product_noalloc)
     const void* one64 = nullptr;   // ... of the constants 1 (unary and binary operations)
     const void* one32 = nullptr;
+    const void* one16 = nullptr;
 };
 struct Executor {
     Handle handle;
@@ -93,6 +95,7 @@ std::mutex g_scratch_mu;
 void* g_scratch_ptr[kMaxDevices] = {};
 void* g_one64_ptr[kMaxDevices] = {};
 void* g_one32_ptr[kMaxDevices] = {};
+void* g_one16_ptr[kMaxDevices] = {};
 bool g_scratch_asked[kMaxDevices] = {};
 
 // Address of `scratch` on `device`, which must be the current device.  nullptr if the runtime
@@ -109,6 +112,7 @@ void* scratch_on(int device) {
         g_scratch_ptr[device] = ptr;
         if (hipGetSymbolAddress(&g_one64_ptr[device], HIP_SYMBOL(one_in_64_bits)) != hipSuccess) { (void)hipGetLastError(); g_one64_ptr[device] = nullptr; }
         if (hipGetSymbolAddress(&g_one32_ptr[device], HIP_SYMBOL(one_in_32_bits)) != hipSuccess) { (void)hipGetLastError(); g_one32_ptr[device] = nullptr; }
+        if (hipGetSymbolAddress(&g_one16_ptr[device], HIP_SYMBOL(one_in_16_bits)) != hipSuccess) { (void)hipGetLastError(); g_one16_ptr[device] = nullptr; }
         g_scratch_asked[device] = true;
     }
     return g_scratch_ptr[device];
@@ -584,6 +588,7 @@ tcx_error_t tcx_create_handle(tcx_handle_t* out) {
             h->scratch = scratch_on(dev);
             h->one64 = g_one64_ptr[dev];
             h->one32 = g_one32_ptr[dev];
+            h->one16 = g_one16_ptr[dev];
         }
     }
     (void)hipGetLastError();
@@ -887,10 +892,15 @@ tcx_error_t run_product(tcx_product_t product, tcx_executor_t executor, tcx_stat
     Executor* e = lookup<Executor>(executor, MAGIC_EXEC);
     if (!p || !e || p->kind != kind) return TCX_ERR_INVALID_HANDLE;
     if (!alpha || !beta || !D) return TCX_ERR_NULL_ARG;
-    if (kind != KIND_CONTRACTION) B = real_bytes_of(p->an.dtype) == 4 ? e->handle.one32 : e->handle.one64;
+    if (kind != KIND_CONTRACTION) {
+        const int rb = real_bytes_of(p->an.dtype);
+        B = rb == 2 ? e->handle.one16 : rb == 4 ? e->handle.one32 : e->handle.one64;
+    }
     Scalars s{0, 0, 0, 0};
     switch (p->an.dtype) {
-        case TCX_F32: s.alpha_re = *(const float*)alpha; s.beta_re = *(const float*)beta; break;
+        case TCX_F32:
+        case TCX_F16:                        // 16-bit tensors take their scalars as floats
+            s.alpha_re = *(const float*)alpha; s.beta_re = *(const float*)beta; break;
         case TCX_F64: s.alpha_re = *(const double*)alpha; s.beta_re = *(const double*)beta; break;
         case TCX_C64:
             s.alpha_re = ((const float*)alpha)[0]; s.alpha_im = ((const float*)alpha)[1];

@@ -12,7 +12,8 @@ namespace tcx {
 namespace {
 
 // Arithmetic policies: `stor` is what memory holds, `acc_t` what products and sums are formed in
-// (the storage type itself, or its 64-bit widening when the plan asks for TCX_PREC_F64).
+// (the storage type itself, its 64-bit widening when the plan asks for TCX_PREC_F64, 32-bit or
+// 64-bit reals for 16-bit storage; the conversion back on the store rounds to nearest even).
 template <class R> struct cplx_of {
     R re, im;
 };
@@ -140,6 +141,10 @@ int launch_reduce(int dtype, int precision, const ReduceArgs& args, void* stream
             if (wide) reduce_operand<RealNum<float, double>><<<gr, bl, 0, st>>>(args);
             else reduce_operand<RealNum<float, float>><<<gr, bl, 0, st>>>(args);
             break;
+        case TCX_F16:
+            if (precision == TCX_PREC_F64) reduce_operand<RealNum<_Float16, double>><<<gr, bl, 0, st>>>(args);
+            else reduce_operand<RealNum<_Float16, float>><<<gr, bl, 0, st>>>(args);
+            break;
         case TCX_C128: reduce_operand<ComplexNum<double, double>><<<gr, bl, 0, st>>>(args); break;
         case TCX_C64:
             if (wide) reduce_operand<ComplexNum<float, double>><<<gr, bl, 0, st>>>(args);
@@ -163,6 +168,10 @@ int launch_generic(int dtype, int precision, const GenericArgs& args, void* stre
         case TCX_F32:
             if (wide) generic_contract<RealNum<float, double>><<<gr, bl, 0, st>>>(args);
             else generic_contract<RealNum<float, float>><<<gr, bl, 0, st>>>(args);
+            break;
+        case TCX_F16:
+            if (precision == TCX_PREC_F64) generic_contract<RealNum<_Float16, double>><<<gr, bl, 0, st>>>(args);
+            else generic_contract<RealNum<_Float16, float>><<<gr, bl, 0, st>>>(args);
             break;
         case TCX_C128: generic_contract<ComplexNum<double, double>><<<gr, bl, 0, st>>>(args); break;
         case TCX_C64:

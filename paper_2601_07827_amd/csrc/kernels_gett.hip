@@ -1651,7 +1651,8 @@ hipError_t launch_complex_shape(int variant, bool akf, bool bkf, bool dnf, const
     return hipErrorInvalidValue;
 }
 
-// 32-bit tensors computed in 64-bit arithmetic: two staged shapes each (64 x 64 and 32 x 32)
+// Tensors whose storage is narrower than the arithmetic (32-bit in 64-bit arithmetic, 16-bit in
+// 32- or 64-bit arithmetic): two staged shapes each (64 x 64 and 32 x 32)
 constexpr int kWideRealShapes[] = {2, 3};
 constexpr int kWideComplexShapes[] = {1, 2};
 template <class P>
@@ -1665,7 +1666,7 @@ hipError_t launch_wide_shape(int variant, bool akf, bool bkf, bool dnf, const Ge
 
 const Shape* shapes_of(int dtype, int* n) {
     if (dtype == TCX_C128 || dtype == TCX_C64) { *n = kNumComplexShapes; return kComplexShapes; }
-    if (dtype == TCX_F64 || dtype == TCX_F32) { *n = kNumRealShapes; return kRealShapes; }
+    if (dtype == TCX_F64 || dtype == TCX_F32 || dtype == TCX_F16) { *n = kNumRealShapes; return kRealShapes; }
     *n = 0;
     return nullptr;
 }
@@ -1716,6 +1717,9 @@ int launch_gett(int dtype, int precision, int variant, bool a_kf, bool b_kf, boo
         case TCX_F32:
             if (wide) return (int)launch_wide_shape<RealPolicy<double, float>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
             return (int)launch_real_shape<RealPolicy<float>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
+        case TCX_F16:        // 16-bit storage is always widened: fp32 MFMAs by default, fp64 on request
+            if (precision == TCX_PREC_F64) return (int)launch_wide_shape<RealPolicy<double, _Float16>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
+            return (int)launch_wide_shape<RealPolicy<float, _Float16>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
         case TCX_C128: return (int)launch_complex_shape<ComplexPolicyT<double>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
         case TCX_C64:
             if (wide) return (int)launch_wide_shape<ComplexPolicyT<double, float>>(variant, a_kf, b_kf, d_nf, args, blocks, st);

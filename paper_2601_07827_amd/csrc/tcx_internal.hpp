@@ -17,13 +17,19 @@ struct Mode {
 };
 
 // ---- element types --------------------------------------------------------------------
-inline int elem_bytes_of(int dtype) { return dtype == TCX_F32 ? 4 : dtype == TCX_C128 ? 16 : 8; }
-inline int real_bytes_of(int dtype) { return dtype == TCX_F32 || dtype == TCX_C64 ? 4 : 8; }
+inline int elem_bytes_of(int dtype) { return dtype == TCX_F16 ? 2 : dtype == TCX_F32 ? 4 : dtype == TCX_C128 ? 16 : 8; }
+inline int real_bytes_of(int dtype) { return dtype == TCX_F16 ? 2 : dtype == TCX_F32 || dtype == TCX_C64 ? 4 : 8; }   // of the storage type
 inline bool is_complex(int dtype) { return dtype == TCX_C64 || dtype == TCX_C128; }
-inline bool valid_dtype(int dtype) { return dtype == TCX_F32 || dtype == TCX_F64 || dtype == TCX_C64 || dtype == TCX_C128; }
-// 32-bit storage with products and sums in 64-bit reals (TCX_PREC_F64)
-inline bool is_widened(int dtype, int precision) { return precision == TCX_PREC_F64 && real_bytes_of(dtype) == 4; }
-inline int compute_real_bytes(int dtype, int precision) { return is_widened(dtype, precision) ? 8 : real_bytes_of(dtype); }
+inline bool valid_dtype(int dtype) {
+    return dtype == TCX_F32 || dtype == TCX_F64 || dtype == TCX_C64 || dtype == TCX_C128 || dtype == TCX_F16;
+}
+// Reals that products and sums are formed in: the storage type's own, 32 bits for 16-bit storage,
+// 64 bits for every plan in TCX_PREC_F64.
+inline int compute_real_bytes(int dtype, int precision) {
+    return precision == TCX_PREC_F64 ? 8 : real_bytes_of(dtype) == 2 ? 4 : real_bytes_of(dtype);
+}
+// storage narrower than the arithmetic: elements are widened as they are read, D is rounded once
+inline bool is_widened(int dtype, int precision) { return compute_real_bytes(dtype, precision) > real_bytes_of(dtype); }
 
 struct TensorDesc {
     int32_t dtype = 0;

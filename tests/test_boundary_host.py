@@ -77,7 +77,7 @@ def test_handle_lifecycle_and_null_conventions(handle):
 
 def test_tensor_info_errors_and_roundtrip(handle):
     assert _code(T.tcx_create_tensor_info, handle, 7, [2], [1]) == T.TCX_ERR_BAD_DTYPE
-    assert _code(T.tcx_create_tensor_info, handle, 4, [2], [1]) == T.TCX_ERR_BAD_DTYPE
+    assert _code(T.tcx_create_tensor_info, handle, 5, [2], [1]) == T.TCX_ERR_BAD_DTYPE
     assert _code(T.tcx_create_tensor_info, handle, -1, [2], [1]) == T.TCX_ERR_BAD_DTYPE
     assert _code(T.tcx_create_tensor_info, handle, T.TCX_F64, [1] * 33, [1] * 33) == T.TCX_ERR_BAD_NMODE
     assert _code(T.tcx_create_tensor_info, handle, T.TCX_F64, [3, 0], [1, 3]) == T.TCX_ERR_BAD_EXTENT
@@ -570,6 +570,42 @@ def test_plan_precision(handle):
             T.tcx_destroy_product(prod)
         for i in infos:
             T.tcx_destroy_tensor_info(i)
+
+
+def test_sixteen_bit_plans(handle):
+    """TCX_F16 (Sec. "The Reference Implementation": real types of 16 bit): storage is always
+    narrower than the arithmetic, so both precisions plan on the generic kernel or the two widened
+    tile shapes and never on the streaming path; a low-intensity product falls to them as well;
+    the four tensors must share the dtype."""
+    e = dict(m=300, n=200, k=64)
+    A, B, D = W.tensor("mk", e), W.tensor("kn", e), W.tensor("mn", e)
+    infos = [T.tcx_create_tensor_info(handle, T.TCX_F16, t.extents, t.strides) for t in (A, B, D)]
+    args = (handle, 0, infos[0], [1, 3], 0, infos[1], [3, 2], 0, infos[2], [1, 2], 0, infos[2], [1, 2])
+    for prec in (T.TCX_PREC_DEFAULT, T.TCX_PREC_F64):
+        plan = T.tcx_create_product(*args, prec)
+        assert T.tcx_product_get(plan, T.TCX_KEY_PRECISION) == prec
+        assert T.tcx_product_get(plan, T.TCX_KEY_PATH) == T.TCX_PATH_GETT_MFMA
+        assert T.tcx_product_get(plan, T.TCX_KEY_VARIANT) in (2, 3)
+        assert _code(T.tcx_product_set, plan, T.TCX_KEY_VARIANT, 0) == T.TCX_ERR_PLAN_REFUSED
+        assert _code(T.tcx_product_set, plan, T.TCX_KEY_FORCE_PATH, T.TCX_PATH_BANDWIDTH) == T.TCX_ERR_PLAN_REFUSED
+        T.tcx_product_set(plan, T.TCX_KEY_SPLIT_K, 2)
+        # partial sums are kept in the arithmetic's reals: 4 or 8 bytes each
+        assert T.tcx_product_get(plan, T.TCX_KEY_WORKSPACE_BYTES) % (8 if prec else 4) == 0
+        T.tcx_destroy_product(plan)
+    f32 = T.tcx_create_tensor_info(handle, T.TCX_F32, D.extents, D.strides)
+    assert _code(T.tcx_create_product, handle, 0, infos[0], [1, 3], 0, infos[1], [3, 2], 0, f32, [1, 2], 0, f32, [1, 2]) == T.TCX_ERR_DTYPE_MIX
+    T.tcx_destroy_tensor_info(f32)
+    for i in infos:
+        T.tcx_destroy_tensor_info(i)
+    # an outer product of 16-bit vectors: not streamed, planned on the tiled or generic kernel
+    e = dict(m=4096, n=4096)
+    u, v, O = W.tensor("m", e), W.tensor("n", e), W.tensor("mn", e)
+    infos = [T.tcx_create_tensor_info(handle, T.TCX_F16, t.extents, t.strides) for t in (u, v, O)]
+    plan = T.tcx_create_product(handle, 0, infos[0], [1], 0, infos[1], [2], 0, infos[2], [1, 2], 0, infos[2], [1, 2])
+    assert T.tcx_product_get(plan, T.TCX_KEY_PATH) in (T.TCX_PATH_GETT_MFMA, T.TCX_PATH_GENERIC)
+    T.tcx_destroy_product(plan)
+    for i in infos:
+        T.tcx_destroy_tensor_info(i)
 
 
 def test_isolated_labels_are_planned_as_reductions_and_broadcasts(handle):
