@@ -787,8 +787,10 @@ tcx_error_t tcx_product_get(tcx_product_t product, int32_t key, void* value, siz
         case TCX_KEY_TILE_N: return put_i64(an.path == TCX_PATH_BANDWIDTH ? p->stream.regA * p->stream.regB : s.mt_n, value, nbytes);
         case TCX_KEY_TILE_K: return put_i64(s.kt, value, nbytes);
         case TCX_KEY_GRID:
-            if (an.path == TCX_PATH_BANDWIDTH)      // the streaming kernels walk their tiles with a grid of at most 8 workgroups per CU
-                return put_i64(std::min<int64_t>(p->stream.num_tiles, (int64_t)(p->handle.num_cu > 0 ? p->handle.num_cu : 256) * 8), value, nbytes);
+            if (an.path == TCX_PATH_BANDWIDTH) {
+                const int need = (int)((std::max(p->stream.itemsA.size(), p->stream.itemsB.size()) + kStreamThreads - 1) / kStreamThreads);
+                return put_i64(stream_grid(p->stream.blocked, p->stream.direct, need, p->stream.num_tiles, p->handle.num_cu), value, nbytes);
+            }
             return put_i64(tiled ? (s.dual ? (tiles_of(an, s) * p->splitK + 1) / 2 : tiles_of(an, s) * p->splitK)
                                  : (an.sizeH * an.sizeM * an.sizeN + 255) / 256, value, nbytes);
         case TCX_KEY_BLOCK: return put_i64(s.threads * (tiled && s.dual ? 2 : 1), value, nbytes);

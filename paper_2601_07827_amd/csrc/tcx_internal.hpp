@@ -251,6 +251,8 @@ bool stream_preferred(const Analysis& an, int elem_bytes);
 // Measurement aid (probes.hip): one launch of a single-purpose kernel; *work = flop or bytes it does.
 int launch_probe(int kind, void* buffer, size_t bytes, int64_t iters, int num_cu, void* stream, double* work);
 
+// Number of workgroups launch_stream starts for a plan (items_per_thread: staged operand elements per thread).
+int64_t stream_grid(bool blocked, bool direct, int items_per_thread, int64_t num_tiles, int num_cu);
 int launch_stream(int dtype, bool blocked, bool direct, const StreamArgs& args, size_t lds_bytes, int num_cu, void* stream,
                   int64_t* grid, int* block);
 
