@@ -210,6 +210,12 @@ std::vector<PlanChoice> rank_plans(const Analysis& an, int num_cu) {
                 us += 3.0 + (2.0 * S + 1.0) * tiles * s.acc_reals * (ebytes > 8 ? 8 : ebytes) / 6e12 * 1e6;
             if (best < 0 || us < best) { best = us; bestS = (int)S; }
         }
+        // Short tiles that already give every CU a workgroup are not cut along K: such a product
+        // is bound by latency, not by the matrix pipe, and the model above overrates the split.
+        // Measured on a 576^3 product in 324 tiles of 32 x 32 (36 slabs each): one launch of the
+        // unsplit tiles 21.3 us; K in 2, 3, 4, 6 parts plus the reduction launch 21.3, 21.0, 22.5,
+        // 22.0 us, with four times the memory traffic (partial sums written and read back).
+        if (bestS > 1 && !(bestS == 2 && s.pair_in_lds) && nk <= 64 && tiles >= cus) bestS = 1;
         ranked.push_back({best, v, bestS});
     }
     std::stable_sort(ranked.begin(), ranked.end(), [](const PlanChoice& x, const PlanChoice& y) { return x.us < y.us; });
@@ -218,7 +224,9 @@ std::vector<PlanChoice> rank_plans(const Analysis& an, int num_cu) {
 
 void choose_plan(const Analysis& an, int num_cu, int* variant, int* splitK) {
     const std::vector<PlanChoice> r = rank_plans(an, num_cu);
-    if (!r.empty()) { *variant = r[0].variant; *splitK = r[0].splitK; }
+    if (r.empty()) return;
+    *variant = r[0].variant;
+    *splitK = r[0].splitK;
 }
 
 void fill_generic(const Analysis& an, GenericArgs* g) {

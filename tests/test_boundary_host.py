@@ -334,10 +334,12 @@ def test_planner_routes_each_configuration(handle):
     # batches slowest: 512 contiguous matrices, one 96x96 complex tile each, two per workgroup
     assert (c4s["TILE_M"], c4s["TILE_N"], c4s["TILE_K"], c4s["BLOCK"], c4s["GRID"], c4s["LAUNCHES"]) == (96, 96, 8, 512, 256, 1)
     c1 = _plan(handle, W.config1())
-    # B's lanes run along k = (c, d) with extent 24: slabs of 16 do not repeat -> classic kernel, split K + reduction
-    assert c1["BLOCK"] == 256 and c1["SPLIT_K"] > 1 and c1["LAUNCHES"] == 2
+    # B's lanes run along k = (c, d) with extent 24: slabs of 16 do not repeat -> classic kernel; its 324
+    # short tiles of 32 x 32 already give every CU a workgroup: one launch, K whole, no workspace
+    assert (c1["TILE_M"], c1["BLOCK"], c1["SPLIT_K"], c1["LAUNCHES"], c1["GRID"]) == (32, 256, 1, 1, 324)
     c3 = _plan(handle, W.config3())
-    assert c3["BLOCK"] == 256                                               # K = (e41, d29): slabs of 16 do not repeat
+    # K = (e41, d29): slabs of 16 do not repeat; 124 tiles do not fill the chip: K is cut, plus the reduction launch
+    assert c3["BLOCK"] == 256 and c3["SPLIT_K"] > 1 and c3["LAUNCHES"] == 2
 
 
 def test_tile_modes_cover_a_cache_line_of_every_tensor(handle):
