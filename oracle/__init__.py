@@ -22,14 +22,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "contraction_oracle.cpp")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
-DT_F32, DT_F64, DT_C64, DT_C128, DT_F16 = 0, 1, 2, 3, 4
+DT_F32, DT_F64, DT_C64, DT_C128, DT_F16, DT_BF16 = 0, 1, 2, 3, 4, 5
 MODE_TRUTH, MODE_TIMED, MODE_LITERAL = 0, 1, 2
 OP_IDENTITY, OP_CONJ = 0, 1
 
 V_OK, V_EXTENT_MISMATCH, V_CD_MISMATCH, V_D_ALIASING, V_ISOLATED, V_BAD_ARG = range(6)
 V_NAMES = ["ok", "extent_mismatch", "cd_mismatch", "d_aliasing", "isolated_index", "bad_arg"]
 
-_NP_DTYPE = {DT_F32: np.float32, DT_F64: np.float64, DT_C64: np.complex64, DT_C128: np.complex128, DT_F16: np.float16}
+_NP_DTYPE = {DT_F32: np.float32, DT_F64: np.float64, DT_C64: np.complex64, DT_C128: np.complex128, DT_F16: np.float16,
+             DT_BF16: np.uint16}      # numpy has no bfloat16: buffers of its bit patterns
 _DT_OF_NP = {np.dtype(v): k for k, v in _NP_DTYPE.items()}
 
 
@@ -56,6 +57,10 @@ def _load():
         _lib.oracle_half_from_double.argtypes = [ctypes.c_double]
         _lib.oracle_half_to_double.restype = ctypes.c_double
         _lib.oracle_half_to_double.argtypes = [ctypes.c_uint16]
+        _lib.oracle_bfloat16_from_double.restype = ctypes.c_uint16
+        _lib.oracle_bfloat16_from_double.argtypes = [ctypes.c_double]
+        _lib.oracle_bfloat16_to_double.restype = ctypes.c_double
+        _lib.oracle_bfloat16_to_double.argtypes = [ctypes.c_uint16]
     return _lib
 
 
@@ -70,6 +75,14 @@ def half_from_double(x: float) -> int:
 
 def half_to_double(bits: int) -> float:
     return float(_load().oracle_half_to_double(int(bits)))
+
+
+def bfloat16_from_double(x: float) -> int:
+    return int(_load().oracle_bfloat16_from_double(float(x)))
+
+
+def bfloat16_to_double(bits: int) -> float:
+    return float(_load().oracle_bfloat16_to_double(int(bits)))
 
 
 def _i64(seq):
@@ -98,7 +111,8 @@ def contract(A, B, C, D, ops: Sequence[int], alpha, beta,
              base=(0, 0, 0, 0), mode: int = MODE_TRUTH, want_S: bool = False):
     """Run the loop nest.  A, B, C, D are (extents, strides, labels); ops = (opA, opB, opC).
 
-    bufX are 1-D numpy arrays of one dtype (float32, float64, complex64 or complex128); bufD is
+    bufX are 1-D numpy arrays of one dtype (float32, float64, complex64, complex128, float16, or
+    uint16 holding bfloat16 bit patterns); bufD is
     written in place (bufC may be bufD, or None when beta == 0).  base[i] is the element
     offset inside the buffer of the element with all indices zero.  Returns (status, S)
     where S is None or a float64 array shaped like bufD holding sum|a||b| per D element.

@@ -53,7 +53,7 @@
 
 namespace {
 
-enum { DT_F32 = 0, DT_F64 = 1, DT_C64 = 2, DT_C128 = 3, DT_F16 = 4 };
+enum { DT_F32 = 0, DT_F64 = 1, DT_C64 = 2, DT_C128 = 3, DT_F16 = 4, DT_BF16 = 5 };
 enum { MODE_TRUTH = 0, MODE_TIMED = 1, MODE_LITERAL = 2 };
 enum { OP_IDENTITY = 0, OP_CONJ = 1 };
 
@@ -194,6 +194,44 @@ inline half16 operator*(half16 a, half16 b) { return half16((long double)a * (lo
 inline half16 operator+(half16 a, half16 b) { return half16((long double)a + (long double)b); }
 inline bool operator==(half16 a, half16 b) { return (long double)a == (long double)b; }
 
+// bfloat16: the upper half of an IEEE binary32 -- 1 sign bit, 8 exponent bits (bias 127), 7 fraction
+// bits; exponent field 0 holds zero and the subnormals (multiples of 2^-133), 255 infinities and
+// NaNs.  Same two conversions: widening exact, narrowing ONE rounding to nearest, ties to even.
+struct bfloat16 {
+    uint16_t bits;
+    bfloat16() : bits(0) {}
+    bfloat16(long double x) {
+        const uint16_t sign = std::signbit(x) ? 0x8000u : 0u;
+        long double a = fabsl(x);
+        if (std::isnan(x)) { bits = sign | 0x7fc0u; return; }
+        if (a == 0.0L) { bits = sign; return; }
+        if (std::isinf(x)) { bits = sign | 0x7f80u; return; }
+        int e = ilogbl(a);
+        if (e < -126) e = -126;
+        const long double quantum = ldexpl(1.0L, e - 7);
+        a = nearbyintl(a / quantum) * quantum;
+        if (a >= ldexpl(1.0L, 128)) { bits = sign | 0x7f80u; return; }
+        if (a == 0.0L) { bits = sign; return; }
+        const int e2 = ilogbl(a);
+        if (e2 < -126) bits = sign | (uint16_t)(a / ldexpl(1.0L, -133));
+        else bits = sign | (uint16_t)((e2 + 127) << 7) | (uint16_t)((long long)(a / ldexpl(1.0L, e2 - 7)) - 128);
+    }
+    bfloat16(double x) : bfloat16((long double)x) {}
+    bfloat16(float x) : bfloat16((long double)x) {}
+    bfloat16(int x) : bfloat16((long double)x) {}
+    operator long double() const {
+        const int ef = (bits >> 7) & 255, frac = bits & 127;
+        long double a;
+        if (ef == 255) a = frac ? (long double)NAN : (long double)INFINITY;
+        else if (ef == 0) a = ldexpl((long double)frac, -133);
+        else a = ldexpl((long double)(128 + frac), ef - 134);
+        return (bits & 0x8000u) ? -a : a;
+    }
+};
+inline bfloat16 operator*(bfloat16 a, bfloat16 b) { return bfloat16((long double)a * (long double)b); }
+inline bfloat16 operator+(bfloat16 a, bfloat16 b) { return bfloat16((long double)a + (long double)b); }
+inline bool operator==(bfloat16 a, bfloat16 b) { return (long double)a == (long double)b; }
+
 // ---- element access helpers -------------------------------------------------------
 template <class T> struct Real { using type = T; };
 template <class R> struct Real<std::complex<R>> { using type = R; };
@@ -217,6 +255,7 @@ inline long double modulus(long double x) { return fabsl(x); }
 inline long double modulus(std::complex<long double> x) { return hypotl(x.real(), x.imag()); }
 inline double modulus(double x) { return std::fabs(x); }
 inline long double modulus(half16 x) { return fabsl((long double)x); }
+inline long double modulus(bfloat16 x) { return fabsl((long double)x); }
 inline float modulus(float x) { return std::fabs(x); }
 inline double modulus(std::complex<double> x) { return std::hypot(x.real(), x.imag()); }
 inline float modulus(std::complex<float> x) { return std::hypot(x.real(), x.imag()); }
@@ -438,6 +477,13 @@ int oracle_contract(int dtype, int mode,
         else
             contract<half16, float>(mode, free_loops, sum_loops, only_A, only_B, opA, opB, opC, (float)alpha[0], (float)beta[0],
                                     (const half16*)A, (const half16*)B, (const half16*)C, (half16*)D, S);
+    } else if (dtype == DT_BF16) {
+        if (mode == MODE_TRUTH)
+            contract<bfloat16, long double>(mode, free_loops, sum_loops, only_A, only_B, opA, opB, opC, alpha[0], beta[0],
+                                            (const bfloat16*)A, (const bfloat16*)B, (const bfloat16*)C, (bfloat16*)D, S);
+        else
+            contract<bfloat16, float>(mode, free_loops, sum_loops, only_A, only_B, opA, opB, opC, (float)alpha[0], (float)beta[0],
+                                      (const bfloat16*)A, (const bfloat16*)B, (const bfloat16*)C, (bfloat16*)D, S);
     } else {
         return V_BAD_ARG;
     }
@@ -447,6 +493,8 @@ int oracle_contract(int dtype, int mode,
 // The two 16-bit conversions on their own, for the tests that pin them.
 uint16_t oracle_half_from_double(double x) { return half16(x).bits; }
 double oracle_half_to_double(uint16_t bits) { half16 h; h.bits = bits; return (double)(long double)h; }
+uint16_t oracle_bfloat16_from_double(double x) { return bfloat16(x).bits; }
+double oracle_bfloat16_to_double(uint16_t bits) { bfloat16 h; h.bits = bits; return (double)(long double)h; }
 
 int oracle_max_threads(void);
 }

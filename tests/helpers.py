@@ -25,25 +25,32 @@ def run_oracle(p: W.Problem, bufA, bufB, bufC, mode=oracle.MODE_TRUTH, want_S=Fa
     return bufD, S
 
 
-UNIT_ROUNDOFF = {"f32": 2.0 ** -24, "f64": 2.0 ** -53, "c128": 2.0 ** -53, "c64": 2.0 ** -24, "f16": 2.0 ** -11}
+UNIT_ROUNDOFF = {"f32": 2.0 ** -24, "f64": 2.0 ** -53, "c128": 2.0 ** -53, "c64": 2.0 ** -24, "f16": 2.0 ** -11,
+                 "bf16": 2.0 ** -8}
 # Gate of the error measure |d - d_truth| / (|alpha| S + |beta| |c|), S = sum |a||b|.
 # 16-bit tensors are computed in 32-bit (or 64-bit) arithmetic and rounded to storage once: the
 # error is one 16-bit rounding of d, at most 2^-11 |d| <= 2^-11 (|alpha| S + |beta||c|), plus the
 # 32-bit accumulation error (|K| + 2) 2^-24 S; the gate is twice the rounding bound.
-TOLERANCE = {"f32": 1e-5, "f64": 1e-12, "c128": 1e-12, "c64": 1e-5, "f16": 2.0 ** -10}
+TOLERANCE = {"f32": 1e-5, "f64": 1e-12, "c128": 1e-12, "c64": 1e-5, "f16": 2.0 ** -10, "bf16": 2.0 ** -7}
 # 32-bit tensors computed with TCX_PREC_F64: sums are exact to 64-bit rounding, D is rounded to
 # storage once: |error| <= 2^-24 |d| (1 + small) <= 2^-24 (|alpha| S + |beta||c|); gate at twice that.
 TOLERANCE_WIDENED = 2.0 ** -23
+
+
+def values_of(p: W.Problem, buf, spec):
+    """The tensor `spec` inside `buf` as numbers (bfloat16 buffers hold bit patterns)."""
+    v = W.strided_view(buf, spec)
+    return W.bf16_values(v) if p.dtype == "bf16" else v
 
 
 def normalised_error(p: W.Problem, got, truth, S, bufC, alpha=None, beta=None):
     """max over the addressed elements of D of |got - truth| / (|alpha| S + |beta||c|)."""
     al = abs(p.alpha if alpha is None else alpha)
     be = abs(p.beta if beta is None else beta)
-    g = W.strided_view(got, p.D).astype(np.complex128 if p.dtype in ("c128", "c64") else np.float64)
-    t = W.strided_view(truth, p.D).astype(g.dtype)
+    g = values_of(p, got, p.D).astype(np.complex128 if p.dtype in ("c128", "c64") else np.float64)
+    t = values_of(p, truth, p.D).astype(g.dtype)
     s = W.strided_view(S, p.D)
-    c = np.abs(W.strided_view(bufC, p.D).astype(g.dtype)) if be != 0 else 0.0
+    c = np.abs(values_of(p, bufC, p.D).astype(g.dtype)) if be != 0 else 0.0
     den = al * s + be * c
     num = np.abs(g - t)
     tiny = np.finfo(np.float64).tiny

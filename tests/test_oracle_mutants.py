@@ -44,6 +44,11 @@ MUTANTS = [
     ("half_ties_away_from_zero", "const long double n = nearbyintl(a / quantum);", "const long double n = roundl(a / quantum);"),
     ("half_subnormal_grid_too_fine", "if (e < -14) e = -14;", "if (e < -15) e = -15;"),
     ("half_exponent_bias_off_by_one", "else a = ldexpl((long double)(1024 + frac), ef - 25);", "else a = ldexpl((long double)(1024 + frac), ef - 24);"),
+    ("bfloat16_rounding_truncates", "a = nearbyintl(a / quantum) * quantum;", "a = floorl(a / quantum) * quantum;"),
+    ("bfloat16_ties_away_from_zero", "a = nearbyintl(a / quantum) * quantum;", "a = roundl(a / quantum) * quantum;"),
+    ("bfloat16_subnormal_grid_too_fine", "if (e < -126) e = -126;", "if (e < -127) e = -127;"),
+    ("bfloat16_exponent_bias_off_by_one", "else a = ldexpl((long double)(128 + frac), ef - 134);", "else a = ldexpl((long double)(128 + frac), ef - 133);"),
+    ("bfloat16_fraction_keeps_hidden_bit", "(uint16_t)((long long)(a / ldexpl(1.0L, e2 - 7)) - 128);", "(uint16_t)((long long)(a / ldexpl(1.0L, e2 - 7)) - 127);"),
     ("half_overflow_limit_too_high", "if (a >= 65536.0L) { bits = sign | 0x7c00u; return; }", "if (a >= 131072.0L) { bits = sign | 0x7c00u; return; }"),
 ]
 
@@ -65,6 +70,8 @@ def _pins_to_run():
         calls.append((pins.test_isolated_labels_brute_force, ("f64", seed)))
     calls.append((pins.test_half_from_double_rounds_to_nearest_even, ()))
     calls.append((pins.test_half_to_double_on_every_bit_pattern, ()))
+    calls.append((pins.test_bfloat16_from_double_rounds_to_nearest_even, ()))
+    calls.append((pins.test_bfloat16_to_double_on_every_bit_pattern, ()))
     calls += [(pins.test_case4_example_is_a_reduction_then_a_contraction, ()), (pins.test_case5_broadcasts_the_product, ())]
     calls += [(pins.test_repeated_label_equals_summed_stride, ()), (pins.test_validation_classes, ()),
               (pins.test_conjugation_symmetry_and_op_equals_preconjugated_copy, ()),
@@ -94,6 +101,10 @@ def test_a_pin_catches_the_planted_mistake(mutant, monkeypatch):
         bad.oracle_half_from_double.argtypes = [ctypes.c_double]
         bad.oracle_half_to_double.restype = ctypes.c_double
         bad.oracle_half_to_double.argtypes = [ctypes.c_uint16]
+        bad.oracle_bfloat16_from_double.restype = ctypes.c_uint16
+        bad.oracle_bfloat16_from_double.argtypes = [ctypes.c_double]
+        bad.oracle_bfloat16_to_double.restype = ctypes.c_double
+        bad.oracle_bfloat16_to_double.argtypes = [ctypes.c_uint16]
         oracle._load()
         monkeypatch.setattr(oracle, "_lib", bad)
         caught = 0

@@ -15,7 +15,7 @@ import pytest
 
 import oracle
 import workloads as W
-from helpers import UNIT_ROUNDOFF, desc, gaps_untouched, normalised_error, random_problem, run_oracle
+from helpers import UNIT_ROUNDOFF, desc, gaps_untouched, normalised_error, random_problem, run_oracle, values_of
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -44,7 +44,7 @@ def brute_exact(p: W.Problem, bufA, bufB, bufC):
     """Exact D as {D index tuple: (Fraction re, Fraction im)}: one pass over the whole index
     space of all distinct labels, each term scattered to its D entry (Eq. case2, read as
     "for every assignment of the labels")."""
-    vA, vB, vC = W.strided_view(bufA, p.A), W.strided_view(bufB, p.B), W.strided_view(bufC, p.D)
+    vA, vB, vC = values_of(p, bufA, p.A), values_of(p, bufB, p.B), values_of(p, bufC, p.D)
     ext = p.extent_of()
     labels = sorted(ext)
     out = {}
@@ -153,6 +153,84 @@ def test_f16_uniform_inputs_round_once():
             for key, val in exact.items():
                 want = np.float16(float(val[0]))          # float(Fraction) is exact here (few terms of 20-bit products)
                 assert v[key] == want, (p, key, mode, v[key], want)
+
+
+# ---- bfloat16 storage: pinned to the format's definition (the upper half of a binary32) -------
+def test_bfloat16_to_double_on_every_bit_pattern():
+    with np.errstate(invalid="ignore"):
+        ref = W.bf16_values(np.arange(65536, dtype=np.uint16)).astype(np.float64)
+    for b in range(65536):
+        got = oracle.bfloat16_to_double(b)
+        if np.isnan(ref[b]):
+            assert np.isnan(got)
+        else:
+            assert got == ref[b] and np.signbit(got) == np.signbit(ref[b]), hex(b)
+
+
+def _nearest_bfloat16(x: float) -> int:
+    """Round to nearest, ties to the even bit pattern, by exact rational comparison with the
+    two neighbouring values out of the table of all finite ones; past the midpoint between the
+    largest value and 2^128: infinity."""
+    pos = W.bf16_values(np.arange(0, 0x7f80, dtype=np.uint16)).astype(np.float64)
+    sign, a = (0x8000 if np.signbit(x) else 0), abs(x)
+    if a == float("inf"):
+        return sign | 0x7f80
+    hi = int(np.searchsorted(pos, a, side="left"))          # first value >= a
+    if hi < len(pos) and pos[hi] == a:
+        return sign | hi
+    lo = hi - 1
+    top = Fraction(float(pos[hi])) if hi < len(pos) else Fraction(2) ** 128
+    dl, dh = Fraction(a) - Fraction(float(pos[lo])), top - Fraction(a)
+    pick = lo if dl < dh else hi if dh < dl else (lo if lo % 2 == 0 else hi)
+    return sign | pick          # pick == 0x7f80 is the pattern of infinity
+
+
+def test_bfloat16_from_double_rounds_to_nearest_even():
+    """Random doubles over the whole range (normal, subnormal, overflowing), every 5th midpoint
+    between neighbouring values (ties to even) and the doubles just beside midpoints; and, on
+    float32 inputs, torch's own float32 -> bfloat16 conversion."""
+    import torch
+    rng = np.random.default_rng(17)
+    big = float(W.bf16_values(np.array([0x7f7f], dtype=np.uint16))[0])
+    xs = [0.0, -0.0, big, big * (1 + 2.0 ** -9), big * (1 + 2.0 ** -8), 2.0 ** 128, 1e39, 2.0 ** -133, 2.0 ** -134, 2.0 ** -134 * (1 + 2.0 ** -40),
+          3 * 2.0 ** -134, 2.0 ** -126, 2.0 ** -126 - 2.0 ** -134, 1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -40, float("inf")]
+    xs += list(rng.uniform(-1, 1, 2000) * 10.0 ** rng.integers(-42, 39, 2000))
+    pos = W.bf16_values(np.arange(0, 0x7f80, dtype=np.uint16)).astype(np.float64)
+    mid = (pos[:-1] + pos[1:]) / 2
+    xs += list(mid[::5]) + list(np.nextafter(mid[::11], np.inf)) + list(np.nextafter(mid[::13], -np.inf))
+    for x in xs:
+        for v in (float(x), -float(x)):
+            assert oracle.bfloat16_from_double(v) == _nearest_bfloat16(v), v
+    f = (rng.uniform(-1, 1, 4000) * 10.0 ** rng.integers(-40, 38, 4000)).astype(np.float32)
+    want = torch.from_numpy(f).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    for v, w in zip(f, want):
+        assert oracle.bfloat16_from_double(float(v)) == int(w), v
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_bfloat16_brute_force(seed):
+    """bfloat16 tensors (buffers of bit patterns).  Integer inputs: all three evaluation orders
+    equal the rational result bit for bit.  Uniform inputs (multiples of 2^-7, a handful of
+    terms: every product and sum exact in any wider type): the truth and the float-sum order are
+    the exact result rounded ONCE to 8 significant bits."""
+    rng = np.random.default_rng(2700 + seed)
+    p = random_problem(rng, "bf16", allow_neg=(seed % 2 == 1))
+    a, b, c = W.make_operands(p, "ints")
+    exact = brute_exact(p, a, b, c)
+    for mode in (oracle.MODE_TRUTH, oracle.MODE_TIMED, oracle.MODE_LITERAL):
+        d, _ = run_oracle(p, a, b, c, mode)
+        v = values_of(p, d, p.D)
+        for key, val in exact.items():
+            assert float(v[key]) == float(val[0]), (p, key, mode)
+        assert gaps_untouched(p, c, d)
+    p = dataclasses.replace(random_problem(rng, "bf16", max_extent=3), alpha=0.5, beta=-2.0)
+    a, b, c = W.make_operands(p, "uniform")
+    exact = brute_exact(p, a, b, c)
+    for mode in (oracle.MODE_TRUTH, oracle.MODE_TIMED):
+        d, _ = run_oracle(p, a, b, c, mode)
+        v = W.strided_view(d, p.D)
+        for key, val in exact.items():
+            assert int(v[key]) == _nearest_bfloat16(float(val[0])), (p, key, mode)      # float(Fraction) exact: few terms of 16-bit products
 
 
 def test_S_is_sum_of_moduli():

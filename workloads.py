@@ -60,9 +60,29 @@ def mix64(seed: int, tag: int, idx: np.ndarray) -> np.ndarray:
     return _hashed(seed, tag, idx, np.uint64, lambda h: h)
 
 
+# numpy has no bfloat16.  A bfloat16 is the upper half of a float32, so buffers of that type are
+# uint16 arrays of bit patterns (dtype "bf16" <-> np.uint16 throughout this module), and the two
+# functions below only move bits: no rounding happens here, a value that is not a bfloat16 is an error.
+BF16 = np.dtype(np.uint16)
+
+
+def bf16_bits(x) -> np.ndarray:
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    assert not np.any(u & np.uint32(0xffff)), "not a bfloat16 value"
+    return (u >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_values(bits) -> np.ndarray:
+    return (np.asarray(bits).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
 def uniform_pm1(seed: int, tag: int, idx: np.ndarray, dtype) -> np.ndarray:
-    """Uniform on [-1, 1): 53 random bits for float64, 24 for float32, 11 for float16 (all exact)."""
+    """Uniform on [-1, 1): 53 random bits for float64, 24 for float32, 11 for float16, 8 for
+    bfloat16 (all exact)."""
     dtype = np.dtype(dtype)
+    if dtype == BF16:            # 8 random bits: multiples of 2^-7, all of them bfloat16 values
+        return bf16_bits(_hashed(seed, tag, idx, np.float32,
+                                 lambda h: (h >> np.uint64(56)).astype(np.float32) * np.float32(2.0 ** -7) - np.float32(1.0)))
     if dtype in (np.complex128, np.complex64):
         real = np.float64 if dtype == np.complex128 else np.float32
         out = np.empty(np.shape(idx), dtype=dtype)
@@ -85,6 +105,8 @@ def uniform_pm1(seed: int, tag: int, idx: np.ndarray, dtype) -> np.ndarray:
 def normal01(seed: int, tag: int, idx: np.ndarray, dtype) -> np.ndarray:
     """Standard normal by Box-Muller on two hashed uniforms (host only)."""
     dtype = np.dtype(dtype)
+    if dtype == BF16:
+        raise ValueError("normal entries are not bfloat16 values; use uniform, ints or ones")
     if dtype in (np.complex128, np.complex64):
         re = normal01(seed, tag, idx.astype(np.uint64) * np.uint64(2), np.float64)
         im = normal01(seed, tag, idx.astype(np.uint64) * np.uint64(2) + np.uint64(1), np.float64)
@@ -99,6 +121,8 @@ def normal01(seed: int, tag: int, idx: np.ndarray, dtype) -> np.ndarray:
 def small_ints(seed: int, tag: int, idx: np.ndarray, dtype, lo: int = -4, hi: int = 4) -> np.ndarray:
     """Integer-valued entries in [lo, hi]: every partial sum of products is exact."""
     dtype = np.dtype(dtype)
+    if dtype == BF16:
+        return bf16_bits(small_ints(seed, tag, idx, np.float32, lo, hi))
     span = np.uint64(hi - lo + 1)
     if dtype in (np.complex128, np.complex64):
         re = small_ints(seed, tag, idx.astype(np.uint64) * np.uint64(2), np.float64, lo, hi)
@@ -109,6 +133,8 @@ def small_ints(seed: int, tag: int, idx: np.ndarray, dtype, lo: int = -4, hi: in
 
 
 def ones(seed, tag, idx, dtype):
+    if np.dtype(dtype) == BF16:
+        return bf16_bits(np.ones(idx.shape, dtype=np.float32))
     return np.ones(idx.shape, dtype=dtype)
 
 
@@ -165,7 +191,7 @@ def tensor(labels: Sequence[str], extent_of: Dict[str, int], memory_order: Optio
 @dataclass(frozen=True)
 class Problem:
     name: str
-    dtype: str                        # "f32" | "f64" | "c64" | "c128" | "f16"
+    dtype: str                        # "f32" | "f64" | "c64" | "c128" | "f16" | "bf16"
     A: TensorSpec
     B: TensorSpec
     D: TensorSpec                     # C shares D's description
@@ -180,7 +206,8 @@ class Problem:
 
     @property
     def np_dtype(self):
-        return {"f32": np.float32, "f64": np.float64, "c64": np.complex64, "c128": np.complex128, "f16": np.float16}[self.dtype]
+        return {"f32": np.float32, "f64": np.float64, "c64": np.complex64, "c128": np.complex128, "f16": np.float16,
+                "bf16": np.uint16}[self.dtype]
 
     def extent_of(self) -> Dict[str, int]:
         out: Dict[str, int] = {}
@@ -257,6 +284,8 @@ def fill(spec: TensorSpec, seed: int, tag: int, dtype, dist: str = "uniform", ba
     dtype = np.dtype(dtype)
     if background is None:
         background = -777.0
+    if dtype == BF16:
+        background = bf16_bits(np.float32(-768.0 if background == -777.0 else background)).reshape(())[()]
     buf = np.full(spec.size, background, dtype=dtype)
     strided_view(buf, spec)[...] = logical_values(spec, seed, tag, dtype, dist)
     return buf
