@@ -67,10 +67,11 @@ typedef intptr_t tcx_status_t;
 
 /* Element types (Sec. "The Reference Implementation": real and complex, 64 and 32 bit, and real
  * 16 bit; the four tensors of a product share one).  Complex elements are (re, im) pairs of their
- * real type.  TCX_F16 is IEEE 754 binary16: the tensors hold 16-bit elements, products and sums
- * are formed in 32-bit reals (TCX_PREC_DEFAULT) or 64-bit reals (TCX_PREC_F64), D is rounded to
- * 16 bits once, on the store (to nearest, ties to even), and alpha and beta are passed as floats. */
-typedef enum { TCX_F32 = 0, TCX_F64 = 1, TCX_C64 = 2, TCX_C128 = 3, TCX_F16 = 4 } tcx_dtype_t;
+ * real type.  TCX_F16 is IEEE 754 binary16 and TCX_BF16 is bfloat16 (the upper half of a binary32):
+ * the tensors hold 16-bit elements, products and sums are formed in 32-bit reals
+ * (TCX_PREC_DEFAULT) or 64-bit reals (TCX_PREC_F64), D is rounded to 16 bits once, on the store
+ * (to nearest, ties to even), and alpha and beta are passed as floats. */
+typedef enum { TCX_F32 = 0, TCX_F64 = 1, TCX_C64 = 2, TCX_C128 = 3, TCX_F16 = 4, TCX_BF16 = 5 } tcx_dtype_t;
 typedef enum { TCX_OP_IDENTITY = 0, TCX_OP_CONJ = 1 } tcx_op_t;          /* conj of a real type is the identity */
 /* The plan's "desired computational precision" (Sec. "Tensor Operation Descriptors").
  *   TCX_PREC_DEFAULT  products and sums in the dtype's own real type (fp32 means fp32 MFMA; 16-bit

@@ -28,7 +28,7 @@ if not os.path.exists(LIB_PATH):
 _lib = ctypes.CDLL(LIB_PATH)
 
 # ---- constants of include/tcx.h ------------------------------------------------------------
-TCX_F32, TCX_F64, TCX_C64, TCX_C128, TCX_F16 = 0, 1, 2, 3, 4
+TCX_F32, TCX_F64, TCX_C64, TCX_C128, TCX_F16, TCX_BF16 = 0, 1, 2, 3, 4, 5
 TCX_OP_IDENTITY, TCX_OP_CONJ = 0, 1
 TCX_PREC_DEFAULT, TCX_PREC_F64 = 0, 1
 TCX_PATH_GENERIC, TCX_PATH_GETT_MFMA, TCX_PATH_BANDWIDTH = 0, 1, 2
@@ -221,7 +221,7 @@ def tcx_product_set(product: int, key: int, value: int) -> None:
 
 
 def _scalar(dtype: int, x):
-    if dtype in (TCX_F32, TCX_F16):          # 16-bit tensors take their scalars as floats
+    if dtype in (TCX_F32, TCX_F16, TCX_BF16):          # 16-bit tensors take their scalars as floats
         return ctypes.c_float(float(x))
     if dtype == TCX_F64:
         return ctypes.c_double(float(x))

@@ -25,7 +25,8 @@ static __device__ __align__(256) unsigned char scratch[TCX_SCRATCH_BYTES];
 // that a unary or binary operation is planned as (C := alpha A + beta B  is  alpha A * 1 + beta B).
 static __device__ __align__(16) double one_in_64_bits[2] = {1.0, 0.0};
 static __device__ __align__(16) float one_in_32_bits[2] = {1.0f, 0.0f};
-static __device__ __align__(16) unsigned short one_in_16_bits[2] = {0x3c00u, 0u};      // IEEE binary16 1.0
+static __device__ __align__(16) unsigned short one_in_16_bits[16] = {0x3c00u, 0, 0, 0, 0, 0, 0, 0,       // 1.0 as IEEE binary16
+                                                                     0x3f80u, 0, 0, 0, 0, 0, 0, 0};      // 16 bytes on: as bfloat16
 
 namespace tcx {
 namespace {
@@ -904,12 +905,14 @@ tcx_error_t run_product(tcx_product_t product, tcx_executor_t executor, tcx_stat
     if (!alpha || !beta || !D) return TCX_ERR_NULL_ARG;
     if (kind != KIND_CONTRACTION) {
         const int rb = real_bytes_of(p->an.dtype);
-        B = rb == 2 ? e->handle.one16 : rb == 4 ? e->handle.one32 : e->handle.one64;
+        B = rb == 4 ? e->handle.one32 : rb == 8 ? e->handle.one64 : e->handle.one16;
+        if (B && p->an.dtype == TCX_BF16) B = (const char*)B + 16;
     }
     Scalars s{0, 0, 0, 0};
     switch (p->an.dtype) {
         case TCX_F32:
-        case TCX_F16:                        // 16-bit tensors take their scalars as floats
+        case TCX_F16:
+        case TCX_BF16:                       // 16-bit tensors take their scalars as floats
             s.alpha_re = *(const float*)alpha; s.beta_re = *(const float*)beta; break;
         case TCX_F64: s.alpha_re = *(const double*)alpha; s.beta_re = *(const double*)beta; break;
         case TCX_C64:

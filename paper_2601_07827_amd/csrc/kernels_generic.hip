@@ -6,6 +6,7 @@
 // the fallback for shapes the tiled kernels do not take.
 #include <hip/hip_runtime.h>
 
+#include "bf16.hpp"
 #include "tcx_internal.hpp"
 
 namespace tcx {
@@ -145,6 +146,10 @@ int launch_reduce(int dtype, int precision, const ReduceArgs& args, void* stream
             if (precision == TCX_PREC_F64) reduce_operand<RealNum<_Float16, double>><<<gr, bl, 0, st>>>(args);
             else reduce_operand<RealNum<_Float16, float>><<<gr, bl, 0, st>>>(args);
             break;
+        case TCX_BF16:
+            if (precision == TCX_PREC_F64) reduce_operand<RealNum<bf16_t, double>><<<gr, bl, 0, st>>>(args);
+            else reduce_operand<RealNum<bf16_t, float>><<<gr, bl, 0, st>>>(args);
+            break;
         case TCX_C128: reduce_operand<ComplexNum<double, double>><<<gr, bl, 0, st>>>(args); break;
         case TCX_C64:
             if (wide) reduce_operand<ComplexNum<float, double>><<<gr, bl, 0, st>>>(args);
@@ -172,6 +177,10 @@ int launch_generic(int dtype, int precision, const GenericArgs& args, void* stre
         case TCX_F16:
             if (precision == TCX_PREC_F64) generic_contract<RealNum<_Float16, double>><<<gr, bl, 0, st>>>(args);
             else generic_contract<RealNum<_Float16, float>><<<gr, bl, 0, st>>>(args);
+            break;
+        case TCX_BF16:
+            if (precision == TCX_PREC_F64) generic_contract<RealNum<bf16_t, double>><<<gr, bl, 0, st>>>(args);
+            else generic_contract<RealNum<bf16_t, float>><<<gr, bl, 0, st>>>(args);
             break;
         case TCX_C128: generic_contract<ComplexNum<double, double>><<<gr, bl, 0, st>>>(args); break;
         case TCX_C64:

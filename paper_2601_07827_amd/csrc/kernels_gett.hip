@@ -26,6 +26,7 @@
 #include <algorithm>
 #include <type_traits>
 
+#include "bf16.hpp"
 #include "tcx_internal.hpp"
 
 namespace tcx {
@@ -1666,7 +1667,7 @@ hipError_t launch_wide_shape(int variant, bool akf, bool bkf, bool dnf, const Ge
 
 const Shape* shapes_of(int dtype, int* n) {
     if (dtype == TCX_C128 || dtype == TCX_C64) { *n = kNumComplexShapes; return kComplexShapes; }
-    if (dtype == TCX_F64 || dtype == TCX_F32 || dtype == TCX_F16) { *n = kNumRealShapes; return kRealShapes; }
+    if (dtype == TCX_F64 || dtype == TCX_F32 || dtype == TCX_F16 || dtype == TCX_BF16) { *n = kNumRealShapes; return kRealShapes; }
     *n = 0;
     return nullptr;
 }
@@ -1720,6 +1721,9 @@ int launch_gett(int dtype, int precision, int variant, bool a_kf, bool b_kf, boo
         case TCX_F16:        // 16-bit storage is always widened: fp32 MFMAs by default, fp64 on request
             if (precision == TCX_PREC_F64) return (int)launch_wide_shape<RealPolicy<double, _Float16>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
             return (int)launch_wide_shape<RealPolicy<float, _Float16>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
+        case TCX_BF16:
+            if (precision == TCX_PREC_F64) return (int)launch_wide_shape<RealPolicy<double, bf16_t>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
+            return (int)launch_wide_shape<RealPolicy<float, bf16_t>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
         case TCX_C128: return (int)launch_complex_shape<ComplexPolicyT<double>>(variant, a_kf, b_kf, d_nf, args, blocks, st);
         case TCX_C64:
             if (wide) return (int)launch_wide_shape<ComplexPolicyT<double, float>>(variant, a_kf, b_kf, d_nf, args, blocks, st);

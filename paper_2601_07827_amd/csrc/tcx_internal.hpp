@@ -17,11 +17,11 @@ struct Mode {
 };
 
 // ---- element types --------------------------------------------------------------------
-inline int elem_bytes_of(int dtype) { return dtype == TCX_F16 ? 2 : dtype == TCX_F32 ? 4 : dtype == TCX_C128 ? 16 : 8; }
-inline int real_bytes_of(int dtype) { return dtype == TCX_F16 ? 2 : dtype == TCX_F32 || dtype == TCX_C64 ? 4 : 8; }   // of the storage type
+inline int elem_bytes_of(int dtype) { return dtype == TCX_F16 || dtype == TCX_BF16 ? 2 : dtype == TCX_F32 ? 4 : dtype == TCX_C128 ? 16 : 8; }
+inline int real_bytes_of(int dtype) { return dtype == TCX_F16 || dtype == TCX_BF16 ? 2 : dtype == TCX_F32 || dtype == TCX_C64 ? 4 : 8; }   // of the storage type
 inline bool is_complex(int dtype) { return dtype == TCX_C64 || dtype == TCX_C128; }
 inline bool valid_dtype(int dtype) {
-    return dtype == TCX_F32 || dtype == TCX_F64 || dtype == TCX_C64 || dtype == TCX_C128 || dtype == TCX_F16;
+    return dtype == TCX_F32 || dtype == TCX_F64 || dtype == TCX_C64 || dtype == TCX_C128 || dtype == TCX_F16 || dtype == TCX_BF16;
 }
 // Reals that products and sums are formed in: the storage type's own, 32 bits for 16-bit storage,
 // 64 bits for every plan in TCX_PREC_F64.

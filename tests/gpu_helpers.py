@@ -8,7 +8,7 @@ import numpy as np
 
 import workloads as W
 
-DT = {"f32": 0, "f64": 1, "c64": 2, "c128": 3, "f16": 4}
+DT = {"f32": 0, "f64": 1, "c64": 2, "c128": 3, "f16": 4, "bf16": 5}
 
 
 def say(msg: str):

@@ -77,7 +77,7 @@ def test_handle_lifecycle_and_null_conventions(handle):
 
 def test_tensor_info_errors_and_roundtrip(handle):
     assert _code(T.tcx_create_tensor_info, handle, 7, [2], [1]) == T.TCX_ERR_BAD_DTYPE
-    assert _code(T.tcx_create_tensor_info, handle, 5, [2], [1]) == T.TCX_ERR_BAD_DTYPE
+    assert _code(T.tcx_create_tensor_info, handle, 6, [2], [1]) == T.TCX_ERR_BAD_DTYPE
     assert _code(T.tcx_create_tensor_info, handle, -1, [2], [1]) == T.TCX_ERR_BAD_DTYPE
     assert _code(T.tcx_create_tensor_info, handle, T.TCX_F64, [1] * 33, [1] * 33) == T.TCX_ERR_BAD_NMODE
     assert _code(T.tcx_create_tensor_info, handle, T.TCX_F64, [3, 0], [1, 3]) == T.TCX_ERR_BAD_EXTENT
@@ -574,14 +574,15 @@ def test_plan_precision(handle):
             T.tcx_destroy_tensor_info(i)
 
 
-def test_sixteen_bit_plans(handle):
-    """TCX_F16 (Sec. "The Reference Implementation": real types of 16 bit): storage is always
+@pytest.mark.parametrize("dt16", [T.TCX_F16, T.TCX_BF16], ids=["f16", "bf16"])
+def test_sixteen_bit_plans(handle, dt16):
+    """TCX_F16, TCX_BF16 (Sec. "The Reference Implementation": real types of 16 bit): storage is always
     narrower than the arithmetic, so both precisions plan on the generic kernel or the two widened
     tile shapes and never on the streaming path; a low-intensity product falls to them as well;
     the four tensors must share the dtype."""
     e = dict(m=300, n=200, k=64)
     A, B, D = W.tensor("mk", e), W.tensor("kn", e), W.tensor("mn", e)
-    infos = [T.tcx_create_tensor_info(handle, T.TCX_F16, t.extents, t.strides) for t in (A, B, D)]
+    infos = [T.tcx_create_tensor_info(handle, dt16, t.extents, t.strides) for t in (A, B, D)]
     args = (handle, 0, infos[0], [1, 3], 0, infos[1], [3, 2], 0, infos[2], [1, 2], 0, infos[2], [1, 2])
     for prec in (T.TCX_PREC_DEFAULT, T.TCX_PREC_F64):
         plan = T.tcx_create_product(*args, prec)
@@ -602,7 +603,7 @@ def test_sixteen_bit_plans(handle):
     # an outer product of 16-bit vectors: not streamed, planned on the tiled or generic kernel
     e = dict(m=4096, n=4096)
     u, v, O = W.tensor("m", e), W.tensor("n", e), W.tensor("mn", e)
-    infos = [T.tcx_create_tensor_info(handle, T.TCX_F16, t.extents, t.strides) for t in (u, v, O)]
+    infos = [T.tcx_create_tensor_info(handle, dt16, t.extents, t.strides) for t in (u, v, O)]
     plan = T.tcx_create_product(handle, 0, infos[0], [1], 0, infos[1], [2], 0, infos[2], [1, 2], 0, infos[2], [1, 2])
     assert T.tcx_product_get(plan, T.TCX_KEY_PATH) in (T.TCX_PATH_GETT_MFMA, T.TCX_PATH_GENERIC)
     T.tcx_destroy_product(plan)

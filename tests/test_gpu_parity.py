@@ -8,7 +8,7 @@ import pytest
 
 import oracle
 import workloads as W
-from helpers import TOLERANCE, TOLERANCE_WIDENED, gaps_untouched, normalised_error, random_problem, run_oracle
+from helpers import TOLERANCE, TOLERANCE_WIDENED, gaps_untouched, normalised_error, random_problem, run_oracle, values_of
 
 pytestmark = pytest.mark.gpu
 
@@ -563,33 +563,34 @@ def test_unary_and_binary_operations(dtype):
     T.tcx_destroy_handle(h)
 
 
+@pytest.mark.parametrize("dt16", ["f16", "bf16"])
 @pytest.mark.parametrize("precision", [0, 1], ids=["arith32", "arith64"])
-def test_sixteen_bit_tensors(precision):
-    """TCX_F16 (Sec. "The Reference Implementation": real types of 16 bit): IEEE binary16 tensors,
+def test_sixteen_bit_tensors(precision, dt16):
+    """TCX_F16, TCX_BF16 (Sec. "The Reference Implementation": real types of 16 bit): IEEE binary16 or bfloat16 tensors,
     products and sums in 32-bit (default) or 64-bit reals, one rounding to 16 bits on the store;
     alpha and beta are floats.  A product with 2048 contracted terms on the generic kernel and on
-    both widened tile shapes, K unsplit and split, and on the plan's own choice (gate 2^-10 of the
-    normaliser: twice one 16-bit rounding); integer inputs bit for bit; random label patterns with
+    both widened tile shapes, K unsplit and split, and on the plan's own choice (gate: twice one 16-bit rounding of
+    the normaliser); integer inputs bit for bit; random label patterns with
     padded and negative strides, with labels of one tensor only (reduction kernel and broadcast);
     a binary operation."""
     import torch
     import paper_2601_07827_amd as T
     from gpu_helpers import DT, run_gpu, say
     e = dict(m=150, n=70, k=2048)
-    p = W.Problem("half_gemm", "f16", W.tensor("km", e), W.tensor("kn", e), W.tensor("mn", e), alpha=0.5, beta=-2.0, seed=W.BASE_SEED + 73)
+    p = W.Problem(dt16 + "_gemm", dt16, W.tensor("km", e), W.tensor("kn", e), W.tensor("mn", e), alpha=0.5, beta=-2.0, seed=W.BASE_SEED + 73)
     a, b, c = W.make_operands(p)
     truth, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
     for path, variant, split in [(GENERIC, None, None)] + [(GETT, v, sp) for v in (2, 3) for sp in (None, 4)] + [(None, None, None)]:
         say("%s path=%s shape=%s split=%s precision=%d" % (p.name, path, variant, split, precision))
         got = run_gpu(p, a, b, c, force_path=path, variant=variant, split_k=split, precision=precision)
         err = normalised_error(p, got, truth, S, c)
-        assert err <= TOLERANCE["f16"], (path, variant, split, err)
+        assert err <= TOLERANCE[dt16], (path, variant, split, err)
     a, b, c = W.make_operands(p, "ints")
-    q = W.Problem(p.name + "_ints", "f16", p.A, p.B, p.D, alpha=2.0, beta=-1.0, seed=p.seed)
+    q = W.Problem(p.name + "_ints", dt16, p.A, p.B, p.D, alpha=2.0, beta=-1.0, seed=p.seed)
     truth, _ = run_oracle(q, a, b, c, oracle.MODE_TRUTH)
     for path, variant in ((GENERIC, None), (GETT, 2), (GETT, 3)):
         got = run_gpu(q, a, b, c, force_path=path, variant=variant, precision=precision)
-        assert np.array_equal(W.strided_view(got, q.D), W.strided_view(truth, q.D))
+        assert np.array_equal(values_of(q, got, q.D), values_of(q, truth, q.D))
     # shapes the tiled path does not take for 16-bit tensors, and the streaming path, are refused
     for path, variant in ((GETT, 0), (GETT, 10), (STREAM, None)):
         with pytest.raises(T.TcxError) as exc:
@@ -597,33 +598,59 @@ def test_sixteen_bit_tensors(precision):
         assert exc.value.code == REFUSED
     rng = np.random.default_rng(1616 + precision)
     for i in range(24):
-        r = random_problem(rng, "f16", max_group=3, max_extent=6, allow_neg=(i % 3 == 0), name="rand%d_f16" % i, isolated=(i % 2 == 1))
+        r = random_problem(rng, dt16, max_group=3, max_extent=6, allow_neg=(i % 3 == 0), name="rand%d_%s" % (i, dt16), isolated=(i % 2 == 1))
         a, b, c = W.make_operands(r)
         truth, S = run_oracle(r, a, b, c, oracle.MODE_TRUTH, want_S=True)
         for path, variant in ((GENERIC, None), (GETT, 2 + i % 2), (None, None)):
             say("%s path=%s shape=%s precision=%d" % (r.name, path, variant, precision))
             got = run_gpu(r, a, b, c, force_path=path, variant=variant, precision=precision)
             assert gaps_untouched(r, c, got)
-            assert normalised_error(r, got, truth, S, c) <= TOLERANCE["f16"], (r, path, variant)
+            assert normalised_error(r, got, truth, S, c) <= TOLERANCE[dt16], (r, path, variant)
     # binary operation: C[g,y,h] := alpha sum_x A[x,h,g] + beta B[g,y,h]
     ext = dict(x=5, h=7, g=11, y=3)
     A, B = W.tensor("xhg", ext), W.tensor("gyh", ext, memory_order="hgy")
     ids = {l: i for i, l in enumerate("xhgy")}
-    av, bv = W.fill(A, 5, W.TAG_A, np.float16, "ints"), W.fill(B, 5, W.TAG_B, np.float16, "ints")
-    expect = (2.0 * W.strided_view(av, A).astype(np.float64).sum(axis=0).T[:, None, :] - 0.5 * W.strided_view(bv, B).astype(np.float64)).astype(np.float16)
+    npdt = p.np_dtype
+    q = W.Problem("binary", dt16, A, B, B)
+    av, bv = W.fill(A, 5, W.TAG_A, npdt, "ints"), W.fill(B, 5, W.TAG_B, npdt, "ints")
+    # halves of small integers: exact in either 16-bit type, so float64 arithmetic gives the stored value
+    expect = 2.0 * values_of(q, av, A).astype(np.float64).sum(axis=0).T[:, None, :] - 0.5 * values_of(q, bv, B).astype(np.float64)
     h = T.tcx_create_handle()
     ex = T.tcx_create_executor(h, torch.cuda.current_stream().cuda_stream)
-    ia, ib = (T.tcx_create_tensor_info(h, DT["f16"], t.extents, t.strides) for t in (A, B))
+    ia, ib = (T.tcx_create_tensor_info(h, DT[dt16], t.extents, t.strides) for t in (A, B))
     plan = T.tcx_create_binary(h, 0, ia, [ids[l] for l in A.labels], 0, ib, [ids[l] for l in B.labels], 0, ib, [ids[l] for l in B.labels], precision)
     dA, dB = torch.from_numpy(av).cuda(), torch.from_numpy(bv).cuda()
-    T.tcx_execute_binary(plan, ex, DT["f16"], 2.0, dA.data_ptr(), -0.5, dB.data_ptr(), dB.data_ptr())
+    T.tcx_execute_binary(plan, ex, DT[dt16], 2.0, dA.data_ptr(), -0.5, dB.data_ptr(), dB.data_ptr())
     torch.cuda.synchronize()
-    assert np.array_equal(W.strided_view(dB.cpu().numpy(), B), expect)
+    assert np.array_equal(values_of(q, dB.cpu().numpy(), B).astype(np.float64), expect)
     T.tcx_destroy_product(plan)
     for i in (ia, ib):
         T.tcx_destroy_tensor_info(i)
     T.tcx_destroy_executor(ex)
     T.tcx_destroy_handle(h)
+
+
+def test_bfloat16_store_rounds_once_from_64_bit_sums():
+    """TCX_BF16 with TCX_PREC_F64: the 64-bit sum is rounded to 16 bits in ONE step.  Two sums that a
+    detour over a 32-bit float would round the wrong way: 1 + 2^-8 + 2^-30 (a hair above the midpoint
+    of 1 and 1 + 2^-7; as a float it is the midpoint itself and the tie would go down to 1) and
+    1 + 2^-7 + 2^-8 - 2^-30 (a hair below the midpoint of 1 + 2^-7 and 1 + 2^-6; the tie would go
+    up).  Expected values: the oracle's, from its long-double sum."""
+    from gpu_helpers import run_gpu, say
+    e = dict(m=2, k=4, n=1)
+    p = W.Problem("bf16_round_once", "bf16", W.tensor("km", e), W.tensor("kn", e), W.tensor("mn", e), alpha=1.0, beta=0.0)
+    A = np.array([[1.0, 2.0 ** -8, 2.0 ** -15, 0.0], [1.0, 2.0 ** -7, 2.0 ** -8, -2.0 ** -15]], dtype=np.float32)      # [m][k]
+    B = np.array([1.0, 1.0, 2.0 ** -15, 2.0 ** -15], dtype=np.float32)
+    a = W.bf16_bits(A.reshape(-1))                       # k fastest, then m
+    b0, b1 = W.bf16_bits(B), W.bf16_bits(np.array([1.0, 1.0, 1.0, 2.0 ** -15], dtype=np.float32))
+    c = np.zeros(2, dtype=np.uint16)
+    for row, b in ((0, b0), (1, b1)):
+        truth, _ = run_oracle(p, a, b, c, oracle.MODE_TRUTH)
+        assert int(truth[row]) == 0x3f81, hex(int(truth[row]))          # both sums round to 1 + 2^-7
+        for path, variant in ((GENERIC, None), (GETT, 2), (GETT, 3)):
+            say("%s row=%d path=%s shape=%s" % (p.name, row, path, variant))
+            got = run_gpu(p, a, b, c, force_path=path, variant=variant, precision=1)
+            assert int(got[row]) == int(truth[row]), (row, path, variant, hex(int(got[row])))
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64"])
