@@ -335,13 +335,13 @@ def cpu_baseline(p: W.Problem):
 
 def config2_sample_indices(p: W.Problem, tile_m: int, tile_n: int, rng, rows=384, cols=192):
     """Rows and columns whose grid of samples (rows x cols of them, 73 728 by default) reaches every
-    launch round and, inside a round, the stretch of tiles of every XCD: tiles are walked in bands
-    of 8 tile rows (one round of 256 workgroups is one band of 8 x 32 tiles), and an XCD's stretch is
-    4 tile columns of a band.  The last row / column of every tile and the first of the next (every
-    tile boundary), the first and last two of the tensor, one seeded random row in every band and
-    column in every group of 4 tile columns, and seeded random ones up to the requested count."""
+    launch round and, inside a round, the stretch of tiles of every XCD: tiles wider than high are walked
+    in bands of 4 tile rows (one round of 256 workgroups is two bands of 4 x 32 tiles), and an XCD's
+    stretch is 8 tile columns of a band.  The last row / column of every tile and the first of the next
+    (every tile boundary), the first and last two of the tensor, one seeded random row in every band and
+    column in every group of 8 tile columns, and seeded random ones up to the requested count."""
     _, M, N, _ = p.sizes()
-    band, group = 8 * tile_m, 4 * tile_n
+    band, group = 4 * tile_m, 8 * tile_n
 
     def pick(extent, tile, stretch, want):
         idx = [0, 1, extent - 2, extent - 1]

@@ -274,14 +274,17 @@ struct Tile {
     int64_t hA, hB, hD;      // base offsets from the hyper index
 };
 
-// Tile number -> tile coordinates.  Tiles are walked in bands of 8 tile-rows; the hyper index
-// is the slowest (Eq. case2: an independent product per value of H).
+// Tile number -> tile coordinates.  Tiles are walked in bands of tile-rows, column by column
+// inside a band, so that the 32 consecutive tiles an XCD receives form a block that shares
+// operand panels through that XCD's L2: 8 rows x 4 columns of square tiles, 4 rows x 8 columns
+// of tiles that are higher than wide (the block's A panels + B panels are then fewest bytes).
+// The hyper index is the slowest (Eq. case2: an independent product per value of H).
 template <bool FAST = false>
 __device__ __forceinline__ Tile locate_tile(int64_t t_all, const GettArgs& g, int mt_m, int mt_n) {
     const int64_t tiles_per_h = (int64_t)g.tilesM * g.tilesN;
     const int64_t h = FAST ? quotient(t_all, tiles_per_h) : t_all / tiles_per_h;
     const int t = (int)(t_all - h * tiles_per_h);
-    constexpr int BAND = 8;
+    const int BAND = mt_m > mt_n ? 4 : 8;
     const int band = t / (BAND * g.tilesN);
     const int first_m = band * BAND;
     const int band_rows = min(BAND, g.tilesM - first_m);

@@ -67,8 +67,8 @@ def test_config_shapes_match_the_stated_sizes():
 
 def test_config2_samples_reach_every_launch_round_and_xcd_stretch():
     """The full-size check of configuration 2 compares a grid of rows x columns of D.  The 4608
-    tiles of 256 x 128 are walked in bands of 8 tile rows; a launch round is 256 consecutive tiles
-    of that order (one band), handed to the 8 XCDs in stretches of 32 consecutive tiles.  Every
+    tiles of 256 x 128 are walked in bands of 4 tile rows; a launch round is 256 consecutive tiles
+    of that order (two bands), handed to the 8 XCDs in stretches of 32 consecutive tiles (4 x 8).  Every
     (round, stretch) pair must hold a sample, or a wrong tile in one of them would go unseen."""
     import bench
     p = W.config2()
@@ -85,8 +85,8 @@ def test_config2_samples_reach_every_launch_round_and_xcd_stretch():
     for m in m_idx:
         for n in n_idx:
             row, col = int(m) // tm, int(n) // tn
-            band = row // 8
-            position = band * 8 * tiles_n + (row % 8) + 8 * col        # place in the tile order
+            band = row // 4
+            position = band * 4 * tiles_n + (row % 4) + 4 * col        # place in the tile order
             launch_round, in_round = divmod(position, 256)
             seen.add((launch_round, in_round // 32))
     assert seen == {(r, x) for r in range(tiles_m * tiles_n // 256) for x in range(8)}
