@@ -630,27 +630,35 @@ def test_sixteen_bit_tensors(precision, dt16):
     T.tcx_destroy_handle(h)
 
 
-def test_bfloat16_store_rounds_once_from_64_bit_sums():
-    """TCX_BF16 with TCX_PREC_F64: the 64-bit sum is rounded to 16 bits in ONE step.  Two sums that a
-    detour over a 32-bit float would round the wrong way: 1 + 2^-8 + 2^-30 (a hair above the midpoint
-    of 1 and 1 + 2^-7; as a float it is the midpoint itself and the tie would go down to 1) and
-    1 + 2^-7 + 2^-8 - 2^-30 (a hair below the midpoint of 1 + 2^-7 and 1 + 2^-6; the tie would go
-    up).  Expected values: the oracle's, from its long-double sum."""
+@pytest.mark.parametrize("dt16", ["f16", "bf16"])
+def test_sixteen_bit_store_rounds_once_from_64_bit_sums(dt16):
+    """16-bit tensors with TCX_PREC_F64: the 64-bit sum is rounded to 16 bits in ONE step.  With p
+    significant bits (11 for binary16, 8 for bfloat16) and u = 2^-p, two sums that a detour over a
+    32-bit float would round the wrong way: 1 + u + 2^-30 (a hair above the midpoint of 1 and
+    1 + 2u; as a float it is the midpoint itself and the tie would go down to 1) and
+    1 + 2u + u - 2^-30 (a hair below the midpoint of 1 + 2u and 1 + 4u; the tie would go up).
+    Both round to 1 + 2u.  Expected values: the oracle's, from its long-double sum."""
     from gpu_helpers import run_gpu, say
+    u = 2.0 ** -11 if dt16 == "f16" else 2.0 ** -8
+    one_plus_2u = 0x3c01 if dt16 == "f16" else 0x3f81
     e = dict(m=2, k=4, n=1)
-    p = W.Problem("bf16_round_once", "bf16", W.tensor("km", e), W.tensor("kn", e), W.tensor("mn", e), alpha=1.0, beta=0.0)
-    A = np.array([[1.0, 2.0 ** -8, 2.0 ** -15, 0.0], [1.0, 2.0 ** -7, 2.0 ** -8, -2.0 ** -15]], dtype=np.float32)      # [m][k]
-    B = np.array([1.0, 1.0, 2.0 ** -15, 2.0 ** -15], dtype=np.float32)
-    a = W.bf16_bits(A.reshape(-1))                       # k fastest, then m
-    b0, b1 = W.bf16_bits(B), W.bf16_bits(np.array([1.0, 1.0, 1.0, 2.0 ** -15], dtype=np.float32))
-    c = np.zeros(2, dtype=np.uint16)
+    p = W.Problem(dt16 + "_round_once", dt16, W.tensor("km", e), W.tensor("kn", e), W.tensor("mn", e), alpha=1.0, beta=0.0)
+
+    def encode(values):          # all of them 16-bit numbers (2^-15 is a subnormal of binary16)
+        v = np.asarray(values, dtype=np.float32)
+        return v.astype(np.float16) if dt16 == "f16" else W.bf16_bits(v)
+    a = encode([1.0, u, 2.0 ** -15, 0.0, 1.0, 2 * u, u, -2.0 ** -15])        # [m][k], k fastest
+    b0, b1 = encode([1.0, 1.0, 2.0 ** -15, 2.0 ** -15]), encode([1.0, 1.0, 1.0, 2.0 ** -15])
+    assert np.array_equal(a.astype(np.float64) if dt16 == "f16" else W.bf16_values(a).astype(np.float64),
+                          [1.0, u, 2.0 ** -15, 0.0, 1.0, 2 * u, u, -2.0 ** -15])
+    c = np.zeros(2, dtype=p.np_dtype)
     for row, b in ((0, b0), (1, b1)):
         truth, _ = run_oracle(p, a, b, c, oracle.MODE_TRUTH)
-        assert int(truth[row]) == 0x3f81, hex(int(truth[row]))          # both sums round to 1 + 2^-7
+        assert int(truth.view(np.uint16)[row]) == one_plus_2u, hex(int(truth.view(np.uint16)[row]))
         for path, variant in ((GENERIC, None), (GETT, 2), (GETT, 3)):
             say("%s row=%d path=%s shape=%s" % (p.name, row, path, variant))
             got = run_gpu(p, a, b, c, force_path=path, variant=variant, precision=1)
-            assert int(got[row]) == int(truth[row]), (row, path, variant, hex(int(got[row])))
+            assert int(got.view(np.uint16)[row]) == one_plus_2u, (row, path, variant, hex(int(got.view(np.uint16)[row])))
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64"])
