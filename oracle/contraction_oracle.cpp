@@ -254,8 +254,6 @@ template <class R, class RA> struct Narrow<std::complex<R>, std::complex<RA>> {
 inline long double modulus(long double x) { return fabsl(x); }
 inline long double modulus(std::complex<long double> x) { return hypotl(x.real(), x.imag()); }
 inline double modulus(double x) { return std::fabs(x); }
-inline long double modulus(half16 x) { return fabsl((long double)x); }
-inline long double modulus(bfloat16 x) { return fabsl((long double)x); }
 inline float modulus(float x) { return std::fabs(x); }
 inline double modulus(std::complex<double> x) { return std::hypot(x.real(), x.imag()); }
 inline float modulus(std::complex<float> x) { return std::hypot(x.real(), x.imag()); }

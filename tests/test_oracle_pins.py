@@ -249,7 +249,7 @@ _PYTHAGOREAN = [(3, 4, 5), (5, 12, 13), (8, 15, 17), (7, 24, 25), (20, 21, 29), 
 
 
 @pytest.mark.parametrize("mode", [oracle.MODE_TRUTH, oracle.MODE_TIMED], ids=["truth", "timed"])
-@pytest.mark.parametrize("dtype", ["c128", "c64", "f64", "f32", "f16"])
+@pytest.mark.parametrize("dtype", ["c128", "c64", "f64", "f32", "f16", "bf16"])
 def test_normaliser_on_exact_moduli(dtype, mode):
     """S = sum_P |op(a)||op(b)| with the complex MODULUS (the error measure's denominator).
     Complex operands are drawn from Gaussian integers with integer moduli, in all sign, swap and
@@ -276,7 +276,8 @@ def test_normaliser_on_exact_moduli(dtype, mode):
                 v[at] = complex(x * int(rng.choice([-1, 1])), y * int(rng.choice([-1, 1])))
             else:
                 r = int(rng.integers(0, 9))
-                v[at] = r * int(rng.choice([-1, 1]))
+                x = r * int(rng.choice([-1, 1]))
+                v[at] = W.bf16_bits(np.float32(x)).reshape(())[()] if dtype == "bf16" else x
             mod[at] = r
         return buf, mod
 
@@ -298,9 +299,9 @@ def einsum_reference(p: W.Problem, bufA, bufB, bufC):
             letters.setdefault(l, "abcdefghijklmnopqrstuvwxyzABCDEFGHIJKLMNOPQRSTUVWXYZ"[len(letters)])
     sub = lambda t: "".join(letters[l] for l in t.labels)
     hi = np.complex128 if p.dtype in ("c128", "c64") else np.float64
-    vA = W.strided_view(bufA, p.A).astype(hi)
-    vB = W.strided_view(bufB, p.B).astype(hi)
-    vC = W.strided_view(bufC, p.D).astype(hi)
+    vA = values_of(p, bufA, p.A).astype(hi)
+    vB = values_of(p, bufB, p.B).astype(hi)
+    vC = values_of(p, bufC, p.D).astype(hi)
     if p.opA:
         vA = np.conj(vA)
     if p.opB:
@@ -313,7 +314,7 @@ def einsum_reference(p: W.Problem, bufA, bufB, bufC):
     return out
 
 
-@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64", "f16"])
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64", "f16", "bf16"])
 @pytest.mark.parametrize("seed", range(10))
 def test_einsum_random_problems(dtype, seed):
     rng = np.random.default_rng(3000 + seed)
@@ -325,8 +326,8 @@ def test_einsum_random_problems(dtype, seed):
         _, S = run_oracle(p, a, b, c, oracle.MODE_TRUTH, want_S=True)
         k = p.sizes()[3]
         bound = (k + 4) * UNIT_ROUNDOFF[p.dtype] * (abs(p.alpha) * W.strided_view(S, p.D)
-                                                    + abs(p.beta) * np.abs(W.strided_view(c, p.D))) * 4
-        assert np.all(np.abs(W.strided_view(d, p.D) - ref) <= bound + 1e-300), (p, mode)
+                                                    + abs(p.beta) * np.abs(values_of(p, c, p.D))) * 4
+        assert np.all(np.abs(values_of(p, d, p.D) - ref) <= bound + 1e-300), (p, mode)
 
 
 @pytest.mark.parametrize("p", W.configs_reduced(), ids=lambda p: p.name)
@@ -456,7 +457,7 @@ def test_all_ones_config1_value():
 
 
 # ---- P4: one-hot operand => pure gather / permutation, bit exact -----------------------
-@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64", "f16"])
+@pytest.mark.parametrize("dtype", ["f64", "f32", "c128", "c64", "f16", "bf16"])
 def test_delta_operand_reproduces_permutation(dtype):
     """B[k..., n...] = prod delta(k_i, n_i)  =>  D[m..., n...] = A[m..., k... = n...]: each
     sum has exactly one non-zero term, so D is a bit-exact re-layout of A."""
@@ -470,8 +471,8 @@ def test_delta_operand_reproduces_permutation(dtype):
     vb = W.strided_view(b, B)
     for k0 in range(5):
         for k1 in range(2):
-            vb[k1, k0, k1, k0] = 1.0
-    c = np.full(D.size, np.nan, dtype=p.np_dtype)          # beta == 0: never read
+            vb[k1, k0, k1, k0] = 0x3f80 if dtype == "bf16" else 1.0
+    c = np.full(D.size, 0x7fc0 if dtype == "bf16" else np.nan, dtype=p.np_dtype)          # NaN; beta == 0: never read
     d, _ = run_oracle(p, a, b, c)
     vA, vD = W.strided_view(a, A), W.strided_view(d, D)
     for m0, m1, k0, k1 in itertools.product(range(3), range(4), range(5), range(2)):
