@@ -529,7 +529,9 @@ def main():
         return pmc_summary(args)
 
     import torch
-    import paper_2601_07827_amd as T          # raises if libtcx.so is not built: no fallback
+    import __graft_entry__
+    __graft_entry__.ensure_built()            # compiles only where no library is there yet
+    import paper_2601_07827_amd as T          # raises if libtcx.so is missing: no fallback
 
     torch.cuda.set_device(0)
     h = T.tcx_create_handle()

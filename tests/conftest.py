@@ -8,5 +8,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+import __graft_entry__  # noqa: E402
+
+__graft_entry__.ensure_built()          # a fresh checkout has no library yet; an existing one is loaded as it is
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
