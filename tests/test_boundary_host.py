@@ -598,6 +598,10 @@ def test_sixteen_bit_plans(handle, dt16):
     f32 = T.tcx_create_tensor_info(handle, T.TCX_F32, D.extents, D.strides)
     assert _code(T.tcx_create_product, handle, 0, infos[0], [1, 3], 0, infos[1], [3, 2], 0, f32, [1, 2], 0, f32, [1, 2]) == T.TCX_ERR_DTYPE_MIX
     T.tcx_destroy_tensor_info(f32)
+    # the two 16-bit formats do not mix either
+    other = T.tcx_create_tensor_info(handle, T.TCX_BF16 if dt16 == T.TCX_F16 else T.TCX_F16, B.extents, B.strides)
+    assert _code(T.tcx_create_product, handle, 0, infos[0], [1, 3], 0, other, [3, 2], 0, infos[2], [1, 2], 0, infos[2], [1, 2]) == T.TCX_ERR_DTYPE_MIX
+    T.tcx_destroy_tensor_info(other)
     for i in infos:
         T.tcx_destroy_tensor_info(i)
     # an outer product of 16-bit vectors: not streamed, planned on the tiled or generic kernel
